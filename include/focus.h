@@ -1,0 +1,112 @@
+/*
+ * focus.h -- C ABI of libfocus.so: the group-gated sparse attention forward of
+ * "Composing Sparse Attention via Learned Grouping" (Focus) on one MI355X.
+ *
+ * Two calls make the hot path:
+ *   focus_assign    scores every query and key vector against K centroids per
+ *                   head (Sec. 2, Eq. 1, in the per-head dot-product form),
+ *                   keeps each token's top-k groups (Sec. 2 "Efficiency at
+ *                   inference", Sec. 3.6), and buckets tokens by group in
+ *                   ascending position (the stable sort of App. D);
+ *   focus_attn_fwd  exact-softmax attention over the pairs that App. D Eq. 3
+ *                   allows, generalised to top-k sets: pair (i,j) is attended
+ *                   iff j <= i and (i - j < window or the two membership sets
+ *                   intersect); each allowed pair enters one softmax once.
+ *
+ * Conventions
+ *   - extern "C", no exceptions, no torch types.  Every call returns a
+ *     focus_status; focus_last_error() gives the message of the last failure on
+ *     the calling thread.
+ *   - q, k, v, out, centroids, workspace, lse, row_pairs are DEVICE pointers of
+ *     the current HIP device; `p` and p->head_map are HOST pointers.
+ *   - q, out: [B,Hq,n,d]; k, v: [B,Hkv,n,d]; contiguous, d innermost, 16-byte
+ *     aligned.  centroids: [Hkv,K,d] fp32 (used as given, never renormalised).
+ *   - The caller owns all buffers.  The library allocates no device memory and
+ *     keeps no state between calls.  The workspace is caller-allocated,
+ *     256-byte aligned, at least focus_workspace_size() bytes, and carries the
+ *     result of focus_assign to focus_attn_fwd (same params, same k).
+ *   - focus_assign and focus_attn_fwd only enqueue work on `stream`
+ *     (a hipStream_t passed as void*, NULL = default stream) and return; the
+ *     caller synchronises.  Inputs are never modified; out must not alias them.
+ *   - Argument errors are detected on the host before anything is launched.
+ *     Non-finite inputs give undefined results.
+ */
+#ifndef FOCUS_H
+#define FOCUS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FOCUS_OK = 0,
+    FOCUS_EINVAL = -1,        /* bad argument (NULL pointer, range, alignment) */
+    FOCUS_EUNSUPPORTED = -2,  /* valid request this build has no kernel for    */
+    FOCUS_EWORKSPACE = -3,    /* workspace too small or misaligned             */
+    FOCUS_EHIP = -4           /* a HIP call failed (launch error text kept)    */
+} focus_status;
+
+typedef enum { FOCUS_F32 = 0, FOCUS_BF16 = 1 } focus_dtype;
+
+typedef struct {
+    int32_t B, Hq, Hkv, n, d;  /* d in {64,128}; Hq % Hkv == 0 unless head_map   */
+    int32_t K, topk;           /* 1 <= topk <= K <= 32 groups per KV head        */
+    int32_t window;            /* >= 1 keys including the query itself; a window
+                                  >= n means plain causal attention              */
+    int32_t causal;            /* 1; causal = 0 is FOCUS_EUNSUPPORTED            */
+    int32_t dtype;             /* focus_dtype of q, k, v, out                    */
+    float scale;               /* logit scale, 0 selects 1/sqrt(d) (Sec. 2)      */
+    float softcap;             /* 0 = off, else logit = softcap*tanh(scale*q.k/softcap),
+                                  applied before masking                         */
+    const int32_t *head_map;   /* HOST [Hq] query head -> KV head (keys, values,
+                                  key membership and centroids); NULL selects
+                                  h / (Hq / Hkv)                                 */
+} focus_params;
+
+/* Bytes of workspace the two calls need for these params.  Pure host code. */
+focus_status focus_workspace_size(const focus_params *p, size_t *bytes);
+
+/* Sec. 2 Eq. 1 + top-k + bucketing.  Fills the workspace: membership bit masks
+ * (bit g = token belongs to group g; ties in the top-k go to the smaller group
+ * index; scores are the fp64 dot products accumulated in index order), per-group
+ * counts and position-ascending index lists, and the internal schedule that
+ * focus_attn_fwd consumes. */
+focus_status focus_assign(const focus_params *p, const void *q, const void *k,
+                          const float *centroids, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/* App. D Eq. 3 with top-k sets, exact softmax (Sec. 1), after focus_assign on
+ * the same workspace.  out [B,Hq,n,d] in p->dtype.  lse (nullable) [B,Hq,n]
+ * fp32: natural log of the sum of exp of the final logits of the row.
+ * row_pairs (nullable) [B,Hq,n] int32: number of pairs the row attended.  The
+ * workspace is written (staging of V). */
+focus_status focus_attn_fwd(const focus_params *p, const void *q, const void *k,
+                            const void *v, void *workspace, size_t workspace_bytes,
+                            void *out, float *lse, int32_t *row_pairs, void *stream);
+
+/* Device pointers INTO the workspace for parity checks; valid until the
+ * workspace is overwritten.  Any output pointer may be NULL.
+ *   mq [B,Hq,n], mk [B,Hkv,n]                   uint32 membership masks
+ *   q_group_counts [B,Hq,K], k_group_counts [B,Hkv,K]
+ *   q_group_lists [B,Hq,topk*n], k_group_lists [B,Hkv,topk*n]: per (b,h) the
+ *     lists of group 0,1,.. back to back, each position-ascending. */
+focus_status focus_workspace_views(const focus_params *p, void *workspace,
+                                   const uint32_t **mq, const uint32_t **mk,
+                                   const int32_t **q_group_counts,
+                                   const int32_t **k_group_counts,
+                                   const int32_t **q_group_lists,
+                                   const int32_t **k_group_lists);
+
+/* Message of the last failure on this thread (static storage, never NULL). */
+const char *focus_last_error(void);
+
+/* major*10000 + minor*100 + patch */
+int focus_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOCUS_H */

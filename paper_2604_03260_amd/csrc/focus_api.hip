@@ -1,0 +1,236 @@
+// Host side of libfocus.so: argument checks, workspace layout, dispatch.
+// Everything that computes runs in the HIP kernels of the other translation units.
+#include "../../include/focus.h"
+#include "focus_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_err[512] = "no error";
+
+focus_status fail(focus_status st, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Validates the params and derives the workspace layout and the head map.
+focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap* hm)
+{
+    using namespace focus;
+    if (!p) return fail(FOCUS_EINVAL, "params is NULL");
+    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->n < 1)
+        return fail(FOCUS_EINVAL, "B, Hq, Hkv, n must be >= 1 (got %d %d %d %d)", p->B, p->Hq, p->Hkv, p->n);
+    if (p->dtype != FOCUS_F32 && p->dtype != FOCUS_BF16)
+        return fail(FOCUS_EINVAL, "unknown dtype %d", p->dtype);
+    if (p->K < 1 || p->K > 32) return fail(FOCUS_EINVAL, "K must be in [1,32] (got %d)", p->K);
+    if (p->topk < 1 || p->topk > p->K)
+        return fail(FOCUS_EINVAL, "topk must be in [1,K] (got %d, K=%d)", p->topk, p->K);
+    if (p->window < 1) return fail(FOCUS_EINVAL, "window must be >= 1 (got %d)", p->window);
+    if (p->causal != 0 && p->causal != 1) return fail(FOCUS_EINVAL, "causal must be 0 or 1");
+    if (!(p->scale >= 0.0f) || !std::isfinite(p->scale))
+        return fail(FOCUS_EINVAL, "scale must be finite and >= 0");
+    if (!(p->softcap >= 0.0f) || !std::isfinite(p->softcap))
+        return fail(FOCUS_EINVAL, "softcap must be finite and >= 0");
+    if (p->d < 1) return fail(FOCUS_EINVAL, "d must be >= 1");
+    if (p->head_map) {
+        for (int h = 0; h < p->Hq; ++h)
+            if (p->head_map[h] < 0 || p->head_map[h] >= p->Hkv)
+                return fail(FOCUS_EINVAL, "head_map[%d]=%d is outside [0,Hkv)", h, p->head_map[h]);
+    } else if (p->Hq % p->Hkv != 0) {
+        return fail(FOCUS_EINVAL, "Hq (%d) is not a multiple of Hkv (%d) and no head_map given", p->Hq, p->Hkv);
+    }
+    // valid, but no kernel in this build
+    if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "non-causal attention is not built");
+    if (p->d != 64 && p->d != 128) return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64 or 128)", p->d);
+    if (p->Hq > MAX_HQ || p->Hkv > MAX_HQ)
+        return fail(FOCUS_EUNSUPPORTED, "more than %d heads is not built", MAX_HQ);
+    if (p->n > (1 << 24)) return fail(FOCUS_EUNSUPPORTED, "n above 2^24 is not built");
+    if ((int64_t)p->B * p->Hq > 65535 || (int64_t)p->B * p->Hkv > 65535)
+        return fail(FOCUS_EUNSUPPORTED, "B*H above 65535 is not built");
+
+    memset(L, 0, sizeof(*L));
+    L->B = p->B; L->Hq = p->Hq; L->Hkv = p->Hkv; L->n = p->n; L->d = p->d;
+    L->K = p->K; L->topk = p->topk; L->window = p->window;
+    L->dtype = p->dtype;
+    L->elem = (p->dtype == FOCUS_F32) ? 4 : 2;
+    L->scale = (p->scale > 0.0f) ? p->scale : (float)(1.0 / std::sqrt((double)p->d));
+    L->softcap = p->softcap;
+    L->dense = (p->window >= p->n || 2 * p->topk > p->K) ? 1 : 0;
+    if (L->dense) {
+        L->NC = 1;
+    } else {
+        uint64_t c = 1;
+        int kk = p->topk;
+        for (int i = 1; i <= kk; ++i) {
+            c = c * (uint64_t)(p->K - kk + i) / (uint64_t)i;
+            if (c > (uint64_t)MAX_CLASSES) break;
+        }
+        if (c > (uint64_t)MAX_CLASSES)
+            return fail(FOCUS_EUNSUPPORTED, "C(K=%d, topk=%d) membership classes exceed %d", p->K, p->topk, MAX_CLASSES);
+        L->NC = (int)c;
+    }
+    L->nblk = (p->n + SB - 1) / SB;
+    L->NT = (p->n + BQ - 1) / BQ + L->NC;
+    L->NQP = L->NT * BQ;
+    L->NKP = ((p->n + KT - 1) / KT + L->NC) * KT;
+
+    for (int h = 0; h < p->Hq; ++h)
+        hm->kv[h] = (uint8_t)(p->head_map ? p->head_map[h] : h / (p->Hq / p->Hkv));
+
+    const size_t BHq = (size_t)p->B * p->Hq, BHk = (size_t)p->B * p->Hkv;
+    const size_t n = (size_t)p->n;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    L->off_mq = take(BHq * n * 4);
+    L->off_mk = take(BHk * n * 4);
+    L->off_qgc = take(BHq * L->K * 4);
+    L->off_kgc = take(BHk * L->K * 4);
+    L->off_qgl = take(BHq * n * L->topk * 4);
+    L->off_kgl = take(BHk * n * L->topk * 4);
+    L->off_qgo = take(BHq * (L->K + 1) * 4);
+    L->off_kgo = take(BHk * (L->K + 1) * 4);
+    L->off_qcls = take(BHq * n);
+    L->off_kcls = take(BHk * ((size_t)L->nblk * SB));
+    L->off_qbc = take(BHq * (L->nblk + 1) * L->NC * 4);
+    L->off_kbc = take(BHk * (L->nblk + 1) * L->NC * 4);
+    L->off_qbg = take(BHq * (L->nblk + 1) * L->K * 4);
+    L->off_kbg = take(BHk * (L->nblk + 1) * L->K * 4);
+    L->off_qcc = take(BHq * L->NC * 4);
+    L->off_kcc = take(BHk * L->NC * 4);
+    L->off_qco = take(BHq * (L->NC + 1) * 4);
+    L->off_kco = take(BHk * (L->NC + 1) * 4);
+    L->off_clsmask = take((size_t)L->NC * 4);
+    L->off_qperm = take(BHq * L->NQP * 4);
+    L->off_kpos = take(BHk * L->NKP * 4);
+    L->off_jobs = take(BHq * L->NT * 4);
+    if (p->dtype == FOCUS_BF16) {
+        L->off_kc = take(BHk * L->NKP * (size_t)p->d * 2);
+        L->off_vt = take(BHk * L->NKP * (size_t)p->d * 2);
+    } else {
+        L->off_kc = L->off_vt = off;
+    }
+    L->total = off;
+    return FOCUS_OK;
+}
+
+focus_status check_ws(const focus::Layout& L, const void* ws, size_t bytes)
+{
+    if (!ws) return fail(FOCUS_EINVAL, "workspace is NULL");
+    if (((uintptr_t)ws & 255) != 0) return fail(FOCUS_EWORKSPACE, "workspace is not 256-byte aligned");
+    if (bytes < L.total)
+        return fail(FOCUS_EWORKSPACE, "workspace has %zu bytes, %zu needed", bytes, L.total);
+    return FOCUS_OK;
+}
+
+bool misaligned16(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+focus_status focus_workspace_size(const focus_params* p, size_t* bytes)
+{
+    if (!bytes) return fail(FOCUS_EINVAL, "bytes is NULL");
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = make_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    *bytes = L.total;
+    return FOCUS_OK;
+}
+
+focus_status focus_assign(const focus_params* p, const void* q, const void* k, const float* centroids,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = make_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (!q || !k || !centroids) return fail(FOCUS_EINVAL, "q, k and centroids must not be NULL");
+    if (misaligned16(q) || misaligned16(k) || misaligned16(centroids))
+        return fail(FOCUS_EINVAL, "q, k and centroids must be 16-byte aligned");
+    st = check_ws(L, workspace, workspace_bytes);
+    if (st != FOCUS_OK) return st;
+    hipError_t e = focus::launch_assign(L, hm, q, k, centroids, (char*)workspace, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_assign: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+focus_status focus_attn_fwd(const focus_params* p, const void* q, const void* k, const void* v,
+                            void* workspace, size_t workspace_bytes, void* out, float* lse,
+                            int32_t* row_pairs, void* stream)
+{
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = make_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (!q || !k || !v || !out) return fail(FOCUS_EINVAL, "q, k, v and out must not be NULL");
+    if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(out))
+        return fail(FOCUS_EINVAL, "q, k, v and out must be 16-byte aligned");
+    if (out == q || out == k || out == v) return fail(FOCUS_EINVAL, "out must not alias an input");
+    st = check_ws(L, workspace, workspace_bytes);
+    if (st != FOCUS_OK) return st;
+    hipError_t e;
+    if (L.dtype == FOCUS_BF16)
+        e = focus::launch_attn_mfma(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
+    else
+        e = focus::launch_attn_simple(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_fwd: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+// Same contract as focus_attn_fwd, but always through the fp32 vector kernel
+// (no matrix cores).  Used by tests to cross-check the MFMA kernel at sizes the
+// CPU oracle cannot cover in full; not declared in the public header.
+focus_status focus_attn_fwd_vector(const focus_params* p, const void* q, const void* k, const void* v,
+                                   void* workspace, size_t workspace_bytes, void* out, float* lse,
+                                   int32_t* row_pairs, void* stream)
+{
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = make_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (!q || !k || !v || !out) return fail(FOCUS_EINVAL, "q, k, v and out must not be NULL");
+    st = check_ws(L, workspace, workspace_bytes);
+    if (st != FOCUS_OK) return st;
+    hipError_t e = focus::launch_attn_simple(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs,
+                                             (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_fwd_vector: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+focus_status focus_workspace_views(const focus_params* p, void* workspace, const uint32_t** mq,
+                                   const uint32_t** mk, const int32_t** q_group_counts,
+                                   const int32_t** k_group_counts, const int32_t** q_group_lists,
+                                   const int32_t** k_group_lists)
+{
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = make_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (!workspace) return fail(FOCUS_EINVAL, "workspace is NULL");
+    char* ws = (char*)workspace;
+    if (mq) *mq = (const uint32_t*)(ws + L.off_mq);
+    if (mk) *mk = (const uint32_t*)(ws + L.off_mk);
+    if (q_group_counts) *q_group_counts = (const int32_t*)(ws + L.off_qgc);
+    if (k_group_counts) *k_group_counts = (const int32_t*)(ws + L.off_kgc);
+    if (q_group_lists) *q_group_lists = (const int32_t*)(ws + L.off_qgl);
+    if (k_group_lists) *k_group_lists = (const int32_t*)(ws + L.off_kgl);
+    return FOCUS_OK;
+}
+
+const char* focus_last_error(void) { return g_err; }
+
+int focus_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,398 @@
+// focus_assign: centroid scoring, top-k membership, bucketing by group and by
+// membership class (Sec. 2 Eq. 1 in per-head dot-product form; Sec. 2
+// "Efficiency at inference"; the stable sort by group of App. D done as a
+// counting sort).
+//
+// Kernels, all launched per (sort block of SB positions, batch*head):
+//   score_topk   streams q (or k) once, scores every token against the K
+//                centroids of its KV head in fp64 (products are exact in fp64,
+//                added in index order, so the result is reproducible bit for
+//                bit), keeps the top-k groups, writes the membership mask, the
+//                class id and the per-block histograms of classes and groups;
+//   scan_blocks  exclusive scan of the histograms over the sort blocks;
+//   plan_heads   class offsets (padded to tile multiples), group list offsets,
+//                the class -> group-mask table and the heaviest-first job list
+//                of query tiles;
+//   scatter      stable ranks inside a block by wavefront ballot + popcount,
+//                coalesced 4-byte writes of the class-ordered position arrays
+//                and of the per-group index lists.
+#include "focus_internal.h"
+#include <hip/hip_bf16.h>
+
+namespace focus {
+
+namespace {
+
+__device__ inline float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// ---------------------------------------------------------------- score + top-k
+constexpr int ROW_CHUNK_BYTES = 128;                 // bytes of every row staged per phase
+constexpr int ROW_STRIDE = ROW_CHUNK_BYTES + 16;     // padded LDS row stride
+
+template <typename T, int KMAX>
+__global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, const T* __restrict__ x,
+                                                        const float* __restrict__ cents, int is_query,
+                                                        char* __restrict__ ws)
+{
+    extern __shared__ __align__(16) char smem[];
+    char* s_rows = smem;                                             // SB * ROW_STRIDE
+    double* s_cent = (double*)(smem + SB * ROW_STRIDE);              // [d][KMAX]
+    __shared__ uint32_t s_binom[33 * 33];
+    __shared__ int s_hist_c[MAX_CLASSES];
+    __shared__ int s_hist_g[32];
+
+    const int tid = threadIdx.x;
+    const int blk = blockIdx.x;
+    const int bh = blockIdx.y;
+    const int H = is_query ? L.Hq : L.Hkv;
+    const int h = bh % H;
+    const int hk = is_query ? hm.kv[h] : h;
+    const int d = L.d, K = L.K, n = L.n;
+    constexpr int EPC = 16 / sizeof(T);                              // elements per 16-byte chunk
+    constexpr int CPR = ROW_CHUNK_BYTES / 16;                        // chunks per staged row
+    const int row_bytes = d * (int)sizeof(T);
+    const int phases = row_bytes / ROW_CHUNK_BYTES;
+
+    for (int e = tid; e < d * KMAX; e += SB) {
+        int t = e / KMAX, g = e % KMAX;
+        s_cent[e] = (g < K) ? (double)cents[((size_t)hk * K + g) * d + t] : 0.0;
+    }
+    for (int e = tid; e < 33 * 33; e += SB) s_binom[e] = binom_u32(e / 33, e % 33);
+    for (int e = tid; e < MAX_CLASSES; e += SB) s_hist_c[e] = 0;
+    if (tid < 32) s_hist_g[tid] = 0;
+
+    double acc[KMAX];
+#pragma unroll
+    for (int g = 0; g < KMAX; ++g) acc[g] = 0.0;
+
+    const int pos = blk * SB + tid;
+    const int rows_here = min(SB, n - blk * SB);
+    const char* gbase = (const char*)x + ((size_t)bh * n + (size_t)blk * SB) * row_bytes;
+
+    for (int ph = 0; ph < phases; ++ph) {
+        __syncthreads();
+        // coalesced: consecutive threads fetch consecutive 16-byte chunks of a 128-byte row segment
+        for (int cid = tid; cid < SB * CPR; cid += SB) {
+            int r = cid / CPR, cc = cid % CPR;
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if (r < rows_here)
+                val = *(const uint4*)(gbase + (size_t)r * row_bytes + ph * ROW_CHUNK_BYTES + cc * 16);
+            *(uint4*)(s_rows + r * ROW_STRIDE + cc * 16) = val;
+        }
+        __syncthreads();
+        const int tbase = ph * (ROW_CHUNK_BYTES / (int)sizeof(T));
+#pragma unroll 1
+        for (int cc = 0; cc < CPR; ++cc) {
+            uint4 val = *(const uint4*)(s_rows + tid * ROW_STRIDE + cc * 16);
+            double xv[EPC];
+            if constexpr (sizeof(T) == 4) {
+                xv[0] = (double)__uint_as_float(val.x); xv[1] = (double)__uint_as_float(val.y);
+                xv[2] = (double)__uint_as_float(val.z); xv[3] = (double)__uint_as_float(val.w);
+            } else {
+                const uint32_t w4[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    xv[2 * e] = (double)bf16_bits_to_f32((uint16_t)(w4[e] & 0xffffu));
+                    xv[2 * e + 1] = (double)bf16_bits_to_f32((uint16_t)(w4[e] >> 16));
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) {
+                const double* cr = s_cent + (size_t)(tbase + cc * EPC + e) * KMAX;
+#pragma unroll
+                for (int g = 0; g < KMAX; ++g) acc[g] = fma(xv[e], cr[g], acc[g]);
+            }
+        }
+    }
+
+    // top-k by rank counting; ties go to the smaller group index
+    uint32_t mask = 0;
+#pragma unroll
+    for (int g = 0; g < KMAX; ++g) {
+        if (g < K) {
+            int beaten = 0;
+#pragma unroll
+            for (int o = 0; o < KMAX; ++o) {
+                if (o < K && o != g)
+                    beaten += (acc[o] > acc[g] || (acc[o] == acc[g] && o < g)) ? 1 : 0;
+            }
+            if (beaten < L.topk) mask |= (1u << g);
+        }
+    }
+    // class = colex rank of the membership set among all topk-subsets
+    int cls = 0;
+    if (!L.dense) {
+        int j = 0;
+        for (int g = 0; g < K; ++g)
+            if ((mask >> g) & 1u) { ++j; cls += (int)s_binom[g * 33 + j]; }
+    }
+    const bool valid = pos < n;
+    uint32_t* masks = (uint32_t*)(ws + (is_query ? L.off_mq : L.off_mk));
+    uint8_t* clsarr = (uint8_t*)(ws + (is_query ? L.off_qcls : L.off_kcls));
+    const size_t cls_stride = is_query ? (size_t)n : (size_t)L.nblk * SB;
+    if (valid) {
+        masks[(size_t)bh * n + pos] = mask;
+        clsarr[(size_t)bh * cls_stride + pos] = (uint8_t)cls;
+        atomicAdd(&s_hist_c[cls], 1);
+        for (int g = 0; g < K; ++g)
+            if ((mask >> g) & 1u) atomicAdd(&s_hist_g[g], 1);
+    }
+    __syncthreads();
+    int* bc = (int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + ((size_t)bh * (L.nblk + 1) + blk) * L.NC;
+    int* bg = (int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + blk) * K;
+    for (int c = tid; c < L.NC; c += SB) bc[c] = s_hist_c[c];
+    if (tid < K) bg[tid] = s_hist_g[tid];
+}
+
+// ---------------------------------------------------------------- scans over sort blocks
+// One work-group per (column, batch*head): exclusive scan of a histogram column
+// over the sort blocks, total in row nblk.
+__global__ __launch_bounds__(256) void scan_blocks_kernel(Layout L, int is_query, char* __restrict__ ws)
+{
+    __shared__ int s_wave[4];
+    __shared__ int s_carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = blockIdx.x;           // [0,NC): class column, [NC,NC+K): group column
+    const int bh = blockIdx.y;
+    int* base;
+    int stride;
+    if (col < L.NC) {
+        base = (int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + (size_t)bh * (L.nblk + 1) * L.NC + col;
+        stride = L.NC;
+    } else {
+        base = (int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + (size_t)bh * (L.nblk + 1) * L.K + (col - L.NC);
+        stride = L.K;
+    }
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < L.nblk; b0 += 256) {
+        const int b = b0 + tid;
+        const int v = (b < L.nblk) ? base[(size_t)b * stride] : 0;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int wbase = 0;
+        for (int w = 0; w < wave; ++w) wbase += s_wave[w];
+        const int carry = s_carry;
+        if (b < L.nblk) base[(size_t)b * stride] = carry + wbase + incl - v;
+        __syncthreads();
+        if (tid == 255) s_carry = carry + wbase + incl;
+        __syncthreads();
+    }
+    if (tid == 0) base[(size_t)L.nblk * stride] = s_carry;
+}
+
+// ---------------------------------------------------------------- per-head plan
+__global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int is_query, char* __restrict__ ws)
+{
+    __shared__ int s_cnt[MAX_CLASSES];
+    __shared__ int s_nt[MAX_CLASSES];
+    __shared__ int s_total;
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.x;
+    const int NC = L.NC, K = L.K;
+    const int* bc_tot = (const int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + ((size_t)bh * (L.nblk + 1) + L.nblk) * NC;
+    const int* bg_tot = (const int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + L.nblk) * K;
+    int* cc = (int*)(ws + (is_query ? L.off_qcc : L.off_kcc)) + (size_t)bh * NC;
+    int* co = (int*)(ws + (is_query ? L.off_qco : L.off_kco)) + (size_t)bh * (NC + 1);
+    int* gc = (int*)(ws + (is_query ? L.off_qgc : L.off_kgc)) + (size_t)bh * K;
+    int* go = (int*)(ws + (is_query ? L.off_qgo : L.off_kgo)) + (size_t)bh * (K + 1);
+    const int pad = is_query ? BQ : KT;
+
+    for (int c = tid; c < NC; c += 256) {
+        int v = bc_tot[c];
+        s_cnt[c] = v;
+        s_nt[c] = (v + BQ - 1) / BQ;
+        cc[c] = v;
+    }
+    if (tid < K) gc[tid] = bg_tot[tid];
+    __syncthreads();
+    if (tid == 0) {
+        int off = 0, tot = 0;
+        for (int c = 0; c < NC; ++c) {
+            co[c] = off;
+            off += (s_cnt[c] + pad - 1) / pad * pad;
+            tot += s_nt[c];
+        }
+        co[NC] = off;
+        s_total = tot;
+        int goff = 0;
+        for (int g = 0; g < K; ++g) { go[g] = goff; goff += bg_tot[g]; }
+        go[K] = goff;
+    }
+    // class -> group mask (written once, by the first query head)
+    if (is_query && bh == 0) {
+        uint32_t* clsmask = (uint32_t*)(ws + L.off_clsmask);
+        for (int c = tid; c < NC; c += 256) {
+            uint32_t m = 0;
+            if (L.dense) {
+                m = 0xffffffffu;
+            } else {
+                uint32_t r = (uint32_t)c;
+                int g = K - 1;
+                for (int j = L.topk; j >= 1; --j) {
+                    while (binom_u32(g, j) > r) --g;      // largest g with C(g,j) <= r
+                    m |= (1u << g);
+                    r -= binom_u32(g, j);
+                    --g;
+                }
+            }
+            clsmask[c] = m;
+        }
+    }
+    __syncthreads();
+    if (!is_query) return;
+    // job list: slot s = how many tiles from the end of its class a tile is; slot-major
+    // order starts every class's last (longest-prefix) tile first
+    int* jobs = (int*)(ws + L.off_jobs) + (size_t)bh * L.NT;
+    const int total = s_total;
+    for (int j = total + tid; j < L.NT; j += 256) jobs[j] = -1;
+    for (int c = 0; c < NC; ++c) {
+        const int ntc = s_nt[c];
+        for (int t = tid; t < ntc; t += 256) {
+            const int s = ntc - 1 - t;
+            int j = 0;
+            for (int c2 = 0; c2 < NC; ++c2) {
+                j += min(s_nt[c2], s);
+                if (c2 < c && s_nt[c2] > s) ++j;
+            }
+            jobs[j] = (c << 24) | t;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- fills
+__global__ void fill_i32_kernel(int* __restrict__ p, size_t count, int value)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < count; i += step) p[i] = value;
+}
+
+// ---------------------------------------------------------------- scatter
+__global__ __launch_bounds__(SB) void scatter_kernel(Layout L, int is_query, char* __restrict__ ws)
+{
+    __shared__ int s_wc[4][MAX_CLASSES];
+    __shared__ int s_wg[4][32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int blk = blockIdx.x, bh = blockIdx.y;
+    const int n = L.n, NC = L.NC, K = L.K;
+    const int pos = blk * SB + tid;
+    const bool valid = pos < n;
+    const uint32_t* masks = (const uint32_t*)(ws + (is_query ? L.off_mq : L.off_mk));
+    const uint8_t* clsarr = (const uint8_t*)(ws + (is_query ? L.off_qcls : L.off_kcls));
+    const size_t cls_stride = is_query ? (size_t)n : (size_t)L.nblk * SB;
+    const uint32_t mask = valid ? masks[(size_t)bh * n + pos] : 0u;
+    const int cls = valid ? (int)clsarr[(size_t)bh * cls_stride + pos] : -1;
+
+    for (int e = tid; e < 4 * MAX_CLASSES; e += SB) (&s_wc[0][0])[e] = 0;
+    __syncthreads();
+
+    const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    // stable rank among the tokens of the same class inside this wavefront
+    int rank_c = 0;
+    unsigned long long todo = __ballot(valid);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int c0 = __shfl(cls, leader, 64);
+        const unsigned long long same = __ballot(valid && cls == c0);
+        if (valid && cls == c0) rank_c = __popcll(same & lt);
+        if (lane == leader) s_wc[wave][c0] = __popcll(same);
+        todo &= ~same;
+    }
+    // per-wavefront totals of every group bit
+    for (int g = 0; g < K; ++g) {
+        const unsigned long long has = __ballot(valid && ((mask >> g) & 1u));
+        if (lane == 0) s_wg[wave][g] = __popcll(has);
+    }
+    __syncthreads();
+
+    const int* bc = (const int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + ((size_t)bh * (L.nblk + 1) + blk) * NC;
+    const int* bg = (const int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + blk) * K;
+    const int* co = (const int*)(ws + (is_query ? L.off_qco : L.off_kco)) + (size_t)bh * (NC + 1);
+    const int* go = (const int*)(ws + (is_query ? L.off_qgo : L.off_kgo)) + (size_t)bh * (K + 1);
+    if (valid) {
+        int before = 0;
+        for (int w = 0; w < wave; ++w) before += s_wc[w][cls];
+        const int dest = co[cls] + bc[cls] + before + rank_c;
+        if (is_query)
+            ((int*)(ws + L.off_qperm))[(size_t)bh * L.NQP + dest] = pos;
+        else
+            ((int*)(ws + L.off_kpos))[(size_t)bh * L.NKP + dest] = pos;
+    }
+    // group lists: position-ascending because ranks follow the position order
+    int* lists = (int*)(ws + (is_query ? L.off_qgl : L.off_kgl)) + (size_t)bh * L.topk * n;
+    for (int g = 0; g < K; ++g) {
+        const bool mine = valid && ((mask >> g) & 1u);
+        const unsigned long long has = __ballot(mine);
+        if (mine) {
+            int bw = 0;
+            for (int w = 0; w < wave; ++w) bw += s_wg[w][g];
+            lists[go[g] + bg[g] + bw + __popcll(has & lt)] = pos;
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, const float* cents, int is_query,
+                        char* ws, hipStream_t st)
+{
+    const int H = is_query ? L.Hq : L.Hkv;
+    dim3 grid(L.nblk, L.B * H);
+    const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
+    const size_t shm = (size_t)SB * ROW_STRIDE + (size_t)L.d * kmax * sizeof(double);
+#define FOCUS_LAUNCH_SCORE(KM)                                                                              \
+    do {                                                                                                    \
+        auto kern = score_topk_kernel<T, KM>;                                                               \
+        if (shm > 48 * 1024) {                                                                              \
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                               (int)shm);                                                   \
+            if (e != hipSuccess) return e;                                                                  \
+        }                                                                                                   \
+        hipLaunchKernelGGL(kern, grid, dim3(SB), shm, st, L, hm, (const T*)x, cents, is_query, ws);         \
+    } while (0)
+    switch (kmax) {
+        case 4: FOCUS_LAUNCH_SCORE(4); break;
+        case 8: FOCUS_LAUNCH_SCORE(8); break;
+        case 16: FOCUS_LAUNCH_SCORE(16); break;
+        default: FOCUS_LAUNCH_SCORE(32); break;
+    }
+#undef FOCUS_LAUNCH_SCORE
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, const void* k,
+                         const float* centroids, char* ws, hipStream_t st)
+{
+    hipError_t e;
+    // pads of the class-ordered position arrays
+    {
+        const size_t nq = (size_t)L.B * L.Hq * L.NQP, nk = (size_t)L.B * L.Hkv * L.NKP;
+        const int gq = (int)min((size_t)8192, (nq + 255) / 256), gk = (int)min((size_t)8192, (nk + 255) / 256);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(gq), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, -1);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kpos), nk, KPOS_PAD);
+    }
+    if (L.dtype == 0) {
+        if ((e = launch_score<float>(L, hm, q, centroids, 1, ws, st)) != hipSuccess) return e;
+        if ((e = launch_score<float>(L, hm, k, centroids, 0, ws, st)) != hipSuccess) return e;
+    } else {
+        if ((e = launch_score<uint16_t>(L, hm, q, centroids, 1, ws, st)) != hipSuccess) return e;
+        if ((e = launch_score<uint16_t>(L, hm, k, centroids, 0, ws, st)) != hipSuccess) return e;
+    }
+    for (int is_query = 1; is_query >= 0; --is_query) {
+        const int H = is_query ? L.Hq : L.Hkv;
+        hipLaunchKernelGGL(scan_blocks_kernel, dim3(L.NC + L.K, L.B * H), dim3(256), 0, st, L, is_query, ws);
+        hipLaunchKernelGGL(plan_heads_kernel, dim3(L.B * H), dim3(256), 0, st, L, is_query, ws);
+        hipLaunchKernelGGL(scatter_kernel, dim3(L.nblk, L.B * H), dim3(SB), 0, st, L, is_query, ws);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace focus

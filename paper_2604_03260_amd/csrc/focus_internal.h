@@ -1,0 +1,74 @@
+// Internal layout of the workspace and the launch entry points shared by the
+// translation units of libfocus.so.  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace focus {
+
+constexpr int SB = 256;        // positions per sort block (one work-group of the bucketing kernels)
+constexpr int BQ = 128;        // query rows per attention tile
+constexpr int KT = 128;        // keys per attention tile; class segments of the permuted keys are padded to this
+constexpr int MAX_CLASSES = 256;
+constexpr int MAX_HQ = 256;
+constexpr int KPOS_PAD = 0x7fffffff;  // position stored in padded key slots: never <= a query position
+
+struct HeadMap {               // query head -> KV head, passed by value to kernels
+    uint8_t kv[MAX_HQ];
+};
+
+// Everything the kernels need to know about shapes and where things live in the
+// workspace (byte offsets from its base, all multiples of 256).
+struct Layout {
+    int B, Hq, Hkv, n, d;
+    int K, topk, window;
+    int dtype;                 // 0 fp32, 1 bf16
+    int elem;                  // bytes per element
+    int NC;                    // number of membership classes (1 in dense mode)
+    int dense;                 // every causal pair allowed: one class, no masks beyond causal
+    int nblk;                  // ceil(n / SB)
+    int NQP;                   // padded per-head length of the class-ordered query index
+    int NKP;                   // padded per-head length of the class-ordered key arrays (multiple of KT)
+    int NT;                    // upper bound of query tiles per head
+    float scale;
+    float softcap;
+
+    size_t off_mq, off_mk;
+    size_t off_qgc, off_kgc;           // group counts
+    size_t off_qgl, off_kgl;           // group lists
+    size_t off_qgo, off_kgo;           // group list offsets [.,K+1]
+    size_t off_qcls, off_kcls;         // class id per position, uint8
+    size_t off_qbc, off_kbc;           // per sort block class histogram -> exclusive prefix [.,nblk,NC]
+    size_t off_qbg, off_kbg;           // per sort block group histogram -> exclusive prefix [.,nblk,K]
+    size_t off_qcc, off_kcc;           // class counts [.,NC]
+    size_t off_qco, off_kco;           // padded class offsets [.,NC+1]
+    size_t off_clsmask;                // group bit mask of each class [NC]
+    size_t off_qperm;                  // [B,Hq,NQP] positions in class order, -1 in pads
+    size_t off_kpos;                   // [B,Hkv,NKP] positions in class order, KPOS_PAD in pads
+    size_t off_jobs;                   // [B,Hq,NT] (class << 24 | tile) heaviest first, -1 unused
+    size_t off_kc;                     // [B,Hkv,NKP,d] keys in class order (bf16 path)
+    size_t off_vt;                     // [B,Hkv,NKP/KT,d,KT] values, transposed per key tile (bf16 path)
+    size_t total;
+};
+
+// colex rank of the k-subset `m` among all k-subsets (device + host)
+__host__ __device__ inline uint32_t binom_u32(int a, int b)
+{
+    if (b < 0 || b > a) return 0;
+    if (b > a - b) b = a - b;
+    uint64_t r = 1;
+    for (int i = 1; i <= b; ++i) r = r * (uint64_t)(a - b + i) / (uint64_t)i;
+    return (uint32_t)r;
+}
+
+hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, const void* k,
+                         const float* centroids, char* ws, hipStream_t st);
+hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q, const void* k,
+                              const void* v, char* ws, void* out, float* lse, int32_t* row_pairs,
+                              hipStream_t st);
+hipError_t launch_attn_mfma(const Layout& L, const HeadMap& hm, const void* q, const void* k,
+                            const void* v, char* ws, void* out, float* lse, int32_t* row_pairs,
+                            hipStream_t st);
+
+}  // namespace focus

@@ -1,0 +1,90 @@
+// Per query tile: which tiles of the class-ordered key arrays it must visit.
+//
+// A query tile holds up to BQ queries of ONE membership class, positions
+// ascending.  Keys are partitioned by class too, so every allowed pair of
+// App. D Eq. 3 (with top-k sets) is met exactly once:
+//   - key class shares a group with the query class: all its keys up to the
+//     tile's last query position (causal prefix);
+//   - otherwise: only its keys inside the union of the rows' local windows.
+// Per-element causal/window checks on positions finish the job inside a tile.
+#pragma once
+#include "focus_internal.h"
+
+namespace focus {
+
+struct TilePlan {
+    int t0[MAX_CLASSES];       // first key tile (global tile index inside the head)
+    int cum[MAX_CLASSES + 1];  // running number of tiles over the classes
+    uint8_t inter[MAX_CLASSES];
+    uint8_t blk_hi[SB];        // class ids of the sort block holding the upper bound
+    uint8_t blk_lo[SB];        // ... and the lower bound of the window span
+    int cls, tile, row0, nvalid, i_lo, i_hi, total;
+};
+
+// All threads of the work-group call this (blockDim.x >= 64).  Returns false when
+// the job slot is unused.
+__device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__ ws, int bhq, int bhk, int job,
+                                       TilePlan& P)
+{
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int NC = L.NC;
+    const int jv = ((const int*)(ws + L.off_jobs))[(size_t)bhq * L.NT + job];
+    if (jv < 0) return false;
+    const int c = jv >> 24, t = jv & 0xffffff;
+    const int* qco = (const int*)(ws + L.off_qco) + (size_t)bhq * (NC + 1);
+    const int* qcc = (const int*)(ws + L.off_qcc) + (size_t)bhq * NC;
+    const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
+    const int row0 = qco[c] + t * BQ;
+    const int nvalid = min(BQ, qcc[c] - t * BQ);
+    const int i_lo = qperm[row0];
+    const int i_hi = qperm[row0 + nvalid - 1];
+    const int x_hi = i_hi + 1;                              // keys with position < x_hi are causal for the tile
+    const int x_lo = max(0, i_lo - L.window + 1);           // keys with position < x_lo are outside every window
+    const uint8_t* kcls = (const uint8_t*)(ws + L.off_kcls) + (size_t)bhk * ((size_t)L.nblk * SB);
+    const int bh_i = x_hi / SB, bl_i = x_lo / SB;
+    const int part_hi = x_hi % SB, part_lo = x_lo % SB;
+    for (int e = tid; e < SB; e += nthr) {
+        P.blk_hi[e] = (e < part_hi) ? kcls[(size_t)bh_i * SB + e] : 0;
+        P.blk_lo[e] = (e < part_lo) ? kcls[(size_t)bl_i * SB + e] : 0;
+    }
+    if (tid == 0) {
+        P.cls = c; P.tile = t; P.row0 = row0; P.nvalid = nvalid; P.i_lo = i_lo; P.i_hi = i_hi;
+    }
+    __syncthreads();
+    const int* kbc = (const int*)(ws + L.off_kbc) + (size_t)bhk * (L.nblk + 1) * NC;
+    const int* kco = (const int*)(ws + L.off_kco) + (size_t)bhk * (NC + 1);
+    const uint32_t* clsmask = (const uint32_t*)(ws + L.off_clsmask);
+    const uint32_t mymask = clsmask[c];
+    for (int c2 = tid; c2 < NC; c2 += nthr) {
+        int pre_hi = kbc[(size_t)bh_i * NC + c2];
+        for (int e = 0; e < part_hi; ++e) pre_hi += (P.blk_hi[e] == c2) ? 1 : 0;
+        const bool inter = (clsmask[c2] & mymask) != 0;
+        const int koff = kco[c2];
+        int a = 0, b = 0;
+        if (inter) {
+            a = koff / KT;
+            b = (koff + pre_hi + KT - 1) / KT;
+        } else {
+            int pre_lo = kbc[(size_t)bl_i * NC + c2];
+            for (int e = 0; e < part_lo; ++e) pre_lo += (P.blk_lo[e] == c2) ? 1 : 0;
+            if (pre_hi > pre_lo) {
+                a = (koff + pre_lo) / KT;
+                b = (koff + pre_hi + KT - 1) / KT;
+            }
+        }
+        P.t0[c2] = a;
+        P.cum[c2 + 1] = b - a;                             // lengths first, summed below
+        P.inter[c2] = inter ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        P.cum[0] = 0;
+        for (int c2 = 0; c2 < NC; ++c2) { run += P.cum[c2 + 1]; P.cum[c2 + 1] = run; }
+        P.total = run;
+    }
+    __syncthreads();
+    return true;
+}
+
+}  // namespace focus

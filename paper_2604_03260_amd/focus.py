@@ -1,0 +1,149 @@
+"""Thin ctypes binding of libfocus.so: argument marshalling only.
+
+The functions mirror include/focus.h one to one (focus_workspace_size,
+focus_assign, focus_attn_fwd, focus_workspace_views, focus_last_error,
+focus_version).  Tensors are torch CUDA tensors used purely as device buffers;
+the calls are enqueued on torch's current stream.  There is no CPU fallback: a
+missing library is an error.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfocus.so")
+
+FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_EHIP = 0, -1, -2, -3, -4
+FOCUS_F32, FOCUS_BF16 = 0, 1
+
+EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_workspace_views",
+           "focus_last_error", "focus_version")
+
+
+class FocusParams(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("n", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("K", ctypes.c_int32), ("topk", ctypes.c_int32),
+        ("window", ctypes.c_int32), ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("softcap", ctypes.c_float),
+        ("head_map", ctypes.POINTER(ctypes.c_int32)),
+    ]
+
+
+class FocusError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("libfocus status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libfocus.so; builds it first only when no built library is present."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    pp = ctypes.POINTER(FocusParams)
+    lib.focus_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.focus_workspace_size.restype = ctypes.c_int
+    lib.focus_assign.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.focus_assign.restype = ctypes.c_int
+    lib.focus_attn_fwd.argtypes = [pp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.focus_attn_fwd.restype = ctypes.c_int
+    lib.focus_attn_fwd_vector.argtypes = [pp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.focus_attn_fwd_vector.restype = ctypes.c_int
+    lib.focus_workspace_views.argtypes = [pp, vp] + [ctypes.POINTER(vp)] * 6
+    lib.focus_workspace_views.restype = ctypes.c_int
+    lib.focus_last_error.argtypes = []
+    lib.focus_last_error.restype = ctypes.c_char_p
+    lib.focus_version.argtypes = []
+    lib.focus_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def make_params(B, Hq, Hkv, n, d, K, topk, window, causal=True, dtype="bf16", scale=0.0, softcap=0.0,
+                head_map=None):
+    """Returns (FocusParams, keepalive) -- keepalive owns the host head_map array."""
+    keep = None
+    hm = None
+    if head_map is not None:
+        keep = (ctypes.c_int32 * len(head_map))(*[int(x) for x in head_map])
+        hm = ctypes.cast(keep, ctypes.POINTER(ctypes.c_int32))
+    p = FocusParams(B, Hq, Hkv, n, d, K, topk, window, 1 if causal else 0,
+                    {"f32": FOCUS_F32, "bf16": FOCUS_BF16}[dtype], scale, softcap, hm)
+    p._keep = keep
+    return p
+
+
+def _check(st):
+    if st != FOCUS_OK:
+        raise FocusError(st, load_library().focus_last_error().decode())
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def focus_version():
+    return load_library().focus_version()
+
+
+def focus_last_error():
+    return load_library().focus_last_error().decode()
+
+
+def focus_workspace_size(p):
+    out = ctypes.c_size_t(0)
+    _check(load_library().focus_workspace_size(ctypes.byref(p), ctypes.byref(out)))
+    return out.value
+
+
+def focus_assign(p, q, k, centroids, workspace):
+    _check(load_library().focus_assign(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(centroids), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream()))
+
+
+def focus_attn_fwd(p, q, k, v, workspace, out, lse=None, row_pairs=None, vector=False):
+    fn = load_library().focus_attn_fwd_vector if vector else load_library().focus_attn_fwd
+    _check(fn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
+              workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse), _ptr(row_pairs), _stream()))
+
+
+def focus_workspace_views(p, workspace):
+    """Returns dict of torch tensors aliasing the workspace (no copies)."""
+    lib = load_library()
+    ptrs = [ctypes.c_void_p(0) for _ in range(6)]
+    _check(lib.focus_workspace_views(ctypes.byref(p), _ptr(workspace), *[ctypes.byref(x) for x in ptrs]))
+    base = workspace.data_ptr()
+    raw = workspace.view(torch.uint8).reshape(-1)
+
+    def view(ptr, count):
+        off = ptr.value - base
+        return raw[off:off + 4 * count].view(torch.int32)
+    B, Hq, Hkv, n, K, topk = p.B, p.Hq, p.Hkv, p.n, p.K, p.topk
+    return {
+        "mq": view(ptrs[0], B * Hq * n).view(B, Hq, n),
+        "mk": view(ptrs[1], B * Hkv * n).view(B, Hkv, n),
+        "q_group_counts": view(ptrs[2], B * Hq * K).view(B, Hq, K),
+        "k_group_counts": view(ptrs[3], B * Hkv * K).view(B, Hkv, K),
+        "q_group_lists": view(ptrs[4], B * Hq * topk * n).view(B, Hq, topk * n),
+        "k_group_lists": view(ptrs[5], B * Hkv * topk * n).view(B, Hkv, topk * n),
+    }
+
+
+def alloc_workspace(p, device="cuda"):
+    nbytes = focus_workspace_size(p)
+    return torch.empty(((nbytes + 255) // 256) * 256, dtype=torch.uint8, device=device)

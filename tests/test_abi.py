@@ -1,0 +1,98 @@
+"""The C-ABI library loads without a GPU, exports what include/focus.h declares,
+and turns bad arguments into status codes on the host (no launches)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_03260_amd import focus
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "focus.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(focus_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = focus.load_library()
+    names = declared_symbols()
+    assert set(names) == set(focus.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_error_string():
+    assert focus.focus_version() >= 100
+    assert isinstance(focus.focus_last_error(), str)
+
+
+def status_of(**kw):
+    base = dict(B=1, Hq=4, Hkv=2, n=256, d=64, K=4, topk=2, window=16)
+    base.update(kw)
+    p = focus.make_params(**base)
+    try:
+        return focus.FOCUS_OK, focus.focus_workspace_size(p)
+    except focus.FocusError as e:
+        return e.status, str(e)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), focus.FOCUS_OK),
+    (dict(K=0), focus.FOCUS_EINVAL),
+    (dict(K=33), focus.FOCUS_EINVAL),
+    (dict(topk=0), focus.FOCUS_EINVAL),
+    (dict(topk=5), focus.FOCUS_EINVAL),
+    (dict(window=0), focus.FOCUS_EINVAL),
+    (dict(n=0), focus.FOCUS_EINVAL),
+    (dict(Hq=5), focus.FOCUS_EINVAL),
+    (dict(Hq=5, head_map=[0, 1, 1, 0, 1]), focus.FOCUS_OK),
+    (dict(head_map=[0, 1, 2, 0]), focus.FOCUS_EINVAL),
+    (dict(scale=-1.0), focus.FOCUS_EINVAL),
+    (dict(softcap=float("nan")), focus.FOCUS_EINVAL),
+    (dict(d=80), focus.FOCUS_EUNSUPPORTED),
+    (dict(causal=False), focus.FOCUS_EUNSUPPORTED),
+    (dict(K=32, topk=8), focus.FOCUS_EUNSUPPORTED),
+    (dict(K=32, topk=1), focus.FOCUS_OK),
+    (dict(K=32, topk=20), focus.FOCUS_OK),          # 2k > K: plain causal attention, one class
+])
+def test_param_validation(kw, want):
+    st, info = status_of(**kw)
+    assert st == want, info
+
+
+def test_null_and_workspace_errors_before_any_launch():
+    lib = focus.load_library()
+    p = focus.make_params(1, 4, 2, 256, 64, 4, 2, 16)
+    need = focus.focus_workspace_size(p)
+    assert need > 0 and need % 256 == 0
+    vp = ctypes.c_void_p
+    # NULL tensors
+    st = lib.focus_assign(ctypes.byref(p), vp(0), vp(0), vp(0), vp(0), 0, vp(0))
+    assert st == focus.FOCUS_EINVAL
+    # fake non-NULL, aligned addresses are never dereferenced on these paths
+    fake = vp(0x1000)
+    st = lib.focus_assign(ctypes.byref(p), fake, fake, fake, vp(0), need, vp(0))
+    assert st == focus.FOCUS_EINVAL and "workspace" in focus.focus_last_error()
+    st = lib.focus_assign(ctypes.byref(p), fake, fake, fake, vp(0x1010), need, vp(0))
+    assert st == focus.FOCUS_EWORKSPACE
+    st = lib.focus_assign(ctypes.byref(p), fake, fake, fake, fake, need - 1, vp(0))
+    assert st == focus.FOCUS_EWORKSPACE
+    st = lib.focus_assign(ctypes.byref(p), vp(0x1004), fake, fake, fake, need, vp(0))
+    assert st == focus.FOCUS_EINVAL and "aligned" in focus.focus_last_error()
+    st = lib.focus_attn_fwd(ctypes.byref(p), fake, fake, fake, fake, need, fake, vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EINVAL and "alias" in focus.focus_last_error()
+    st = lib.focus_attn_fwd(ctypes.byref(p), fake, fake, fake, fake, need, vp(0), vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EINVAL
+    st = lib.focus_workspace_size(None, None)
+    assert st == focus.FOCUS_EINVAL
+
+
+def test_workspace_size_grows_with_problem():
+    a = focus.focus_workspace_size(focus.make_params(1, 4, 2, 256, 64, 4, 2, 16))
+    b = focus.focus_workspace_size(focus.make_params(1, 4, 2, 512, 64, 4, 2, 16))
+    c = focus.focus_workspace_size(focus.make_params(2, 4, 2, 512, 64, 4, 2, 16))
+    assert a < b < c

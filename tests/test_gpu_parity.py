@@ -1,0 +1,160 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 CPU oracle on the
+same seeded bytes.  Integer results (membership, lists, pair counts) bit-exact;
+outputs within the stated tolerances (bf16: max-abs 2e-2, mean-abs 2e-3;
+fp32: 1e-5)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_03260_amd import workloads
+from paper_2604_03260_amd.workloads import CONFIGS, Workload
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def small(name, **kw):
+    base = dict(name=name, config_id=90, B=1, Hq=4, Hkv=2, n=600, d=64, dtype="f32", K=4, topk=2, window=32)
+    base.update(kw)
+    return Workload(**base)
+
+
+SMALL_CASES = [
+    small("ragged_f32", n=777),
+    small("ragged_bf16", n=777, dtype="bf16", d=128),
+    small("one_token", n=1),
+    small("two_tokens", n=2, dtype="bf16"),
+    small("shorter_than_window", n=100, window=128),
+    small("window_one", n=300, window=1, topk=1),
+    small("tile_multiple", n=512, window=64, dtype="bf16"),
+    small("tile_plus_one", n=513, window=64, dtype="bf16", d=128),
+    small("hard_k8", n=1500, K=8, topk=1, window=100, dtype="bf16", d=128, Hq=8, Hkv=2),
+    small("k8_top2_mix", n=1400, K=8, topk=2, window=64, dtype="bf16", d=128, mixture=8),
+    small("k8_top3", n=900, K=8, topk=3, window=16),
+    small("k16_top1", n=900, K=16, topk=1, window=16, dtype="bf16"),
+    small("k32_top1", n=700, K=32, topk=1, window=8),
+    small("k5_top2", n=640, K=5, topk=2, window=20, dtype="bf16"),
+    small("k2_top1", n=1100, K=2, topk=1, window=50, dtype="bf16", d=128),
+    small("dense_window", n=700, window=700),
+    small("dense_k1", n=700, K=1, topk=1, window=4, dtype="bf16"),
+    small("dense_all_groups", n=520, K=4, topk=4, dtype="bf16", d=128),
+    small("dense_pigeonhole", n=520, K=4, topk=3),
+    small("softcap_f32", n=640, softcap=3.0),
+    small("softcap_bf16", n=900, softcap=50.0, dtype="bf16", d=128, K=8, topk=2, mixture=8),
+    small("batch_mha", B=3, Hq=3, Hkv=3, n=400, dtype="bf16"),
+    small("gqa8", Hq=8, Hkv=1, n=700, dtype="bf16", d=128),
+]
+
+
+@pytest.mark.parametrize("wl", SMALL_CASES, ids=[w.name for w in SMALL_CASES])
+def test_small_cases_all_rows(wl):
+    say("case", wl)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    stats = harness.check_attn(wl, inp, res, mq, mk)
+    harness.check_pair_totals(wl, res, mq, mk)
+    say(wl.name, stats)
+
+
+def test_custom_head_map_and_scale():
+    wl = small("head_map", Hq=5, Hkv=3, n=500, dtype="bf16", d=128)
+    hm = [2, 0, 0, 1, 2]
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp, head_map=hm, scale=0.2)
+    mq, mk = harness.check_assign(wl, inp, res, head_map=hm)
+    say(harness.check_attn(wl, inp, res, mq, mk, head_map=hm, scale=0.2))
+
+
+def test_all_tokens_in_one_class():
+    # identical centroids: every score ties, the two smallest group ids win everywhere
+    wl = small("ties", n=700, dtype="bf16")
+    inp = workloads.make_inputs(wl, "cuda")
+    inp["centroids"][:] = inp["centroids"][:, :1].clone()
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    assert np.all(mq == 0b0011) and np.all(mk == 0b0011)
+    harness.check_attn(wl, inp, res, mq, mk)
+
+
+def test_disjoint_roles_only_window_survives():
+    # queries all land in group 0 and keys in group 1: the mask is the window alone
+    wl = small("window_only", n=900, K=2, topk=1, window=37, Hq=2, Hkv=2)
+    inp = workloads.make_inputs(wl, "cuda")
+    c = torch.zeros_like(inp["centroids"])
+    c[:, 0, 0] = 1.0
+    c[:, 1, 1] = 1.0
+    inp["centroids"] = c
+    inp["q"][..., 0] = 50.0
+    inp["k"][..., 1] = 50.0
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    assert np.all(mq == 1) and np.all(mk == 2)
+    harness.check_attn(wl, inp, res, mq, mk, tol=dict(out_max=1e-4, out_mean=1e-5, lse=1e-3))
+    want = np.minimum(np.arange(wl.n) + 1, wl.window)
+    assert np.array_equal(res["row_pairs"].cpu().numpy()[0, 0], want)
+
+
+def test_deterministic_bytes():
+    wl = small("determinism", n=1500, dtype="bf16", d=128, K=8, topk=2)
+    inp = workloads.make_inputs(wl, "cuda")
+    a = harness.run_gpu(wl, inp)
+    b = harness.run_gpu(wl, inp)
+    for key in ("out", "lse", "row_pairs"):
+        assert torch.equal(a[key], b[key]), key
+    for key in a["views"]:
+        assert torch.equal(a["views"][key], b["views"][key]), key
+
+
+def test_vector_and_matrix_core_kernels_agree():
+    # bf16 through both attention kernels on the same workspace
+    wl = small("two_kernels", n=3000, dtype="bf16", d=128, K=4, topk=2, window=300, Hq=4, Hkv=1)
+    inp = workloads.make_inputs(wl, "cuda")
+    a = harness.run_gpu(wl, inp)
+    b = harness.run_gpu(wl, inp, vector=True)
+    assert torch.equal(a["row_pairs"], b["row_pairs"])
+    diff = (a["out"].float() - b["out"].float()).abs()
+    assert diff.max().item() <= 2e-2 and diff.mean().item() <= 2e-3
+    assert (a["lse"] - b["lse"]).abs().max().item() <= 1e-2
+
+
+# ---------------------------------------------------------------- the benchmark configurations
+def test_cfg1_full_all_rows():
+    wl = CONFIGS["cfg1"]
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    say("cfg1", harness.check_attn(wl, inp, res, mq, mk))
+    harness.check_pair_totals(wl, res, mq, mk)
+
+
+def test_cfg2_full_sampled_rows():
+    wl = CONFIGS["cfg2"]
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    rows = workloads.sample_rows(wl, 4096)
+    say("cfg2", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    harness.check_pair_totals(wl, res, mq, mk)
+
+
+def test_cfg2_one_batch_all_rows():
+    wl = CONFIGS["cfg2"].scaled(B=1, Hq=4, Hkv=4, n=2048)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    say("cfg2 slice", harness.check_attn(wl, inp, res, mq, mk))
+
+
+def test_cfg3_full_sampled_rows():
+    wl = CONFIGS["cfg3"]
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    rows = workloads.sample_rows(wl, 1024)
+    say("cfg3", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    harness.check_pair_totals(wl, res, mq, mk)
