@@ -392,7 +392,9 @@ hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, cons
         hipLaunchKernelGGL(plan_heads_kernel, dim3(L.B * H), dim3(256), 0, st, L, is_query, ws);
         hipLaunchKernelGGL(scatter_kernel, dim3(L.nblk, L.B * H), dim3(SB), 0, st, L, is_query, ws);
     }
-    return hipGetLastError();
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (L.dtype == 1) return launch_gather_k(L, k, ws, st);   // class-ordered key copy for the MFMA kernel
+    return hipSuccess;
 }
 
 }  // namespace focus
