@@ -61,18 +61,14 @@ def check_attn(wl, inp, res, mq, mk, rows=None, head_map=None, scale=0.0, tol=No
     pb = problem_of(wl, head_map, scale)
     qh, kh, vh = (workloads.to_host_bits(inp[x]) for x in ("q", "k", "v"))
     o_ref, lse_ref, pairs_ref = fo.attn_rows(pb, qh, kh, vh, mq, mk, rows=rows)
-    out = res["out"].float().cpu().numpy().astype(np.float64)
-    lse = res["lse"].cpu().numpy().astype(np.float64) if res["lse"] is not None else None
-    rp = res["row_pairs"].cpu().numpy() if res["row_pairs"] is not None else None
     if rows is None:
-        o_got = out.reshape(-1, wl.d)
-        lse_got = lse.reshape(-1) if lse is not None else None
-        rp_got = rp.reshape(-1) if rp is not None else None
+        sel = lambda t: t.reshape((-1,) + tuple(t.shape[3:]))
     else:
-        b, h, i = rows[:, 0], rows[:, 1], rows[:, 2]
-        o_got = out[b, h, i]
-        lse_got = lse[b, h, i] if lse is not None else None
-        rp_got = rp[b, h, i] if rp is not None else None
+        ridx = torch.from_numpy(rows.astype(np.int64)).to(res["out"].device)
+        sel = lambda t: t[ridx[:, 0], ridx[:, 1], ridx[:, 2]]       # gather on the device first
+    o_got = sel(res["out"]).float().cpu().numpy().astype(np.float64)
+    lse_got = sel(res["lse"]).cpu().numpy().astype(np.float64) if res["lse"] is not None else None
+    rp_got = sel(res["row_pairs"]).cpu().numpy() if res["row_pairs"] is not None else None
     t = dict(TOL[wl.dtype])
     if tol:
         t.update(tol)

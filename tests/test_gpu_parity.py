@@ -158,3 +158,46 @@ def test_cfg3_full_sampled_rows():
     rows = workloads.sample_rows(wl, 1024)
     say("cfg3", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
     harness.check_pair_totals(wl, res, mq, mk)
+
+
+@pytest.mark.parametrize("name", ["cfg4a", "cfg4b"])
+def test_cfg4_full_sampled_rows(name):
+    wl = CONFIGS[name]
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    rows = workloads.sample_rows(wl, 2048)
+    say(name, harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    allowed, gp = harness.check_pair_totals(wl, res, mq, mk)
+    say(name, "allowed fraction", float(allowed.sum()) / (wl.Hq * (wl.n * (wl.n + 1) // 2)))
+
+
+def test_cfg5_full_sampled_rows_and_group_pair_counts():
+    wl = CONFIGS["cfg5"]
+    inp = workloads.make_inputs(wl, "cuda")
+    say("cfg5 inputs ready")
+    res = harness.run_gpu(wl, inp)
+    say("cfg5 gpu done")
+    mq, mk = harness.check_assign(wl, inp, res)
+    say("cfg5 membership and lists bit-exact")
+    rows = workloads.sample_rows(wl, 4096)
+    say("cfg5", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    allowed, gp = harness.check_pair_totals(wl, res, mq, mk)
+    # exact per-group pair counts from the device's own group lists: for group g,
+    # sum over its query positions of the number of its key positions <= that position
+    v = res["views"]
+    G = wl.Hq // wl.Hkv
+    for h in range(0, wl.Hq, 5):
+        qc = v["q_group_counts"][0, h].cpu().numpy()
+        kc = v["k_group_counts"][0, h // G].cpu().numpy()
+        ql = v["q_group_lists"][0, h]
+        kl = v["k_group_lists"][0, h // G]
+        qo = kofs = 0
+        for g in range(wl.K):
+            qpos = ql[qo:qo + int(qc[g])]
+            kpos = kl[kofs:kofs + int(kc[g])]
+            cnt = torch.searchsorted(kpos, qpos, right=True).to(torch.int64).sum().item()
+            assert cnt == int(gp[0, h, g]), (h, g, cnt, int(gp[0, h, g]))
+            qo += int(qc[g])
+            kofs += int(kc[g])
+    say("cfg5 allowed fraction", float(allowed.sum()) / (wl.Hq * (wl.n * (wl.n + 1) // 2)))
