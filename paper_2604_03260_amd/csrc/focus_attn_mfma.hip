@@ -6,7 +6,7 @@
 // bucketed by membership class, position-ascending inside a class, every class
 // segment padded to a multiple of KT with position KPOS_PAD and zero data):
 //   Kc [B*Hkv][NKP][D]            keys, row-major: a key tile is one contiguous block
-//   Vt [B*Hkv][NKP/KT][D][KT]     values, transposed per key tile, the 16 keys of
+//   Vt [B*Hkv][NKP/KT][D][KT]     values, transposed per key tile (KT = 64 keys), the 16 keys of
 //                                 every 16-key group stored in MFMA k-slot order
 // One work-group = 4 wavefronts = one query tile of BQ=128 rows of one class;
 // each wavefront owns 32 query rows.  The scores are computed transposed,
@@ -24,6 +24,7 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (keeps staging in registers)
 
 constexpr int NTHR = 256;
 constexpr float LOG2E = 1.4426950408889634f;
@@ -86,12 +87,21 @@ __global__ __launch_bounds__(NTHR) void gather_vt_kernel(Layout L, const uint16_
 }
 
 // ---------------------------------------------------------------- attention
+// 16-byte chunk swizzle: 16 consecutive rows must land on 16 different chunk slots of a
+// 256-byte bank line.  Rows of 256 bytes: slot ^= row & 15; rows of 128 bytes: slot ^= (row >> 1) & 7.
+template <int ROW_BYTES>
+__device__ inline int swz(int row, int ch)
+{
+    if constexpr (ROW_BYTES == 256) return ch ^ (row & 15);
+    else return ch ^ ((row >> 1) & 7);
+}
+
 template <int D>
 struct Smem {
     TilePlan plan;
     int kpos[KT];
-    __attribute__((aligned(16))) char k[KT * D * 2];     // [key][D] bf16, 16-byte chunks XOR-swizzled by row
-    __attribute__((aligned(16))) char vt[D * KT * 2];    // [d][KT] bf16, same swizzle
+    __attribute__((aligned(16))) char k[KT * D * 2];     // [key][D] bf16, chunks swizzled
+    __attribute__((aligned(16))) char vt[D * KT * 2];    // [d][KT] bf16, chunks swizzled
 };
 
 template <int D, bool SOFTCAP, bool PAIRS>
@@ -100,12 +110,15 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
                                                             const char* __restrict__ ws, uint16_t* __restrict__ out,
                                                             float* __restrict__ lse, int32_t* __restrict__ row_pairs)
 {
-    extern __shared__ __align__(16) char smem_raw[];
-    Smem<D>& S = *reinterpret_cast<Smem<D>*>(smem_raw);
+    __shared__ Smem<D> S;
     constexpr int KS = D / 16;          // k-steps of the QK^T contraction
     constexpr int DB = D / 32;          // 32-row blocks of O^T
     constexpr int KCH = D / 8;          // 16-byte chunks per key row
-    constexpr int KSW = (KCH < 16) ? KCH : 16;
+    constexpr int KB = KT / 32;         // 32-key blocks per tile
+    constexpr int NLK = KT * KCH / NTHR;        // 16-byte loads per thread for a K tile
+    constexpr int NLV = D * (KT / 8) / NTHR;    // ... and for a V^T tile
+    constexpr int VCH = KT / 8;                 // chunks per V^T row
+    constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift before O is rescaled
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n32 = lane & 31, hh = lane >> 5;
@@ -140,12 +153,12 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     // Q rows as the B operand: lane (n32, hh) holds Q[row][16*ks + 8*hh .. +7]
     bf16x8 qreg[KS];
     {
-        const uint4* qrow = (const uint4*)(q + ((size_t)bhq * L.n + (rvalid ? qpos : 0)) * D);
+        const bf16x8* qrow = (const bf16x8*)(q + ((size_t)bhq * L.n + (rvalid ? qpos : 0)) * D);
+        bf16x8 zero;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            uint4 val = rvalid ? qrow[2 * ks + hh] : make_uint4(0, 0, 0, 0);
-            __builtin_memcpy(&qreg[ks], &val, 16);
-        }
+        for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qreg[ks] = rvalid ? qrow[2 * ks + hh] : zero;
     }
 
     f32x16 o[DB];
@@ -153,82 +166,90 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m_run = -INFINITY;   // running max of the logits in log2 units
+    float m_ref = -INFINITY;   // reference max of the row in log2 units (may lag the true max)
     float l_run = 0.f;         // this lane's share of the running sum
     int npairs = 0;
 
     const float sl2 = L.scale * LOG2E;
-    const float cap = L.softcap;
-    const float cap_l2 = cap * LOG2E;
-    const float two_over_cap_l2 = (cap > 0.f) ? 2.f * L.scale * LOG2E / cap : 0.f;
+    const float cap_l2 = L.softcap * LOG2E;
+    const float two_over_cap_l2 = (L.softcap > 0.f) ? 2.f * L.scale * LOG2E / L.softcap : 0.f;
 
-    const uint4* kc_base = (const uint4*)(ws + L.off_kc) + (size_t)bhk * L.NKP * KCH;
-    const uint4* vt_base = (const uint4*)(ws + L.off_vt) + (size_t)bhk * (L.NKP / KT) * (size_t)(D * KT / 8);
+    const u32x4* kc_base = (const u32x4*)(ws + L.off_kc) + (size_t)bhk * L.NKP * KCH;
+    const u32x4* vt_base = (const u32x4*)(ws + L.off_vt) + (size_t)bhk * L.NKP * KCH;
     const int* kpos_base = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP;
 
-    int cur = 0;
+    // register staging of the next tile: global loads fly while the current tile is computed
+    u32x4 st_k[NLK], st_v[NLV];
+    int st_kpos;
+#define FOCUS_ISSUE_LOADS(TILE)                                                              \
+    do {                                                                                     \
+        const u32x4* ksrc_ = kc_base + (size_t)(TILE) * (KT * KCH);                          \
+        _Pragma("unroll") for (int i = 0; i < NLK; ++i) st_k[i] = ksrc_[tid + i * NTHR];     \
+        const u32x4* vsrc_ = vt_base + (size_t)(TILE) * (D * VCH);                           \
+        _Pragma("unroll") for (int i = 0; i < NLV; ++i) st_v[i] = vsrc_[tid + i * NTHR];     \
+        st_kpos = kpos_base[(size_t)(TILE) * KT + (tid & (KT - 1))];                         \
+    } while (0)
+#define FOCUS_COMMIT_LOADS()                                                                 \
+    do {                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < NLK; ++i) {                                    \
+            const int id_ = tid + i * NTHR;                                                  \
+            const int row_ = id_ / KCH, ch_ = id_ % KCH;                                     \
+            *(u32x4*)(S.k + row_ * (D * 2) + swz<D * 2>(row_, ch_) * 16) = st_k[i];          \
+        }                                                                                    \
+        _Pragma("unroll") for (int i = 0; i < NLV; ++i) {                                    \
+            const int id_ = tid + i * NTHR;                                                  \
+            const int row_ = id_ / VCH, ch_ = id_ % VCH;                                     \
+            *(u32x4*)(S.vt + row_ * (KT * 2) + swz<KT * 2>(row_, ch_) * 16) = st_v[i];       \
+        }                                                                                    \
+        if (tid < KT) S.kpos[tid] = st_kpos;                                                 \
+    } while (0)
+
+    if (total == 0) return;      // cannot happen (the diagonal is always allowed); keeps the loads in bounds
+    int cur = 0, cur_ld = 0;
+    int tile_ld = S.plan.t0[0];
+    while (0 >= S.plan.cum[cur_ld + 1]) ++cur_ld;
+    tile_ld = S.plan.t0[cur_ld];
+    FOCUS_ISSUE_LOADS(tile_ld);
+    FOCUS_COMMIT_LOADS();
     for (int it = 0; it < total; ++it) {
         while (it >= S.plan.cum[cur + 1]) ++cur;
-        const int tile = S.plan.t0[cur] + (it - S.plan.cum[cur]);
         const bool inter = S.plan.inter[cur] != 0;
-
-        __syncthreads();                                     // previous tile fully consumed
-        {
-            const uint4* ksrc = kc_base + (size_t)tile * (KT * KCH);
-#pragma unroll
-            for (int i = 0; i < KT * KCH / NTHR; ++i) {
-                const int id = tid + i * NTHR;
-                const int row = id / KCH, ch = id % KCH;
-                const uint4 val = ksrc[id];
-                *(uint4*)(S.k + row * (D * 2) + ((ch ^ (row % KSW)) * 16)) = val;
-            }
-            const uint4* vsrc = vt_base + (size_t)tile * (D * KT / 8);
-#pragma unroll
-            for (int i = 0; i < D * (KT / 8) / NTHR; ++i) {
-                const int id = tid + i * NTHR;
-                const int row = id / 16, ch = id % 16;
-                const uint4 val = vsrc[id];
-                *(uint4*)(S.vt + row * (KT * 2) + ((ch ^ (row % 16)) * 16)) = val;
-            }
-            if (tid < KT) S.kpos[tid] = kpos_base[(size_t)tile * KT + tid];
+        __syncthreads();                                     // tile `it` is in LDS
+        if (it + 1 < total) {                                // next tile (the last one is re-read, harmlessly)
+            while (it + 1 >= S.plan.cum[cur_ld + 1]) ++cur_ld;
+            tile_ld = S.plan.t0[cur_ld] + (it + 1 - S.plan.cum[cur_ld]);
         }
-        __syncthreads();
+        FOCUS_ISSUE_LOADS(tile_ld);
 
-        // ---- S^T = K Q^T: 4 blocks of 32 keys x 32 queries per wavefront
-        f32x16 s[4];
+        // ---- S^T = K Q^T: KB blocks of 32 keys x 32 queries per wavefront
+        f32x16 s[KB];
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
+        for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
             const int row = kb * 32 + n32;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const int ch = 2 * ks + hh;
-                bf16x8 a = *(const bf16x8*)(S.k + row * (D * 2) + ((ch ^ (row % KSW)) * 16));
+                bf16x8 a = *(const bf16x8*)(S.k + row * (D * 2) + swz<D * 2>(row, 2 * ks + hh) * 16);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[kb], 0, 0, 0);
             }
         }
 
-        // ---- logits in log2 units, softcap, mask
-        const bool interior = inter && (S.kpos[KT - 1] <= i_lo);
+        // ---- softcap (to log2 units) and mask
+        if constexpr (SOFTCAP) {
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
+            for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float xv = s[kb][r];
-                if constexpr (SOFTCAP) {
-                    // cap*tanh(scale*x/cap) = cap*(1 - 2/(1+exp(2*scale*x/cap))), then to log2 units
-                    const float e2 = __builtin_amdgcn_exp2f(xv * two_over_cap_l2);
-                    xv = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2);
-                } else {
-                    xv *= sl2;
+                for (int r = 0; r < 16; ++r) {
+                    // cap*tanh(scale*x/cap) = cap*(1 - 2/(1+exp(2*scale*x/cap))), in log2 units
+                    const float e2 = __builtin_amdgcn_exp2f(s[kb][r] * two_over_cap_l2);
+                    s[kb][r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2);
                 }
-                s[kb][r] = xv;
-            }
         }
+        const bool interior = inter && (S.kpos[KT - 1] <= i_lo);
         if (!interior) {
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
+            for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int4 kp4 = *(const int4*)(&S.kpos[kb * 32 + 8 * r4 + 4 * hh]);
@@ -242,52 +263,61 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
                 }
             }
         } else {
-            if constexpr (PAIRS) npairs += 64;
+            if constexpr (PAIRS) npairs += KT / 2;
         }
 
-        // ---- online softmax (one row per lane pair)
+        // ---- online softmax (one row per lane pair); the reference max is only moved when
+        //      the true max has drifted by more than the threshold, so O is rarely rescaled
         float mx = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.f;
-        bf16x8 pb[4][2];
+        const float m2 = SOFTCAP ? mx : mx * sl2;            // scale > 0: max commutes with scaling
+        const bool upd = m2 > m_ref + RESCALE_THRESHOLD;     // m_ref = -inf: any finite max updates
+        if (__any(upd)) {
+            const float alpha = upd ? __builtin_amdgcn_exp2f(m_ref - m2) : 1.f;
+            m_ref = upd ? m2 : m_ref;
+            l_run *= alpha;
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        }
+        const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
+        float psum = 0.f;
+        bf16x8 pb[KB][2];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_use);
+                const float arg = SOFTCAP ? (s[kb][r] - m_use) : fmaf(s[kb][r], sl2, -m_use);
+                const float p = __builtin_amdgcn_exp2f(arg);
                 psum += p;
                 pb[kb][r / 8][r % 8] = (__bf16)p;
             }
         }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        l_run += psum;
 
         // ---- O^T += V^T P^T
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             const int row = db * 32 + n32;
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
+            for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
-                    const int ch = kb * 4 + s2 * 2 + hh;
-                    bf16x8 a = *(const bf16x8*)(S.vt + row * (KT * 2) + ((ch ^ (row % 16)) * 16));
+                    bf16x8 a = *(const bf16x8*)(S.vt + row * (KT * 2) + swz<KT * 2>(row, kb * 4 + s2 * 2 + hh) * 16);
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kb][s2], o[db], 0, 0, 0);
                 }
             }
         }
+        __syncthreads();                                     // every wavefront is done with tile `it`
+        FOCUS_COMMIT_LOADS();
     }
+#undef FOCUS_ISSUE_LOADS
+#undef FOCUS_COMMIT_LOADS
 
     // ---- epilogue
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -312,7 +342,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
         }
     }
     if (hh == 0) {
-        if (lse) lse[(size_t)bhq * L.n + qpos] = (m_run + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E);
+        if (lse) lse[(size_t)bhq * L.n + qpos] = (m_ref + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E);
         if constexpr (PAIRS) row_pairs[(size_t)bhq * L.n + qpos] = npairs;
     }
 }
@@ -322,11 +352,8 @@ hipError_t launch_one(const Layout& L, const HeadMap& hm, int default_map, const
                       float* lse, int32_t* row_pairs, hipStream_t st)
 {
     auto kern = attn_mfma_kernel<D, SOFTCAP, PAIRS>;
-    const int shm = (int)sizeof(Smem<D>);
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, shm);
-    if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), shm, st, L, hm, default_map, (const uint16_t*)q,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), 0, st, L, hm, default_map, (const uint16_t*)q,
                        (const char*)ws, (uint16_t*)out, lse, row_pairs);
     return hipGetLastError();
 }

@@ -9,7 +9,7 @@ namespace focus {
 
 constexpr int SB = 256;        // positions per sort block (one work-group of the bucketing kernels)
 constexpr int BQ = 128;        // query rows per attention tile
-constexpr int KT = 128;        // keys per attention tile; class segments of the permuted keys are padded to this
+constexpr int KT = 64;         // keys per attention tile; class segments of the permuted keys are padded to this
 constexpr int MAX_CLASSES = 256;
 constexpr int MAX_HQ = 256;
 constexpr int KPOS_PAD = 0x7fffffff;  // position stored in padded key slots: never <= a query position
