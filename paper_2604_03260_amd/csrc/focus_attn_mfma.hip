@@ -17,6 +17,7 @@
 // operand of O^T += V^T P^T; the A operand comes from the transposed V tile.
 #include "focus_internal.h"
 #include "focus_tileplan.h"
+#include <cstdlib>
 
 namespace focus {
 
@@ -365,6 +366,8 @@ hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const v
     dim3 ggrid(L.NKP / KT, L.B * L.Hkv);
     hipLaunchKernelGGL(gather_vt_kernel<D>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)v, ws);
     const bool sc = L.softcap > 0.f, pairs = row_pairs != nullptr;
+    static const int variant = [] { const char* e = getenv("FOCUS_MFMA_VARIANT"); return e ? atoi(e) : 3; }();
+    if (variant == 3) return launch_attn_mfma3_core(L, hm, default_map, q, ws, out, lse, row_pairs, st);
     if (sc) {
         return pairs ? launch_one<D, true, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
                      : launch_one<D, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);

@@ -1,0 +1,398 @@
+// Software-pipelined matrix-core attention kernel with direct global->LDS loads.
+//
+// Same data layout, tile plan and arithmetic as focus_attn_mfma.hip (App. D Eq. 3
+// with top-k sets, exact softmax of Sec. 1, one online softmax per row).  What
+// differs is how a wavefront's work is ordered and how tiles reach LDS:
+//
+//  * A key tile of 64 is two units of 32 keys.  While the vector ALUs turn the
+//    scores of one unit into probabilities, the matrix cores run the products of
+//    its neighbours, inside ONE instruction stream:
+//      phase A of tile t:  MFMA  O += V(t-1,u1) P1(t-1)   and   S1 = K(t,u1) Q^T
+//                          VALU  P0 = softmax-step(S0)
+//      phase B of tile t:  MFMA  O += V(t,u0) P0          and   S0 = K(t+1,u0) Q^T
+//                          VALU  P1 = softmax-step(S1)
+//    The 16 LDS operands of a phase are read as one batch at its start.
+//  * K and V^T tiles are double-buffered in LDS and filled with
+//    global_load_lds_dwordx4: 64 lanes x 16 bytes land at M0 + lane*16, so the
+//    XOR swizzle is applied on the global side (each lane fetches the chunk that
+//    belongs in its LDS slot).  The loads of K(t+2), V(t+1) and the key positions
+//    of tile t+2 are issued in the middle of tile t, right after the one barrier
+//    per tile, and waited for with s_waitcnt vmcnt(0) just before the next one.
+#include "focus_internal.h"
+#include "focus_tileplan.h"
+
+namespace focus {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NTHR = 256;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift before O is rescaled
+
+template <int ROW_BYTES>
+__device__ inline int swz(int row, int ch)
+{
+    if constexpr (ROW_BYTES == 256) return ch ^ (row & 15);
+    else return ch ^ ((row >> 1) & 7);
+}
+
+template <int D>
+struct Smem3 {
+    TilePlan plan;
+    __attribute__((aligned(16))) int kpos[3][KT];
+    __attribute__((aligned(16))) char k[2][KT * D * 2];     // [stage][key][D] bf16, chunks swizzled
+    __attribute__((aligned(16))) char vt[2][D * KT * 2];    // [stage][d][KT] bf16, chunks swizzled
+};
+
+// max of the two half-waves (lane l and lane l^32 hold the same query row)
+__device__ inline float halfwave_max(float x)
+{
+    const unsigned xi = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// 64 lanes x 16 bytes: lane l fetches global (sbase + voff) into LDS byte address lds_addr + 16*l.
+// sbase and lds_addr must be wave-uniform.
+__device__ inline void dma16(const void* sbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+
+__device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)p; }
+
+template <int D, bool SOFTCAP, bool PAIRS>
+__global__ __launch_bounds__(NTHR, 2) void attn_mfma3_kernel(Layout L, HeadMap hm, int default_map,
+                                                             const uint16_t* __restrict__ q,
+                                                             const char* __restrict__ ws, uint16_t* __restrict__ out,
+                                                             float* __restrict__ lse, int32_t* __restrict__ row_pairs)
+{
+    __shared__ Smem3<D> S;
+    constexpr int KS = D / 16;          // MFMAs of one QK^T unit
+    constexpr int DB = D / 32;          // 32-row blocks of O^T
+    constexpr int NPV = DB * 2;         // MFMAs of one PV unit
+    constexpr int TILE_BYTES = KT * D * 2;      // bytes of a K tile and of a V^T tile
+    constexpr int NW = TILE_BYTES / 1024 / 4;   // 1-KB wave loads per wavefront and tile
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n32 = lane & 31, hh = lane >> 5;
+
+    const int BH = L.B * L.Hq;
+    const int job = blockIdx.x / BH;
+    const int x = blockIdx.x % BH;
+    int b, h;
+    if (default_map) {
+        const int BHk = L.B * L.Hkv, G = L.Hq / L.Hkv;
+        const int kvlin = x % BHk, g = x / BHk;
+        b = kvlin / L.Hkv;
+        h = (kvlin % L.Hkv) * G + g;
+    } else {
+        b = x / L.Hq;
+        h = x % L.Hq;
+    }
+    const int bhq = b * L.Hq + h;
+    const int bhk = b * L.Hkv + hm.kv[h];
+    if (!plan_query_tile(L, ws, bhq, bhk, job, S.plan)) return;
+
+    const int rloc = wave * 32 + n32;
+    const bool rvalid = rloc < S.plan.nvalid;
+    const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
+    const int qpos = rvalid ? qperm[S.plan.row0 + rloc] : -1;
+    const int i_lo = S.plan.i_lo;
+    const int total = S.plan.total;
+    const int w = L.window;
+    if (total == 0) return;      // cannot happen (the diagonal is always allowed)
+
+    bf16x8 qreg[KS];
+    {
+        const bf16x8* qrow = (const bf16x8*)(q + ((size_t)bhq * L.n + (rvalid ? qpos : 0)) * D);
+        bf16x8 zero;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qreg[ks] = rvalid ? qrow[2 * ks + hh] : zero;
+    }
+
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    float m_ref = -INFINITY, l_run = 0.f;
+    int npairs = 0;
+
+    const float sl2 = L.scale * LOG2E;
+    const float cap_l2 = L.softcap * LOG2E;
+    const float two_over_cap_l2 = (L.softcap > 0.f) ? 2.f * L.scale * LOG2E / L.softcap : 0.f;
+
+    const char* kc_base = ws + L.off_kc + (size_t)bhk * L.NKP * (D * 2);
+    const char* vt_base = ws + L.off_vt + (size_t)bhk * L.NKP * (D * 2);
+    const char* kpos_base = ws + L.off_kpos + (size_t)bhk * L.NKP * 4;
+
+    // per-lane source offsets of the swizzled DMA: wave `wave` fills the 1-KB LDS blocks wave + 4*i
+    // of a tile; block j holds rows 4j..4j+3 (256-byte rows) or 8j..8j+7 (128-byte rows), and the
+    // swizzle key of a row depends only on (j mod 4) = wave, so one offset serves every i.
+    unsigned voff_k, voff_v;
+    {
+        const int r128 = wave * 8 + lane / 8;                         // 128-byte rows
+        const unsigned off128 = (unsigned)((r128 * 8 + ((lane % 8) ^ ((wave & 1) * 4 + lane / 16))) * 16);
+        const int r256 = wave * 4 + lane / 16;                        // 256-byte rows
+        const unsigned off256 = (unsigned)((r256 * 16 + ((lane % 16) ^ r256)) * 16);
+        voff_k = (D == 128) ? off256 : off128;
+        voff_v = off128;
+    }
+    const unsigned lds_k0 = lds_addr_of(&S.k[0][0]), lds_v0 = lds_addr_of(&S.vt[0][0]);
+    const unsigned lds_kp0 = lds_addr_of(&S.kpos[0][0]);
+
+#define F4_DMA_K(TILE, STAGE)                                                                        \
+    do {                                                                                             \
+        const char* src_ = kc_base + (size_t)(TILE) * TILE_BYTES;                                    \
+        _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
+            dma16(src_ + i * 4096, voff_k, lds_k0 + (STAGE) * TILE_BYTES + (wave + 4 * i) * 1024);   \
+    } while (0)
+#define F4_DMA_V(TILE, STAGE)                                                                        \
+    do {                                                                                             \
+        const char* src_ = vt_base + (size_t)(TILE) * TILE_BYTES;                                    \
+        _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
+            dma16(src_ + i * 4096, voff_v, lds_v0 + (STAGE) * TILE_BYTES + (wave + 4 * i) * 1024);   \
+    } while (0)
+#define F4_DMA_KPOS(TILE, BUF)                                                                       \
+    do {                                                                                             \
+        if (wave == 0 && lane < KT / 4)                                                              \
+            dma16(kpos_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_kp0 + (BUF) * (KT * 4)); \
+    } while (0)
+#define F4_WAIT_DMA() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
+
+    // LDS operand reads of one unit
+#define F4_READ_K(DST, KST, U)                                                                       \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                              \
+        const int row_ = (U) * 32 + n32;                                                             \
+        DST[ks] = *(const bf16x8*)(S.k[KST] + row_ * (D * 2) + swz<D * 2>(row_, 2 * ks + hh) * 16);  \
+    }
+#define F4_READ_V(DST, VST, U)                                                                       \
+    _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                \
+        _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {                                           \
+            const int row_ = db * 32 + n32;                                                          \
+            DST[db * 2 + s2] = *(const bf16x8*)(S.vt[VST] + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
+        }
+
+    // tile cursors: cur (tile t, for flags), c1 (tile t+1), c2 (tile t+2); indices are scalar
+    int cur = 0, c1 = 0, c2 = 0;
+    auto tile_at = [&](int it, int& c) {
+        const int itc = min(it, total - 1);              // past the end: re-read the last tile, harmlessly
+        while (itc >= S.plan.cum[c + 1]) ++c;
+        return __builtin_amdgcn_readfirstlane(S.plan.t0[c] + (itc - S.plan.cum[c]));
+    };
+
+    // ---- prologue: K(0), V(0) -> stage 0; K(1) -> stage 1; kpos(0), kpos(1); zero V stage 1
+    {
+        const int t0 = tile_at(0, c1);
+        const int t1 = tile_at(1, c1);
+        F4_DMA_K(t0, 0);
+        F4_DMA_V(t0, 0);
+        F4_DMA_K(t1, 1);
+        F4_DMA_KPOS(t0, 0);
+        F4_DMA_KPOS(t1, 1);
+        const u32x4 z4 = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < TILE_BYTES / 16; i += NTHR) *(u32x4*)(S.vt[1] + i * 16) = z4;
+        F4_WAIT_DMA();
+    }
+    __syncthreads();
+    f32x16 s0, s1;
+    bf16x8 p0[2], p1[2];
+    bf16x8 ak[KS], av[NPV];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { p1[0][e] = (__bf16)0.f; p1[1][e] = (__bf16)0.f; p0[0][e] = (__bf16)0.f; p0[1][e] = (__bf16)0.f; }
+    F4_READ_K(ak, 0, 0)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], s0, 0, 0, 0);
+
+    // softmax step on one unit's scores: SIN (f32x16, consumed) -> POUT (2 x bf16x8), split in two parts.
+    // PPEND: probabilities of the previous unit whose PV product has not been issued yet.
+#define F4_SOFTMAX_PRE(SIN, U, KPB, PPEND)                                                               \
+    if constexpr (SOFTCAP) {                                                                             \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                 \
+            const float e2_ = __builtin_amdgcn_exp2f(SIN[r] * two_over_cap_l2);                          \
+            SIN[r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2_);                           \
+        }                                                                                                \
+    }                                                                                                    \
+    if (!interior) {                                                                                     \
+        _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4) {                                               \
+            const int4 kp4_ = *(const int4*)(&S.kpos[KPB][(U) * 32 + 8 * r4 + 4 * hh]);                  \
+            const int kp_[4] = {kp4_.x, kp4_.y, kp4_.z, kp4_.w};                                         \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                              \
+                const bool ok_ = kp_[e] <= qpos && (inter || kp_[e] > qpos - w);                         \
+                SIN[r4 * 4 + e] = ok_ ? SIN[r4 * 4 + e] : -INFINITY;                                     \
+                if constexpr (PAIRS) npairs += ok_ ? 1 : 0;                                              \
+            }                                                                                            \
+        }                                                                                                \
+    } else {                                                                                             \
+        if constexpr (PAIRS) npairs += 16;                                                               \
+    }                                                                                                    \
+    {                                                                                                    \
+        float mx_ = SIN[0];                                                                              \
+        _Pragma("unroll") for (int r = 1; r < 16; ++r) mx_ = fmaxf(mx_, SIN[r]);                         \
+        mx_ = halfwave_max(mx_);                                                                         \
+        const float m2_ = SOFTCAP ? mx_ : mx_ * sl2;                                                     \
+        const bool upd_ = m2_ > m_ref + RESCALE_THRESHOLD;                                               \
+        if (__any(upd_)) {                                                                               \
+            const float alpha_ = upd_ ? __builtin_amdgcn_exp2f(m_ref - m2_) : 1.f;                       \
+            m_ref = upd_ ? m2_ : m_ref;                                                                  \
+            l_run *= alpha_;                                                                             \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db)                                            \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][r] *= alpha_;                       \
+            /* probabilities still waiting for their PV product were taken against the old reference */ \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
+                PPEND[0][e] = (__bf16)((float)PPEND[0][e] * alpha_);                                     \
+                PPEND[1][e] = (__bf16)((float)PPEND[1][e] * alpha_);                                     \
+            }                                                                                            \
+        }                                                                                                \
+    }
+#define F4_SOFTMAX_EXP(SIN, POUT)                                                                        \
+    {                                                                                                    \
+        const float m_use_ = (m_ref == -INFINITY) ? 0.f : m_ref;                                         \
+        float psum_ = 0.f;                                                                               \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                 \
+            const float arg_ = SOFTCAP ? (SIN[r] - m_use_) : fmaf(SIN[r], sl2, -m_use_);                 \
+            const float p_ = __builtin_amdgcn_exp2f(arg_);                                               \
+            psum_ += p_;                                                                                 \
+            POUT[r / 8][r % 8] = (__bf16)p_;                                                             \
+        }                                                                                                \
+        l_run += psum_;                                                                                  \
+    }
+    // the MFMAs of a phase: PV with pending probabilities PP, then the QK^T unit into SOUT
+#define F4_MFMAS(PP, SOUT)                                                                               \
+    _Pragma("unroll") for (int i = 0; i < NPV; ++i)                                                      \
+        o[i / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], PP[i % 2], o[i / 2], 0, 0, 0);         \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) SOUT[r] = 0.f;                                        \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                    \
+        SOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], SOUT, 0, 0, 0);
+    // keeps values computed / loaded where they are written in the source (no sinking past a branch)
+#define F4_PIN2(P_) asm volatile("" : "+v"(P_[0]), "+v"(P_[1]))
+#define F4_PIN_OPERANDS()                                                                                \
+    _Pragma("unroll") for (int i = 0; i < KS; ++i) asm volatile("" : "+v"(ak[i]));                       \
+    _Pragma("unroll") for (int i = 0; i < NPV; ++i) asm volatile("" : "+v"(av[i]));
+
+    int kb_cur = 0;                                          // kpos buffer of tile t (t mod 3)
+    for (int it = 0; it < total; ++it) {
+        while (it >= S.plan.cum[cur + 1]) ++cur;
+        const bool inter = S.plan.inter[cur] != 0;
+        const int tl1 = tile_at(it + 1, c1);
+        const int tl2 = tile_at(it + 2, c2);
+        const bool interior = inter && (S.kpos[kb_cur][KT - 1] <= i_lo);
+        const int sc = it & 1, sn = sc ^ 1;                  // LDS stages: K(t),V(t) in sc; K(t+1),V(t-1) in sn
+        const int kb_nn = (kb_cur >= 1) ? kb_cur - 1 : 2;    // (t+2) mod 3
+
+        // ---- phase A: VALU softmax(S0) -> P0 ; MFMA O += V(t-1,u1) P1 and S1 = K(t,u1) Q^T
+        F4_READ_V(av, sn, 1)
+        F4_READ_K(ak, sc, 1)
+        F4_PIN_OPERANDS()
+        F4_SOFTMAX_PRE(s0, 0, kb_cur, p1)
+        F4_MFMAS(p1, s1)
+        F4_SOFTMAX_EXP(s0, p0)
+        __builtin_amdgcn_iglp_opt(3);
+        F4_PIN2(p0);
+
+        // ---- one barrier per tile: every wavefront is done with K(t) and V(t-1); K(t+1), V(t) have landed
+        F4_WAIT_DMA();
+        __syncthreads();
+        F4_DMA_K(tl2, sc);
+        F4_DMA_V(tl1, sn);
+        F4_DMA_KPOS(tl2, kb_nn);
+
+        // ---- phase B: VALU softmax(S1) -> P1 ; MFMA O += V(t,u0) P0 and S0 = K(t+1,u0) Q^T
+        F4_READ_V(av, sc, 0)
+        F4_READ_K(ak, sn, 0)
+        F4_PIN_OPERANDS()
+        F4_SOFTMAX_PRE(s1, 1, kb_cur, p0)
+        F4_MFMAS(p0, s0)
+        F4_SOFTMAX_EXP(s1, p1)
+        __builtin_amdgcn_iglp_opt(3);
+        F4_PIN2(p1);
+
+        kb_cur = (kb_cur == 2) ? 0 : kb_cur + 1;
+    }
+    // ---- drain: O += V(T-1,u1) P1 (V(T-1) was complete before the last barrier)
+    {
+        const int sl = (total - 1) & 1;
+        F4_READ_V(av, sl, 1)
+#pragma unroll
+        for (int i = 0; i < NPV; ++i)
+            o[i / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], p1[i % 2], o[i / 2], 0, 0, 0);
+    }
+    F4_WAIT_DMA();                                           // nothing may still be writing LDS when the block ends
+#undef F4_DMA_K
+#undef F4_DMA_V
+#undef F4_DMA_KPOS
+#undef F4_WAIT_DMA
+#undef F4_READ_K
+#undef F4_READ_V
+#undef F4_SOFTMAX_PRE
+#undef F4_SOFTMAX_EXP
+#undef F4_MFMAS
+#undef F4_PIN2
+#undef F4_PIN_OPERANDS
+
+    // ---- epilogue
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if constexpr (PAIRS) npairs += __shfl_xor(npairs, 32, 64);
+    if (!rvalid) return;
+    const float inv = 1.f / l_tot;
+    uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * D;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int dcol = db * 32 + 8 * r4 + 4 * hh;
+            __bf16 e0 = (__bf16)(o[db][r4 * 4 + 0] * inv), e1 = (__bf16)(o[db][r4 * 4 + 1] * inv);
+            __bf16 e2 = (__bf16)(o[db][r4 * 4 + 2] * inv), e3 = (__bf16)(o[db][r4 * 4 + 3] * inv);
+            uint16_t u0, u1, u2, u3;
+            __builtin_memcpy(&u0, &e0, 2); __builtin_memcpy(&u1, &e1, 2);
+            __builtin_memcpy(&u2, &e2, 2); __builtin_memcpy(&u3, &e3, 2);
+            uint2 val;
+            val.x = u0 | ((uint32_t)u1 << 16);
+            val.y = u2 | ((uint32_t)u3 << 16);
+            *(uint2*)(orow + dcol) = val;
+        }
+    }
+    if (hh == 0) {
+        if (lse) lse[(size_t)bhq * L.n + qpos] = (m_ref + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E);
+        if constexpr (PAIRS) row_pairs[(size_t)bhq * L.n + qpos] = npairs;
+    }
+}
+
+template <int D, bool SOFTCAP, bool PAIRS>
+hipError_t launch3(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
+                   float* lse, int32_t* row_pairs, hipStream_t st)
+{
+    const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
+    hipLaunchKernelGGL((attn_mfma3_kernel<D, SOFTCAP, PAIRS>), dim3(grid), dim3(NTHR), 0, st, L, hm, default_map,
+                       (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn_mfma3_core(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws,
+                                  void* out, float* lse, int32_t* row_pairs, hipStream_t st)
+{
+    const bool sc = L.softcap > 0.f, pairs = row_pairs != nullptr;
+#define F3_DISPATCH(DD)                                                                                   \
+    if (sc) return pairs ? launch3<DD, true, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)    \
+                         : launch3<DD, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);  \
+    return pairs ? launch3<DD, false, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)           \
+                 : launch3<DD, false, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    if (L.d == 64) { F3_DISPATCH(64) }
+    F3_DISPATCH(128)
+#undef F3_DISPATCH
+}
+
+}  // namespace focus
