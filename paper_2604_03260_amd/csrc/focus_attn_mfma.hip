@@ -11,24 +11,44 @@
 // One work-group = 4 wavefronts = one query tile of BQ=128 rows of one class;
 // each wavefront owns 32 query rows.  The scores are computed transposed,
 // S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q rows held
-// in registers), so that one lane holds 16x4 scores of ONE query row: row max
-// and row sum are in-lane reductions plus one exchange between the two half
-// waves.  The probabilities, rounded to bf16, are already laid out as the B
-// operand of O^T += V^T P^T; the A operand comes from the transposed V tile.
+// in registers), so that one lane holds 16 scores of ONE query row per 32-key
+// unit: row max and row sum are in-lane reductions plus one exchange between
+// the two half waves.  The probabilities, rounded to bf16, are already laid out
+// as the B operand of O^T += V^T P^T; the A operand comes from the transposed V tile.
+//
+// How a wavefront's work is ordered and how tiles reach LDS:
+//  * A key tile of 64 is two units of 32 keys.  While the vector ALUs turn the
+//    scores of one unit into probabilities, the matrix cores run the products of
+//    its neighbours, inside ONE instruction stream:
+//      phase A of tile t:  MFMA  O += V(t-1,u1) P1(t-1)   and   S1 = K(t,u1) Q^T
+//                          VALU  P0 = softmax-step(S0)
+//      phase B of tile t:  MFMA  O += V(t,u0) P0          and   S0 = K(t+1,u0) Q^T
+//                          VALU  P1 = softmax-step(S1)
+//    The 16 LDS operands of a phase are read as one batch at its start.
+//  * K and V^T tiles are double-buffered in LDS and filled with
+//    global_load_lds_dwordx4: 64 lanes x 16 bytes land at M0 + lane*16, so the
+//    XOR swizzle is applied on the global side (each lane fetches the chunk that
+//    belongs in its LDS slot).  The loads of K(t+2), V(t+1) and the key positions
+//    of tile t+2 are issued in the middle of tile t, right after the one barrier
+//    per tile, and waited for with s_waitcnt vmcnt(0) just before the next one.
+//  * The softmax reference max of a row only moves when the true max has drifted
+//    by more than RESCALE_THRESHOLD (log2 units), so O is rarely rescaled; the
+//    row sum adds the bf16-rounded probabilities (v_dot2), the numbers PV uses.
 #include "focus_internal.h"
 #include "focus_tileplan.h"
-#include <cstdlib>
 
 namespace focus {
 
 namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (keeps staging in registers)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NTHR = 256;
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift before O is rescaled
 
 // within a 16-key group: MFMA k-slot p16 = h*8 + e  <->  key 8*(e/4) + 4*h + e%4,
 // the order in which a lane of the S^T accumulator holds its keys
@@ -88,8 +108,6 @@ __global__ __launch_bounds__(NTHR) void gather_vt_kernel(Layout L, const uint16_
 }
 
 // ---------------------------------------------------------------- attention
-// 16-byte chunk swizzle: 16 consecutive rows must land on 16 different chunk slots of a
-// 256-byte bank line.  Rows of 256 bytes: slot ^= row & 15; rows of 128 bytes: slot ^= (row >> 1) & 7.
 template <int ROW_BYTES>
 __device__ inline int swz(int row, int ch)
 {
@@ -100,32 +118,46 @@ __device__ inline int swz(int row, int ch)
 template <int D>
 struct Smem {
     TilePlan plan;
-    int kpos[KT];
-    __attribute__((aligned(16))) char k[KT * D * 2];     // [key][D] bf16, chunks swizzled
-    __attribute__((aligned(16))) char vt[D * KT * 2];    // [d][KT] bf16, chunks swizzled
+    __attribute__((aligned(16))) int kpos[3][KT];
+    __attribute__((aligned(16))) char k[2][KT * D * 2];     // [stage][key][D] bf16, chunks swizzled
+    __attribute__((aligned(16))) char vt[2][D * KT * 2];    // [stage][d][KT] bf16, chunks swizzled
 };
+
+// max of the two half-waves (lane l and lane l^32 hold the same query row)
+__device__ inline float halfwave_max(float x)
+{
+    const unsigned xi = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// 64 lanes x 16 bytes: lane l fetches global (sbase + voff) into LDS byte address lds_addr + 16*l.
+// sbase and lds_addr must be wave-uniform.
+__device__ inline void dma16(const void* sbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+
+__device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)p; }
 
 template <int D, bool SOFTCAP, bool PAIRS>
 __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm, int default_map,
-                                                            const uint16_t* __restrict__ q,
-                                                            const char* __restrict__ ws, uint16_t* __restrict__ out,
-                                                            float* __restrict__ lse, int32_t* __restrict__ row_pairs)
+                                                             const uint16_t* __restrict__ q,
+                                                             const char* __restrict__ ws, uint16_t* __restrict__ out,
+                                                             float* __restrict__ lse, int32_t* __restrict__ row_pairs)
 {
     __shared__ Smem<D> S;
-    constexpr int KS = D / 16;          // k-steps of the QK^T contraction
+    constexpr int KS = D / 16;          // MFMAs of one QK^T unit
     constexpr int DB = D / 32;          // 32-row blocks of O^T
-    constexpr int KCH = D / 8;          // 16-byte chunks per key row
-    constexpr int KB = KT / 32;         // 32-key blocks per tile
-    constexpr int NLK = KT * KCH / NTHR;        // 16-byte loads per thread for a K tile
-    constexpr int NLV = D * (KT / 8) / NTHR;    // ... and for a V^T tile
-    constexpr int VCH = KT / 8;                 // chunks per V^T row
-    constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift before O is rescaled
+    constexpr int NPV = DB * 2;         // MFMAs of one PV unit
+    constexpr int TILE_BYTES = KT * D * 2;      // bytes of a K tile and of a V^T tile
+    constexpr int NW = TILE_BYTES / 1024 / 4;   // 1-KB wave loads per wavefront and tile
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n32 = lane & 31, hh = lane >> 5;
 
-    // work-group -> (job slot, head): heads fastest so the heavy slots of all heads start
-    // first; with the default head map the query heads of one KV head share blockIdx % 8
     const int BH = L.B * L.Hq;
     const int job = blockIdx.x / BH;
     const int x = blockIdx.x % BH;
@@ -143,15 +175,15 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     const int bhk = b * L.Hkv + hm.kv[h];
     if (!plan_query_tile(L, ws, bhq, bhk, job, S.plan)) return;
 
-    const int rloc = wave * 32 + n32;                       // query row inside the tile
+    const int rloc = wave * 32 + n32;
     const bool rvalid = rloc < S.plan.nvalid;
     const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
     const int qpos = rvalid ? qperm[S.plan.row0 + rloc] : -1;
     const int i_lo = S.plan.i_lo;
     const int total = S.plan.total;
     const int w = L.window;
+    if (total == 0) return;      // cannot happen (the diagonal is always allowed)
 
-    // Q rows as the B operand: lane (n32, hh) holds Q[row][16*ks + 8*hh .. +7]
     bf16x8 qreg[KS];
     {
         const bf16x8* qrow = (const bf16x8*)(q + ((size_t)bhq * L.n + (rvalid ? qpos : 0)) * D);
@@ -167,158 +199,253 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m_ref = -INFINITY;   // reference max of the row in log2 units (may lag the true max)
-    float l_run = 0.f;         // this lane's share of the running sum
+    float m_ref = -INFINITY, l_run = 0.f;
     int npairs = 0;
 
     const float sl2 = L.scale * LOG2E;
     const float cap_l2 = L.softcap * LOG2E;
     const float two_over_cap_l2 = (L.softcap > 0.f) ? 2.f * L.scale * LOG2E / L.softcap : 0.f;
 
-    const u32x4* kc_base = (const u32x4*)(ws + L.off_kc) + (size_t)bhk * L.NKP * KCH;
-    const u32x4* vt_base = (const u32x4*)(ws + L.off_vt) + (size_t)bhk * L.NKP * KCH;
-    const int* kpos_base = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP;
+    const char* kc_base = ws + L.off_kc + (size_t)bhk * L.NKP * (D * 2);
+    const char* vt_base = ws + L.off_vt + (size_t)bhk * L.NKP * (D * 2);
+    const char* kpos_base = ws + L.off_kpos + (size_t)bhk * L.NKP * 4;
 
-    // register staging of the next tile: global loads fly while the current tile is computed
-    u32x4 st_k[NLK], st_v[NLV];
-    int st_kpos;
-#define FOCUS_ISSUE_LOADS(TILE)                                                              \
-    do {                                                                                     \
-        const u32x4* ksrc_ = kc_base + (size_t)(TILE) * (KT * KCH);                          \
-        _Pragma("unroll") for (int i = 0; i < NLK; ++i) st_k[i] = ksrc_[tid + i * NTHR];     \
-        const u32x4* vsrc_ = vt_base + (size_t)(TILE) * (D * VCH);                           \
-        _Pragma("unroll") for (int i = 0; i < NLV; ++i) st_v[i] = vsrc_[tid + i * NTHR];     \
-        st_kpos = kpos_base[(size_t)(TILE) * KT + (tid & (KT - 1))];                         \
-    } while (0)
-#define FOCUS_COMMIT_LOADS()                                                                 \
-    do {                                                                                     \
-        _Pragma("unroll") for (int i = 0; i < NLK; ++i) {                                    \
-            const int id_ = tid + i * NTHR;                                                  \
-            const int row_ = id_ / KCH, ch_ = id_ % KCH;                                     \
-            *(u32x4*)(S.k + row_ * (D * 2) + swz<D * 2>(row_, ch_) * 16) = st_k[i];          \
-        }                                                                                    \
-        _Pragma("unroll") for (int i = 0; i < NLV; ++i) {                                    \
-            const int id_ = tid + i * NTHR;                                                  \
-            const int row_ = id_ / VCH, ch_ = id_ % VCH;                                     \
-            *(u32x4*)(S.vt + row_ * (KT * 2) + swz<KT * 2>(row_, ch_) * 16) = st_v[i];       \
-        }                                                                                    \
-        if (tid < KT) S.kpos[tid] = st_kpos;                                                 \
-    } while (0)
-
-    if (total == 0) return;      // cannot happen (the diagonal is always allowed); keeps the loads in bounds
-    int cur = 0, cur_ld = 0;
-    int tile_ld = S.plan.t0[0];
-    while (0 >= S.plan.cum[cur_ld + 1]) ++cur_ld;
-    tile_ld = S.plan.t0[cur_ld];
-    FOCUS_ISSUE_LOADS(tile_ld);
-    FOCUS_COMMIT_LOADS();
-    for (int it = 0; it < total; ++it) {
-        while (it >= S.plan.cum[cur + 1]) ++cur;
-        const bool inter = S.plan.inter[cur] != 0;
-        __syncthreads();                                     // tile `it` is in LDS
-        if (it + 1 < total) {                                // next tile (the last one is re-read, harmlessly)
-            while (it + 1 >= S.plan.cum[cur_ld + 1]) ++cur_ld;
-            tile_ld = S.plan.t0[cur_ld] + (it + 1 - S.plan.cum[cur_ld]);
-        }
-        FOCUS_ISSUE_LOADS(tile_ld);
-
-        // ---- S^T = K Q^T: KB blocks of 32 keys x 32 queries per wavefront
-        f32x16 s[KB];
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-            const int row = kb * 32 + n32;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 a = *(const bf16x8*)(S.k + row * (D * 2) + swz<D * 2>(row, 2 * ks + hh) * 16);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], s[kb], 0, 0, 0);
-            }
-        }
-
-        // ---- softcap (to log2 units) and mask
-        if constexpr (SOFTCAP) {
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // cap*tanh(scale*x/cap) = cap*(1 - 2/(1+exp(2*scale*x/cap))), in log2 units
-                    const float e2 = __builtin_amdgcn_exp2f(s[kb][r] * two_over_cap_l2);
-                    s[kb][r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2);
-                }
-        }
-        const bool interior = inter && (S.kpos[KT - 1] <= i_lo);
-        if (!interior) {
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int4 kp4 = *(const int4*)(&S.kpos[kb * 32 + 8 * r4 + 4 * hh]);
-                    const int kp[4] = {kp4.x, kp4.y, kp4.z, kp4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool ok = kp[e] <= qpos && (inter || kp[e] > qpos - w);
-                        s[kb][r4 * 4 + e] = ok ? s[kb][r4 * 4 + e] : -INFINITY;
-                        if constexpr (PAIRS) npairs += ok ? 1 : 0;
-                    }
-                }
-            }
-        } else {
-            if constexpr (PAIRS) npairs += KT / 2;
-        }
-
-        // ---- online softmax (one row per lane pair); the reference max is only moved when
-        //      the true max has drifted by more than the threshold, so O is rarely rescaled
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m2 = SOFTCAP ? mx : mx * sl2;            // scale > 0: max commutes with scaling
-        const bool upd = m2 > m_ref + RESCALE_THRESHOLD;     // m_ref = -inf: any finite max updates
-        if (__any(upd)) {
-            const float alpha = upd ? __builtin_amdgcn_exp2f(m_ref - m2) : 1.f;
-            m_ref = upd ? m2 : m_ref;
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-        }
-        const float m_use = (m_ref == -INFINITY) ? 0.f : m_ref;
-        float psum = 0.f;
-        bf16x8 pb[KB][2];
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float arg = SOFTCAP ? (s[kb][r] - m_use) : fmaf(s[kb][r], sl2, -m_use);
-                const float p = __builtin_amdgcn_exp2f(arg);
-                psum += p;
-                pb[kb][r / 8][r % 8] = (__bf16)p;
-            }
-        }
-        l_run += psum;
-
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            const int row = db * 32 + n32;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    bf16x8 a = *(const bf16x8*)(S.vt + row * (KT * 2) + swz<KT * 2>(row, kb * 4 + s2 * 2 + hh) * 16);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kb][s2], o[db], 0, 0, 0);
-                }
-            }
-        }
-        __syncthreads();                                     // every wavefront is done with tile `it`
-        FOCUS_COMMIT_LOADS();
+    // per-lane source offsets of the swizzled DMA: wave `wave` fills the 1-KB LDS blocks wave + 4*i
+    // of a tile; block j holds rows 4j..4j+3 (256-byte rows) or 8j..8j+7 (128-byte rows), and the
+    // swizzle key of a row depends only on (j mod 4) = wave, so one offset serves every i.
+    unsigned voff_k, voff_v;
+    {
+        const int r128 = wave * 8 + lane / 8;                         // 128-byte rows
+        const unsigned off128 = (unsigned)((r128 * 8 + ((lane % 8) ^ ((wave & 1) * 4 + lane / 16))) * 16);
+        const int r256 = wave * 4 + lane / 16;                        // 256-byte rows
+        const unsigned off256 = (unsigned)((r256 * 16 + ((lane % 16) ^ r256)) * 16);
+        voff_k = (D == 128) ? off256 : off128;
+        voff_v = off128;
     }
-#undef FOCUS_ISSUE_LOADS
-#undef FOCUS_COMMIT_LOADS
+    const unsigned lds_k0 = lds_addr_of(&S.k[0][0]), lds_v0 = lds_addr_of(&S.vt[0][0]);
+    const unsigned lds_kp0 = lds_addr_of(&S.kpos[0][0]);
+
+#define F4_DMA_K(TILE, STAGE)                                                                        \
+    do {                                                                                             \
+        const char* src_ = kc_base + (size_t)(TILE) * TILE_BYTES;                                    \
+        _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
+            dma16(src_ + i * 4096, voff_k, lds_k0 + (STAGE) * TILE_BYTES + (wave + 4 * i) * 1024);   \
+    } while (0)
+#define F4_DMA_V(TILE, STAGE)                                                                        \
+    do {                                                                                             \
+        const char* src_ = vt_base + (size_t)(TILE) * TILE_BYTES;                                    \
+        _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
+            dma16(src_ + i * 4096, voff_v, lds_v0 + (STAGE) * TILE_BYTES + (wave + 4 * i) * 1024);   \
+    } while (0)
+#define F4_DMA_KPOS(TILE, BUF)                                                                       \
+    do {                                                                                             \
+        if (wave == 0 && lane < KT / 4)                                                              \
+            dma16(kpos_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_kp0 + (BUF) * (KT * 4)); \
+    } while (0)
+#define F4_WAIT_DMA() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
+
+    // LDS operand reads of one unit
+#define F4_READ_K(DST, KST, U)                                                                       \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                              \
+        const int row_ = (U) * 32 + n32;                                                             \
+        DST[ks] = *(const bf16x8*)(S.k[KST] + row_ * (D * 2) + swz<D * 2>(row_, 2 * ks + hh) * 16);  \
+    }
+#define F4_READ_V(DST, VST, U)                                                                       \
+    _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                \
+        _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {                                           \
+            const int row_ = db * 32 + n32;                                                          \
+            DST[db * 2 + s2] = *(const bf16x8*)(S.vt[VST] + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
+        }
+
+    // Scalar walk over the tile sequence (class by class).  A tile travels as one packed word:
+    // bits 0..29 tile index, bit 30 "class shares a group" flag, bit 31 "no mask needed" flag.
+    // LDS is touched only when the walk enters a new class; past the end the last tile repeats.
+    int w_c = -1, w_t = 0, w_end = 0, w_int_end = 0, w_flag = 0, w_last = 0;
+    auto next_tile = [&]() -> unsigned {
+        if (w_t >= w_end) {
+            int c = w_c + 1;
+            while (c < L.NC && S.plan.cum[c + 1] == S.plan.cum[c]) ++c;
+            if (c < L.NC) {
+                w_c = __builtin_amdgcn_readfirstlane(c);
+                w_t = __builtin_amdgcn_readfirstlane(S.plan.t0[c]);
+                w_end = w_t + __builtin_amdgcn_readfirstlane(S.plan.cum[c + 1] - S.plan.cum[c]);
+                w_int_end = w_t + __builtin_amdgcn_readfirstlane(S.plan.nint[c]);
+                w_flag = __builtin_amdgcn_readfirstlane((int)S.plan.inter[c]) << 30;
+            } else {
+                return (unsigned)w_last;                      // sequence exhausted
+            }
+        }
+        w_last = w_t | w_flag | ((w_t < w_int_end) ? (int)0x80000000u : 0);
+        ++w_t;
+        return (unsigned)w_last;
+    };
+    constexpr unsigned TILE_MASK = 0x3fffffffu;
+
+    // ---- prologue: K(0), V(0) -> stage 0; K(1) -> stage 1; kpos(0), kpos(1); zero V stage 1
+    unsigned pk0, pk1, pk2;                                  // packed tiles t, t+1, t+2
+    {
+        pk0 = next_tile();
+        pk1 = next_tile();
+        pk2 = next_tile();
+        const int t0 = (int)(pk0 & TILE_MASK), t1 = (int)(pk1 & TILE_MASK);
+        F4_DMA_K(t0, 0);
+        F4_DMA_V(t0, 0);
+        F4_DMA_K(t1, 1);
+        F4_DMA_KPOS(t0, 0);
+        F4_DMA_KPOS(t1, 1);
+        const u32x4 z4 = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < TILE_BYTES / 16; i += NTHR) *(u32x4*)(S.vt[1] + i * 16) = z4;
+        F4_WAIT_DMA();
+    }
+    __syncthreads();
+    f32x16 s0, s1;
+    bf16x8 p0[2], p1[2];
+    bf16x2 ones2;
+    ones2[0] = (__bf16)1.0f;
+    ones2[1] = (__bf16)1.0f;
+    bf16x8 ak[KS], av[NPV];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { p1[0][e] = (__bf16)0.f; p1[1][e] = (__bf16)0.f; p0[0][e] = (__bf16)0.f; p0[1][e] = (__bf16)0.f; }
+    F4_READ_K(ak, 0, 0)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], s0, 0, 0, 0);
+
+    // softmax step on one unit's scores: SIN (f32x16, consumed) -> POUT (2 x bf16x8), split in two parts.
+    // PPEND: probabilities of the previous unit whose PV product has not been issued yet.
+#define F4_SOFTMAX_PRE(SIN, U, KPB, PPEND)                                                               \
+    if constexpr (SOFTCAP) {                                                                             \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                 \
+            const float e2_ = __builtin_amdgcn_exp2f(SIN[r] * two_over_cap_l2);                          \
+            SIN[r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2_);                           \
+        }                                                                                                \
+    }                                                                                                    \
+    if (!interior) {                                                                                     \
+        _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4) {                                               \
+            const int4 kp4_ = *(const int4*)(&S.kpos[KPB][(U) * 32 + 8 * r4 + 4 * hh]);                  \
+            const int kp_[4] = {kp4_.x, kp4_.y, kp4_.z, kp4_.w};                                         \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                              \
+                const bool ok_ = kp_[e] <= qpos && (inter || kp_[e] > qpos - w);                         \
+                SIN[r4 * 4 + e] = ok_ ? SIN[r4 * 4 + e] : -INFINITY;                                     \
+                if constexpr (PAIRS) npairs += ok_ ? 1 : 0;                                              \
+            }                                                                                            \
+        }                                                                                                \
+    } else {                                                                                             \
+        if constexpr (PAIRS) npairs += 16;                                                               \
+    }                                                                                                    \
+    {                                                                                                    \
+        float mx_ = SIN[0];                                                                              \
+        _Pragma("unroll") for (int r = 1; r < 16; ++r) mx_ = fmaxf(mx_, SIN[r]);                         \
+        mx_ = halfwave_max(mx_);                                                                         \
+        const float m2_ = SOFTCAP ? mx_ : mx_ * sl2;                                                     \
+        const bool upd_ = m2_ > m_ref + RESCALE_THRESHOLD;                                               \
+        if (__any(upd_)) {                                                                               \
+            const float alpha_ = upd_ ? __builtin_amdgcn_exp2f(m_ref - m2_) : 1.f;                       \
+            m_ref = upd_ ? m2_ : m_ref;                                                                  \
+            l_run *= alpha_;                                                                             \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db)                                            \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][r] *= alpha_;                       \
+            /* probabilities still waiting for their PV product were taken against the old reference */ \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
+                PPEND[0][e] = (__bf16)((float)PPEND[0][e] * alpha_);                                     \
+                PPEND[1][e] = (__bf16)((float)PPEND[1][e] * alpha_);                                     \
+            }                                                                                            \
+        }                                                                                                \
+    }
+#define F4_SOFTMAX_EXP(SIN, POUT)                                                                        \
+    {                                                                                                    \
+        const float m_use_ = (m_ref == -INFINITY) ? 0.f : m_ref;                                         \
+        float psum_ = 0.f;                                                                               \
+        _Pragma("unroll") for (int r = 0; r < 16; r += 2) {                                              \
+            const float a0_ = SOFTCAP ? (SIN[r] - m_use_) : fmaf(SIN[r], sl2, -m_use_);                  \
+            const float a1_ = SOFTCAP ? (SIN[r + 1] - m_use_) : fmaf(SIN[r + 1], sl2, -m_use_);          \
+            bf16x2 pr_;                                                                                  \
+            pr_[0] = (__bf16)__builtin_amdgcn_exp2f(a0_);                                                \
+            pr_[1] = (__bf16)__builtin_amdgcn_exp2f(a1_);                                                \
+            /* the row sum adds the ROUNDED probabilities, the same numbers the PV product uses */      \
+            psum_ = __builtin_amdgcn_fdot2_f32_bf16(pr_, ones2, psum_, false);                           \
+            POUT[r / 8][r % 8] = pr_[0];                                                                 \
+            POUT[r / 8][r % 8 + 1] = pr_[1];                                                             \
+        }                                                                                                \
+        l_run += psum_;                                                                                  \
+    }
+    // the MFMAs of a phase: PV with pending probabilities PP, then the QK^T unit into SOUT
+#define F4_MFMAS(PP, SOUT)                                                                               \
+    _Pragma("unroll") for (int i = 0; i < NPV; ++i)                                                      \
+        o[i / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], PP[i % 2], o[i / 2], 0, 0, 0);         \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) SOUT[r] = 0.f;                                        \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                    \
+        SOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], SOUT, 0, 0, 0);
+    // keeps values computed / loaded where they are written in the source (no sinking past a branch)
+#define F4_PIN2(P_) asm volatile("" : "+v"(P_[0]), "+v"(P_[1]))
+#define F4_PIN_OPERANDS()                                                                                \
+    _Pragma("unroll") for (int i = 0; i < KS; ++i) asm volatile("" : "+v"(ak[i]));                       \
+    _Pragma("unroll") for (int i = 0; i < NPV; ++i) asm volatile("" : "+v"(av[i]));
+
+    int kb_cur = 0;                                          // kpos buffer of tile t (t mod 3)
+    // One key tile.  SC is the LDS stage of K(t), V(t); K(t+1), V(t-1) sit in the other.
+#define F4_TILE(SC)                                                                                      \
+    {                                                                                                    \
+        const int sc = (SC), sn = (SC) ^ 1;                                                              \
+        const bool inter = (pk0 >> 30) & 1u;                                                             \
+        const bool interior = (pk0 >> 31) != 0;                                                          \
+        const int tl1 = (int)(pk1 & TILE_MASK);                                                          \
+        const int tl2 = (int)(pk2 & TILE_MASK);                                                          \
+        const int kb_nn = (kb_cur >= 1) ? kb_cur - 1 : 2;    /* (t+2) mod 3 */                           \
+        /* phase A: VALU softmax(S0) -> P0 ; MFMA O += V(t-1,u1) P1 and S1 = K(t,u1) Q^T */              \
+        F4_READ_V(av, sn, 1)                                                                             \
+        F4_READ_K(ak, sc, 1)                                                                             \
+        F4_PIN_OPERANDS()                                                                                \
+        F4_SOFTMAX_PRE(s0, 0, kb_cur, p1)                                                                \
+        F4_MFMAS(p1, s1)                                                                                 \
+        F4_SOFTMAX_EXP(s0, p0)                                                                           \
+        __builtin_amdgcn_iglp_opt(3);                                                                    \
+        F4_PIN2(p0);                                                                                     \
+        /* one barrier per tile: all are done with K(t), V(t-1); K(t+1), V(t) have landed */             \
+        F4_WAIT_DMA();                                                                                   \
+        __syncthreads();                                                                                 \
+        F4_DMA_K(tl2, sc);                                                                               \
+        F4_DMA_V(tl1, sn);                                                                               \
+        F4_DMA_KPOS(tl2, kb_nn);                                                                         \
+        /* phase B: VALU softmax(S1) -> P1 ; MFMA O += V(t,u0) P0 and S0 = K(t+1,u0) Q^T */              \
+        F4_READ_V(av, sc, 0)                                                                             \
+        F4_READ_K(ak, sn, 0)                                                                             \
+        F4_PIN_OPERANDS()                                                                                \
+        F4_SOFTMAX_PRE(s1, 1, kb_cur, p0)                                                                \
+        F4_MFMAS(p0, s0)                                                                                 \
+        F4_SOFTMAX_EXP(s1, p1)                                                                           \
+        __builtin_amdgcn_iglp_opt(3);                                                                    \
+        F4_PIN2(p1);                                                                                     \
+        kb_cur = (kb_cur == 2) ? 0 : kb_cur + 1;                                                         \
+        pk0 = pk1;                                                                                       \
+        pk1 = pk2;                                                                                       \
+        pk2 = next_tile();                                                                               \
+    }
+    for (int it = 0; it < total; ++it) {
+        F4_TILE(it & 1)
+    }
+#undef F4_TILE
+    // ---- drain: O += V(T-1,u1) P1 (V(T-1) was complete before the last barrier)
+    {
+        const int sl = (total - 1) & 1;
+        F4_READ_V(av, sl, 1)
+#pragma unroll
+        for (int i = 0; i < NPV; ++i)
+            o[i / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], p1[i % 2], o[i / 2], 0, 0, 0);
+    }
+    F4_WAIT_DMA();                                           // nothing may still be writing LDS when the block ends
+#undef F4_DMA_K
+#undef F4_DMA_V
+#undef F4_DMA_KPOS
+#undef F4_WAIT_DMA
+#undef F4_READ_K
+#undef F4_READ_V
+#undef F4_SOFTMAX_PRE
+#undef F4_SOFTMAX_EXP
+#undef F4_MFMAS
+#undef F4_PIN2
+#undef F4_PIN_OPERANDS
 
     // ---- epilogue
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -352,10 +479,9 @@ template <int D, bool SOFTCAP, bool PAIRS>
 hipError_t launch_one(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
                       float* lse, int32_t* row_pairs, hipStream_t st)
 {
-    auto kern = attn_mfma_kernel<D, SOFTCAP, PAIRS>;
     const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NTHR), 0, st, L, hm, default_map, (const uint16_t*)q,
-                       (const char*)ws, (uint16_t*)out, lse, row_pairs);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, SOFTCAP, PAIRS>), dim3(grid), dim3(NTHR), 0, st, L, hm, default_map,
+                       (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
     return hipGetLastError();
 }
 
@@ -366,8 +492,6 @@ hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const v
     dim3 ggrid(L.NKP / KT, L.B * L.Hkv);
     hipLaunchKernelGGL(gather_vt_kernel<D>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)v, ws);
     const bool sc = L.softcap > 0.f, pairs = row_pairs != nullptr;
-    static const int variant = [] { const char* e = getenv("FOCUS_MFMA_VARIANT"); return e ? atoi(e) : 3; }();
-    if (variant == 3) return launch_attn_mfma3_core(L, hm, default_map, q, ws, out, lse, row_pairs, st);
     if (sc) {
         return pairs ? launch_one<D, true, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
                      : launch_one<D, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);

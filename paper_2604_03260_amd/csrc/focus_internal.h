@@ -65,8 +65,6 @@ __host__ __device__ inline uint32_t binom_u32(int a, int b)
 hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                          const float* centroids, char* ws, hipStream_t st);
 hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t st);
-hipError_t launch_attn_mfma3_core(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws,
-                                  void* out, float* lse, int32_t* row_pairs, hipStream_t st);
 hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                               const void* v, char* ws, void* out, float* lse, int32_t* row_pairs,
                               hipStream_t st);

@@ -16,6 +16,7 @@ struct TilePlan {
     int t0[MAX_CLASSES];       // first key tile (global tile index inside the head)
     int cum[MAX_CLASSES + 1];  // running number of tiles over the classes
     uint8_t inter[MAX_CLASSES];
+    int nint[MAX_CLASSES];     // leading tiles of the class whose keys all precede the tile's first query
     uint8_t blk_hi[SB];        // class ids of the sort block holding the upper bound
     uint8_t blk_lo[SB];        // ... and the lower bound of the window span
     int cls, tile, row0, nvalid, i_lo, i_hi, total;
@@ -75,6 +76,8 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
         P.t0[c2] = a;
         P.cum[c2 + 1] = b - a;                             // lengths first, summed below
         P.inter[c2] = inter ? 1 : 0;
+        // keys before the sort block that holds i_lo+1 are at positions <= i_lo: no causal test needed
+        P.nint[c2] = inter ? min(b - a, kbc[(size_t)((i_lo + 1) / SB) * NC + c2] / KT) : 0;
     }
     __syncthreads();
     if (tid == 0) {
