@@ -110,6 +110,7 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->off_qco = take(BHq * (L->NC + 1) * 4);
     L->off_kco = take(BHk * (L->NC + 1) * 4);
     L->off_clsmask = take((size_t)L->NC * 4);
+    L->off_cent64 = take((size_t)p->Hkv * p->d * 32 * 8);
     L->off_qperm = take(BHq * L->NQP * 4);
     L->off_kpos = take(BHk * L->NKP * 4);
     L->off_jobs = take(BHq * L->NT * 4);

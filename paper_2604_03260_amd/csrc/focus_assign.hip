@@ -31,12 +31,10 @@ constexpr int ROW_STRIDE = ROW_CHUNK_BYTES + 16;     // padded LDS row stride
 
 template <typename T, int KMAX>
 __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, const T* __restrict__ x,
-                                                        const float* __restrict__ cents, int is_query,
+                                                        const double* __restrict__ cent64, int is_query,
                                                         char* __restrict__ ws)
 {
-    extern __shared__ __align__(16) char smem[];
-    char* s_rows = smem;                                             // SB * ROW_STRIDE
-    double* s_cent = (double*)(smem + SB * ROW_STRIDE);              // [d][KMAX]
+    __shared__ __align__(16) char s_rows[SB * ROW_STRIDE];
     __shared__ uint32_t s_binom[33 * 33];
     __shared__ int s_hist_c[MAX_CLASSES];
     __shared__ int s_hist_g[32];
@@ -53,10 +51,9 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     const int row_bytes = d * (int)sizeof(T);
     const int phases = row_bytes / ROW_CHUNK_BYTES;
 
-    for (int e = tid; e < d * KMAX; e += SB) {
-        int t = e / KMAX, g = e % KMAX;
-        s_cent[e] = (g < K) ? (double)cents[((size_t)hk * K + g) * d + t] : 0.0;
-    }
+    // centroids of this KV head as fp64 [d][KMAX]: a wave-uniform, read-only table -> scalar loads,
+    // the values feed v_fma_f64 straight from SGPRs
+    const double* __restrict__ cd = cent64 + (size_t)hk * d * KMAX;
     for (int e = tid; e < 33 * 33; e += SB) s_binom[e] = binom_u32(e / 33, e % 33);
     for (int e = tid; e < MAX_CLASSES; e += SB) s_hist_c[e] = 0;
     if (tid < 32) s_hist_g[tid] = 0;
@@ -98,7 +95,7 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
             }
 #pragma unroll
             for (int e = 0; e < EPC; ++e) {
-                const double* cr = s_cent + (size_t)(tbase + cc * EPC + e) * KMAX;
+                const double* cr = cd + (size_t)(tbase + cc * EPC + e) * KMAX;
 #pragma unroll
                 for (int g = 0; g < KMAX; ++g) acc[g] = fma(xv[e], cr[g], acc[g]);
             }
@@ -142,6 +139,17 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     int* bg = (int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + blk) * K;
     for (int c = tid; c < L.NC; c += SB) bc[c] = s_hist_c[c];
     if (tid < K) bg[tid] = s_hist_g[tid];
+}
+
+// centroids fp32 [Hkv][K][d] -> fp64 [Hkv][d][KMAX] (zero-padded groups)
+__global__ void cent_to_f64_kernel(const float* __restrict__ cents, double* __restrict__ out, int Hkv, int K, int d,
+                                   int kmax)
+{
+    const int total = Hkv * d * kmax;
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
+        const int g = e % kmax, t = (e / kmax) % d, hk = e / (kmax * d);
+        out[e] = (g < K) ? (double)cents[((size_t)hk * K + g) * d + t] : 0.0;
+    }
 }
 
 // ---------------------------------------------------------------- scans over sort blocks
@@ -339,30 +347,18 @@ __global__ __launch_bounds__(SB) void scatter_kernel(Layout L, int is_query, cha
 }
 
 template <typename T>
-hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, const float* cents, int is_query,
-                        char* ws, hipStream_t st)
+hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, int is_query, char* ws, hipStream_t st)
 {
     const int H = is_query ? L.Hq : L.Hkv;
     dim3 grid(L.nblk, L.B * H);
     const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
-    const size_t shm = (size_t)SB * ROW_STRIDE + (size_t)L.d * kmax * sizeof(double);
-#define FOCUS_LAUNCH_SCORE(KM)                                                                              \
-    do {                                                                                                    \
-        auto kern = score_topk_kernel<T, KM>;                                                               \
-        if (shm > 48 * 1024) {                                                                              \
-            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                               (int)shm);                                                   \
-            if (e != hipSuccess) return e;                                                                  \
-        }                                                                                                   \
-        hipLaunchKernelGGL(kern, grid, dim3(SB), shm, st, L, hm, (const T*)x, cents, is_query, ws);         \
-    } while (0)
+    const double* cent64 = (const double*)(ws + L.off_cent64);
     switch (kmax) {
-        case 4: FOCUS_LAUNCH_SCORE(4); break;
-        case 8: FOCUS_LAUNCH_SCORE(8); break;
-        case 16: FOCUS_LAUNCH_SCORE(16); break;
-        default: FOCUS_LAUNCH_SCORE(32); break;
+        case 4: hipLaunchKernelGGL((score_topk_kernel<T, 4>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
+        case 8: hipLaunchKernelGGL((score_topk_kernel<T, 8>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
+        case 16: hipLaunchKernelGGL((score_topk_kernel<T, 16>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
+        default: hipLaunchKernelGGL((score_topk_kernel<T, 32>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
     }
-#undef FOCUS_LAUNCH_SCORE
     return hipGetLastError();
 }
 
@@ -379,12 +375,17 @@ hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, cons
         hipLaunchKernelGGL(fill_i32_kernel, dim3(gq), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, -1);
         hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kpos), nk, KPOS_PAD);
     }
+    {
+        const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
+        hipLaunchKernelGGL(cent_to_f64_kernel, dim3(64), dim3(256), 0, st, centroids, (double*)(ws + L.off_cent64),
+                           L.Hkv, L.K, L.d, kmax);
+    }
     if (L.dtype == 0) {
-        if ((e = launch_score<float>(L, hm, q, centroids, 1, ws, st)) != hipSuccess) return e;
-        if ((e = launch_score<float>(L, hm, k, centroids, 0, ws, st)) != hipSuccess) return e;
+        if ((e = launch_score<float>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
+        if ((e = launch_score<float>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
     } else {
-        if ((e = launch_score<uint16_t>(L, hm, q, centroids, 1, ws, st)) != hipSuccess) return e;
-        if ((e = launch_score<uint16_t>(L, hm, k, centroids, 0, ws, st)) != hipSuccess) return e;
+        if ((e = launch_score<uint16_t>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
+        if ((e = launch_score<uint16_t>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
     }
     for (int is_query = 1; is_query >= 0; --is_query) {
         const int H = is_query ? L.Hq : L.Hkv;

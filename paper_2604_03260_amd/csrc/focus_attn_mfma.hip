@@ -141,6 +141,31 @@ __device__ inline void dma16(const void* sbase, unsigned voff, unsigned lds_addr
 
 __device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)p; }
 
+// 16-byte LDS read whose completion the compiler does not track (see F4_WAIT_OPERANDS)
+__device__ inline bf16x8 lds_read16_async(unsigned addr)
+{
+    bf16x8 r;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr));
+    return r;
+}
+__device__ inline void wait_lds_operands(bf16x8 (&a)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]));
+}
+__device__ inline void wait_lds_operands(bf16x8 (&a)[4])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+}
+__device__ inline void pin_operands(bf16x8 (&a)[8])
+{
+    asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]));
+}
+__device__ inline void pin_operands(bf16x8 (&a)[4])
+{
+    asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+}
+
 template <int D, bool SOFTCAP, bool PAIRS>
 __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm, int default_map,
                                                              const uint16_t* __restrict__ q,
@@ -244,23 +269,28 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     } while (0)
 #define F4_WAIT_DMA() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
 
-    // LDS operand reads of one unit
+    // LDS operand reads of one unit, issued as inline asm so that they stay where they are written
+    // and are NOT waited for at once: the vector work that follows runs while they are in flight,
+    // and F4_WAIT_OPERANDS() (s_waitcnt lgkmcnt(0), tied to every operand register) precedes the MFMAs.
 #define F4_READ_K(DST, KST, U)                                                                       \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                              \
         const int row_ = (U) * 32 + n32;                                                             \
-        DST[ks] = *(const bf16x8*)(S.k[KST] + row_ * (D * 2) + swz<D * 2>(row_, 2 * ks + hh) * 16);  \
+        DST[ks] = lds_read16_async(lds_k0 + (KST) * TILE_BYTES + row_ * (D * 2) + swz<D * 2>(row_, 2 * ks + hh) * 16); \
     }
 #define F4_READ_V(DST, VST, U)                                                                       \
     _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                \
         _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {                                           \
             const int row_ = db * 32 + n32;                                                          \
-            DST[db * 2 + s2] = *(const bf16x8*)(S.vt[VST] + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
+            DST[db * 2 + s2] = lds_read16_async(lds_v0 + (VST) * TILE_BYTES + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
         }
+#define F4_WAIT_OPERANDS()                                                                           \
+    wait_lds_operands(ak);                                                                           \
+    pin_operands(av);
 
     // Scalar walk over the tile sequence (class by class).  A tile travels as one packed word:
     // bits 0..29 tile index, bit 30 "class shares a group" flag, bit 31 "no mask needed" flag.
     // LDS is touched only when the walk enters a new class; past the end the last tile repeats.
-    int w_c = -1, w_t = 0, w_end = 0, w_int_end = 0, w_flag = 0, w_last = 0;
+    int w_c = -1, w_t = 0, w_end = 0, w_int_beg = 0, w_int_end = 0, w_flag = 0, w_last = 0;
     auto next_tile = [&]() -> unsigned {
         if (w_t >= w_end) {
             int c = w_c + 1;
@@ -269,13 +299,14 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
                 w_c = __builtin_amdgcn_readfirstlane(c);
                 w_t = __builtin_amdgcn_readfirstlane(S.plan.t0[c]);
                 w_end = w_t + __builtin_amdgcn_readfirstlane(S.plan.cum[c + 1] - S.plan.cum[c]);
-                w_int_end = w_t + __builtin_amdgcn_readfirstlane(S.plan.nint[c]);
+                w_int_beg = __builtin_amdgcn_readfirstlane(S.plan.ibeg[c]);
+                w_int_end = __builtin_amdgcn_readfirstlane(S.plan.iend[c]);
                 w_flag = __builtin_amdgcn_readfirstlane((int)S.plan.inter[c]) << 30;
             } else {
                 return (unsigned)w_last;                      // sequence exhausted
             }
         }
-        w_last = w_t | w_flag | ((w_t < w_int_end) ? (int)0x80000000u : 0);
+        w_last = w_t | w_flag | ((w_t >= w_int_beg && w_t < w_int_end) ? (int)0x80000000u : 0);
         ++w_t;
         return (unsigned)w_last;
     };
@@ -309,6 +340,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
 #pragma unroll
     for (int e = 0; e < 8; ++e) { p1[0][e] = (__bf16)0.f; p1[1][e] = (__bf16)0.f; p0[0][e] = (__bf16)0.f; p0[1][e] = (__bf16)0.f; }
     F4_READ_K(ak, 0, 0)
+    wait_lds_operands(ak);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], s0, 0, 0, 0);
 
@@ -326,7 +358,8 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
             const int4 kp4_ = *(const int4*)(&S.kpos[KPB][(U) * 32 + 8 * r4 + 4 * hh]);                  \
             const int kp_[4] = {kp4_.x, kp4_.y, kp4_.z, kp4_.w};                                         \
             _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                              \
-                const bool ok_ = kp_[e] <= qpos && (inter || kp_[e] > qpos - w);                         \
+                /* 0 <= qpos - kpos < wlim in one unsigned compare; pads (INT_MAX) and qpos = -1 fail */ \
+                const bool ok_ = (unsigned)(qpos - kp_[e]) < wlim;                                       \
                 SIN[r4 * 4 + e] = ok_ ? SIN[r4 * 4 + e] : -INFINITY;                                     \
                 if constexpr (PAIRS) npairs += ok_ ? 1 : 0;                                              \
             }                                                                                            \
@@ -379,16 +412,12 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
         SOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], SOUT, 0, 0, 0);
     // keeps values computed / loaded where they are written in the source (no sinking past a branch)
 #define F4_PIN2(P_) asm volatile("" : "+v"(P_[0]), "+v"(P_[1]))
-#define F4_PIN_OPERANDS()                                                                                \
-    _Pragma("unroll") for (int i = 0; i < KS; ++i) asm volatile("" : "+v"(ak[i]));                       \
-    _Pragma("unroll") for (int i = 0; i < NPV; ++i) asm volatile("" : "+v"(av[i]));
-
     int kb_cur = 0;                                          // kpos buffer of tile t (t mod 3)
     // One key tile.  SC is the LDS stage of K(t), V(t); K(t+1), V(t-1) sit in the other.
 #define F4_TILE(SC)                                                                                      \
     {                                                                                                    \
         const int sc = (SC), sn = (SC) ^ 1;                                                              \
-        const bool inter = (pk0 >> 30) & 1u;                                                             \
+        const unsigned wlim = ((pk0 >> 30) & 1u) ? 0x80000000u : (unsigned)w;   /* causal only / window */ \
         const bool interior = (pk0 >> 31) != 0;                                                          \
         const int tl1 = (int)(pk1 & TILE_MASK);                                                          \
         const int tl2 = (int)(pk2 & TILE_MASK);                                                          \
@@ -396,8 +425,8 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
         /* phase A: VALU softmax(S0) -> P0 ; MFMA O += V(t-1,u1) P1 and S1 = K(t,u1) Q^T */              \
         F4_READ_V(av, sn, 1)                                                                             \
         F4_READ_K(ak, sc, 1)                                                                             \
-        F4_PIN_OPERANDS()                                                                                \
         F4_SOFTMAX_PRE(s0, 0, kb_cur, p1)                                                                \
+        F4_WAIT_OPERANDS()                                                                               \
         F4_MFMAS(p1, s1)                                                                                 \
         F4_SOFTMAX_EXP(s0, p0)                                                                           \
         __builtin_amdgcn_iglp_opt(3);                                                                    \
@@ -411,8 +440,8 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
         /* phase B: VALU softmax(S1) -> P1 ; MFMA O += V(t,u0) P0 and S0 = K(t+1,u0) Q^T */              \
         F4_READ_V(av, sc, 0)                                                                             \
         F4_READ_K(ak, sn, 0)                                                                             \
-        F4_PIN_OPERANDS()                                                                                \
         F4_SOFTMAX_PRE(s1, 1, kb_cur, p0)                                                                \
+        F4_WAIT_OPERANDS()                                                                               \
         F4_MFMAS(p0, s0)                                                                                 \
         F4_SOFTMAX_EXP(s1, p1)                                                                           \
         __builtin_amdgcn_iglp_opt(3);                                                                    \
@@ -430,6 +459,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     {
         const int sl = (total - 1) & 1;
         F4_READ_V(av, sl, 1)
+        wait_lds_operands(av);
 #pragma unroll
         for (int i = 0; i < NPV; ++i)
             o[i / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], p1[i % 2], o[i / 2], 0, 0, 0);
@@ -445,7 +475,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
 #undef F4_SOFTMAX_EXP
 #undef F4_MFMAS
 #undef F4_PIN2
-#undef F4_PIN_OPERANDS
+#undef F4_WAIT_OPERANDS
 
     // ---- epilogue
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);

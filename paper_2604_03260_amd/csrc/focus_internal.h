@@ -44,6 +44,7 @@ struct Layout {
     size_t off_qcc, off_kcc;           // class counts [.,NC]
     size_t off_qco, off_kco;           // padded class offsets [.,NC+1]
     size_t off_clsmask;                // group bit mask of each class [NC]
+    size_t off_cent64;                 // centroids as fp64 [Hkv][d][KMAX], KMAX = K rounded up to 4/8/16/32
     size_t off_qperm;                  // [B,Hq,NQP] positions in class order, -1 in pads
     size_t off_kpos;                   // [B,Hkv,NKP] positions in class order, KPOS_PAD in pads
     size_t off_jobs;                   // [B,Hq,NT] (class << 24 | tile) heaviest first, -1 unused

@@ -16,7 +16,8 @@ struct TilePlan {
     int t0[MAX_CLASSES];       // first key tile (global tile index inside the head)
     int cum[MAX_CLASSES + 1];  // running number of tiles over the classes
     uint8_t inter[MAX_CLASSES];
-    int nint[MAX_CLASSES];     // leading tiles of the class whose keys all precede the tile's first query
+    int ibeg[MAX_CLASSES];     // tiles [ibeg, iend) of the class need no per-element causal/window test
+    int iend[MAX_CLASSES];
     uint8_t blk_hi[SB];        // class ids of the sort block holding the upper bound
     uint8_t blk_lo[SB];        // ... and the lower bound of the window span
     int cls, tile, row0, nvalid, i_lo, i_hi, total;
@@ -76,8 +77,22 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
         P.t0[c2] = a;
         P.cum[c2 + 1] = b - a;                             // lengths first, summed below
         P.inter[c2] = inter ? 1 : 0;
-        // keys before the sort block that holds i_lo+1 are at positions <= i_lo: no causal test needed
-        P.nint[c2] = inter ? min(b - a, kbc[(size_t)((i_lo + 1) / SB) * NC + c2] / KT) : 0;
+        // Tiles that need no per-element test, from prefix counts at sort-block boundaries (conservative):
+        // keys before the sort block that holds i_lo+1 sit at positions <= i_lo (causal for every row);
+        // for a class without a common group they must also lie above i_hi - window for every row.
+        const int cnt_below = kbc[(size_t)((i_lo + 1) / SB) * NC + c2];
+        int ib = a, ie = a;
+        if (inter) {
+            ie = a + min(b - a, cnt_below / KT);
+        } else if (b > a) {
+            const int x_in = i_hi - L.window + 1;
+            const int lo_blk = (x_in <= 0) ? 0 : min(L.nblk, (x_in + SB - 1) / SB);
+            ib = max(a, (koff + kbc[(size_t)lo_blk * NC + c2] + KT - 1) / KT);
+            ie = min(b, (koff + cnt_below) / KT);
+            if (ie < ib) ie = ib;
+        }
+        P.ibeg[c2] = ib;
+        P.iend[c2] = ie;
     }
     __syncthreads();
     if (tid == 0) {
