@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 
 BF16_MFMA_PEAK_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 FP32_VECTOR_PEAK_TFLOPS = 157.3
+# HBM bytes per launch of the attention kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this
+# command (profiles/attn_mfma_kernel_cfg3_counters.txt); None where no counter run was made
+MEASURED_TRAFFIC_BYTES = {"cfg3": 6.08e9}
 
 
 def main():
@@ -33,6 +36,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain device copy of q (known size) so a counter run can be calibrated")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every config is single-GPU); "
@@ -96,6 +101,10 @@ def main():
         t_attn = sum(e[1].elapsed_time(e[2]) for e in ev) / nsteps
         return wall * 1e3 / nsteps, t_assign, t_attn
 
+    if args.calib_copy:
+        calib = q.clone()                 # reads and writes q.numel()*elem bytes once
+        torch.cuda.synchronize()
+        del calib
     ms_step, ms_assign, ms_attn = timed(p, ws, steps, warmup)
     out_focus = out
     out = torch.empty_like(q)          # later runs (dense mode) must not overwrite the checked output
@@ -133,7 +142,7 @@ def main():
             "peak": peak,
             "unit": "TFLOP/s",
             "frac": tflops_attn / peak,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
             "note": "achieved = 4*d*allowed_pairs / mean focus_attn_fwd time (HIP events; includes the V staging kernel)",
         },
         "paper_context": "paper reports 2.0x (K=4, top-2) and 8.6x (K=8, 1M tokens) over dense FlashAttention on H100-80GB",
