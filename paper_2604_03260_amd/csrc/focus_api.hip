@@ -80,8 +80,9 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
         L->NC = (int)c;
     }
     L->nblk = (p->n + SB - 1) / SB;
-    L->NT = (p->n + BQ - 1) / BQ + L->NC;
-    L->NQP = L->NT * BQ;
+    L->BQ = (p->dtype == FOCUS_BF16) ? 128 * MFMA_QB : BQ_VECTOR;
+    L->NT = (p->n + L->BQ - 1) / L->BQ + L->NC;
+    L->NQP = L->NT * L->BQ;
     L->NKP = ((p->n + KT - 1) / KT + L->NC) * KT;
 
     for (int h = 0; h < p->Hq; ++h)

@@ -210,12 +210,12 @@ __global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int is_query,
     int* co = (int*)(ws + (is_query ? L.off_qco : L.off_kco)) + (size_t)bh * (NC + 1);
     int* gc = (int*)(ws + (is_query ? L.off_qgc : L.off_kgc)) + (size_t)bh * K;
     int* go = (int*)(ws + (is_query ? L.off_qgo : L.off_kgo)) + (size_t)bh * (K + 1);
-    const int pad = is_query ? BQ : KT;
+    const int pad = is_query ? L.BQ : KT;
 
     for (int c = tid; c < NC; c += 256) {
         int v = bc_tot[c];
         s_cnt[c] = v;
-        s_nt[c] = (v + BQ - 1) / BQ;
+        s_nt[c] = (v + L.BQ - 1) / L.BQ;
         cc[c] = v;
     }
     if (tid < K) gc[tid] = bg_tot[tid];

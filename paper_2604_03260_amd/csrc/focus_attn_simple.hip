@@ -1,7 +1,8 @@
 // fp32 vector attention kernel (no matrix cores): the path for fp32 inputs and an
 // independent on-device cross-check of the MFMA kernel for bf16 inputs.
 //
-// One work-group owns one query tile (<= BQ queries of one membership class).
+// One work-group owns one query tile (<= L.BQ queries of one membership class) and
+// handles it in passes of BQ_VECTOR rows.
 // A row is shared by d/32 adjacent lanes, each holding 32 of the d components
 // of q and of the output accumulator.  Keys and values are gathered 32 at a
 // time through the class-ordered position array into LDS as fp32; the allowed
@@ -32,14 +33,14 @@ template <> __device__ inline float from_f32<float>(float v) { return v; }
 template <> __device__ inline uint16_t from_f32<uint16_t>(float v) { return f32_to_bf16_rne(v); }
 
 template <typename T, int D>
-__global__ __launch_bounds__(BQ * (D / 32)) void attn_simple_kernel(Layout L, HeadMap hm, const T* __restrict__ q,
+__global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layout L, HeadMap hm, const T* __restrict__ q,
                                                                     const T* __restrict__ k, const T* __restrict__ v,
                                                                     const char* __restrict__ ws, T* __restrict__ out,
                                                                     float* __restrict__ lse,
                                                                     int32_t* __restrict__ row_pairs)
 {
     constexpr int TPR = D / 32;
-    constexpr int NTHR = BQ * TPR;
+    constexpr int NTHR = BQ_VECTOR * TPR;
     __shared__ TilePlan P;
     __shared__ __align__(16) float s_k[SUB * D];
     __shared__ __align__(16) float s_v[SUB * D];
@@ -52,7 +53,8 @@ __global__ __launch_bounds__(BQ * (D / 32)) void attn_simple_kernel(Layout L, He
     const int bhk = b * L.Hkv + hm.kv[h];
     if (!plan_query_tile(L, ws, bhq, bhk, job, P)) return;
 
-    const int row = tid / TPR, part = tid % TPR;
+    for (int pass = 0; pass * BQ_VECTOR < P.nvalid; ++pass) {
+    const int row = pass * BQ_VECTOR + tid / TPR, part = tid % TPR;
     const bool rvalid = row < P.nvalid;
     const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
     const int qpos = rvalid ? qperm[P.row0 + row] : -1;
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(BQ * (D / 32)) void attn_simple_kernel(Layout L, He
             }
         }
     }
-    if (!rvalid) return;
+    if (rvalid) {
     const float inv = 1.f / l;
     T* orow = out + ((size_t)bhq * L.n + qpos) * D + part * 32;
 #pragma unroll
@@ -137,6 +139,8 @@ __global__ __launch_bounds__(BQ * (D / 32)) void attn_simple_kernel(Layout L, He
         if (lse) lse[(size_t)bhq * L.n + qpos] = m + logf(l);
         if (row_pairs) row_pairs[(size_t)bhq * L.n + qpos] = npairs;
     }
+    }
+    }   // pass
 }
 
 }  // namespace
@@ -146,7 +150,7 @@ hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q,
 {
     dim3 grid(L.NT, L.B * L.Hq);
 #define FOCUS_LAUNCH_SIMPLE(T, D)                                                                      \
-    hipLaunchKernelGGL((attn_simple_kernel<T, D>), grid, dim3(BQ*(D / 32)), 0, st, L, hm, (const T*)q, \
+    hipLaunchKernelGGL((attn_simple_kernel<T, D>), grid, dim3(BQ_VECTOR*(D / 32)), 0, st, L, hm, (const T*)q, \
                        (const T*)k, (const T*)v, (const char*)ws, (T*)out, lse, row_pairs)
     if (L.dtype == 0) {
         if (L.d == 64) FOCUS_LAUNCH_SIMPLE(float, 64); else FOCUS_LAUNCH_SIMPLE(float, 128);

@@ -1,6 +1,6 @@
 // Per query tile: which tiles of the class-ordered key arrays it must visit.
 //
-// A query tile holds up to BQ queries of ONE membership class, positions
+// A query tile holds up to L.BQ queries of ONE membership class, positions
 // ascending.  Keys are partitioned by class too, so every allowed pair of
 // App. D Eq. 3 (with top-k sets) is met exactly once:
 //   - key class shares a group with the query class: all its keys up to the
@@ -36,8 +36,8 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
     const int* qco = (const int*)(ws + L.off_qco) + (size_t)bhq * (NC + 1);
     const int* qcc = (const int*)(ws + L.off_qcc) + (size_t)bhq * NC;
     const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
-    const int row0 = qco[c] + t * BQ;
-    const int nvalid = min(BQ, qcc[c] - t * BQ);
+    const int row0 = qco[c] + t * L.BQ;
+    const int nvalid = min(L.BQ, qcc[c] - t * L.BQ);
     const int i_lo = qperm[row0];
     const int i_hi = qperm[row0 + nvalid - 1];
     const int x_hi = i_hi + 1;                              // keys with position < x_hi are causal for the tile
