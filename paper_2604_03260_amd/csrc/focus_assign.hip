@@ -25,6 +25,24 @@ namespace {
 
 __device__ inline float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// Pascal's triangle up to C(32, .), built at compile time: the class of a token is the colex rank of
+// its membership set, a sum of binomials.
+struct BinomTable { uint32_t v[33 * 33]; };
+constexpr BinomTable make_binom_table()
+{
+    BinomTable t{};
+    for (int a = 0; a <= 32; ++a) {
+        for (int b = 0; b <= 32; ++b) {
+            uint32_t x = 0;
+            if (b == 0 || b == a) x = (b <= a) ? 1u : 0u;
+            else if (b < a) x = t.v[(a - 1) * 33 + b - 1] + t.v[(a - 1) * 33 + b];
+            t.v[a * 33 + b] = x;
+        }
+    }
+    return t;
+}
+__device__ __constant__ BinomTable g_binom = make_binom_table();
+
 // ---------------------------------------------------------------- score + top-k
 constexpr int ROW_CHUNK_BYTES = 128;                 // bytes of every row staged per phase
 constexpr int ROW_STRIDE = ROW_CHUNK_BYTES + 16;     // padded LDS row stride
@@ -35,7 +53,6 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
                                                         char* __restrict__ ws)
 {
     __shared__ __align__(16) char s_rows[SB * ROW_STRIDE];
-    __shared__ uint32_t s_binom[33 * 33];
     __shared__ int s_hist_c[MAX_CLASSES];
     __shared__ int s_hist_g[32];
 
@@ -54,7 +71,6 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     // centroids of this KV head as fp64 [d][KMAX]: a wave-uniform, read-only table -> scalar loads,
     // the values feed v_fma_f64 straight from SGPRs
     const double* __restrict__ cd = cent64 + (size_t)hk * d * KMAX;
-    for (int e = tid; e < 33 * 33; e += SB) s_binom[e] = binom_u32(e / 33, e % 33);
     for (int e = tid; e < MAX_CLASSES; e += SB) s_hist_c[e] = 0;
     if (tid < 32) s_hist_g[tid] = 0;
 
@@ -121,7 +137,7 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     if (!L.dense) {
         int j = 0;
         for (int g = 0; g < K; ++g)
-            if ((mask >> g) & 1u) { ++j; cls += (int)s_binom[g * 33 + j]; }
+            if ((mask >> g) & 1u) { ++j; cls += (int)g_binom.v[g * 33 + j]; }
     }
     const bool valid = pos < n;
     uint32_t* masks = (uint32_t*)(ws + (is_query ? L.off_mq : L.off_mk));
