@@ -47,6 +47,10 @@ __device__ __constant__ BinomTable g_binom = make_binom_table();
 constexpr int ROW_CHUNK_BYTES = 128;                 // bytes of every row staged per phase
 constexpr int ROW_STRIDE = ROW_CHUNK_BYTES + 16;     // padded LDS row stride
 
+constexpr int NBW = 4;          // sort blocks handled by one work-group of the scoring kernel
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 template <typename T, int KMAX>
 __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, const T* __restrict__ x,
                                                         const double* __restrict__ cent64, int is_query,
@@ -57,16 +61,18 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     __shared__ int s_hist_g[32];
 
     const int tid = threadIdx.x;
-    const int blk = blockIdx.x;
+    const int blk0 = blockIdx.x * NBW;
     const int bh = blockIdx.y;
     const int H = is_query ? L.Hq : L.Hkv;
     const int h = bh % H;
     const int hk = is_query ? hm.kv[h] : h;
     const int d = L.d, K = L.K, n = L.n;
     constexpr int EPC = 16 / sizeof(T);                              // elements per 16-byte chunk
-    constexpr int CPR = ROW_CHUNK_BYTES / 16;                        // chunks per staged row
+    constexpr int CPR = ROW_CHUNK_BYTES / 16;                        // chunks per staged row = loads per thread
     const int row_bytes = d * (int)sizeof(T);
     const int phases = row_bytes / ROW_CHUNK_BYTES;
+    const int nb_here = min(NBW, L.nblk - blk0);
+    const int total_steps = nb_here * phases;                        // (block, 128-byte column phase) pairs
 
     // centroids of this KV head as fp64 [d][KMAX]: a wave-uniform, read-only table -> scalar loads,
     // the values feed v_fma_f64 straight from SGPRs
@@ -78,35 +84,51 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
 #pragma unroll
     for (int g = 0; g < KMAX; ++g) acc[g] = 0.0;
 
-    const int pos = blk * SB + tid;
-    const int rows_here = min(SB, n - blk * SB);
-    const char* gbase = (const char*)x + ((size_t)bh * n + (size_t)blk * SB) * row_bytes;
+    uint32_t* masks = (uint32_t*)(ws + (is_query ? L.off_mq : L.off_mk));
+    uint8_t* clsarr = (uint8_t*)(ws + (is_query ? L.off_qcls : L.off_kcls));
+    const size_t cls_stride = is_query ? (size_t)n : (size_t)L.nblk * SB;
+    const char* xbase = (const char*)x + (size_t)bh * n * row_bytes;
 
-    for (int ph = 0; ph < phases; ++ph) {
-        __syncthreads();
-        // coalesced: consecutive threads fetch consecutive 16-byte chunks of a 128-byte row segment
-        for (int cid = tid; cid < SB * CPR; cid += SB) {
-            int r = cid / CPR, cc = cid % CPR;
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (r < rows_here)
-                val = *(const uint4*)(gbase + (size_t)r * row_bytes + ph * ROW_CHUNK_BYTES + cc * 16);
-            *(uint4*)(s_rows + r * ROW_STRIDE + cc * 16) = val;
+    // Register staging of the next step: its global loads fly while the current step is computed.
+    // Coalesced: consecutive threads fetch consecutive 16-byte chunks of a 128-byte row segment.
+    u32x4 st[CPR];
+#define FOCUS_SCORE_LOAD(STEP)                                                                       \
+    do {                                                                                             \
+        const int bi_ = (STEP) / phases, ph_ = (STEP) % phases;                                      \
+        const int rows_ = min(SB, n - (blk0 + bi_) * SB);                                            \
+        const char* g_ = xbase + (size_t)(blk0 + bi_) * SB * row_bytes + ph_ * ROW_CHUNK_BYTES;      \
+        _Pragma("unroll") for (int i = 0; i < CPR; ++i) {                                            \
+            const int cid_ = tid + i * SB;                                                           \
+            const int r_ = cid_ / CPR, cc_ = cid_ % CPR;                                             \
+            const u32x4 z_ = {0u, 0u, 0u, 0u};                                                       \
+            st[i] = (r_ < rows_) ? *(const u32x4*)(g_ + (size_t)r_ * row_bytes + cc_ * 16) : z_;     \
+        }                                                                                            \
+    } while (0)
+
+    FOCUS_SCORE_LOAD(0);
+    for (int step = 0; step < total_steps; ++step) {
+        const int bi = step / phases, ph = step % phases;
+        __syncthreads();                                             // the previous step's reads are done
+#pragma unroll
+        for (int i = 0; i < CPR; ++i) {
+            const int cid = tid + i * SB;
+            *(u32x4*)(s_rows + (cid / CPR) * ROW_STRIDE + (cid % CPR) * 16) = st[i];
         }
         __syncthreads();
+        if (step + 1 < total_steps) FOCUS_SCORE_LOAD(step + 1);
         const int tbase = ph * (ROW_CHUNK_BYTES / (int)sizeof(T));
 #pragma unroll 1
         for (int cc = 0; cc < CPR; ++cc) {
-            uint4 val = *(const uint4*)(s_rows + tid * ROW_STRIDE + cc * 16);
+            const u32x4 val = *(const u32x4*)(s_rows + tid * ROW_STRIDE + cc * 16);
             double xv[EPC];
             if constexpr (sizeof(T) == 4) {
-                xv[0] = (double)__uint_as_float(val.x); xv[1] = (double)__uint_as_float(val.y);
-                xv[2] = (double)__uint_as_float(val.z); xv[3] = (double)__uint_as_float(val.w);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xv[e] = (double)__uint_as_float(val[e]);
             } else {
-                const uint32_t w4[4] = {val.x, val.y, val.z, val.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    xv[2 * e] = (double)bf16_bits_to_f32((uint16_t)(w4[e] & 0xffffu));
-                    xv[2 * e + 1] = (double)bf16_bits_to_f32((uint16_t)(w4[e] >> 16));
+                    xv[2 * e] = (double)bf16_bits_to_f32((uint16_t)(val[e] & 0xffffu));
+                    xv[2 * e + 1] = (double)bf16_bits_to_f32((uint16_t)(val[e] >> 16));
                 }
             }
 #pragma unroll
@@ -116,45 +138,48 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
                 for (int g = 0; g < KMAX; ++g) acc[g] = fma(xv[e], cr[g], acc[g]);
             }
         }
-    }
+        if (ph != phases - 1) continue;
 
-    // top-k by rank counting; ties go to the smaller group index
-    uint32_t mask = 0;
+        // ---- a sort block is complete: top-k by rank counting; ties go to the smaller group index
+        const int blk = blk0 + bi;
+        const int pos = blk * SB + tid;
+        uint32_t mask = 0;
 #pragma unroll
-    for (int g = 0; g < KMAX; ++g) {
-        if (g < K) {
-            int beaten = 0;
+        for (int g = 0; g < KMAX; ++g) {
+            if (g < K) {
+                int beaten = 0;
 #pragma unroll
-            for (int o = 0; o < KMAX; ++o) {
-                if (o < K && o != g)
-                    beaten += (acc[o] > acc[g] || (acc[o] == acc[g] && o < g)) ? 1 : 0;
+                for (int o = 0; o < KMAX; ++o) {
+                    if (o < K && o != g)
+                        beaten += (acc[o] > acc[g] || (acc[o] == acc[g] && o < g)) ? 1 : 0;
+                }
+                if (beaten < L.topk) mask |= (1u << g);
             }
-            if (beaten < L.topk) mask |= (1u << g);
         }
+#pragma unroll
+        for (int g = 0; g < KMAX; ++g) acc[g] = 0.0;
+        // class = colex rank of the membership set among all topk-subsets
+        int cls = 0;
+        if (!L.dense) {
+            int j = 0;
+            for (int g = 0; g < K; ++g)
+                if ((mask >> g) & 1u) { ++j; cls += (int)g_binom.v[g * 33 + j]; }
+        }
+        if (pos < n) {
+            masks[(size_t)bh * n + pos] = mask;
+            clsarr[(size_t)bh * cls_stride + pos] = (uint8_t)cls;
+            atomicAdd(&s_hist_c[cls], 1);
+            for (int g = 0; g < K; ++g)
+                if ((mask >> g) & 1u) atomicAdd(&s_hist_g[g], 1);
+        }
+        __syncthreads();
+        int* bc = (int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + ((size_t)bh * (L.nblk + 1) + blk) * L.NC;
+        int* bg = (int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + blk) * K;
+        for (int c = tid; c < L.NC; c += SB) { bc[c] = s_hist_c[c]; s_hist_c[c] = 0; }
+        if (tid < K) { bg[tid] = s_hist_g[tid]; s_hist_g[tid] = 0; }
+        // the next block's atomics come after the two barriers of its first step
     }
-    // class = colex rank of the membership set among all topk-subsets
-    int cls = 0;
-    if (!L.dense) {
-        int j = 0;
-        for (int g = 0; g < K; ++g)
-            if ((mask >> g) & 1u) { ++j; cls += (int)g_binom.v[g * 33 + j]; }
-    }
-    const bool valid = pos < n;
-    uint32_t* masks = (uint32_t*)(ws + (is_query ? L.off_mq : L.off_mk));
-    uint8_t* clsarr = (uint8_t*)(ws + (is_query ? L.off_qcls : L.off_kcls));
-    const size_t cls_stride = is_query ? (size_t)n : (size_t)L.nblk * SB;
-    if (valid) {
-        masks[(size_t)bh * n + pos] = mask;
-        clsarr[(size_t)bh * cls_stride + pos] = (uint8_t)cls;
-        atomicAdd(&s_hist_c[cls], 1);
-        for (int g = 0; g < K; ++g)
-            if ((mask >> g) & 1u) atomicAdd(&s_hist_g[g], 1);
-    }
-    __syncthreads();
-    int* bc = (int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + ((size_t)bh * (L.nblk + 1) + blk) * L.NC;
-    int* bg = (int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + blk) * K;
-    for (int c = tid; c < L.NC; c += SB) bc[c] = s_hist_c[c];
-    if (tid < K) bg[tid] = s_hist_g[tid];
+#undef FOCUS_SCORE_LOAD
 }
 
 // centroids fp32 [Hkv][K][d] -> fp64 [Hkv][d][KMAX] (zero-padded groups)
@@ -366,7 +391,7 @@ template <typename T>
 hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, int is_query, char* ws, hipStream_t st)
 {
     const int H = is_query ? L.Hq : L.Hkv;
-    dim3 grid(L.nblk, L.B * H);
+    dim3 grid((L.nblk + NBW - 1) / NBW, L.B * H);
     const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
     const double* cent64 = (const double*)(ws + L.off_cent64);
     switch (kmax) {
