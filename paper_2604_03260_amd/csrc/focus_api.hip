@@ -80,7 +80,9 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
         L->NC = (int)c;
     }
     L->nblk = (p->n + SB - 1) / SB;
-    L->BQ = (p->dtype == FOCUS_BF16) ? 128 * MFMA_QB : BQ_VECTOR;
+    // bf16 at long n: 256-row tiles (8 wavefronts share every K/V tile: half the L2->LDS traffic per FLOP,
+    // which is what bounds the kernel once a KV head's K/V no longer sits in L2/MALL)
+    L->BQ = (p->dtype == FOCUS_BF16 && p->n >= LONG_N) ? 256 : BQ_VECTOR;
     L->NT = (p->n + L->BQ - 1) / L->BQ + L->NC;
     L->NQP = L->NT * L->BQ;
     L->NKP = ((p->n + KT - 1) / KT + L->NC) * KT;

@@ -8,7 +8,7 @@
 //   Kc [B*Hkv][NKP][D]            keys, row-major: a key tile is one contiguous block
 //   Vt [B*Hkv][NKP/KT][D][KT]     values, transposed per key tile (KT = 64 keys), the 16 keys of
 //                                 every 16-key group stored in MFMA k-slot order
-// One work-group = 4 wavefronts = one query tile of BQ=128 rows of one class;
+// One work-group = MFMA_WAVES wavefronts = one query tile of 32*MFMA_WAVES rows of one class;
 // each wavefront owns 32 query rows.  The scores are computed transposed,
 // S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q rows held
 // in registers), so that one lane holds 16 scores of ONE query row per 32-key
@@ -166,8 +166,8 @@ __device__ inline void pin_operands(bf16x8 (&a)[4])
     asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
 }
 
-template <int D, bool SOFTCAP, bool PAIRS>
-__global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm, int default_map,
+template <int D, int MFMA_WAVES, bool SOFTCAP, bool PAIRS>
+__global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_kernel(Layout L, HeadMap hm, int default_map,
                                                              const uint16_t* __restrict__ q,
                                                              const char* __restrict__ ws, uint16_t* __restrict__ out,
                                                              float* __restrict__ lse, int32_t* __restrict__ row_pairs)
@@ -177,7 +177,8 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     constexpr int DB = D / 32;          // 32-row blocks of O^T
     constexpr int NPV = DB * 2;         // MFMAs of one PV unit
     constexpr int TILE_BYTES = KT * D * 2;      // bytes of a K tile and of a V^T tile
-    constexpr int NW = TILE_BYTES / 1024 / 4;   // 1-KB wave loads per wavefront and tile
+    constexpr int NW = TILE_BYTES / 1024 / MFMA_WAVES;   // 1-KB wave loads per wavefront and tile
+    constexpr int ATHR = 64 * MFMA_WAVES;                // threads of the work-group
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -243,7 +244,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
         const int r128 = wave * 8 + lane / 8;                         // 128-byte rows
         const unsigned off128 = (unsigned)((r128 * 8 + ((lane % 8) ^ ((wave & 1) * 4 + lane / 16))) * 16);
         const int r256 = wave * 4 + lane / 16;                        // 256-byte rows
-        const unsigned off256 = (unsigned)((r256 * 16 + ((lane % 16) ^ r256)) * 16);
+        const unsigned off256 = (unsigned)((r256 * 16 + ((lane % 16) ^ (r256 & 15))) * 16);
         voff_k = (D == 128) ? off256 : off128;
         voff_v = off128;
     }
@@ -254,13 +255,13 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     do {                                                                                             \
         const char* src_ = kc_base + (size_t)(TILE) * TILE_BYTES;                                    \
         _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
-            dma16(src_ + i * 4096, voff_k, lds_k0 + (STAGE) * TILE_BYTES + (wave + 4 * i) * 1024);   \
+            dma16(src_ + i * (1024 * MFMA_WAVES), voff_k, lds_k0 + (STAGE) * TILE_BYTES + (wave + MFMA_WAVES * i) * 1024); \
     } while (0)
 #define F4_DMA_V(TILE, STAGE)                                                                        \
     do {                                                                                             \
         const char* src_ = vt_base + (size_t)(TILE) * TILE_BYTES;                                    \
         _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
-            dma16(src_ + i * 4096, voff_v, lds_v0 + (STAGE) * TILE_BYTES + (wave + 4 * i) * 1024);   \
+            dma16(src_ + i * (1024 * MFMA_WAVES), voff_v, lds_v0 + (STAGE) * TILE_BYTES + (wave + MFMA_WAVES * i) * 1024); \
     } while (0)
 #define F4_DMA_KPOS(TILE, BUF)                                                                       \
     do {                                                                                             \
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
         F4_DMA_KPOS(t0, 0);
         F4_DMA_KPOS(t1, 1);
         const u32x4 z4 = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < TILE_BYTES / 16; i += NTHR) *(u32x4*)(S.vt[1] + i * 16) = z4;
+        for (int i = tid; i < TILE_BYTES / 16; i += ATHR) *(u32x4*)(S.vt[1] + i * 16) = z4;
         F4_WAIT_DMA();
     }
     __syncthreads();
@@ -505,14 +506,27 @@ __global__ __launch_bounds__(NTHR, 2) void attn_mfma_kernel(Layout L, HeadMap hm
     }
 }
 
-template <int D, bool SOFTCAP, bool PAIRS>
+template <int D, int WAVES, bool SOFTCAP, bool PAIRS>
 hipError_t launch_one(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
                       float* lse, int32_t* row_pairs, hipStream_t st)
 {
     const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
-    hipLaunchKernelGGL((attn_mfma_kernel<D, SOFTCAP, PAIRS>), dim3(grid), dim3(NTHR), 0, st, L, hm, default_map,
-                       (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, WAVES, SOFTCAP, PAIRS>), dim3(grid), dim3(64 * WAVES), 0, st, L, hm,
+                       default_map, (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
     return hipGetLastError();
+}
+
+template <int D, int WAVES>
+hipError_t launch_w(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
+                    float* lse, int32_t* row_pairs, hipStream_t st)
+{
+    const bool sc = L.softcap > 0.f, pairs = row_pairs != nullptr;
+    if (sc) {
+        return pairs ? launch_one<D, WAVES, true, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                     : launch_one<D, WAVES, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    }
+    return pairs ? launch_one<D, WAVES, false, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                 : launch_one<D, WAVES, false, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
 }
 
 template <int D>
@@ -521,13 +535,9 @@ hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const v
 {
     dim3 ggrid(L.NKP / KT, L.B * L.Hkv);
     hipLaunchKernelGGL(gather_vt_kernel<D>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)v, ws);
-    const bool sc = L.softcap > 0.f, pairs = row_pairs != nullptr;
-    if (sc) {
-        return pairs ? launch_one<D, true, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-                     : launch_one<D, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
-    }
-    return pairs ? launch_one<D, false, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-                 : launch_one<D, false, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    // the query tile size fixed by focus_assign selects the work-group shape: 4 or 8 wavefronts
+    if (L.BQ == 256) return launch_w<D, 8>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    return launch_w<D, 4>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
 }
 
 }  // namespace

@@ -9,7 +9,7 @@ namespace focus {
 
 constexpr int SB = 256;        // positions per sort block (one work-group of the bucketing kernels)
 constexpr int BQ_VECTOR = 128; // query rows the fp32 vector kernel handles per pass (and its tile size)
-constexpr int MFMA_QB = 1;     // 32-row query blocks per wavefront of the MFMA kernel: its tile has 4*32*MFMA_QB rows
+constexpr int LONG_N = 1 << 18; // from this sequence length on the MFMA kernel uses 8-wavefront work-groups (256-row tiles)
 constexpr int KT = 64;         // keys per attention tile; class segments of the permuted keys are padded to this
 constexpr int MAX_CLASSES = 256;
 constexpr int MAX_HQ = 256;
@@ -26,7 +26,7 @@ struct Layout {
     int K, topk, window;
     int dtype;                 // 0 fp32, 1 bf16
     int elem;                  // bytes per element
-    int BQ;                    // query rows per attention tile (128 for fp32, 128*MFMA_QB for bf16)
+    int BQ;                    // query rows per attention tile (128; 256 for bf16 at n >= LONG_N)
     int NC;                    // number of membership classes (1 in dense mode)
     int dense;                 // every causal pair allowed: one class, no masks beyond causal
     int nblk;                  // ceil(n / SB)

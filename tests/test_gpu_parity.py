@@ -201,3 +201,19 @@ def test_cfg5_full_sampled_rows_and_group_pair_counts():
             qo += int(qc[g])
             kofs += int(kc[g])
     say("cfg5 allowed fraction", float(allowed.sum()) / (wl.Hq * (wl.n * (wl.n + 1) // 2)))
+
+
+def test_long_sequence_uses_256_row_tiles():
+    # n >= 2^18 switches the bf16 kernel to 8-wavefront work-groups (256-row query tiles); the vector
+    # kernel then walks each tile in two passes.  Ragged n so the last tiles are partial.
+    wl = small("long_n", n=262144 + 77, Hq=2, Hkv=1, d=64, dtype="bf16", K=4, topk=2, window=2048)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    rows = workloads.sample_rows(wl, 256)
+    say("long_n", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    harness.check_pair_totals(wl, res, mq, mk)
+    vec = harness.run_gpu(wl, inp, vector=True)
+    assert torch.equal(res["row_pairs"], vec["row_pairs"])
+    diff = (res["out"].float() - vec["out"].float()).abs()
+    assert diff.max().item() <= 2e-2 and diff.mean().item() <= 2e-3
