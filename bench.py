@@ -158,6 +158,35 @@ def main():
         result["speedup_vs_dense_step"] = ms_step_d / ms_step
         del wsd
 
+    # context: the GPT-2 124M shape (short sequences), same step, reported beside the headline workload
+    if wl.name == "cfg3" and not args.no_dense:
+        w2 = workloads.CONFIGS["cfg2"]
+        i2 = workloads.make_inputs(w2, "cuda")
+        p2 = focus.make_params(w2.B, w2.Hq, w2.Hkv, w2.n, w2.d, w2.K, w2.topk, w2.window, causal=True,
+                               dtype=w2.dtype, softcap=w2.softcap)
+        ws2 = focus.alloc_workspace(p2)
+        o2 = torch.empty_like(i2["q"])
+        rp2 = torch.empty((w2.B, w2.Hq, w2.n), dtype=torch.int32, device="cuda")
+        focus.focus_assign(p2, i2["q"], i2["k"], i2["centroids"], ws2)
+        focus.focus_attn_fwd(p2, i2["q"], i2["k"], i2["v"], ws2, o2, None, rp2)
+        torch.cuda.synchronize()
+        allowed2 = int(rp2.to(torch.int64).sum().item())
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        n2 = 20
+        ev[0].record()
+        for _ in range(n2):
+            focus.focus_assign(p2, i2["q"], i2["k"], i2["centroids"], ws2)
+            focus.focus_attn_fwd(p2, i2["q"], i2["k"], i2["v"], ws2, o2, None, None)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms2 = ev[0].elapsed_time(ev[1]) / n2
+        result["other_workloads"] = {"cfg2": {
+            "workload": "cfg2: B=8 H=12 n=4096 d=64 K=4 topk=2 window=256 bf16 (4-cluster mixture)",
+            "ms_per_step": ms2, "tokens_per_s": w2.B * w2.n / (ms2 * 1e-3),
+            "useful_tflops_step": 4.0 * w2.d * allowed2 / (ms2 * 1e-3) / 1e12,
+            "allowed_fraction": allowed2 / (w2.B * w2.Hq * (w2.n * (w2.n + 1) // 2))}}
+        del i2, ws2, o2, rp2
+
     if not args.no_cpu_baseline:
         from oracle import focus_oracle as fo
         pb = fo.Problem(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.K, wl.topk, wl.window, causal=True,
