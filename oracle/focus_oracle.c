@@ -367,3 +367,111 @@ int focus_oracle_num_threads(void)
 #endif
     return nt;
 }
+
+/* ------------------------------------------------------------------ router
+ * The paper's router (Sec. 2, Eq. 1 and the Sinkhorn recipe below it): one soft
+ * assignment per token of a layer, shared by every head and by the query and
+ * key roles:
+ *     z_i = W_g^T h_i            (h_i: hidden state, dm values; W_g: dm x dg)
+ *     S[i,g] = z_i . C[g]        (C: K x dg centroids)
+ *     no normalisation (iters = 0):   g_i = S[i,:] / tau
+ *     Sinkhorn (iters = N > 0):       Q = exp(S / tau); N times { every column divided by its
+ *                                     sum over the tokens of the sequence, then every row divided
+ *                                     by its sum over the groups };  g_i = Q[i,:]
+ * Inference keeps the topk largest entries of g_i (Sec. 2 "Efficiency at inference").
+ *
+ * Readings (restated in the design notes): fp64 throughout; the projection adds
+ * products in chunks of 64 consecutive hidden components, in index order inside a
+ * chunk and chunk by chunk after that; S adds over the dg components in index
+ * order; before the exponential the largest score of the sequence is subtracted
+ * (the first column step divides any common factor out again, so the recipe is
+ * unchanged, and exp cannot overflow); Sinkhorn runs per batch element over its
+ * n tokens; ties in the top-k go to the smaller group index.
+ *
+ * hidden [B,n,dm] in dtype (0 fp32, 1 bf16 bits); wg [dm,dg] fp32; cent [K,dg] fp32.
+ * z_out [B,n,dg], g_out [B,n,K] nullable fp64; masks [B,n] (bit g = member).
+ */
+int focus_oracle_route(int32_t B, int32_t n, int32_t dm, int32_t dg, int32_t K, int32_t topk,
+                       int32_t dtype, const void *hidden, const float *wg, const float *cent,
+                       double tau, int32_t iters, double *z_out, double *g_out, uint32_t *masks)
+{
+    if (B < 1 || n < 1 || dm < 1 || dg < 1 || K < 1 || K > 32 || topk < 1 || topk > K) return -1;
+    if (!(tau > 0.0) || iters < 0 || !hidden || !wg || !cent || !masks) return -1;
+    if (dtype != 0 && dtype != 1) return -1;
+    double *Q = (double *)malloc(sizeof(double) * (size_t)n * K);
+    if (!Q) return -2;
+    for (int b = 0; b < B; ++b) {
+        /* projection and scores */
+#pragma omp parallel for schedule(static)
+        for (int i = 0; i < n; ++i) {
+            double z[256];
+            const int64_t row = ((int64_t)b * n + i) * dm;
+            for (int j = 0; j < dg && j < 256; ++j) {
+                double acc = 0.0;
+                for (int c0 = 0; c0 < dm; c0 += 64) {
+                    double part = 0.0;
+                    int c1 = c0 + 64 < dm ? c0 + 64 : dm;
+                    for (int t = c0; t < c1; ++t) part += widen(hidden, dtype, row + t) * (double)wg[(int64_t)t * dg + j];
+                    acc += part;
+                }
+                z[j] = acc;
+                if (z_out) z_out[((int64_t)b * n + i) * dg + j] = acc;
+            }
+            for (int g = 0; g < K; ++g) {
+                double s = 0.0;
+                for (int j = 0; j < dg; ++j) s += z[j] * (double)cent[(int64_t)g * dg + j];
+                Q[(int64_t)i * K + g] = s;
+            }
+        }
+        if (iters == 0) {
+            for (int64_t e = 0; e < (int64_t)n * K; ++e) Q[e] = Q[e] / tau;
+        } else {
+            double smax = Q[0];
+            for (int64_t e = 1; e < (int64_t)n * K; ++e) if (Q[e] > smax) smax = Q[e];
+            for (int64_t e = 0; e < (int64_t)n * K; ++e) Q[e] = exp((Q[e] - smax) / tau);
+            for (int it = 0; it < iters; ++it) {
+                for (int g = 0; g < K; ++g) {            /* columns: sum over the tokens */
+                    double cs = 0.0;
+                    for (int i = 0; i < n; ++i) cs += Q[(int64_t)i * K + g];
+                    for (int i = 0; i < n; ++i) Q[(int64_t)i * K + g] /= cs;
+                }
+                for (int i = 0; i < n; ++i) {            /* rows: sum over the groups */
+                    double rs = 0.0;
+                    for (int g = 0; g < K; ++g) rs += Q[(int64_t)i * K + g];
+                    for (int g = 0; g < K; ++g) Q[(int64_t)i * K + g] /= rs;
+                }
+            }
+        }
+        for (int i = 0; i < n; ++i) {
+            const double *s = Q + (int64_t)i * K;
+            uint32_t m = 0;
+            for (int g = 0; g < K; ++g) {
+                int beaten_by = 0;
+                for (int o = 0; o < K; ++o) {
+                    if (o == g) continue;
+                    if (s[o] > s[g] || (s[o] == s[g] && o < g)) ++beaten_by;
+                }
+                if (beaten_by < topk) m |= (1u << g);
+            }
+            masks[(int64_t)b * n + i] = m;
+            if (g_out) for (int g = 0; g < K; ++g) g_out[((int64_t)b * n + i) * K + g] = s[g];
+        }
+    }
+    free(Q);
+    return 0;
+}
+
+/* Attention rows when membership is one mask per TOKEN (the paper's per-layer
+ * assignment): the same mask serves every query head and every KV head. */
+int focus_oracle_broadcast_masks(const oracle_params *p, const uint32_t *token_masks,
+                                 uint32_t *mq, uint32_t *mk)
+{
+    if (check_params(p) || !token_masks || !mq || !mk) return -1;
+    for (int b = 0; b < p->B; ++b) {
+        for (int h = 0; h < p->Hq; ++h)
+            memcpy(mq + ((int64_t)b * p->Hq + h) * p->n, token_masks + (int64_t)b * p->n, sizeof(uint32_t) * (size_t)p->n);
+        for (int h = 0; h < p->Hkv; ++h)
+            memcpy(mk + ((int64_t)b * p->Hkv + h) * p->n, token_masks + (int64_t)b * p->n, sizeof(uint32_t) * (size_t)p->n);
+    }
+    return 0;
+}

@@ -174,3 +174,42 @@ def pair_counts(pb, mq, mk):
     _rc(_load().focus_oracle_pair_counts(ctypes.byref(p), _ptr(mq), _ptr(mk), _ptr(allowed), _ptr(gp)),
         "pair_counts")
     return allowed, gp
+
+
+def route(hidden, wg, cent, topk, tau=0.1, iters=10, dtype="f32", want_soft=False):
+    """The paper's router (Sec. 2 Eq. 1 + Sinkhorn).  hidden [B,n,dm] (float32, or uint16 bf16 bits),
+    wg [dm,dg] f32, cent [K,dg] f32.  Returns masks [B,n] u32 (and z [B,n,dg], g [B,n,K] f64)."""
+    lib = _load()
+    lib.focus_oracle_route.restype = ctypes.c_int
+    want = np.float32 if dtype == "f32" else np.uint16
+    hidden = np.ascontiguousarray(hidden)
+    assert hidden.dtype == want and hidden.ndim == 3
+    B, n, dm = hidden.shape
+    wg = np.ascontiguousarray(wg, dtype=np.float32)
+    cent = np.ascontiguousarray(cent, dtype=np.float32)
+    dg, K = wg.shape[1], cent.shape[0]
+    assert wg.shape == (dm, dg) and cent.shape == (K, dg) and dg <= 256
+    masks = np.empty((B, n), dtype=np.uint32)
+    z = np.empty((B, n, dg), dtype=np.float64) if want_soft else None
+    g = np.empty((B, n, K), dtype=np.float64) if want_soft else None
+    _rc(lib.focus_oracle_route(ctypes.c_int32(B), ctypes.c_int32(n), ctypes.c_int32(dm), ctypes.c_int32(dg),
+                               ctypes.c_int32(K), ctypes.c_int32(topk),
+                               ctypes.c_int32({"f32": 0, "bf16": 1}[dtype]), _ptr(hidden), _ptr(wg), _ptr(cent),
+                               ctypes.c_double(tau), ctypes.c_int32(iters), _ptr(z), _ptr(g), _ptr(masks)),
+        "route")
+    if want_soft:
+        return masks, z, g
+    return masks
+
+
+def broadcast_masks(pb, token_masks):
+    """One mask per token -> (mq [B,Hq,n], mk [B,Hkv,n])."""
+    lib = _load()
+    lib.focus_oracle_broadcast_masks.restype = ctypes.c_int
+    tm = np.ascontiguousarray(token_masks, dtype=np.uint32)
+    assert tm.shape == (pb.B, pb.n)
+    mq = np.empty((pb.B, pb.Hq, pb.n), dtype=np.uint32)
+    mk = np.empty((pb.B, pb.Hkv, pb.n), dtype=np.uint32)
+    p = pb._c()
+    _rc(lib.focus_oracle_broadcast_masks(ctypes.byref(p), _ptr(tm), _ptr(mq), _ptr(mk)), "broadcast_masks")
+    return mq, mk
