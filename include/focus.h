@@ -87,6 +87,50 @@ focus_status focus_attn_fwd(const focus_params *p, const void *q, const void *k,
                             const void *v, void *workspace, size_t workspace_bytes,
                             void *out, float *lse, int32_t *row_pairs, void *stream);
 
+/* ---- the per-layer router in front of the attention (Sec. 2 Eq. 1 and the Sinkhorn recipe) ----
+ *
+ * The paper routes once per layer: a token's hidden state h_i is projected by W_g (d_model x d_g),
+ * scored against K centroids of width d_g, optionally Sinkhorn-normalised over the sequence, and its
+ * topk best groups are its membership for every head, as a query and as a key. */
+typedef struct {
+    int32_t B, n;              /* hidden is [B,n,d_model]                              */
+    int32_t d_model;           /* multiple of 8                                        */
+    int32_t d_g;               /* router width: 4, 8, 16, 32 or 64                     */
+    int32_t K, topk;           /* 1 <= topk <= K <= 32                                 */
+    int32_t dtype;             /* focus_dtype of hidden                                */
+    int32_t sinkhorn_iters;    /* N >= 0; 0 = no normalisation (scores / tau)          */
+    double tau;                /* temperature > 0                                      */
+} focus_route_params;
+
+/* Bytes of workspace focus_route needs.  Pure host code. */
+focus_status focus_route_workspace_size(const focus_route_params *rp, size_t *bytes);
+
+/* z_i = W_g^T h_i, S[i,g] = z_i . C[g] (Sec. 2 Eq. 1), all in fp64: the products of the
+ * projection are added in chunks of 64 consecutive hidden components (index order inside a
+ * chunk, chunk sums in chunk order), S over the d_g components in index order.
+ * sinkhorn_iters = 0: g_i = S[i,:] / tau.  Otherwise Q = exp((S - max S of the sequence) / tau),
+ * then N rounds per batch element of {every column divided by its sum over the n tokens, every
+ * row divided by its sum over the K groups} (evaluated as diagonal scalings of Q), g_i = Q[i,:].
+ * token_masks [B,n] uint32 receives the topk largest entries of g_i as bits (ties to the smaller
+ * group index); soft (nullable) [B,n,K] fp64 receives g itself.
+ * hidden, w_g [d_model,d_g] fp32, centroids [K,d_g] fp32, route_workspace (256-byte aligned),
+ * token_masks and soft are DEVICE pointers; rp is a HOST pointer.  Only enqueues on `stream`.
+ * Scores so far apart that a whole row or column of Q underflows give NaN rows, as the
+ * recipe itself does. */
+focus_status focus_route(const focus_route_params *rp, const void *hidden, const float *w_g,
+                         const float *centroids, void *route_workspace, size_t workspace_bytes,
+                         uint32_t *token_masks, double *soft, void *stream);
+
+/* focus_assign for memberships given per token (the router's output): token_masks [B,n]
+ * uint32 DEVICE, each a topk-subset of the K groups, shared by all query and KV heads of
+ * the token.  Fills the workspace exactly as focus_assign does (masks, counts, lists,
+ * schedule), so focus_attn_fwd follows unchanged.  A mask with another popcount or with
+ * bits at or above K is replaced by the first topk groups; invalid_count (nullable, DEVICE
+ * int32) receives how many were replaced. */
+focus_status focus_assign_tokens(const focus_params *p, const uint32_t *token_masks, const void *k,
+                                 void *workspace, size_t workspace_bytes, int32_t *invalid_count,
+                                 void *stream);
+
 /* Device pointers INTO the workspace for parity checks; valid until the
  * workspace is overwritten.  Any output pointer may be NULL.
  *   mq [B,Hq,n], mk [B,Hkv,n]                   uint32 membership masks

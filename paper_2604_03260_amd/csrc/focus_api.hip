@@ -3,6 +3,7 @@
 #include "../../include/focus.h"
 #include "focus_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -138,6 +139,43 @@ focus_status check_ws(const focus::Layout& L, const void* ws, size_t bytes)
 
 bool misaligned16(const void* p) { return ((uintptr_t)p & 15) != 0; }
 
+// Validates the router params and derives its workspace layout.
+focus_status make_route_layout(const focus_route_params* rp, focus::RouteLayout* R)
+{
+    if (!rp) return fail(FOCUS_EINVAL, "route params is NULL");
+    if (rp->B < 1 || rp->n < 1) return fail(FOCUS_EINVAL, "B and n must be >= 1 (got %d %d)", rp->B, rp->n);
+    if (rp->d_model < 1) return fail(FOCUS_EINVAL, "d_model must be >= 1");
+    if (rp->d_g < 1) return fail(FOCUS_EINVAL, "d_g must be >= 1");
+    if (rp->K < 1 || rp->K > 32) return fail(FOCUS_EINVAL, "K must be in [1,32] (got %d)", rp->K);
+    if (rp->topk < 1 || rp->topk > rp->K)
+        return fail(FOCUS_EINVAL, "topk must be in [1,K] (got %d, K=%d)", rp->topk, rp->K);
+    if (rp->dtype != FOCUS_F32 && rp->dtype != FOCUS_BF16) return fail(FOCUS_EINVAL, "unknown dtype %d", rp->dtype);
+    if (rp->sinkhorn_iters < 0) return fail(FOCUS_EINVAL, "sinkhorn_iters must be >= 0");
+    if (!(rp->tau > 0.0) || !std::isfinite(rp->tau)) return fail(FOCUS_EINVAL, "tau must be finite and > 0");
+    if (rp->d_model % 8 != 0) return fail(FOCUS_EUNSUPPORTED, "d_model %d is not a multiple of 8", rp->d_model);
+    if (rp->d_g != 4 && rp->d_g != 8 && rp->d_g != 16 && rp->d_g != 32 && rp->d_g != 64)
+        return fail(FOCUS_EUNSUPPORTED, "d_g %d is not built (4, 8, 16, 32 or 64)", rp->d_g);
+    if (rp->n > (1 << 24)) return fail(FOCUS_EUNSUPPORTED, "n above 2^24 is not built");
+    if (rp->B > 65535) return fail(FOCUS_EUNSUPPORTED, "B above 65535 is not built");
+    if (rp->sinkhorn_iters > 1000) return fail(FOCUS_EUNSUPPORTED, "more than 1000 Sinkhorn rounds is not built");
+    memset(R, 0, sizeof(*R));
+    R->B = rp->B; R->n = rp->n; R->dm = rp->d_model; R->dg = rp->d_g; R->K = rp->K; R->topk = rp->topk;
+    R->dtype = rp->dtype; R->iters = rp->sinkhorn_iters; R->tau = rp->tau;
+    R->nproj = (rp->n + 63) / 64;
+    R->nsink = std::min(256, (rp->n + 255) / 256);
+    R->sink_tokens = (rp->n + R->nsink - 1) / R->nsink;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    R->off_w64 = take((size_t)rp->d_model * rp->d_g * 8);
+    R->off_c64 = take((size_t)rp->K * rp->d_g * 8);
+    R->off_S = take((size_t)rp->B * rp->n * rp->K * 8);
+    R->off_maxpart = take((size_t)rp->B * R->nproj * 8);
+    R->off_smax = take((size_t)rp->B * 8);
+    R->off_colpart = take((size_t)2 * rp->B * R->nsink * 32 * 8);
+    R->total = off;
+    return FOCUS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -210,6 +248,52 @@ focus_status focus_attn_fwd_vector(const focus_params* p, const void* q, const v
     hipError_t e = focus::launch_attn_simple(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs,
                                              (hipStream_t)stream);
     if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_fwd_vector: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+focus_status focus_route_workspace_size(const focus_route_params* rp, size_t* bytes)
+{
+    if (!bytes) return fail(FOCUS_EINVAL, "bytes is NULL");
+    focus::RouteLayout R;
+    focus_status st = make_route_layout(rp, &R);
+    if (st != FOCUS_OK) return st;
+    *bytes = R.total;
+    return FOCUS_OK;
+}
+
+focus_status focus_route(const focus_route_params* rp, const void* hidden, const float* w_g, const float* centroids,
+                         void* route_workspace, size_t workspace_bytes, uint32_t* token_masks, double* soft,
+                         void* stream)
+{
+    focus::RouteLayout R;
+    focus_status st = make_route_layout(rp, &R);
+    if (st != FOCUS_OK) return st;
+    if (!hidden || !w_g || !centroids || !token_masks)
+        return fail(FOCUS_EINVAL, "hidden, w_g, centroids and token_masks must not be NULL");
+    if (misaligned16(hidden)) return fail(FOCUS_EINVAL, "hidden must be 16-byte aligned");
+    if (!route_workspace) return fail(FOCUS_EINVAL, "route workspace is NULL");
+    if (((uintptr_t)route_workspace & 255) != 0) return fail(FOCUS_EWORKSPACE, "route workspace is not 256-byte aligned");
+    if (workspace_bytes < R.total)
+        return fail(FOCUS_EWORKSPACE, "route workspace has %zu bytes, %zu needed", workspace_bytes, R.total);
+    hipError_t e = focus::launch_route(R, hidden, w_g, centroids, (char*)route_workspace, token_masks, soft,
+                                       (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_route: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+focus_status focus_assign_tokens(const focus_params* p, const uint32_t* token_masks, const void* k, void* workspace,
+                                 size_t workspace_bytes, int32_t* invalid_count, void* stream)
+{
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = make_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (!token_masks || !k) return fail(FOCUS_EINVAL, "token_masks and k must not be NULL");
+    if (misaligned16(k)) return fail(FOCUS_EINVAL, "k must be 16-byte aligned");
+    st = check_ws(L, workspace, workspace_bytes);
+    if (st != FOCUS_OK) return st;
+    hipError_t e = focus::launch_assign_tokens(L, token_masks, k, (char*)workspace, invalid_count, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_assign_tokens: %s", hipGetErrorString(e));
     return FOCUS_OK;
 }
 

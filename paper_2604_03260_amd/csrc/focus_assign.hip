@@ -387,6 +387,62 @@ __global__ __launch_bounds__(SB) void scatter_kernel(Layout L, int is_query, cha
     }
 }
 
+// ---------------------------------------------------------------- membership given per token
+// The paper's router assigns one membership per token of a layer, shared by all heads and by the
+// query and key roles (Sec. 2).  One work-group per (sort block, batch element) turns the token
+// masks into class ids and histograms once and writes them for every query and KV head, in the
+// same places score_topk fills.  A mask that is not a topk-subset of the K groups would index
+// outside the class tables: it is replaced by the first topk groups and counted.
+__global__ __launch_bounds__(SB) void token_classes_kernel(Layout L, const uint32_t* __restrict__ token_masks,
+                                                           char* __restrict__ ws, int32_t* __restrict__ invalid_count)
+{
+    __shared__ int s_hist_c[MAX_CLASSES];
+    __shared__ int s_hist_g[32];
+    const int tid = threadIdx.x;
+    const int blk = blockIdx.x, b = blockIdx.y;
+    const int n = L.n, K = L.K;
+    const int pos = blk * SB + tid;
+    for (int e = tid; e < MAX_CLASSES; e += SB) s_hist_c[e] = 0;
+    if (tid < 32) s_hist_g[tid] = 0;
+    __syncthreads();
+    uint32_t mask = 0;
+    int cls = 0;
+    if (pos < n) {
+        mask = token_masks[(size_t)b * n + pos];
+        const uint32_t allowed = (K == 32) ? 0xffffffffu : ((1u << K) - 1u);
+        if ((mask & ~allowed) != 0u || __popc(mask) != L.topk) {
+            mask = (L.topk == 32) ? 0xffffffffu : ((1u << L.topk) - 1u);
+            if (invalid_count) atomicAdd(invalid_count, 1);
+        }
+        if (!L.dense) {
+            int j = 0;
+            for (int g = 0; g < K; ++g)
+                if ((mask >> g) & 1u) { ++j; cls += (int)g_binom.v[g * 33 + j]; }
+        }
+        atomicAdd(&s_hist_c[cls], 1);
+        for (int g = 0; g < K; ++g)
+            if ((mask >> g) & 1u) atomicAdd(&s_hist_g[g], 1);
+    }
+    __syncthreads();
+    for (int is_query = 1; is_query >= 0; --is_query) {
+        const int H = is_query ? L.Hq : L.Hkv;
+        uint32_t* masks = (uint32_t*)(ws + (is_query ? L.off_mq : L.off_mk));
+        uint8_t* clsarr = (uint8_t*)(ws + (is_query ? L.off_qcls : L.off_kcls));
+        const size_t cls_stride = is_query ? (size_t)n : (size_t)L.nblk * SB;
+        for (int h = 0; h < H; ++h) {
+            const size_t bh = (size_t)b * H + h;
+            if (pos < n) {
+                masks[bh * n + pos] = mask;
+                clsarr[bh * cls_stride + pos] = (uint8_t)cls;
+            }
+            int* bc = (int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + (bh * (L.nblk + 1) + blk) * L.NC;
+            int* bg = (int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + (bh * (L.nblk + 1) + blk) * K;
+            for (int c = tid; c < L.NC; c += SB) bc[c] = s_hist_c[c];
+            if (tid < K) bg[tid] = s_hist_g[tid];
+        }
+    }
+}
+
 template <typename T>
 hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, int is_query, char* ws, hipStream_t st)
 {
@@ -405,17 +461,39 @@ hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, int i
 
 }  // namespace
 
+namespace {
+
+// pads of the class-ordered position arrays
+void launch_pad_fills(const Layout& L, char* ws, hipStream_t st)
+{
+    const size_t nq = (size_t)L.B * L.Hq * L.NQP, nk = (size_t)L.B * L.Hkv * L.NKP;
+    const int gq = (int)min((size_t)8192, (nq + 255) / 256), gk = (int)min((size_t)8192, (nk + 255) / 256);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(gq), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, -1);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kpos), nk, KPOS_PAD);
+}
+
+// from masks, class ids and block histograms to the class-ordered arrays, group lists and job lists
+hipError_t launch_bucketing(const Layout& L, const void* k, char* ws, hipStream_t st)
+{
+    for (int is_query = 1; is_query >= 0; --is_query) {
+        const int H = is_query ? L.Hq : L.Hkv;
+        hipLaunchKernelGGL(scan_blocks_kernel, dim3(L.NC + L.K, L.B * H), dim3(256), 0, st, L, is_query, ws);
+        hipLaunchKernelGGL(plan_heads_kernel, dim3(L.B * H), dim3(256), 0, st, L, is_query, ws);
+        hipLaunchKernelGGL(scatter_kernel, dim3(L.nblk, L.B * H), dim3(SB), 0, st, L, is_query, ws);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (L.dtype == 1) return launch_gather_k(L, k, ws, st);   // class-ordered key copy for the MFMA kernel
+    return hipSuccess;
+}
+
+}  // namespace
+
 hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                          const float* centroids, char* ws, hipStream_t st)
 {
     hipError_t e;
-    // pads of the class-ordered position arrays
-    {
-        const size_t nq = (size_t)L.B * L.Hq * L.NQP, nk = (size_t)L.B * L.Hkv * L.NKP;
-        const int gq = (int)min((size_t)8192, (nq + 255) / 256), gk = (int)min((size_t)8192, (nk + 255) / 256);
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(gq), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, -1);
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kpos), nk, KPOS_PAD);
-    }
+    launch_pad_fills(L, ws, st);
     {
         const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
         hipLaunchKernelGGL(cent_to_f64_kernel, dim3(64), dim3(256), 0, st, centroids, (double*)(ws + L.off_cent64),
@@ -428,15 +506,18 @@ hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, cons
         if ((e = launch_score<uint16_t>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
         if ((e = launch_score<uint16_t>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
     }
-    for (int is_query = 1; is_query >= 0; --is_query) {
-        const int H = is_query ? L.Hq : L.Hkv;
-        hipLaunchKernelGGL(scan_blocks_kernel, dim3(L.NC + L.K, L.B * H), dim3(256), 0, st, L, is_query, ws);
-        hipLaunchKernelGGL(plan_heads_kernel, dim3(L.B * H), dim3(256), 0, st, L, is_query, ws);
-        hipLaunchKernelGGL(scatter_kernel, dim3(L.nblk, L.B * H), dim3(SB), 0, st, L, is_query, ws);
-    }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (L.dtype == 1) return launch_gather_k(L, k, ws, st);   // class-ordered key copy for the MFMA kernel
-    return hipSuccess;
+    return launch_bucketing(L, k, ws, st);
+}
+
+hipError_t launch_assign_tokens(const Layout& L, const uint32_t* token_masks, const void* k, char* ws,
+                                int32_t* invalid_count, hipStream_t st)
+{
+    launch_pad_fills(L, ws, st);
+    if (invalid_count) hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, st, invalid_count, (size_t)1, 0);
+    hipLaunchKernelGGL(token_classes_kernel, dim3(L.nblk, L.B), dim3(SB), 0, st, L, token_masks, ws, invalid_count);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_bucketing(L, k, ws, st);
 }
 
 }  // namespace focus

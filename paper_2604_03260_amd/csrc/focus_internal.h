@@ -65,6 +65,28 @@ __host__ __device__ inline uint32_t binom_u32(int a, int b)
     return (uint32_t)r;
 }
 
+// Shapes and workspace offsets of the router (focus_route).
+struct RouteLayout {
+    int B, n, dm, dg, K, topk;
+    int dtype;                 // of the hidden states: 0 fp32, 1 bf16
+    int iters;                 // Sinkhorn rounds, 0 = none
+    double tau;
+    int nproj;                 // work-groups of the projection per sequence = ceil(n / 64)
+    int nsink;                 // work-groups of a Sinkhorn pass per sequence (<= 256)
+    int sink_tokens;           // tokens per Sinkhorn work-group
+    size_t off_w64;            // W_g as fp64 [dm][dg]
+    size_t off_c64;            // C as fp64 [K][dg]
+    size_t off_S;              // [B][n][K] fp64: scores, then exp((S - max)/tau) in place
+    size_t off_maxpart;        // [B][nproj] fp64
+    size_t off_smax;           // [B] fp64
+    size_t off_colpart;        // [2][B][nsink][KP] fp64 column partial sums, ping-pong between passes
+    size_t total;
+};
+
+hipError_t launch_route(const RouteLayout& R, const void* hidden, const float* wg, const float* cent, char* ws,
+                        uint32_t* masks, double* soft, hipStream_t st);
+hipError_t launch_assign_tokens(const Layout& L, const uint32_t* token_masks, const void* k, char* ws,
+                                int32_t* invalid_count, hipStream_t st);
 hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                          const float* centroids, char* ws, hipStream_t st);
 hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t st);

@@ -1,8 +1,8 @@
 """Thin ctypes binding of libfocus.so: argument marshalling only.
 
 The functions mirror include/focus.h one to one (focus_workspace_size,
-focus_assign, focus_attn_fwd, focus_workspace_views, focus_last_error,
-focus_version).  Tensors are torch CUDA tensors used purely as device buffers;
+focus_assign, focus_attn_fwd, focus_workspace_views, focus_route_workspace_size,
+focus_route, focus_assign_tokens, focus_last_error, focus_version).  Tensors are torch CUDA tensors used purely as device buffers;
 the calls are enqueued on torch's current stream.  There is no CPU fallback: a
 missing library is an error.
 """
@@ -18,7 +18,16 @@ FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_EHIP = 0, -1
 FOCUS_F32, FOCUS_BF16 = 0, 1
 
 EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_workspace_views",
+           "focus_route_workspace_size", "focus_route", "focus_assign_tokens",
            "focus_last_error", "focus_version")
+
+
+class FocusRouteParams(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("n", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_g", ctypes.c_int32),
+        ("K", ctypes.c_int32), ("topk", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("sinkhorn_iters", ctypes.c_int32), ("tau", ctypes.c_double),
+    ]
 
 
 class FocusParams(ctypes.Structure):
@@ -62,6 +71,13 @@ def load_library():
     lib.focus_attn_fwd_vector.restype = ctypes.c_int
     lib.focus_workspace_views.argtypes = [pp, vp] + [ctypes.POINTER(vp)] * 6
     lib.focus_workspace_views.restype = ctypes.c_int
+    rp = ctypes.POINTER(FocusRouteParams)
+    lib.focus_route_workspace_size.argtypes = [rp, ctypes.POINTER(sz)]
+    lib.focus_route_workspace_size.restype = ctypes.c_int
+    lib.focus_route.argtypes = [rp, vp, vp, vp, vp, sz, vp, vp, vp]
+    lib.focus_route.restype = ctypes.c_int
+    lib.focus_assign_tokens.argtypes = [pp, vp, vp, vp, sz, vp, vp]
+    lib.focus_assign_tokens.restype = ctypes.c_int
     lib.focus_last_error.argtypes = []
     lib.focus_last_error.restype = ctypes.c_char_p
     lib.focus_version.argtypes = []
@@ -120,6 +136,35 @@ def focus_attn_fwd(p, q, k, v, workspace, out, lse=None, row_pairs=None, vector=
     fn = load_library().focus_attn_fwd_vector if vector else load_library().focus_attn_fwd
     _check(fn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
               workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse), _ptr(row_pairs), _stream()))
+
+
+def make_route_params(B, n, d_model, d_g, K, topk, dtype="bf16", sinkhorn_iters=10, tau=0.1):
+    return FocusRouteParams(B, n, d_model, d_g, K, topk, {"f32": FOCUS_F32, "bf16": FOCUS_BF16}[dtype],
+                            sinkhorn_iters, tau)
+
+
+def focus_route_workspace_size(rp):
+    out = ctypes.c_size_t(0)
+    _check(load_library().focus_route_workspace_size(ctypes.byref(rp), ctypes.byref(out)))
+    return out.value
+
+
+def alloc_route_workspace(rp, device="cuda"):
+    nbytes = focus_route_workspace_size(rp)
+    return torch.empty(((nbytes + 255) // 256) * 256, dtype=torch.uint8, device=device)
+
+
+def focus_route(rp, hidden, w_g, centroids, route_workspace, token_masks, soft=None):
+    _check(load_library().focus_route(ctypes.byref(rp), _ptr(hidden), _ptr(w_g), _ptr(centroids),
+                                      _ptr(route_workspace),
+                                      route_workspace.numel() * route_workspace.element_size(),
+                                      _ptr(token_masks), _ptr(soft), _stream()))
+
+
+def focus_assign_tokens(p, token_masks, k, workspace, invalid_count=None):
+    _check(load_library().focus_assign_tokens(ctypes.byref(p), _ptr(token_masks), _ptr(k), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(),
+                                              _ptr(invalid_count), _stream()))
 
 
 def focus_workspace_views(p, workspace):

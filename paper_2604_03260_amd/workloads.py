@@ -100,6 +100,43 @@ def make_inputs(wl, device="cpu"):
     return {"q": q, "k": k, "v": v, "centroids": c64.float().contiguous()}
 
 
+ROUTER_DG = 16          # the paper's router width (Sec. 3.1: a 16-dimensional projection suffices)
+
+
+def make_router_inputs(wl, device="cpu", d_model=None, d_g=ROUTER_DG):
+    """Inputs of the per-layer router for the same shape: hidden [B,n,d_model] with
+    d_model = Hq*d unless given, W_g [d_model,d_g] ~ N(0, 1/d_model), router centroids
+    [K,d_g] ~ N(0,1) rows L2-normalised (so scores have unit scale and scores/tau at the
+    paper's tau = 0.1 stay far inside the range of exp).  Tensor ids hidden=7 W_g=8
+    router-centroids=9 router-means=10; the mixture configs add the same per-token cluster
+    mean (cluster ids as for q, k, v) in hidden space."""
+    device = torch.device(device)
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    base = 1000 * wl.config_id
+    dm = d_model if d_model is not None else wl.Hq * wl.d
+    g = _gen(device, base + 7)
+    hidden = torch.empty((wl.B, wl.n, dm), dtype=tdt, device=device)
+    mu = z = None
+    if wl.mixture > 0:
+        gz = _gen(device, base + 4)
+        wts = 1.0 / torch.arange(1, wl.mixture + 1, device=device, dtype=torch.float32)
+        z = torch.multinomial(wts.expand(wl.B, -1), wl.n, replacement=True, generator=gz)
+        mu = torch.randn((wl.mixture, dm), generator=_gen(device, base + 10), device=device,
+                         dtype=torch.float32) * wl.sigma
+    rows = max(1, min(wl.n, (1 << 24) // dm))
+    for b in range(wl.B):
+        for r0 in range(0, wl.n, rows):
+            r1 = min(wl.n, r0 + rows)
+            x = torch.randn((r1 - r0, dm), generator=g, device=device, dtype=torch.float32)
+            if mu is not None:
+                x += mu[z[b, r0:r1]]
+            hidden[b, r0:r1] = x.to(tdt)
+    w_g = torch.randn((dm, d_g), generator=_gen(device, base + 8), device=device, dtype=torch.float32) / dm ** 0.5
+    c = torch.randn((wl.K, d_g), generator=_gen(device, base + 9), device=device, dtype=torch.float64)
+    c = c / c.norm(dim=-1, keepdim=True)
+    return {"hidden": hidden, "w_g": w_g.contiguous(), "router_centroids": c.float().contiguous()}
+
+
 def sample_rows(wl, count, device="cpu"):
     """Seeded (b,h,i) triples: the window/sequence edge rows of every head first,
     then uniform draws.  Returns an int32 numpy array [count,3]."""

@@ -96,3 +96,50 @@ def test_workspace_size_grows_with_problem():
     b = focus.focus_workspace_size(focus.make_params(1, 4, 2, 512, 64, 4, 2, 16))
     c = focus.focus_workspace_size(focus.make_params(2, 4, 2, 512, 64, 4, 2, 16))
     assert a < b < c
+
+
+# ---------------------------------------------------------------- router entry points
+def route_status(**kw):
+    base = dict(B=1, n=300, d_model=768, d_g=16, K=8, topk=2, dtype="bf16", sinkhorn_iters=10, tau=0.1)
+    base.update(kw)
+    rp = focus.make_route_params(**base)
+    out = ctypes.c_size_t(0)
+    st = focus.load_library().focus_route_workspace_size(ctypes.byref(rp), ctypes.byref(out))
+    return st, out.value
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), focus.FOCUS_OK),
+    (dict(sinkhorn_iters=0), focus.FOCUS_OK),
+    (dict(n=0), focus.FOCUS_EINVAL),
+    (dict(K=33), focus.FOCUS_EINVAL),
+    (dict(topk=9), focus.FOCUS_EINVAL),
+    (dict(tau=0.0), focus.FOCUS_EINVAL),
+    (dict(tau=float("nan")), focus.FOCUS_EINVAL),
+    (dict(sinkhorn_iters=-1), focus.FOCUS_EINVAL),
+    (dict(d_model=100), focus.FOCUS_EUNSUPPORTED),
+    (dict(d_g=12), focus.FOCUS_EUNSUPPORTED),
+    (dict(d_g=64, K=32, topk=4), focus.FOCUS_OK),
+])
+def test_route_param_validation(kw, want):
+    st, size = route_status(**kw)
+    assert st == want, focus.focus_last_error()
+    if want == focus.FOCUS_OK:
+        assert size > 0 and size % 256 == 0
+
+
+def test_route_null_and_workspace_errors_before_any_launch():
+    lib = focus.load_library()
+    vp = ctypes.c_void_p
+    rp = focus.make_route_params(1, 300, 768, 16, 8, 2)
+    need = focus.focus_route_workspace_size(rp)
+    fake = vp(0x1000)
+    assert lib.focus_route(ctypes.byref(rp), vp(0), fake, fake, fake, need, fake, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_route(ctypes.byref(rp), fake, fake, fake, vp(0), need, fake, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_route(ctypes.byref(rp), fake, fake, fake, vp(0x1010), need, fake, vp(0), vp(0)) == focus.FOCUS_EWORKSPACE
+    assert lib.focus_route(ctypes.byref(rp), fake, fake, fake, fake, need - 1, fake, vp(0), vp(0)) == focus.FOCUS_EWORKSPACE
+    assert lib.focus_route(ctypes.byref(rp), vp(0x1008), fake, fake, fake, need, fake, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    p = focus.make_params(1, 4, 2, 256, 64, 4, 2, 16)
+    wneed = focus.focus_workspace_size(p)
+    assert lib.focus_assign_tokens(ctypes.byref(p), vp(0), fake, fake, wneed, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_assign_tokens(ctypes.byref(p), fake, fake, fake, wneed - 1, vp(0), vp(0)) == focus.FOCUS_EWORKSPACE

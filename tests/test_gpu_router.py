@@ -1,0 +1,181 @@
+"""GPU parity of the router front-end (focus_route, focus_assign_tokens) against the CPU oracle.
+
+Bars: without Sinkhorn the membership is bit-exact (the fp64 sums run in the same
+order on both sides).  With Sinkhorn the exponential and the sums over the sequence
+round differently, so the soft assignment is compared at a relative 1e-9 and the
+membership must agree on every token whose top-k decision the oracle takes with a
+relative margin above 1e-8 (in practice: everywhere).  Downstream, attention on the
+routed membership goes through the same checks as the per-head path.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import focus_oracle as fo
+from paper_2604_03260_amd import focus, workloads
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+
+SOFT_RTOL = 1e-9
+MARGIN = 1e-8
+
+
+def run_route(wl, rin, iters, tau=0.1, want_soft=True):
+    hidden = rin["hidden"]
+    dm, dg = hidden.shape[-1], rin["w_g"].shape[1]
+    rp = focus.make_route_params(wl.B, wl.n, dm, dg, wl.K, wl.topk, dtype=wl.dtype, sinkhorn_iters=iters, tau=tau)
+    rws = focus.alloc_route_workspace(rp)
+    masks = torch.full((wl.B, wl.n), -1, dtype=torch.int32, device="cuda")
+    soft = torch.full((wl.B, wl.n, wl.K), float("nan"), dtype=torch.float64, device="cuda") if want_soft else None
+    focus.focus_route(rp, hidden, rin["w_g"], rin["router_centroids"], rws, masks, soft)
+    torch.cuda.synchronize()
+    return masks, soft
+
+
+def oracle_route(wl, rin, iters, tau=0.1):
+    return fo.route(workloads.to_host_bits(rin["hidden"]), rin["w_g"].cpu().numpy(),
+                    rin["router_centroids"].cpu().numpy(), wl.topk, tau=tau, iters=iters, dtype=wl.dtype,
+                    want_soft=True)
+
+
+def check_route(wl, rin, iters, tau=0.1):
+    masks, soft = run_route(wl, rin, iters, tau)
+    m_ref, _, g_ref = oracle_route(wl, rin, iters, tau)
+    got = masks.cpu().numpy().view(np.uint32)
+    g_got = soft.cpu().numpy()
+    assert np.isfinite(g_got).all()
+    if iters == 0:
+        assert np.array_equal(g_got, g_ref), "scores differ: max %g" % np.abs(g_got - g_ref).max()
+        assert np.array_equal(got, m_ref), "membership differs in %d places" % int((got != m_ref).sum())
+        return got
+    rel = np.abs(g_got - g_ref) / np.maximum(np.abs(g_ref), 1e-300)
+    assert rel.max() <= SOFT_RTOL, "soft assignment: max relative error %g" % rel.max()
+    assert np.abs(g_got.sum(-1) - 1.0).max() < 1e-12
+    srt = np.sort(g_ref, axis=-1)[..., ::-1]
+    if wl.topk < wl.K:
+        margin = (srt[..., wl.topk - 1] - srt[..., wl.topk]) / srt[..., wl.topk - 1]
+    else:
+        margin = np.ones(got.shape)
+    decided = margin > MARGIN
+    assert np.array_equal(got[decided], m_ref[decided]), "membership differs on decided tokens"
+    popc = np.array([bin(int(x)).count("1") for x in got.ravel()])
+    assert (popc == wl.topk).all()
+    if wl.n > 1:                    # a single token is normalised to exactly 1/K everywhere: all ties
+        assert decided.mean() > 0.999
+    return got
+
+
+SMALL = [
+    # B, n, dm, dg, K, topk, dtype, iters
+    (1, 300, 96, 16, 4, 2, "f32", 0),
+    (2, 777, 200, 16, 8, 2, "bf16", 0),
+    (1, 64, 8, 4, 1, 1, "f32", 0),
+    (1, 1000, 768, 16, 4, 2, "bf16", 10),
+    (2, 513, 264, 8, 8, 1, "f32", 10),
+    (1, 5000, 128, 32, 16, 3, "bf16", 3),
+    (3, 130, 64, 64, 32, 4, "f32", 2),
+    (1, 1, 64, 16, 4, 2, "bf16", 10),
+    (1, 70000, 64, 16, 8, 2, "bf16", 10),      # more than 256 tokens per Sinkhorn work-group
+]
+
+
+@pytest.mark.parametrize("B,n,dm,dg,K,topk,dtype,iters", SMALL)
+def test_route_small(B, n, dm, dg, K, topk, dtype, iters):
+    wl = workloads.Workload("r", 40 + dg + K, B, 1, 1, n, 64, dtype, K, topk, 16, mixture=3 if K > 4 else 0)
+    rin = workloads.make_router_inputs(wl, "cuda", d_model=dm, d_g=dg)
+    check_route(wl, rin, iters)
+
+
+def test_route_is_deterministic():
+    wl = workloads.Workload("r", 61, 2, 1, 1, 3000, 64, "bf16", 8, 2, 16)
+    rin = workloads.make_router_inputs(wl, "cuda", d_model=512)
+    m0, s0 = run_route(wl, rin, 10)
+    m1, s1 = run_route(wl, rin, 10)
+    assert torch.equal(m0, m1) and torch.equal(s0, s1)
+
+
+def test_route_temperature_and_ties():
+    # equal centroids: every score ties, membership = the first topk groups; tau only rescales
+    wl = workloads.Workload("r", 62, 1, 1, 1, 500, 64, "f32", 6, 3, 16)
+    rin = workloads.make_router_inputs(wl, "cuda", d_model=64)
+    rin["router_centroids"] = rin["router_centroids"][:1].repeat(6, 1).contiguous()
+    for iters in (0, 4):
+        masks, _ = run_route(wl, rin, iters)
+        assert (masks == 0b111).all()
+    rin = workloads.make_router_inputs(wl, "cuda", d_model=64)
+    a = check_route(wl, rin, 0, tau=0.1)
+    b = check_route(wl, rin, 0, tau=0.5)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", None), ("cfg2", 1024), ("cfg3", 2048), ("cfg4a", 3000), ("cfg4b", 1500)])
+def test_routed_attention_matches_oracle(name, n):
+    """route -> assign_tokens -> attention, every row against the oracle fed the oracle's own routing."""
+    base = workloads.CONFIGS[name]
+    wl = base if n is None else base.scaled(n=n, B=min(base.B, 2), Hq=min(base.Hq, 8), Hkv=min(base.Hkv, 2),
+                                            window=max(8, base.window * n // base.n))
+    inp = workloads.make_inputs(wl, "cuda")
+    rin = workloads.make_router_inputs(wl, "cuda", d_model=256)
+    tm = check_route(wl, rin, 10)
+    m_ref, _, _ = oracle_route(wl, rin, 10)
+    assert np.array_equal(tm, m_ref)
+
+    p = harness.params_of(wl)
+    ws = focus.alloc_workspace(p)
+    bad = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    focus.focus_assign_tokens(p, torch.from_numpy(tm.view(np.int32)).cuda(), inp["k"], ws, bad)
+    out = torch.empty_like(inp["q"])
+    lse = torch.empty((wl.B, wl.Hq, wl.n), dtype=torch.float32, device="cuda")
+    rp = torch.empty((wl.B, wl.Hq, wl.n), dtype=torch.int32, device="cuda")
+    focus.focus_attn_fwd(p, inp["q"], inp["k"], inp["v"], ws, out, lse, rp)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    res = dict(out=out, lse=lse, row_pairs=rp, views=focus.focus_workspace_views(p, ws))
+    pb = harness.problem_of(wl)
+    mq, mk = fo.broadcast_masks(pb, m_ref)
+    v = res["views"]
+    assert np.array_equal(v["mq"].cpu().numpy().view(np.uint32), mq)
+    assert np.array_equal(v["mk"].cpu().numpy().view(np.uint32), mk)
+    for side, m in (("q", mq), ("k", mk)):
+        counts, lists = fo.group_lists(pb, m)
+        assert np.array_equal(v[side + "_group_counts"].cpu().numpy(), counts)
+        assert np.array_equal(v[side + "_group_lists"].cpu().numpy(), lists)
+    harness.check_attn(wl, inp, res, mq, mk)
+    harness.check_pair_totals(wl, res, mq, mk)
+
+
+def test_assign_tokens_replaces_invalid_masks():
+    wl = workloads.CONFIGS["cfg1"].scaled(n=600, Hq=2, Hkv=2)
+    inp = workloads.make_inputs(wl, "cuda")
+    rng = np.random.default_rng(5)
+    valid = np.array([0b0011, 0b0101, 0b0110, 0b1001, 0b1010, 0b1100], dtype=np.uint32)
+    tm = valid[rng.integers(0, 6, size=(wl.B, wl.n))]
+    tm[0, 3] = 0b0111          # three groups
+    tm[0, 77] = 0              # none
+    tm[0, 300] = 0b110000      # groups that do not exist
+    p = harness.params_of(wl)
+    ws = focus.alloc_workspace(p)
+    bad = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    focus.focus_assign_tokens(p, torch.from_numpy(tm.view(np.int32)).cuda(), inp["k"], ws, bad)
+    out = torch.empty_like(inp["q"])
+    rp = torch.empty((wl.B, wl.Hq, wl.n), dtype=torch.int32, device="cuda")
+    lse = torch.empty((wl.B, wl.Hq, wl.n), dtype=torch.float32, device="cuda")
+    focus.focus_attn_fwd(p, inp["q"], inp["k"], inp["v"], ws, out, lse, rp)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 3
+    fixed = tm.copy()
+    fixed[0, [3, 77, 300]] = 0b0011
+    pb = harness.problem_of(wl)
+    mq, mk = fo.broadcast_masks(pb, fixed)
+    res = dict(out=out, lse=lse, row_pairs=rp)
+    harness.check_attn(wl, inp, res, mq, mk)
+
+
+@pytest.mark.parametrize("name", ["cfg3"])
+def test_route_full_size(name):
+    """The headline shape's router (32768 tokens, d_model 4096, d_g 16, 10 Sinkhorn rounds)."""
+    wl = workloads.CONFIGS[name]
+    rin = workloads.make_router_inputs(wl, "cuda")
+    check_route(wl, rin, 10)
+    check_route(wl, rin, 0)
