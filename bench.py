@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 
 BF16_MFMA_PEAK_TFLOPS = 2516.6      # 256 CU x 2.4 GHz x 4096 FLOP/clk/CU (dense)
 FP32_VECTOR_PEAK_TFLOPS = 157.3
+FP64_VECTOR_PEAK_TFLOPS = 78.6
 # HBM bytes per launch of the attention kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this
 # command (profiles/attn_mfma_kernel_cfg3_counters.txt); None where no counter run was made
 MEASURED_TRAFFIC_BYTES = {"cfg3": 6.08e9}
@@ -35,6 +36,7 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-router", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of q (known size) so a counter run can be calibrated")
@@ -187,12 +189,63 @@ def main():
             "allowed_fraction": allowed2 / (w2.B * w2.Hq * (w2.n * (w2.n + 1) // 2))}}
         del i2, ws2, o2, rp2
 
+    mq_host = mk_host = None
+    if not args.no_cpu_baseline:       # the router leg below reuses the workspace: keep the per-head membership
+        mq_host = views["mq"].cpu().numpy().view(np.uint32).copy()
+        mk_host = views["mk"].cpu().numpy().view(np.uint32).copy()
+
+    # the paper's own front-end: one routing per token from the layer's hidden state (Sec. 2), then the same
+    # bucketing and attention; reported beside the headline path, never part of `value`
+    if not args.no_router:
+        rin = workloads.make_router_inputs(wl, "cuda")
+        dm, dg = rin["hidden"].shape[-1], rin["w_g"].shape[1]
+        tmasks = torch.empty((wl.B, wl.n), dtype=torch.int32, device="cuda")
+        rp10 = focus.make_route_params(wl.B, wl.n, dm, dg, wl.K, wl.topk, dtype=wl.dtype, sinkhorn_iters=10, tau=0.1)
+        rp0 = focus.make_route_params(wl.B, wl.n, dm, dg, wl.K, wl.topk, dtype=wl.dtype, sinkhorn_iters=0, tau=0.1)
+        rws = focus.alloc_route_workspace(rp10)
+        rpairs = torch.empty((wl.B, wl.Hq, wl.n), dtype=torch.int32, device="cuda")
+        focus.focus_route(rp10, rin["hidden"], rin["w_g"], rin["router_centroids"], rws, tmasks)
+        focus.focus_assign_tokens(p, tmasks, k, ws)
+        focus.focus_attn_fwd(p, q, k, v, ws, out, None, rpairs)
+        torch.cuda.synchronize()
+        r_allowed = int(rpairs.to(torch.int64).sum().item())
+        del rpairs
+        rsteps = max(3, steps // 2)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(rsteps)]
+        for s in range(rsteps):
+            ev[s][0].record()
+            focus.focus_route(rp0, rin["hidden"], rin["w_g"], rin["router_centroids"], rws, tmasks)
+            ev[s][1].record()
+            focus.focus_route(rp10, rin["hidden"], rin["w_g"], rin["router_centroids"], rws, tmasks)
+            ev[s][2].record()
+            focus.focus_assign_tokens(p, tmasks, k, ws)
+            ev[s][3].record()
+            focus.focus_attn_fwd(p, q, k, v, ws, out, None, None)
+            ev[s][4].record()
+        torch.cuda.synchronize()
+        t_proj, t_route, t_tok, t_rattn = (sum(e[i].elapsed_time(e[i + 1]) for e in ev) / rsteps for i in range(4))
+        proj_flop = 2.0 * wl.B * wl.n * dm * dg
+        result["router_path"] = {
+            "workload": "hidden [B=%d, n=%d, d_model=%d] %s, d_g=%d, K=%d, top-%d, tau=0.1, 10 Sinkhorn rounds"
+                        % (wl.B, wl.n, dm, wl.dtype, dg, wl.K, wl.topk),
+            "ms_route": t_route, "ms_route_no_sinkhorn": t_proj, "ms_assign_tokens": t_tok, "ms_attn": t_rattn,
+            "ms_per_step": t_route + t_tok + t_rattn,
+            "tokens_per_s": wl.B * wl.n / ((t_route + t_tok + t_rattn) * 1e-3),
+            "allowed_fraction": r_allowed / causal_pairs,
+            "useful_tflops_step": 4.0 * wl.d * r_allowed / ((t_route + t_tok + t_rattn) * 1e-3) / 1e12,
+            "roofline": {"bound": "alu", "kernel": "route_project_kernel", "achieved": proj_flop / (t_proj * 1e-3) / 1e12,
+                         "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": proj_flop / (t_proj * 1e-3) / 1e12 / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                         "note": "achieved = 2*B*n*d_model*d_g fp64 FLOP / mean focus_route time without Sinkhorn "
+                                 "(projection + two table conversions)"},
+        }
+        del rin, rws, tmasks
+
     if not args.no_cpu_baseline:
         from oracle import focus_oracle as fo
         pb = fo.Problem(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.K, wl.topk, wl.window, causal=True,
                         dtype=wl.dtype, softcap=wl.softcap)
-        mq = views["mq"].cpu().numpy().view(np.uint32)
-        mk = views["mk"].cpu().numpy().view(np.uint32)
+        mq, mk = mq_host, mk_host
         qh, kh, vh = (workloads.to_host_bits(t) for t in (q, k, v))
         rows_all = workloads.sample_rows(wl, min(wl.B * wl.Hq * wl.n, 1 << 20))
         # calibrate on a few rows, then size the sample to about cpu_seconds

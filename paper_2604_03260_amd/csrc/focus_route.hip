@@ -314,17 +314,16 @@ hipError_t launch_project(const RouteLayout& R, const void* hidden, char* ws, ui
     hipLaunchKernelGGL((route_project_kernel<T, JW, NW>), grid, dim3(64 * NW), lds, st, R, (const T*)hidden, w64, \
                        c64, ws, masks, soft)
     // JW router outputs per wavefront: more of them amortise the fp64 conversion of every hidden value,
-    // fewer give more wavefronts when the token count alone cannot fill the chip
-    const long waves_full = (long)R.nproj * R.B;
+    // fewer give more wavefronts.  A wavefront issues one fp64 instruction about every 16 cycles, a SIMD
+    // one every 4: the fp64 rate needs 4 or more wavefronts per SIMD, so the split follows the token count
+    // (measured at d_model 4096..8192, d_g 16: 8 x 2 wins from 2048 groups of 64 tokens on, 4 x 4 below,
+    // 16 x 1 nowhere).
+    const long groups = (long)R.nproj * R.B;
     switch (R.dg) {
         case 4: FOCUS_PROJ(4, 1); break;
-        case 8: if (waves_full >= 2048) FOCUS_PROJ(8, 1); else FOCUS_PROJ(4, 2); break;
-        case 16:
-            if (waves_full >= 2048) FOCUS_PROJ(16, 1);
-            else if (waves_full >= 1024) FOCUS_PROJ(8, 2);
-            else FOCUS_PROJ(4, 4);
-            break;
-        case 32: if (waves_full >= 1024) FOCUS_PROJ(16, 2); else FOCUS_PROJ(8, 4); break;
+        case 8: FOCUS_PROJ(4, 2); break;
+        case 16: if (groups >= 2048) FOCUS_PROJ(8, 2); else FOCUS_PROJ(4, 4); break;
+        case 32: FOCUS_PROJ(8, 4); break;
         default: FOCUS_PROJ(16, 4); break;
     }
 #undef FOCUS_PROJ
