@@ -188,10 +188,10 @@ int focus_oracle_group_lists(const oracle_params *p, const uint32_t *masks, int 
  * out: [nrows,d] fp64; lse: [nrows] (nullable); row_pairs: [nrows] (nullable);
  * probs: [nrows,n] (nullable) the full probability rows.
  */
-int focus_oracle_attn_rows(const oracle_params *p, const void *q, const void *k,
-                           const void *v, const uint32_t *mq, const uint32_t *mk,
-                           int64_t nrows, const int32_t *rows, double *out,
-                           double *lse, int64_t *row_pairs, double *probs)
+static int attn_rows_impl(const oracle_params *p, int pair_set, const void *q, const void *k,
+                          const void *v, const uint32_t *mq, const uint32_t *mk,
+                          int64_t nrows, const int32_t *rows, double *out,
+                          double *lse, int64_t *row_pairs, double *probs)
 {
     if (check_params(p) || !q || !k || !v || !mq || !mk || !out) return -1;
     const int n = p->n, d = p->d, Hq = p->Hq, Hkv = p->Hkv, w = p->window;
@@ -233,8 +233,18 @@ int focus_oracle_attn_rows(const oracle_params *p, const void *q, const void *k,
                     int local = p->causal ? (j > i - w && j <= i)
                                           : ((i - j < w) && (j - i < w));
                     int share = (mi & mk[kbase + j]) != 0;
-                    allowed[j] = (unsigned char)(in_range && (local || share));
+                    int ok = (pair_set == 1) ? share                 /* set A: shares a group        */
+                           : (pair_set == 2) ? (local && !share)     /* set B: local, no shared group */
+                                             : (local || share);     /* the whole mask               */
+                    allowed[j] = (unsigned char)(in_range && ok);
                     npairs += allowed[j];
+                }
+                if (npairs == 0) {                    /* only the sets A and B can leave a row empty */
+                    for (int t = 0; t < d; ++t) out[r * d + t] = 0.0;
+                    if (probs) for (int j = 0; j < n; ++j) probs[r * n + j] = 0.0;
+                    if (lse) lse[r] = -INFINITY;
+                    if (row_pairs) row_pairs[r] = 0;
+                    continue;
                 }
                 /* logits and masked softmax */
                 double mx = -INFINITY;
@@ -272,6 +282,48 @@ int focus_oracle_attn_rows(const oracle_params *p, const void *q, const void *k,
         free(allowed); free(x); free(qi);
     }
     return bad ? -1 : 0;
+}
+
+int focus_oracle_attn_rows(const oracle_params *p, const void *q, const void *k,
+                           const void *v, const uint32_t *mq, const uint32_t *mk,
+                           int64_t nrows, const int32_t *rows, double *out,
+                           double *lse, int64_t *row_pairs, double *probs)
+{
+    return attn_rows_impl(p, 0, q, k, v, mq, mk, nrows, rows, out, lse, row_pairs, probs);
+}
+
+/* The paper's disjoint decomposition of the mask (App. D), with group sets in place of the
+ * hard assignment g(i): pair_set 1 = A, causal pairs that share a group; pair_set 2 = B,
+ * causal pairs inside the window that share none; 0 = their union, the whole mask.  Softmax
+ * attention restricted to the set; a row with no pair in the set gives out = 0, lse = -inf. */
+int focus_oracle_attn_rows_set(const oracle_params *p, int32_t pair_set, const void *q, const void *k,
+                               const void *v, const uint32_t *mq, const uint32_t *mk,
+                               int64_t nrows, const int32_t *rows, double *out,
+                               double *lse, int64_t *row_pairs, double *probs)
+{
+    if (pair_set < 0 || pair_set > 2) return -1;
+    return attn_rows_impl(p, pair_set, q, k, v, mq, mk, nrows, rows, out, lse, row_pairs, probs);
+}
+
+/* App. D "Merge": o = (e^{lA} oA + e^{lB} oB) / (e^{lA} + e^{lB}) per query row, and the
+ * log-sum-exp of the union.  The larger of lA, lB is taken out of both exponentials first; a set
+ * with lse = -inf weighs nothing. */
+int focus_oracle_merge(int64_t nrows, int32_t d, const double *oa, const double *la,
+                       const double *ob, const double *lb, double *out, double *lse)
+{
+    if (nrows < 0 || d < 1 || !oa || !la || !ob || !lb || !out) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        const double m = la[r] > lb[r] ? la[r] : lb[r];
+        if (m == -INFINITY) {
+            for (int t = 0; t < d; ++t) out[r * d + t] = 0.0;
+            if (lse) lse[r] = -INFINITY;
+            continue;
+        }
+        const double ea = exp(la[r] - m), eb = exp(lb[r] - m);
+        for (int t = 0; t < d; ++t) out[r * d + t] = (ea * oa[r * d + t] + eb * ob[r * d + t]) / (ea + eb);
+        if (lse) lse[r] = m + log(ea + eb);
+    }
+    return 0;
 }
 
 /* -------------------------------------------------------------- pair counts

@@ -136,8 +136,12 @@ def group_lists(pb, masks):
     return counts, lists
 
 
-def attn_rows(pb, q, k, v, mq, mk, rows=None, want_probs=False):
-    """rows: int array [nrows,3] of (b,h,i) or None for every row.
+PAIR_SETS = {"all": 0, "A": 1, "B": 2}
+
+
+def attn_rows(pb, q, k, v, mq, mk, rows=None, want_probs=False, pair_set="all"):
+    """rows: int array [nrows,3] of (b,h,i) or None for every row.  pair_set: "all" (the whole mask),
+    "A" (pairs that share a group) or "B" (window pairs that share none), App. D.
     Returns out [nrows,d] f64, lse [nrows] f64, row_pairs [nrows] i64 (and probs [nrows,n])."""
     pb._check_tensor(q, pb.Hq)
     pb._check_tensor(k, pb.Hkv)
@@ -156,12 +160,29 @@ def attn_rows(pb, q, k, v, mq, mk, rows=None, want_probs=False):
     pairs = np.empty((nrows,), dtype=np.int64)
     probs = np.zeros((nrows, pb.n), dtype=np.float64) if want_probs else None
     p = pb._c()
-    _rc(_load().focus_oracle_attn_rows(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(mq), _ptr(mk),
-                                       ctypes.c_int64(nrows), _ptr(rows_arr), _ptr(out), _ptr(lse),
-                                       _ptr(pairs), _ptr(probs)), "attn_rows")
+    lib = _load()
+    lib.focus_oracle_attn_rows_set.restype = ctypes.c_int
+    _rc(lib.focus_oracle_attn_rows_set(ctypes.byref(p), ctypes.c_int32(PAIR_SETS[pair_set]), _ptr(q), _ptr(k),
+                                       _ptr(v), _ptr(mq), _ptr(mk), ctypes.c_int64(nrows), _ptr(rows_arr),
+                                       _ptr(out), _ptr(lse), _ptr(pairs), _ptr(probs)), "attn_rows")
     if want_probs:
         return out, lse, pairs, probs
     return out, lse, pairs
+
+
+def merge(oa, la, ob, lb):
+    """App. D merge of two disjoint partial attentions: returns (out [nrows,d], lse [nrows])."""
+    lib = _load()
+    lib.focus_oracle_merge.restype = ctypes.c_int
+    oa, ob = (np.ascontiguousarray(x, dtype=np.float64) for x in (oa, ob))
+    la, lb = (np.ascontiguousarray(x, dtype=np.float64) for x in (la, lb))
+    nrows, d = oa.shape
+    assert ob.shape == (nrows, d) and la.shape == (nrows,) and lb.shape == (nrows,)
+    out = np.empty((nrows, d), dtype=np.float64)
+    lse = np.empty((nrows,), dtype=np.float64)
+    _rc(lib.focus_oracle_merge(ctypes.c_int64(nrows), ctypes.c_int32(d), _ptr(oa), _ptr(la), _ptr(ob), _ptr(lb),
+                               _ptr(out), _ptr(lse)), "merge")
+    return out, lse
 
 
 def pair_counts(pb, mq, mk):
