@@ -131,6 +131,35 @@ focus_status focus_assign_tokens(const focus_params *p, const uint32_t *token_ma
                                  void *workspace, size_t workspace_bytes, int32_t *invalid_count,
                                  void *stream);
 
+/* ---- the paper's two-call evaluation (App. D), as a measured comparator of the fused kernel ----
+ *
+ * App. D splits the mask into two disjoint sets, A = causal pairs of the same group and
+ * B = causal pairs inside the window of different groups, evaluates each with its own softmax
+ * and merges the two results through their log-sum-exp values.  With top-k sets: A = pairs whose
+ * membership sets intersect, B = window pairs whose sets do not.  These calls run after
+ * focus_assign (or focus_assign_tokens) on the same workspace, like focus_attn_fwd. */
+typedef enum { FOCUS_PAIRS_ALL = 0, FOCUS_PAIRS_SHARED = 1, FOCUS_PAIRS_CROSS_LOCAL = 2 } focus_pair_set;
+
+/* focus_attn_fwd restricted to one pair set.  A row with no pair in the set gets out = 0,
+ * lse = -inf, row_pairs = 0.  FOCUS_EUNSUPPORTED for a restricted set when window >= n. */
+focus_status focus_attn_fwd_set(const focus_params *p, int32_t pair_set, const void *q, const void *k,
+                                const void *v, void *workspace, size_t workspace_bytes, void *out,
+                                float *lse, int32_t *row_pairs, void *stream);
+
+/* App. D "Merge": out = (e^{lse_a} out_a + e^{lse_b} out_b) / (e^{lse_a} + e^{lse_b}) per row and
+ * lse (nullable) = log(e^{lse_a} + e^{lse_b}); rows of d components (a multiple of 8) in dtype,
+ * lse fp32; all DEVICE pointers, 16-byte aligned; out may alias out_a or out_b. */
+focus_status focus_attn_merge(int64_t rows, int32_t d, int32_t dtype, const void *out_a,
+                              const float *lse_a, const void *out_b, const float *lse_b, void *out,
+                              float *lse, void *stream);
+
+/* Set A, set B, merge: three launches on `stream`.  part_out: DEVICE scratch of 2 x [B,Hq,n,d]
+ * elements of p->dtype, part_lse: DEVICE scratch of 2 x [B,Hq,n] fp32, both caller-owned. */
+focus_status focus_attn_fwd_two_call(const focus_params *p, const void *q, const void *k,
+                                     const void *v, void *workspace, size_t workspace_bytes,
+                                     void *out, float *lse, void *part_out, float *part_lse,
+                                     void *stream);
+
 /* Device pointers INTO the workspace for parity checks; valid until the
  * workspace is overwritten.  Any output pointer may be NULL.
  *   mq [B,Hq,n], mk [B,Hkv,n]                   uint32 membership masks

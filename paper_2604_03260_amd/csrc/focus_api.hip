@@ -208,27 +208,90 @@ focus_status focus_assign(const focus_params* p, const void* q, const void* k, c
     return FOCUS_OK;
 }
 
-focus_status focus_attn_fwd(const focus_params* p, const void* q, const void* k, const void* v,
-                            void* workspace, size_t workspace_bytes, void* out, float* lse,
-                            int32_t* row_pairs, void* stream)
+namespace {
+
+// one launch of the attention kernels over the whole mask (pair_set 0) or one of its two disjoint parts
+focus_status attn_launch(const focus_params* p, int pair_set, const void* q, const void* k, const void* v,
+                         void* workspace, size_t workspace_bytes, void* out, float* lse, int32_t* row_pairs,
+                         void* stream, const char* who)
 {
     focus::Layout L;
     focus::HeadMap hm;
     focus_status st = make_layout(p, &L, &hm);
     if (st != FOCUS_OK) return st;
+    if (pair_set < 0 || pair_set > 2) return fail(FOCUS_EINVAL, "pair_set must be 0, 1 or 2 (got %d)", pair_set);
+    if (pair_set != 0 && p->window >= p->n && 2 * p->topk <= p->K)
+        return fail(FOCUS_EUNSUPPORTED, "the two-set decomposition is not built for window >= n "
+                                        "(every causal pair is local: one launch over the whole mask is the answer)");
     if (!q || !k || !v || !out) return fail(FOCUS_EINVAL, "q, k, v and out must not be NULL");
     if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(out))
         return fail(FOCUS_EINVAL, "q, k, v and out must be 16-byte aligned");
     if (out == q || out == k || out == v) return fail(FOCUS_EINVAL, "out must not alias an input");
     st = check_ws(L, workspace, workspace_bytes);
     if (st != FOCUS_OK) return st;
+    L.pair_set = pair_set;
     hipError_t e;
     if (L.dtype == FOCUS_BF16)
         e = focus::launch_attn_mfma(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
     else
         e = focus::launch_attn_simple(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
-    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_fwd: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "%s: %s", who, hipGetErrorString(e));
     return FOCUS_OK;
+}
+
+}  // namespace
+
+focus_status focus_attn_fwd(const focus_params* p, const void* q, const void* k, const void* v,
+                            void* workspace, size_t workspace_bytes, void* out, float* lse,
+                            int32_t* row_pairs, void* stream)
+{
+    return attn_launch(p, 0, q, k, v, workspace, workspace_bytes, out, lse, row_pairs, stream, "focus_attn_fwd");
+}
+
+focus_status focus_attn_fwd_set(const focus_params* p, int32_t pair_set, const void* q, const void* k, const void* v,
+                                void* workspace, size_t workspace_bytes, void* out, float* lse, int32_t* row_pairs,
+                                void* stream)
+{
+    return attn_launch(p, pair_set, q, k, v, workspace, workspace_bytes, out, lse, row_pairs, stream,
+                       "focus_attn_fwd_set");
+}
+
+focus_status focus_attn_merge(int64_t rows, int32_t d, int32_t dtype, const void* out_a, const float* lse_a,
+                              const void* out_b, const float* lse_b, void* out, float* lse, void* stream)
+{
+    if (rows < 0 || d < 8 || d % 8 != 0) return fail(FOCUS_EINVAL, "rows must be >= 0 and d a positive multiple of 8");
+    if (dtype != FOCUS_F32 && dtype != FOCUS_BF16) return fail(FOCUS_EINVAL, "unknown dtype %d", dtype);
+    if (!out_a || !lse_a || !out_b || !lse_b || !out) return fail(FOCUS_EINVAL, "partial outputs, their lse and out must not be NULL");
+    if (misaligned16(out_a) || misaligned16(out_b) || misaligned16(out))
+        return fail(FOCUS_EINVAL, "out_a, out_b and out must be 16-byte aligned");
+    if (rows == 0) return FOCUS_OK;
+    hipError_t e = focus::launch_attn_merge((size_t)rows, d, dtype, out_a, lse_a, out_b, lse_b, out, lse,
+                                            (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_merge: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+focus_status focus_attn_fwd_two_call(const focus_params* p, const void* q, const void* k, const void* v,
+                                     void* workspace, size_t workspace_bytes, void* out, float* lse, void* part_out,
+                                     float* part_lse, void* stream)
+{
+    if (!p) return fail(FOCUS_EINVAL, "params is NULL");
+    if (!part_out || !part_lse) return fail(FOCUS_EINVAL, "part_out and part_lse must not be NULL");
+    if (misaligned16(part_out)) return fail(FOCUS_EINVAL, "part_out must be 16-byte aligned");
+    const size_t rows = (size_t)p->B * (size_t)p->Hq * (size_t)p->n;
+    const size_t elem = (p->dtype == FOCUS_F32) ? 4 : 2;
+    char* oa = (char*)part_out;
+    char* ob = oa + rows * (size_t)p->d * elem;
+    float* la = part_lse;
+    float* lb = part_lse + rows;
+    focus_status st = attn_launch(p, 1, q, k, v, workspace, workspace_bytes, oa, la, nullptr, stream,
+                                  "focus_attn_fwd_two_call (set A)");
+    if (st != FOCUS_OK) return st;
+    st = attn_launch(p, 2, q, k, v, workspace, workspace_bytes, ob, lb, nullptr, stream,
+                     "focus_attn_fwd_two_call (set B)");
+    if (st != FOCUS_OK) return st;
+    if (!out) return fail(FOCUS_EINVAL, "out must not be NULL");
+    return focus_attn_merge((int64_t)rows, p->d, p->dtype, oa, la, ob, lb, out, lse, stream);
 }
 
 // Same contract as focus_attn_fwd, but always through the fp32 vector kernel

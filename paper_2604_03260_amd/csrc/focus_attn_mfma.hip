@@ -208,7 +208,20 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     const int i_lo = S.plan.i_lo;
     const int total = S.plan.total;
     const int w = L.window;
-    if (total == 0) return;      // cannot happen (the diagonal is always allowed)
+    if (total == 0) {
+        // Only a launch restricted to one of the two pair sets can leave a tile without keys
+        // (the whole mask always holds the diagonal): its rows are empty, out = 0 and lse = -inf.
+        if (rvalid) {
+            uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * D + hh * (D / 2);
+#pragma unroll
+            for (int e = 0; e < D / 2; e += 4) *(uint2*)(orow + e) = make_uint2(0u, 0u);
+            if (hh == 0) {
+                if (lse) lse[(size_t)bhq * L.n + qpos] = -INFINITY;
+                if constexpr (PAIRS) row_pairs[(size_t)bhq * L.n + qpos] = 0;
+            }
+        }
+        return;
+    }
 
     bf16x8 qreg[KS];
     {
@@ -482,7 +495,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if constexpr (PAIRS) npairs += __shfl_xor(npairs, 32, 64);
     if (!rvalid) return;
-    const float inv = 1.f / l_tot;
+    const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;      // an empty row (restricted pair set): out = 0, lse = -inf
     uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db) {

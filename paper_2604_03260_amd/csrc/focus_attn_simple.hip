@@ -131,7 +131,7 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
         }
     }
     if (rvalid) {
-    const float inv = 1.f / l;
+    const float inv = (l > 0.f) ? 1.f / l : 0.f;     // empty row (launch restricted to one pair set): out = 0, lse = -inf
     T* orow = out + ((size_t)bhq * L.n + qpos) * D + part * 32;
 #pragma unroll
     for (int e = 0; e < 32; ++e) orow[e] = from_f32<T>(o[e] * inv);
@@ -143,7 +143,89 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
     }   // pass
 }
 
+// 8 consecutive components of a row (16-byte aligned: d is a multiple of 8) as fp32 and back
+__device__ inline void load8(const float* p, float (&x)[8])
+{
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ inline void load8(const uint16_t* p, float (&x)[8])
+{
+    const uint4 u = *(const uint4*)p;
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = __uint_as_float(w[e] << 16);
+        x[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+}
+__device__ inline void store8(float* p, const float (&y)[8])
+{
+    *(float4*)p = make_float4(y[0], y[1], y[2], y[3]);
+    *(float4*)(p + 4) = make_float4(y[4], y[5], y[6], y[7]);
+}
+__device__ inline void store8(uint16_t* p, const float (&y)[8])
+{
+    uint4 u;
+    u.x = f32_to_bf16_rne(y[0]) | ((uint32_t)f32_to_bf16_rne(y[1]) << 16);
+    u.y = f32_to_bf16_rne(y[2]) | ((uint32_t)f32_to_bf16_rne(y[3]) << 16);
+    u.z = f32_to_bf16_rne(y[4]) | ((uint32_t)f32_to_bf16_rne(y[5]) << 16);
+    u.w = f32_to_bf16_rne(y[6]) | ((uint32_t)f32_to_bf16_rne(y[7]) << 16);
+    *(uint4*)p = u;
+}
+
+// App. D "Merge": two partial attentions over disjoint pair sets with their log-sum-exp values give
+// the attention over the union, o = (e^{lA} oA + e^{lB} oB) / (e^{lA} + e^{lB}).  One thread per
+// 8 consecutive components of a row; an empty part (lse = -inf) weighs nothing.
+template <typename T>
+__global__ __launch_bounds__(256) void attn_merge_kernel(size_t rows, int d, const T* __restrict__ oa,
+                                                         const float* __restrict__ la, const T* __restrict__ ob,
+                                                         const float* __restrict__ lb, T* __restrict__ out,
+                                                         float* __restrict__ lse)
+{
+    const int cpr = d / 8;
+    const size_t total = rows * (size_t)cpr;
+    for (size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = id / cpr;
+        const int c = (int)(id % cpr);
+        const float a = la[r], b = lb[r];
+        const float m = fmaxf(a, b);
+        float wa = 0.f, wb = 0.f, l = -INFINITY;
+        if (m != -INFINITY) {
+            const float ea = expf(a - m), eb = expf(b - m);
+            const float inv = 1.f / (ea + eb);
+            wa = ea * inv;
+            wb = eb * inv;
+            l = m + logf(ea + eb);
+        }
+        const T* pa = oa + r * d + c * 8;
+        const T* pb = ob + r * d + c * 8;
+        T* po = out + r * d + c * 8;
+        float xa[8], xb[8], y[8];
+        load8(pa, xa);
+        load8(pb, xb);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y[e] = wa * xa[e] + wb * xb[e];
+        store8(po, y);
+        if (c == 0 && lse) lse[r] = l;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_attn_merge(size_t rows, int d, int dtype, const void* oa, const float* la, const void* ob,
+                             const float* lb, void* out, float* lse, hipStream_t st)
+{
+    const size_t total = rows * (size_t)(d / 8);
+    const unsigned grid = (unsigned)min((size_t)(256 * 64), (total + 255) / 256);
+    if (dtype == 0)
+        hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(grid), dim3(256), 0, st, rows, d, (const float*)oa, la,
+                           (const float*)ob, lb, (float*)out, lse);
+    else
+        hipLaunchKernelGGL(attn_merge_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, rows, d, (const uint16_t*)oa, la,
+                           (const uint16_t*)ob, lb, (uint16_t*)out, lse);
+    return hipGetLastError();
+}
 
 hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q, const void* k, const void* v,
                               char* ws, void* out, float* lse, int32_t* row_pairs, hipStream_t st)

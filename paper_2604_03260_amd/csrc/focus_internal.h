@@ -29,6 +29,8 @@ struct Layout {
     int BQ;                    // query rows per attention tile (128; 256 for bf16 at n >= LONG_N)
     int NC;                    // number of membership classes (1 in dense mode)
     int dense;                 // every causal pair allowed: one class, no masks beyond causal
+    int pair_set;              // which pairs a launch attends: 0 the whole mask, 1 only pairs that share a group
+                               // (set A of App. D), 2 only window pairs that share none (set B)
     int nblk;                  // ceil(n / SB)
     int NQP;                   // padded per-head length of the class-ordered query index
     int NKP;                   // padded per-head length of the class-ordered key arrays (multiple of KT)
@@ -93,6 +95,8 @@ hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t
 hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                               const void* v, char* ws, void* out, float* lse, int32_t* row_pairs,
                               hipStream_t st);
+hipError_t launch_attn_merge(size_t rows, int d, int dtype, const void* oa, const float* la, const void* ob,
+                             const float* lb, void* out, float* lse, hipStream_t st);
 hipError_t launch_attn_mfma(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                             const void* v, char* ws, void* out, float* lse, int32_t* row_pairs,
                             hipStream_t st);

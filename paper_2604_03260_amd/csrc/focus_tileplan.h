@@ -7,6 +7,8 @@
 //     tile's last query position (causal prefix);
 //   - otherwise: only its keys inside the union of the rows' local windows.
 // Per-element causal/window checks on positions finish the job inside a tile.
+// A launch may be restricted to one of the two disjoint parts (App. D): the classes that share
+// a group (set A) or the window spans of those that share none (set B); a tile may then have nothing to visit.
 #pragma once
 #include "focus_internal.h"
 
@@ -64,9 +66,11 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
         const int koff = kco[c2];
         int a = 0, b = 0;
         if (inter) {
-            a = koff / KT;
-            b = (koff + pre_hi + KT - 1) / KT;
-        } else {
+            if (L.pair_set != 2) {                         // set B skips the classes that share a group
+                a = koff / KT;
+                b = (koff + pre_hi + KT - 1) / KT;
+            }
+        } else if (L.pair_set != 1) {                      // set A skips the classes that share none
             int pre_lo = kbc[(size_t)bl_i * NC + c2];
             for (int e = 0; e < part_lo; ++e) pre_lo += (P.blk_lo[e] == c2) ? 1 : 0;
             if (pre_hi > pre_lo) {

@@ -19,6 +19,7 @@ FOCUS_F32, FOCUS_BF16 = 0, 1
 
 EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_workspace_views",
            "focus_route_workspace_size", "focus_route", "focus_assign_tokens",
+           "focus_attn_fwd_set", "focus_attn_merge", "focus_attn_fwd_two_call",
            "focus_last_error", "focus_version")
 
 
@@ -71,6 +72,12 @@ def load_library():
     lib.focus_attn_fwd_vector.restype = ctypes.c_int
     lib.focus_workspace_views.argtypes = [pp, vp] + [ctypes.POINTER(vp)] * 6
     lib.focus_workspace_views.restype = ctypes.c_int
+    lib.focus_attn_fwd_set.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.focus_attn_fwd_set.restype = ctypes.c_int
+    lib.focus_attn_merge.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
+    lib.focus_attn_merge.restype = ctypes.c_int
+    lib.focus_attn_fwd_two_call.argtypes = [pp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp]
+    lib.focus_attn_fwd_two_call.restype = ctypes.c_int
     rp = ctypes.POINTER(FocusRouteParams)
     lib.focus_route_workspace_size.argtypes = [rp, ctypes.POINTER(sz)]
     lib.focus_route_workspace_size.restype = ctypes.c_int
@@ -136,6 +143,29 @@ def focus_attn_fwd(p, q, k, v, workspace, out, lse=None, row_pairs=None, vector=
     fn = load_library().focus_attn_fwd_vector if vector else load_library().focus_attn_fwd
     _check(fn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
               workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse), _ptr(row_pairs), _stream()))
+
+
+FOCUS_PAIRS_ALL, FOCUS_PAIRS_SHARED, FOCUS_PAIRS_CROSS_LOCAL = 0, 1, 2
+
+
+def focus_attn_fwd_set(p, pair_set, q, k, v, workspace, out, lse=None, row_pairs=None):
+    _check(load_library().focus_attn_fwd_set(ctypes.byref(p), pair_set, _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse),
+                                             _ptr(row_pairs), _stream()))
+
+
+def focus_attn_merge(out_a, lse_a, out_b, lse_b, out, lse=None):
+    d = out_a.shape[-1]
+    rows = out_a.numel() // d
+    dtype = FOCUS_F32 if out_a.dtype == torch.float32 else FOCUS_BF16
+    _check(load_library().focus_attn_merge(rows, d, dtype, _ptr(out_a), _ptr(lse_a), _ptr(out_b), _ptr(lse_b),
+                                           _ptr(out), _ptr(lse), _stream()))
+
+
+def focus_attn_fwd_two_call(p, q, k, v, workspace, out, lse, part_out, part_lse):
+    _check(load_library().focus_attn_fwd_two_call(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse),
+                                                  _ptr(part_out), _ptr(part_lse), _stream()))
 
 
 def make_route_params(B, n, d_model, d_g, K, topk, dtype="bf16", sinkhorn_iters=10, tau=0.1):

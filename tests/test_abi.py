@@ -143,3 +143,30 @@ def test_route_null_and_workspace_errors_before_any_launch():
     wneed = focus.focus_workspace_size(p)
     assert lib.focus_assign_tokens(ctypes.byref(p), vp(0), fake, fake, wneed, vp(0), vp(0)) == focus.FOCUS_EINVAL
     assert lib.focus_assign_tokens(ctypes.byref(p), fake, fake, fake, wneed - 1, vp(0), vp(0)) == focus.FOCUS_EWORKSPACE
+
+
+# ---------------------------------------------------------------- two-call entry points
+def test_two_call_argument_errors_before_any_launch():
+    lib = focus.load_library()
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)
+    p = focus.make_params(1, 4, 2, 256, 64, 4, 1, 16)
+    need = focus.focus_workspace_size(p)
+    st = lib.focus_attn_fwd_set(ctypes.byref(p), 3, fake, fake, fake, fake, need, vp(0x2000), vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EINVAL and "pair_set" in focus.focus_last_error()
+    st = lib.focus_attn_fwd_set(ctypes.byref(p), 1, fake, fake, fake, fake, need, vp(0), vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EINVAL
+    st = lib.focus_attn_fwd_set(ctypes.byref(p), 1, fake, fake, fake, fake, need - 1, vp(0x2000), vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EWORKSPACE
+    wide = focus.make_params(1, 4, 2, 256, 64, 4, 1, 256)          # window = n
+    st = lib.focus_attn_fwd_set(ctypes.byref(wide), 2, fake, fake, fake, fake, need, vp(0x2000), vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EUNSUPPORTED
+    # merge: shapes, NULLs, alignment
+    assert lib.focus_attn_merge(4, 60, focus.FOCUS_BF16, fake, fake, fake, fake, fake, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_attn_merge(4, 64, 7, fake, fake, fake, fake, fake, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_attn_merge(4, 64, focus.FOCUS_BF16, fake, vp(0), fake, fake, fake, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_attn_merge(4, 64, focus.FOCUS_BF16, vp(0x1008), fake, fake, fake, fake, vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_attn_merge(0, 64, focus.FOCUS_BF16, fake, fake, fake, fake, fake, vp(0), vp(0)) == focus.FOCUS_OK
+    # two-call: scratch is required
+    st = lib.focus_attn_fwd_two_call(ctypes.byref(p), fake, fake, fake, fake, need, vp(0x2000), vp(0), vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EINVAL and "part_out" in focus.focus_last_error()
