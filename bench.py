@@ -37,6 +37,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-router", action="store_true")
+    ap.add_argument("--no-two-call", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of q (known size) so a counter run can be calibrated")
@@ -188,6 +189,37 @@ def main():
             "useful_tflops_step": 4.0 * w2.d * allowed2 / (ms2 * 1e-3) / 1e12,
             "allowed_fraction": allowed2 / (w2.B * w2.Hq * (w2.n * (w2.n + 1) // 2))}}
         del i2, ws2, o2, rp2
+
+    # the paper's own evaluation order (App. D): the set of pairs that share a group, the set of window pairs
+    # that share none, one softmax each, merged through their log-sum-exp -- built from the same kernels, on
+    # the same membership, as a comparator of the fused single-softmax launch
+    if not args.no_two_call and wl.window < wl.n:
+        part_out = torch.empty((2,) + tuple(q.shape), dtype=q.dtype, device="cuda")
+        part_lse = torch.empty((2, wl.B, wl.Hq, wl.n), dtype=torch.float32, device="cuda")
+        focus.focus_assign(p, q, k, cents, ws)
+        tsteps = max(2, steps // 2)
+        for _ in range(1):
+            focus.focus_attn_fwd_two_call(p, q, k, v, ws, out, lse, part_out, part_lse)
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(tsteps)]
+        for s in range(tsteps):
+            ev[s][0].record()
+            focus.focus_attn_fwd_set(p, focus.FOCUS_PAIRS_SHARED, q, k, v, ws, part_out[0], part_lse[0], None)
+            ev[s][1].record()
+            focus.focus_attn_fwd_set(p, focus.FOCUS_PAIRS_CROSS_LOCAL, q, k, v, ws, part_out[1], part_lse[1], None)
+            ev[s][2].record()
+            focus.focus_attn_merge(part_out[0], part_lse[0], part_out[1], part_lse[1], out, lse)
+            ev[s][3].record()
+        torch.cuda.synchronize()
+        t_a, t_b, t_m = (sum(e[i].elapsed_time(e[i + 1]) for e in ev) / tsteps for i in range(3))
+        result["two_call"] = {
+            "what": "App. D: set A (shared group, causal) + set B (window, no shared group) + log-sum-exp merge, "
+                    "same kernels and membership; the fused launch is ms_attn",
+            "ms_set_a": t_a, "ms_set_b": t_b, "ms_merge": t_m, "ms_attn_two_call": t_a + t_b + t_m,
+            "fused_speedup": (t_a + t_b + t_m) / ms_attn,
+            "max_abs_diff_vs_fused": float((out.float() - out_focus.float()).abs().max().item()),
+        }
+        del part_out, part_lse
 
     mq_host = mk_host = None
     if not args.no_cpu_baseline:       # the router leg below reuses the workspace: keep the per-head membership
