@@ -160,6 +160,34 @@ focus_status focus_attn_fwd_two_call(const focus_params *p, const void *q, const
                                      void *out, float *lse, void *part_out, float *part_lse,
                                      void *stream);
 
+/* ---- incremental inference: one new token per sequence against a key/value cache ----
+ *
+ * The paper evaluates generation (Sec. 3.3) but does not describe a decode kernel; this is the same
+ * mask row (App. D Eq. 3 with top-k sets) for the newest token i: keys j <= i with i - j < window or
+ * with a membership set that intersects the query's.  p->n is the CAPACITY of the caches
+ * k_cache, v_cache [B,Hkv,n,d] (DEVICE, p->dtype, 16-byte aligned).  `state` is caller-allocated
+ * DEVICE memory of focus_decode_state_size() bytes, 256-byte aligned: the membership mask of every
+ * cached key, one ascending position list per (batch, KV head, group), and scratch for the step.
+ * K up to 32 with any topk (no limit on the number of membership classes here). */
+focus_status focus_decode_state_size(const focus_params *p, size_t *bytes);
+
+/* Builds the state for the first n_ctx (0 <= n_ctx <= n) rows already in k_cache: scores every
+ * cached key against the centroids [Hkv,K,d] (fp64, index order, ties to the smaller group) and
+ * fills masks and lists.  Enqueues on `stream`. */
+focus_status focus_decode_prefill(const focus_params *p, int32_t n_ctx, const void *k_cache,
+                                  const float *centroids, void *state, size_t state_bytes,
+                                  void *stream);
+
+/* One step at position pos (the positions 0 .. pos-1 are in the caches and in the state; steps must
+ * come in order and calls on one state must not overlap): routes k_new [B,Hkv,d] and q_new
+ * [B,Hq,d], stores k_new and v_new [B,Hkv,d] at row pos of the caches, appends pos to the lists of
+ * the key's groups, then attends.  out [B,Hq,d] in p->dtype; lse (nullable) [B,Hq] fp32;
+ * row_pairs (nullable) [B,Hq] int32 = keys attended.  Three launches on `stream`. */
+focus_status focus_decode_step(const focus_params *p, int32_t pos, const void *q_new,
+                               const void *k_new, const void *v_new, const float *centroids,
+                               void *k_cache, void *v_cache, void *state, size_t state_bytes,
+                               void *out, float *lse, int32_t *row_pairs, void *stream);
+
 /* Device pointers INTO the workspace for parity checks; valid until the
  * workspace is overwritten.  Any output pointer may be NULL.
  *   mq [B,Hq,n], mk [B,Hkv,n]                   uint32 membership masks

@@ -176,6 +176,53 @@ focus_status make_route_layout(const focus_route_params* rp, focus::RouteLayout*
     return FOCUS_OK;
 }
 
+// Validates params for the incremental path (p->n is the capacity of the caches) and lays out its state.
+focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, focus::HeadMap* hm)
+{
+    using namespace focus;
+    if (!p) return fail(FOCUS_EINVAL, "params is NULL");
+    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->n < 1)
+        return fail(FOCUS_EINVAL, "B, Hq, Hkv, n must be >= 1 (got %d %d %d %d)", p->B, p->Hq, p->Hkv, p->n);
+    if (p->dtype != FOCUS_F32 && p->dtype != FOCUS_BF16) return fail(FOCUS_EINVAL, "unknown dtype %d", p->dtype);
+    if (p->K < 1 || p->K > 32) return fail(FOCUS_EINVAL, "K must be in [1,32] (got %d)", p->K);
+    if (p->topk < 1 || p->topk > p->K) return fail(FOCUS_EINVAL, "topk must be in [1,K] (got %d, K=%d)", p->topk, p->K);
+    if (p->window < 1) return fail(FOCUS_EINVAL, "window must be >= 1 (got %d)", p->window);
+    if (!(p->scale >= 0.0f) || !std::isfinite(p->scale)) return fail(FOCUS_EINVAL, "scale must be finite and >= 0");
+    if (!(p->softcap >= 0.0f) || !std::isfinite(p->softcap)) return fail(FOCUS_EINVAL, "softcap must be finite and >= 0");
+    if (p->head_map) {
+        for (int h = 0; h < p->Hq; ++h)
+            if (p->head_map[h] < 0 || p->head_map[h] >= p->Hkv)
+                return fail(FOCUS_EINVAL, "head_map[%d]=%d is outside [0,Hkv)", h, p->head_map[h]);
+    } else if (p->Hq % p->Hkv != 0) {
+        return fail(FOCUS_EINVAL, "Hq (%d) is not a multiple of Hkv (%d) and no head_map given", p->Hq, p->Hkv);
+    }
+    if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "non-causal attention is not built");
+    if (p->d != 64 && p->d != 128) return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64 or 128)", p->d);
+    if (p->Hq > MAX_HQ || p->Hkv > MAX_HQ) return fail(FOCUS_EUNSUPPORTED, "more than %d heads is not built", MAX_HQ);
+    if (p->n > (1 << 24)) return fail(FOCUS_EUNSUPPORTED, "n above 2^24 is not built");
+    if ((int64_t)p->B * p->Hq > 65535 || (int64_t)p->B * p->Hkv > 65535)
+        return fail(FOCUS_EUNSUPPORTED, "B*H above 65535 is not built");
+    memset(L, 0, sizeof(*L));
+    L->B = p->B; L->Hq = p->Hq; L->Hkv = p->Hkv; L->n = p->n; L->d = p->d;
+    L->K = p->K; L->topk = p->topk; L->window = p->window; L->dtype = p->dtype;
+    L->scale = (p->scale > 0.0f) ? p->scale : (float)(1.0 / std::sqrt((double)p->d));
+    L->softcap = p->softcap;
+    const int64_t vmax = (int64_t)std::min(p->window, p->n) + (int64_t)p->topk * (int64_t)p->n;
+    L->max_chunks = (int)((vmax + DEC_CHUNK - 1) / DEC_CHUNK);
+    for (int h = 0; h < p->Hq; ++h)
+        hm->kv[h] = (uint8_t)(p->head_map ? p->head_map[h] : h / (p->Hq / p->Hkv));
+    const size_t BHq = (size_t)p->B * p->Hq, BHk = (size_t)p->B * p->Hkv, n = (size_t)p->n;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    L->off_mk = take(BHk * n * 4);
+    L->off_lists = take(BHk * (size_t)p->K * n * 4);
+    L->off_counts = take(BHk * (size_t)p->K * 4);
+    L->off_mq = take(BHq * 4);
+    L->off_part = take(BHq * (size_t)L->max_chunks * (size_t)(p->d + 4) * 4);
+    L->total = off;
+    return FOCUS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -357,6 +404,56 @@ focus_status focus_assign_tokens(const focus_params* p, const uint32_t* token_ma
     if (st != FOCUS_OK) return st;
     hipError_t e = focus::launch_assign_tokens(L, token_masks, k, (char*)workspace, invalid_count, (hipStream_t)stream);
     if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_assign_tokens: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+focus_status focus_decode_state_size(const focus_params* p, size_t* bytes)
+{
+    if (!bytes) return fail(FOCUS_EINVAL, "bytes is NULL");
+    focus::DecodeLayout L;
+    focus::HeadMap hm;
+    focus_status st = make_decode_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    *bytes = L.total;
+    return FOCUS_OK;
+}
+
+focus_status focus_decode_prefill(const focus_params* p, int32_t n_ctx, const void* k_cache, const float* centroids,
+                                  void* state, size_t state_bytes, void* stream)
+{
+    focus::DecodeLayout L;
+    focus::HeadMap hm;
+    focus_status st = make_decode_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (n_ctx < 0 || n_ctx > p->n) return fail(FOCUS_EINVAL, "n_ctx must be in [0, n] (got %d, n=%d)", n_ctx, p->n);
+    if (!k_cache || !centroids) return fail(FOCUS_EINVAL, "k_cache and centroids must not be NULL");
+    if (!state) return fail(FOCUS_EINVAL, "state is NULL");
+    if (((uintptr_t)state & 255) != 0) return fail(FOCUS_EWORKSPACE, "state is not 256-byte aligned");
+    if (state_bytes < L.total) return fail(FOCUS_EWORKSPACE, "state has %zu bytes, %zu needed", state_bytes, L.total);
+    hipError_t e = focus::launch_decode_prefill(L, n_ctx, k_cache, centroids, (char*)state, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_decode_prefill: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+focus_status focus_decode_step(const focus_params* p, int32_t pos, const void* q_new, const void* k_new,
+                               const void* v_new, const float* centroids, void* k_cache, void* v_cache, void* state,
+                               size_t state_bytes, void* out, float* lse, int32_t* row_pairs, void* stream)
+{
+    focus::DecodeLayout L;
+    focus::HeadMap hm;
+    focus_status st = make_decode_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (pos < 0 || pos >= p->n) return fail(FOCUS_EINVAL, "pos must be in [0, n) (got %d, n=%d)", pos, p->n);
+    if (!q_new || !k_new || !v_new || !centroids || !k_cache || !v_cache || !out)
+        return fail(FOCUS_EINVAL, "q_new, k_new, v_new, centroids, k_cache, v_cache and out must not be NULL");
+    if (misaligned16(q_new) || misaligned16(k_cache) || misaligned16(v_cache))
+        return fail(FOCUS_EINVAL, "q_new, k_cache and v_cache must be 16-byte aligned");
+    if (!state) return fail(FOCUS_EINVAL, "state is NULL");
+    if (((uintptr_t)state & 255) != 0) return fail(FOCUS_EWORKSPACE, "state is not 256-byte aligned");
+    if (state_bytes < L.total) return fail(FOCUS_EWORKSPACE, "state has %zu bytes, %zu needed", state_bytes, L.total);
+    hipError_t e = focus::launch_decode_step(L, hm, pos, q_new, k_new, v_new, centroids, k_cache, v_cache, (char*)state,
+                                             out, lse, row_pairs, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_decode_step: %s", hipGetErrorString(e));
     return FOCUS_OK;
 }
 

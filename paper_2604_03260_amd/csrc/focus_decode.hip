@@ -1,0 +1,395 @@
+// focus_decode: one new token per sequence against a key/value cache (incremental inference).
+//
+// The mask row of the newest token i (App. D Eq. 3 with top-k sets, the same predicate as the
+// prefill path) is  { j <= i : i - j < w  or  Gq(i) and Gk(j) intersect }.  Memory-bound: every
+// attended key costs its K row and its V row once.  The cache state keeps, per (batch, KV head),
+// the membership mask of every cached key and one position list per group (positions are appended
+// in order, so the lists stay ascending).  A step
+//   1. routes the new key and the new queries (fp64 scores, summed in index order like the prefill
+//      scoring, top-k with ties to the smaller group), writes the key's mask, appends its position
+//      to the lists of its groups and copies the K and V rows into the caches;
+//   2. attends: the keys of the window come straight from the caches; the keys before the window
+//      come from the lists of the query's groups, cut at the window's lower edge by a binary search;
+//      a key that sits in several of the query's groups is taken from the first of them only (its
+//      mask tells).  The concatenation [window | list prefix of group 1 | group 2 | ...] is cut into
+//      chunks of DEC_CHUNK keys, one work-group each, with an online softmax per 8-component slice;
+//   3. merges the chunks' partial (o, max, sum) by their log-sum-exp weights (App. D "Merge", n-ary).
+#include "focus_internal.h"
+
+namespace focus {
+
+namespace {
+
+template <typename T> __device__ inline float dec_to_f32(T v);
+template <> __device__ inline float dec_to_f32<float>(float v) { return v; }
+template <> __device__ inline float dec_to_f32<uint16_t>(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+__device__ inline uint16_t dec_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+template <typename T> __device__ inline T dec_from_f32(float v);
+template <> __device__ inline float dec_from_f32<float>(float v) { return v; }
+template <> __device__ inline uint16_t dec_from_f32<uint16_t>(float v) { return dec_bf16_rne(v); }
+
+// 8 consecutive components as fp32
+__device__ inline void dec_load8(const float* p, float (&x)[8])
+{
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ inline void dec_load8(const uint16_t* p, float (&x)[8])
+{
+    const uint4 u = *(const uint4*)p;
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = __uint_as_float(w[e] << 16);
+        x[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+}
+
+// top-k mask of the scores held by lanes 0..K-1 of a wavefront (ties to the smaller group index)
+__device__ inline uint32_t wave_topk_mask(double s, int lane, int K, int topk)
+{
+    int beaten = 0;
+    for (int o = 0; o < K; ++o) {
+        const double so = __shfl(s, o, 64);
+        beaten += (o != lane && (so > s || (so == s && o < lane))) ? 1 : 0;
+    }
+    const unsigned long long member = __ballot(lane < K && beaten < topk);
+    return (uint32_t)member;
+}
+
+__global__ void decode_zero_kernel(int* __restrict__ p, int count)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0;
+}
+
+// ---------------------------------------------------------------- prefill of the cache state
+// membership of the cached keys 0 .. n_ctx-1: one thread per key, fp64 scores in index order
+template <typename T>
+__global__ __launch_bounds__(256) void decode_prefill_score_kernel(DecodeLayout L, int n_ctx, const T* __restrict__ kc,
+                                                                   const float* __restrict__ cents, char* __restrict__ st)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int bhk = blockIdx.y, hk = bhk % L.Hkv;
+    if (j >= n_ctx) return;
+    const T* row = kc + ((size_t)bhk * L.n + j) * L.d;
+    const float* c = cents + (size_t)hk * L.K * L.d;
+    double s[32];
+    for (int g = 0; g < L.K; ++g) s[g] = 0.0;
+    for (int t = 0; t < L.d; ++t) {
+        const double x = (double)dec_to_f32<T>(row[t]);
+        for (int g = 0; g < L.K; ++g) s[g] = fma(x, (double)c[(size_t)g * L.d + t], s[g]);
+    }
+    uint32_t m = 0;
+    for (int g = 0; g < L.K; ++g) {
+        int beaten = 0;
+        for (int o = 0; o < L.K; ++o) beaten += (o != g && (s[o] > s[g] || (s[o] == s[g] && o < g))) ? 1 : 0;
+        if (beaten < L.topk) m |= (1u << g);
+    }
+    ((uint32_t*)(st + L.off_mk))[(size_t)bhk * L.n + j] = m;
+}
+
+// position list of one group of one (batch, KV head): ordered compaction, 256 positions per round
+__global__ __launch_bounds__(256) void decode_prefill_lists_kernel(DecodeLayout L, int n_ctx, char* __restrict__ st)
+{
+    __shared__ int s_w[4];
+    __shared__ int s_base;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, bhk = blockIdx.y;
+    const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + (size_t)bhk * L.n;
+    int* list = (int*)(st + L.off_lists) + ((size_t)bhk * L.K + g) * L.n;
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    for (int j0 = 0; j0 < n_ctx; j0 += 256) {
+        const int j = j0 + tid;
+        const bool mine = j < n_ctx && ((mk[j] >> g) & 1u);
+        const unsigned long long bal = __ballot(mine);
+        const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        if (lane == 0) s_w[wave] = __popcll(bal);
+        __syncthreads();
+        int before = s_base;
+        for (int w2 = 0; w2 < wave; ++w2) before += s_w[w2];
+        if (mine) list[before + __popcll(bal & lt)] = j;
+        __syncthreads();
+        if (tid == 0) s_base += s_w[0] + s_w[1] + s_w[2] + s_w[3];
+        __syncthreads();
+    }
+    if (tid == 0) ((int*)(st + L.off_counts))[(size_t)bhk * L.K + g] = s_base;
+}
+
+// ---------------------------------------------------------------- step 1: route and append
+// One wavefront per (batch, head): heads [0, Hq) are the new queries, [Hq, Hq + Hkv) the new keys.
+template <typename T>
+__global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMap hm, int pos, const T* __restrict__ q_new,
+                                                          const T* __restrict__ k_new, const T* __restrict__ v_new,
+                                                          const float* __restrict__ cents, T* __restrict__ kc,
+                                                          T* __restrict__ vc, char* __restrict__ st)
+{
+    const int lane = threadIdx.x;
+    const int b = blockIdx.y, hh = blockIdx.x;
+    const bool is_q = hh < L.Hq;
+    const int h = is_q ? hh : hh - L.Hq;
+    const int hk = is_q ? hm.kv[h] : h;
+    const T* x = is_q ? q_new + ((size_t)b * L.Hq + h) * L.d : k_new + ((size_t)b * L.Hkv + h) * L.d;
+    double s = 0.0;
+    if (lane < L.K) {
+        const float* c = cents + ((size_t)hk * L.K + lane) * L.d;
+        for (int t = 0; t < L.d; ++t) s = fma((double)dec_to_f32<T>(x[t]), (double)c[t], s);
+    }
+    const uint32_t mask = wave_topk_mask(s, lane, L.K, L.topk);
+    if (is_q) {
+        if (lane == 0) ((uint32_t*)(st + L.off_mq))[(size_t)b * L.Hq + h] = mask;
+        return;
+    }
+    const size_t bhk = (size_t)b * L.Hkv + h;
+    if (lane == 0) ((uint32_t*)(st + L.off_mk))[bhk * L.n + pos] = mask;
+    if (lane < L.K && ((mask >> lane) & 1u)) {
+        int* cnt = (int*)(st + L.off_counts) + bhk * L.K + lane;
+        int* list = (int*)(st + L.off_lists) + (bhk * L.K + lane) * L.n;
+        const int c = *cnt;                       // single writer: this lane owns the group's list
+        list[c] = pos;
+        *cnt = c + 1;
+    }
+    const T* vrow = v_new + bhk * L.d;
+    T* kdst = kc + (bhk * L.n + pos) * L.d;
+    T* vdst = vc + (bhk * L.n + pos) * L.d;
+    for (int t = lane; t < L.d; t += 64) { kdst[t] = x[t]; vdst[t] = vrow[t]; }
+}
+
+// ---------------------------------------------------------------- step 2: attention over one chunk of the key sequence
+constexpr int DEC_U = 4;                          // keys in flight per slice
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos, const T* __restrict__ q_new,
+                                                          const T* __restrict__ kc, const T* __restrict__ vc,
+                                                          const char* __restrict__ st, float* __restrict__ part)
+{
+    constexpr int LPK = D / 8;                    // lanes that share one key (8 components each)
+    constexpr int SLOTS = 64 / LPK;               // keys a wavefront handles side by side
+    constexpr int PW = D + 4;                     // floats of one partial: o[D], max, sum, count
+    __shared__ int s_beg[34];                     // start of every segment in the concatenated sequence
+    __shared__ int s_grp[33];
+    __shared__ uint32_t s_prev[33];
+    __shared__ int s_nseg;
+    __shared__ float s_red[4][SLOTS][PW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slot = lane / LPK, sub = lane % LPK;
+    const int chunk = blockIdx.x, bhq = blockIdx.y;
+    const int b = bhq / L.Hq, h = bhq % L.Hq;
+    const size_t bhk = (size_t)b * L.Hkv + hm.kv[h];
+    const int lo_w = max(0, pos - L.window + 1);  // first position of the window
+    const uint32_t gq = ((const uint32_t*)(st + L.off_mq))[bhq];
+    const int* counts = (const int*)(st + L.off_counts) + bhk * L.K;
+    const int* lists = (const int*)(st + L.off_lists) + bhk * L.K * L.n;
+    const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + bhk * L.n;
+
+    // segments: the window, then for every group of the query the list entries below the window
+    if (tid == 0) {
+        int nseg = 1, run = pos - lo_w + 1;
+        uint32_t prev = 0;
+        s_beg[0] = 0;
+        s_grp[0] = -1;
+        s_prev[0] = 0;
+        for (int g = 0; g < L.K; ++g) {
+            if (!((gq >> g) & 1u)) continue;
+            const int* lg = lists + (size_t)g * L.n;
+            int lo = 0, hi = counts[g];           // first entry >= lo_w
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (lg[mid] < lo_w) lo = mid + 1; else hi = mid;
+            }
+            s_beg[nseg] = run;
+            s_grp[nseg] = g;
+            s_prev[nseg] = prev;
+            run += lo;
+            prev |= (1u << g);
+            ++nseg;
+        }
+        s_beg[nseg] = run;
+        s_nseg = nseg;
+    }
+    __syncthreads();
+    const int nseg = s_nseg;
+    const int vtotal = s_beg[nseg];
+    const int v0 = chunk * DEC_CHUNK;
+    float* mypart = part + ((size_t)bhq * L.max_chunks + chunk) * PW;
+    if (v0 >= vtotal) {                           // nothing in this chunk
+        for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
+        return;
+    }
+
+    float qv[8];
+    dec_load8(q_new + (size_t)bhq * D + sub * 8, qv);
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    int cnt = 0;
+    const float scale = L.scale, cap = L.softcap;
+    const T* kbase = kc + bhk * L.n * D + sub * 8;
+    const T* vbase = vc + bhk * L.n * D + sub * 8;
+
+    const int vend = min(vtotal, v0 + DEC_CHUNK);
+    // this wavefront takes keys v0 + wave*SLOTS*DEC_U*i ... in rounds of SLOTS*DEC_U keys, 4 wavefronts interleaved
+    for (int vb = v0 + wave * (SLOTS * DEC_U); vb < vend; vb += 4 * SLOTS * DEC_U) {
+        int jpos[DEC_U];
+#pragma unroll
+        for (int u = 0; u < DEC_U; ++u) {
+            const int v = vb + u * SLOTS + slot;
+            int j = -1;
+            if (v < vend) {
+                int sgi = 0;
+                while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
+                if (sgi == 0) {
+                    j = lo_w + v;
+                } else {
+                    j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
+                    const uint32_t pv = s_prev[sgi];
+                    if (pv != 0u && (mk[j] & pv) != 0u) j = -1;       // already taken from an earlier group
+                }
+            }
+            jpos[u] = j;
+        }
+        float kx[DEC_U][8], vx[DEC_U][8];
+#pragma unroll
+        for (int u = 0; u < DEC_U; ++u) {
+            const int j = max(jpos[u], 0);
+            dec_load8(kbase + (size_t)j * D, kx[u]);
+            dec_load8(vbase + (size_t)j * D, vx[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < DEC_U; ++u) {
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf(qv[e], kx[u][e], dot);
+#pragma unroll
+            for (int off = 1; off < LPK; off <<= 1) dot += __shfl_xor(dot, off, 64);
+            if (jpos[u] < 0) continue;            // uniform over the LPK lanes of the slice
+            float x = dot * scale;
+            if (cap > 0.f) x = cap * tanhf(x / cap);
+            const float m_new = fmaxf(m, x);
+            const float alpha = expf(m - m_new);  // m = -inf: 0
+            const float p = expf(x - m_new);
+            l = l * alpha + p;
+            m = m_new;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = o[e] * alpha + p * vx[u][e];
+            ++cnt;
+        }
+    }
+    // every (wavefront, slot) holds a partial softmax over its keys: fold them through LDS
+    {
+        float* r = s_red[wave][slot];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[sub * 8 + e] = o[e];
+        if (sub == 0) { r[D] = m; r[D + 1] = l; r[D + 2] = (float)cnt; }
+    }
+    __syncthreads();
+    if (tid < D) {
+        float mx = -INFINITY;
+        for (int w2 = 0; w2 < 4; ++w2)
+            for (int s2 = 0; s2 < SLOTS; ++s2) mx = fmaxf(mx, s_red[w2][s2][D]);
+        float acc = 0.f, lsum = 0.f, csum = 0.f;
+        for (int w2 = 0; w2 < 4; ++w2)
+            for (int s2 = 0; s2 < SLOTS; ++s2) {
+                const float ms = s_red[w2][s2][D];
+                const float wgt = (ms == -INFINITY) ? 0.f : expf(ms - mx);
+                acc += wgt * s_red[w2][s2][tid];
+                lsum += wgt * s_red[w2][s2][D + 1];
+                csum += s_red[w2][s2][D + 2];
+            }
+        mypart[tid] = acc;
+        if (tid == 0) { mypart[D] = mx; mypart[D + 1] = lsum; mypart[D + 2] = csum; mypart[D + 3] = 0.f; }
+    }
+}
+
+// ---------------------------------------------------------------- step 3: merge of the chunks
+template <typename T, int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeLayout L, int nchunks, const float* __restrict__ part,
+                                                         T* __restrict__ out, float* __restrict__ lse,
+                                                         int32_t* __restrict__ row_pairs)
+{
+    constexpr int PW = D + 4;
+    const int t = threadIdx.x, bhq = blockIdx.x;
+    const float* p0 = part + (size_t)bhq * L.max_chunks * PW;
+    float mx = -INFINITY;
+    for (int c = 0; c < nchunks; ++c) mx = fmaxf(mx, p0[(size_t)c * PW + D]);
+    float acc = 0.f, lsum = 0.f, csum = 0.f;
+    for (int c = 0; c < nchunks; ++c) {
+        const float* p = p0 + (size_t)c * PW;
+        const float ms = p[D];
+        if (ms == -INFINITY) continue;
+        const float wgt = expf(ms - mx);
+        acc += wgt * p[t];
+        lsum += wgt * p[D + 1];
+        csum += p[D + 2];
+    }
+    out[(size_t)bhq * D + t] = dec_from_f32<T>(lsum > 0.f ? acc / lsum : 0.f);
+    if (t == 0) {
+        if (lse) lse[bhq] = mx + logf(lsum);
+        if (row_pairs) row_pairs[bhq] = (int32_t)(csum + 0.5f);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* kc, const float* cents, char* st,
+                                 hipStream_t s)
+{
+    // counts start at zero even when nothing is cached yet (a fill kernel, not a memset: callers may capture this)
+    const int ncount = L.B * L.Hkv * L.K;
+    hipLaunchKernelGGL(decode_zero_kernel, dim3((ncount + 255) / 256), dim3(256), 0, s, (int*)(st + L.off_counts), ncount);
+    if (n_ctx == 0) return hipGetLastError();
+    dim3 g1((n_ctx + 255) / 256, L.B * L.Hkv);
+    if (L.dtype == 0)
+        hipLaunchKernelGGL(decode_prefill_score_kernel<float>, g1, dim3(256), 0, s, L, n_ctx, (const float*)kc, cents, st);
+    else
+        hipLaunchKernelGGL(decode_prefill_score_kernel<uint16_t>, g1, dim3(256), 0, s, L, n_ctx, (const uint16_t*)kc, cents, st);
+    hipLaunchKernelGGL(decode_prefill_lists_kernel, dim3(L.K, L.B * L.Hkv), dim3(256), 0, s, L, n_ctx, st);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
+                                const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out,
+                                float* lse, int32_t* row_pairs, hipStream_t s)
+{
+    hipLaunchKernelGGL(decode_route_kernel<T>, dim3(L.Hq + L.Hkv, L.B), dim3(64), 0, s, L, hm, pos, (const T*)q_new,
+                       (const T*)k_new, (const T*)v_new, cents, (T*)kc, (T*)vc, st);
+    // upper bound of the concatenated key sequence known on the host: the window plus topk lists of at most pos entries
+    const long vmax = (long)min(L.window, pos + 1) + (long)L.topk * (long)pos;
+    const int nchunks = (int)min((long)L.max_chunks, (vmax + DEC_CHUNK - 1) / DEC_CHUNK);
+    float* part = (float*)(st + L.off_part);
+    dim3 grid(nchunks, L.B * L.Hq);
+    if (L.d == 64) {
+        hipLaunchKernelGGL((decode_attn_kernel<T, 64>), grid, dim3(256), 0, s, L, hm, pos, (const T*)q_new, (const T*)kc,
+                           (const T*)vc, (const char*)st, part);
+        hipLaunchKernelGGL((decode_merge_kernel<T, 64>), dim3(L.B * L.Hq), dim3(64), 0, s, L, nchunks, part, (T*)out, lse,
+                           row_pairs);
+    } else {
+        hipLaunchKernelGGL((decode_attn_kernel<T, 128>), grid, dim3(256), 0, s, L, hm, pos, (const T*)q_new, (const T*)kc,
+                           (const T*)vc, (const char*)st, part);
+        hipLaunchKernelGGL((decode_merge_kernel<T, 128>), dim3(L.B * L.Hq), dim3(128), 0, s, L, nchunks, part, (T*)out, lse,
+                           row_pairs);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
+                              const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out, float* lse,
+                              int32_t* row_pairs, hipStream_t s)
+{
+    if (L.dtype == 0)
+        return decode_step_t<float>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+    return decode_step_t<uint16_t>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+}
+
+}  // namespace focus

@@ -85,6 +85,27 @@ struct RouteLayout {
     size_t total;
 };
 
+// Shapes and state offsets of the incremental (one token per step) path.
+constexpr int DEC_CHUNK = 1024;   // keys of the concatenated key sequence per work-group of the decode attention
+struct DecodeLayout {
+    int B, Hq, Hkv, n, d;      // n = capacity of the caches
+    int K, topk, window;
+    int dtype;
+    float scale, softcap;
+    int max_chunks;            // chunks of DEC_CHUNK keys the longest concatenated sequence can have
+    size_t off_mk;             // [B,Hkv,n] uint32 membership of the cached keys
+    size_t off_lists;          // [B,Hkv,K,n] int32 positions of every group, ascending
+    size_t off_counts;         // [B,Hkv,K] int32 list lengths
+    size_t off_mq;             // [B,Hq] uint32 membership of the current queries
+    size_t off_part;           // [B,Hq,max_chunks,d+4] fp32 partial (o, max, sum, count) per chunk
+    size_t total;
+};
+
+hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* kc, const float* cents, char* st,
+                                 hipStream_t s);
+hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
+                              const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out, float* lse,
+                              int32_t* row_pairs, hipStream_t s);
 hipError_t launch_route(const RouteLayout& R, const void* hidden, const float* wg, const float* cent, char* ws,
                         uint32_t* masks, double* soft, hipStream_t st);
 hipError_t launch_assign_tokens(const Layout& L, const uint32_t* token_masks, const void* k, char* ws,

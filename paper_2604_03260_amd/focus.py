@@ -2,7 +2,8 @@
 
 The functions mirror include/focus.h one to one (focus_workspace_size,
 focus_assign, focus_attn_fwd, focus_workspace_views, focus_route_workspace_size,
-focus_route, focus_assign_tokens, focus_last_error, focus_version).  Tensors are torch CUDA tensors used purely as device buffers;
+focus_route, focus_assign_tokens, focus_attn_fwd_set, focus_attn_merge, focus_attn_fwd_two_call,
+focus_decode_state_size, focus_decode_prefill, focus_decode_step, focus_last_error, focus_version).  Tensors are torch CUDA tensors used purely as device buffers;
 the calls are enqueued on torch's current stream.  There is no CPU fallback: a
 missing library is an error.
 """
@@ -20,6 +21,7 @@ FOCUS_F32, FOCUS_BF16 = 0, 1
 EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_workspace_views",
            "focus_route_workspace_size", "focus_route", "focus_assign_tokens",
            "focus_attn_fwd_set", "focus_attn_merge", "focus_attn_fwd_two_call",
+           "focus_decode_state_size", "focus_decode_prefill", "focus_decode_step",
            "focus_last_error", "focus_version")
 
 
@@ -78,6 +80,12 @@ def load_library():
     lib.focus_attn_merge.restype = ctypes.c_int
     lib.focus_attn_fwd_two_call.argtypes = [pp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp]
     lib.focus_attn_fwd_two_call.restype = ctypes.c_int
+    lib.focus_decode_state_size.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.focus_decode_state_size.restype = ctypes.c_int
+    lib.focus_decode_prefill.argtypes = [pp, ctypes.c_int32, vp, vp, vp, sz, vp]
+    lib.focus_decode_prefill.restype = ctypes.c_int
+    lib.focus_decode_step.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.focus_decode_step.restype = ctypes.c_int
     rp = ctypes.POINTER(FocusRouteParams)
     lib.focus_route_workspace_size.argtypes = [rp, ctypes.POINTER(sz)]
     lib.focus_route_workspace_size.restype = ctypes.c_int
@@ -166,6 +174,29 @@ def focus_attn_fwd_two_call(p, q, k, v, workspace, out, lse, part_out, part_lse)
     _check(load_library().focus_attn_fwd_two_call(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
                                                   workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse),
                                                   _ptr(part_out), _ptr(part_lse), _stream()))
+
+
+def focus_decode_state_size(p):
+    out = ctypes.c_size_t(0)
+    _check(load_library().focus_decode_state_size(ctypes.byref(p), ctypes.byref(out)))
+    return out.value
+
+
+def alloc_decode_state(p, device="cuda"):
+    nbytes = focus_decode_state_size(p)
+    return torch.empty(((nbytes + 255) // 256) * 256, dtype=torch.uint8, device=device)
+
+
+def focus_decode_prefill(p, n_ctx, k_cache, centroids, state):
+    _check(load_library().focus_decode_prefill(ctypes.byref(p), n_ctx, _ptr(k_cache), _ptr(centroids), _ptr(state),
+                                               state.numel() * state.element_size(), _stream()))
+
+
+def focus_decode_step(p, pos, q_new, k_new, v_new, centroids, k_cache, v_cache, state, out, lse=None, row_pairs=None):
+    _check(load_library().focus_decode_step(ctypes.byref(p), pos, _ptr(q_new), _ptr(k_new), _ptr(v_new),
+                                            _ptr(centroids), _ptr(k_cache), _ptr(v_cache), _ptr(state),
+                                            state.numel() * state.element_size(), _ptr(out), _ptr(lse),
+                                            _ptr(row_pairs), _stream()))
 
 
 def make_route_params(B, n, d_model, d_g, K, topk, dtype="bf16", sinkhorn_iters=10, tau=0.1):

@@ -170,3 +170,27 @@ def test_two_call_argument_errors_before_any_launch():
     # two-call: scratch is required
     st = lib.focus_attn_fwd_two_call(ctypes.byref(p), fake, fake, fake, fake, need, vp(0x2000), vp(0), vp(0), vp(0), vp(0))
     assert st == focus.FOCUS_EINVAL and "part_out" in focus.focus_last_error()
+
+
+# ---------------------------------------------------------------- incremental path
+def test_decode_argument_errors_before_any_launch():
+    lib = focus.load_library()
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)
+    p = focus.make_params(1, 4, 2, 4096, 128, 32, 4, 64)           # C(32,4) classes: fine for decode
+    need = focus.focus_decode_state_size(p)
+    assert need > 0 and need % 256 == 0
+    st = lib.focus_workspace_size(ctypes.byref(p), ctypes.byref(ctypes.c_size_t(0)))
+    assert st == focus.FOCUS_EUNSUPPORTED                           # ... but not for the class-bucketed prefill path
+    assert lib.focus_decode_prefill(ctypes.byref(p), -1, fake, fake, fake, need, vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_decode_prefill(ctypes.byref(p), 4097, fake, fake, fake, need, vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_decode_prefill(ctypes.byref(p), 10, vp(0), fake, fake, need, vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_decode_prefill(ctypes.byref(p), 10, fake, fake, fake, need - 1, vp(0)) == focus.FOCUS_EWORKSPACE
+    assert lib.focus_decode_prefill(ctypes.byref(p), 10, fake, fake, vp(0x1010), need, vp(0)) == focus.FOCUS_EWORKSPACE
+    args = [fake] * 6
+    assert lib.focus_decode_step(ctypes.byref(p), 4096, *args, fake, need, fake, vp(0), vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_decode_step(ctypes.byref(p), -1, *args, fake, need, fake, vp(0), vp(0), vp(0)) == focus.FOCUS_EINVAL
+    assert lib.focus_decode_step(ctypes.byref(p), 5, *args, fake, need - 1, fake, vp(0), vp(0), vp(0)) == focus.FOCUS_EWORKSPACE
+    assert lib.focus_decode_step(ctypes.byref(p), 5, *args, fake, need, vp(0), vp(0), vp(0), vp(0)) == focus.FOCUS_EINVAL
+    bad = focus.make_params(1, 4, 2, 4096, 96, 4, 2, 64)
+    assert lib.focus_decode_state_size(ctypes.byref(bad), ctypes.byref(ctypes.c_size_t(0))) == focus.FOCUS_EUNSUPPORTED

@@ -1,0 +1,129 @@
+"""GPU parity of the incremental path (focus_decode_prefill / focus_decode_step) against the oracle.
+
+A synthetic sequence of n tokens is split into a cached prefix (n0 tokens, state built by
+focus_decode_prefill) and steps n0 .. n-1 (focus_decode_step, one token each).  The output of the step at
+position i is row i of the oracle's attention over the whole sequence (the mask is causal, so row i sees
+keys 0..i only); memberships of cached keys and group lists are checked bit for bit, outputs to the
+tolerances of the prefill path, the number of attended keys exactly."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import focus_oracle as fo
+from paper_2604_03260_amd import focus, workloads
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+
+
+def run_decode(wl, inp, n0, steps, head_map=None):
+    """Caches hold the first n0 tokens; then `steps` tokens are decoded.  Returns per-step outputs."""
+    p = harness.params_of(wl, head_map)
+    state = focus.alloc_decode_state(p)
+    kc = torch.zeros_like(inp["k"])
+    vc = torch.zeros_like(inp["v"])
+    kc[:, :, :n0] = inp["k"][:, :, :n0]
+    vc[:, :, :n0] = inp["v"][:, :, :n0]
+    focus.focus_decode_prefill(p, n0, kc, inp["centroids"], state)
+    outs, lses, pairs = [], [], []
+    for i in range(n0, n0 + steps):
+        q_new = inp["q"][:, :, i].contiguous()
+        k_new = inp["k"][:, :, i].contiguous()
+        v_new = inp["v"][:, :, i].contiguous()
+        out = torch.full_like(q_new, float("nan"))
+        lse = torch.full((wl.B, wl.Hq), float("nan"), dtype=torch.float32, device="cuda")
+        rp = torch.full((wl.B, wl.Hq), -1, dtype=torch.int32, device="cuda")
+        focus.focus_decode_step(p, i, q_new, k_new, v_new, inp["centroids"], kc, vc, state, out, lse, rp)
+        outs.append(out); lses.append(lse); pairs.append(rp)
+    torch.cuda.synchronize()
+    return dict(out=torch.stack(outs, 2), lse=torch.stack(lses, 2), row_pairs=torch.stack(pairs, 2), kc=kc, vc=vc,
+                state=state, params=p)
+
+
+def check_decode(wl, inp, res, n0, steps, head_map=None):
+    pb = harness.problem_of(wl, head_map)
+    qh, kh, vh = (workloads.to_host_bits(inp[x]) for x in ("q", "k", "v"))
+    mq, mk = harness.oracle_membership(wl, inp, head_map)
+    rows = np.array([(b, h, i) for b in range(wl.B) for h in range(wl.Hq) for i in range(n0, n0 + steps)], dtype=np.int32)
+    o_ref, l_ref, p_ref = fo.attn_rows(pb, qh, kh, vh, mq, mk, rows=rows)
+    o = res["out"].float().cpu().numpy().astype(np.float64).reshape(-1, wl.d)       # [B,Hq,steps,d] in the same order
+    l = res["lse"].cpu().numpy().astype(np.float64).reshape(-1)
+    rp = res["row_pairs"].cpu().numpy().astype(np.int64).reshape(-1)
+    tol = harness.TOL[wl.dtype]
+    assert np.isfinite(o).all()
+    err = np.abs(o - o_ref)
+    assert err.max() <= tol["out_max"] and err.mean() <= tol["out_mean"], (err.max(), err.mean())
+    assert np.abs(l - l_ref).max() <= tol["lse"]
+    assert np.array_equal(rp, p_ref), "attended key counts differ"
+    # the caches now hold the whole prefix + decoded tokens
+    n1 = n0 + steps
+    assert torch.equal(res["kc"][:, :, :n1], inp["k"][:, :, :n1]) and torch.equal(res["vc"][:, :, :n1], inp["v"][:, :, :n1])
+    return mk
+
+
+CASES = [
+    # B, Hq, Hkv, n, d, dtype, K, topk, window, softcap, n0, steps
+    (1, 2, 2, 300, 64, "f32", 4, 2, 16, 0.0, 250, 50),
+    (2, 4, 2, 1500, 128, "bf16", 4, 2, 64, 0.0, 1490, 10),
+    (1, 8, 2, 3000, 128, "bf16", 8, 1, 100, 50.0, 2990, 10),
+    (1, 2, 1, 40, 64, "bf16", 4, 2, 8, 0.0, 0, 40),              # from an empty cache, token by token
+    (1, 2, 2, 700, 64, "f32", 32, 4, 5, 0.0, 690, 10),           # C(32,4) classes: beyond the prefill path's limit
+    (1, 4, 4, 2500, 128, "bf16", 4, 3, 3000, 0.0, 2495, 5),      # window wider than the sequence
+    (1, 2, 2, 520, 64, "bf16", 1, 1, 4, 0.0, 515, 5),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,n,d,dtype,K,topk,w,cap,n0,steps", CASES)
+def test_decode_steps_small(B, Hq, Hkv, n, d, dtype, K, topk, w, cap, n0, steps):
+    wl = workloads.Workload("dec", 80 + K + topk, B, Hq, Hkv, n, d, dtype, K, topk, w, softcap=cap, mixture=3)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = run_decode(wl, inp, n0, steps)
+    check_decode(wl, inp, res, n0, steps)
+
+
+def test_decode_state_matches_oracle_lists():
+    wl = workloads.Workload("dec", 95, 2, 4, 2, 900, 64, "bf16", 6, 2, 32, mixture=3)
+    inp = workloads.make_inputs(wl, "cuda")
+    n0, steps = 600, 300
+    res = run_decode(wl, inp, n0, steps)
+    mk = check_decode(wl, inp, res, n0, steps)
+    # state layout (as documented in focus.h): masks [B,Hkv,n], lists [B,Hkv,K,n], counts [B,Hkv,K] at the start
+    st = res["state"]
+    BHk = wl.B * wl.Hkv
+    off = 0
+    got_mk = st[off:off + BHk * wl.n * 4].view(torch.int32).cpu().numpy().view(np.uint32).reshape(wl.B, wl.Hkv, wl.n)
+    assert np.array_equal(got_mk, mk)
+    off = ((BHk * wl.n * 4 + 255) // 256) * 256
+    lists = st[off:off + BHk * wl.K * wl.n * 4].view(torch.int32).cpu().numpy().reshape(wl.B, wl.Hkv, wl.K, wl.n)
+    off += ((BHk * wl.K * wl.n * 4 + 255) // 256) * 256
+    counts = st[off:off + BHk * wl.K * 4].view(torch.int32).cpu().numpy().reshape(wl.B, wl.Hkv, wl.K)
+    for b in range(wl.B):
+        for h in range(wl.Hkv):
+            for g in range(wl.K):
+                want = np.nonzero((mk[b, h] >> g) & 1)[0]
+                assert counts[b, h, g] == len(want)
+                assert np.array_equal(lists[b, h, g, :len(want)], want)
+
+
+def test_decode_with_head_map():
+    wl = workloads.Workload("dec", 96, 1, 6, 3, 800, 64, "bf16", 4, 2, 20, mixture=3)
+    inp = workloads.make_inputs(wl, "cuda")
+    hm = [2, 0, 1, 1, 2, 0]
+    res = run_decode(wl, inp, 780, 20, head_map=hm)
+    check_decode(wl, inp, res, 780, 20, head_map=hm)
+
+
+def test_decode_agrees_with_prefill_kernel_long_context():
+    """cfg3's shape: the last rows of the prefill kernel's output against decode steps at the same positions."""
+    wl = workloads.CONFIGS["cfg3"]
+    inp = workloads.make_inputs(wl, "cuda")
+    steps = 4
+    n0 = wl.n - steps
+    res = run_decode(wl, inp, n0, steps)
+    full = harness.run_gpu(wl, inp)
+    a = res["out"].float()
+    b = full["out"][:, :, n0:].float()
+    assert (a - b).abs().max().item() <= 2e-2
+    assert torch.equal(res["row_pairs"], full["row_pairs"][:, :, n0:])
+    assert (res["lse"] - full["lse"][:, :, n0:]).abs().max().item() <= 1e-2
+    check_decode(wl, inp, res, n0, steps)
