@@ -217,6 +217,7 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     L->off_mk = take(BHk * n * 4);
     L->off_lists = take(BHk * (size_t)p->K * n * 4);
     L->off_counts = take(BHk * (size_t)p->K * 4);
+    L->off_wp = take(BHk * (size_t)p->K * 4);
     L->off_mq = take(BHq * 4);
     L->off_part = take(BHq * (size_t)L->max_chunks * (size_t)(p->d + 4) * 4);
     L->total = off;

@@ -9,7 +9,8 @@
 //      scoring, top-k with ties to the smaller group), writes the key's mask, appends its position
 //      to the lists of its groups and copies the K and V rows into the caches;
 //   2. attends: the keys of the window come straight from the caches; the keys before the window
-//      come from the lists of the query's groups, cut at the window's lower edge by a binary search;
+//      come from the lists of the query's groups, cut at the window's lower edge (a per-list pointer that
+//      step 1 advances with the window);
 //      a key that sits in several of the query's groups is taken from the first of them only (its
 //      mask tells).  The concatenation [window | list prefix of group 1 | group 2 | ...] is cut into
 //      chunks of DEC_CHUNK keys, one work-group each, with an online softmax per 8-component slice;
@@ -107,9 +108,13 @@ __global__ __launch_bounds__(256) void decode_prefill_lists_kernel(DecodeLayout 
     int* list = (int*)(st + L.off_lists) + ((size_t)bhk * L.K + g) * L.n;
     if (tid == 0) s_base = 0;
     __syncthreads();
+    // entries below the window of the next step (position n_ctx): positions < n_ctx - window + 1
+    const int lo_next = n_ctx - L.window + 1;
+    int below = 0;
     for (int j0 = 0; j0 < n_ctx; j0 += 256) {
         const int j = j0 + tid;
         const bool mine = j < n_ctx && ((mk[j] >> g) & 1u);
+        below += (mine && j < lo_next) ? 1 : 0;
         const unsigned long long bal = __ballot(mine);
         const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
         if (lane == 0) s_w[wave] = __popcll(bal);
@@ -122,26 +127,42 @@ __global__ __launch_bounds__(256) void decode_prefill_lists_kernel(DecodeLayout 
         __syncthreads();
     }
     if (tid == 0) ((int*)(st + L.off_counts))[(size_t)bhk * L.K + g] = s_base;
+    // block-wide sum of `below` -> the group's window pointer
+    __syncthreads();
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) below += __shfl_xor(below, off, 64);
+    if (lane == 0) s_w[wave] = below;
+    __syncthreads();
+    if (tid == 0) ((int*)(st + L.off_wp))[(size_t)bhk * L.K + g] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
 }
 
 // ---------------------------------------------------------------- step 1: route and append
 // One wavefront per (batch, head): heads [0, Hq) are the new queries, [Hq, Hq + Hkv) the new keys.
+// The vector and the K centroid rows are staged in LDS first, so the fp64 chain of lane g (group g,
+// components in index order) runs from LDS instead of waiting for a global load per component.
 template <typename T>
 __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMap hm, int pos, const T* __restrict__ q_new,
                                                           const T* __restrict__ k_new, const T* __restrict__ v_new,
                                                           const float* __restrict__ cents, T* __restrict__ kc,
                                                           T* __restrict__ vc, char* __restrict__ st)
 {
+    __shared__ float s_x[128];
+    __shared__ float s_c[32 * 129];               // row stride d + 1: the K lanes read K different rows
     const int lane = threadIdx.x;
     const int b = blockIdx.y, hh = blockIdx.x;
     const bool is_q = hh < L.Hq;
     const int h = is_q ? hh : hh - L.Hq;
     const int hk = is_q ? hm.kv[h] : h;
-    const T* x = is_q ? q_new + ((size_t)b * L.Hq + h) * L.d : k_new + ((size_t)b * L.Hkv + h) * L.d;
+    const int d = L.d;
+    const T* x = is_q ? q_new + ((size_t)b * L.Hq + h) * d : k_new + ((size_t)b * L.Hkv + h) * d;
+    for (int t = lane; t < d; t += 64) s_x[t] = dec_to_f32<T>(x[t]);
+    const float* c = cents + (size_t)hk * L.K * d;
+    for (int e = lane; e < L.K * d; e += 64) s_c[(e / d) * (d + 1) + e % d] = c[e];
+    __syncthreads();
     double s = 0.0;
     if (lane < L.K) {
-        const float* c = cents + ((size_t)hk * L.K + lane) * L.d;
-        for (int t = 0; t < L.d; ++t) s = fma((double)dec_to_f32<T>(x[t]), (double)c[t], s);
+        const float* cr = s_c + lane * (d + 1);
+        for (int t = 0; t < d; ++t) s = fma((double)s_x[t], (double)cr[t], s);
     }
     const uint32_t mask = wave_topk_mask(s, lane, L.K, L.topk);
     if (is_q) {
@@ -153,18 +174,86 @@ __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMa
     if (lane < L.K && ((mask >> lane) & 1u)) {
         int* cnt = (int*)(st + L.off_counts) + bhk * L.K + lane;
         int* list = (int*)(st + L.off_lists) + (bhk * L.K + lane) * L.n;
-        const int c = *cnt;                       // single writer: this lane owns the group's list
-        list[c] = pos;
-        *cnt = c + 1;
+        const int cn = *cnt;                      // single writer: this lane owns the group's list
+        list[cn] = pos;
+        *cnt = cn + 1;
     }
-    const T* vrow = v_new + bhk * L.d;
-    T* kdst = kc + (bhk * L.n + pos) * L.d;
-    T* vdst = vc + (bhk * L.n + pos) * L.d;
-    for (int t = lane; t < L.d; t += 64) { kdst[t] = x[t]; vdst[t] = vrow[t]; }
+    if (lane < L.K) {
+        // window pointer: number of list entries below this step's window.  The window's lower edge moves
+        // with pos and positions are unique, so the pointer normally advances by at most one per step.
+        const int lo_w = pos - L.window + 1;
+        const int cn = ((const int*)(st + L.off_counts))[bhk * L.K + lane] - (((mask >> lane) & 1u) ? 1 : 0);
+        const int* list = (const int*)(st + L.off_lists) + (bhk * L.K + lane) * L.n;
+        int* wp = (int*)(st + L.off_wp) + bhk * L.K + lane;
+        int w = *wp;
+        while (w < cn && list[w] < lo_w) ++w;     // entries before this step's append only (pos itself is in the window)
+        *wp = w;
+    }
+    const T* vrow = v_new + bhk * d;
+    T* kdst = kc + (bhk * L.n + pos) * d;
+    T* vdst = vc + (bhk * L.n + pos) * d;
+    for (int t = lane; t < d; t += 64) { kdst[t] = x[t]; vdst[t] = vrow[t]; }
 }
 
 // ---------------------------------------------------------------- step 2: attention over one chunk of the key sequence
-constexpr int DEC_U = 4;                          // keys in flight per slice
+// 8 consecutive components of a cache row, kept packed until they are used
+template <typename T> struct Raw8;
+template <> struct Raw8<uint16_t> {
+    uint4 u;
+    __device__ inline void load(const uint16_t* p) { u = *(const uint4*)p; }
+    __device__ inline void unpack(float (&x)[8]) const
+    {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[2 * e] = __uint_as_float(w[e] << 16);
+            x[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+        }
+    }
+};
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ inline void load(const float* p) { a = *(const float4*)p; b = *(const float4*)(p + 4); }
+    __device__ inline void unpack(float (&x)[8]) const
+    {
+        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    }
+};
+
+// sum over the LPK (8 or 16) adjacent lanes that share a key, by DPP lane permutations (no LDS):
+// xor 1, xor 2 inside quads, then mirror inside 8 lanes, then mirror inside the 16-lane row
+template <int LPK>
+__device__ inline float slice_sum(float x)
+{
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));   // row_half_mirror
+    if constexpr (LPK == 16)
+        x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false));  // row_mirror
+    return x;
+}
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 dec_bf16x2;
+
+// q . k over the 8 components of a slice: bf16 pairs go straight into v_dot2 (exact products, fp32 sum)
+__device__ inline float slice_dot(const Raw8<uint16_t>& q, const Raw8<uint16_t>& k)
+{
+    float d = 0.f;
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, q.u.x), __builtin_bit_cast(dec_bf16x2, k.u.x), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, q.u.y), __builtin_bit_cast(dec_bf16x2, k.u.y), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, q.u.z), __builtin_bit_cast(dec_bf16x2, k.u.z), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, q.u.w), __builtin_bit_cast(dec_bf16x2, k.u.w), d, false);
+    return d;
+}
+__device__ inline float slice_dot(const Raw8<float>& q, const Raw8<float>& k)
+{
+    float d = q.a.x * k.a.x;
+    d = fmaf(q.a.y, k.a.y, d); d = fmaf(q.a.z, k.a.z, d); d = fmaf(q.a.w, k.a.w, d);
+    d = fmaf(q.b.x, k.b.x, d); d = fmaf(q.b.y, k.b.y, d); d = fmaf(q.b.z, k.b.z, d); d = fmaf(q.b.w, k.b.w, d);
+    return d;
+}
+
+constexpr float DEC_LOG2E = 1.4426950408889634f;
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos, const T* __restrict__ q_new,
@@ -173,11 +262,13 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
 {
     constexpr int LPK = D / 8;                    // lanes that share one key (8 components each)
     constexpr int SLOTS = 64 / LPK;               // keys a wavefront handles side by side
-    constexpr int PW = D + 4;                     // floats of one partial: o[D], max, sum, count
+    constexpr int PW = D + 4;                     // floats of one partial: o[D], max (log2 units), sum, count
+    constexpr int U = sizeof(T) == 2 ? 8 : 4;     // keys in flight per slice: U K rows and U V rows loaded before use
     __shared__ int s_beg[34];                     // start of every segment in the concatenated sequence
     __shared__ int s_grp[33];
     __shared__ uint32_t s_prev[33];
     __shared__ int s_nseg;
+    __shared__ int s_j[DEC_CHUNK];                // cache row of every key of the chunk, -1 = skipped
     __shared__ float s_red[4][SLOTS][PW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -187,7 +278,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     const size_t bhk = (size_t)b * L.Hkv + hm.kv[h];
     const int lo_w = max(0, pos - L.window + 1);  // first position of the window
     const uint32_t gq = ((const uint32_t*)(st + L.off_mq))[bhq];
-    const int* counts = (const int*)(st + L.off_counts) + bhk * L.K;
+    const int* wptr = (const int*)(st + L.off_wp) + bhk * L.K;
     const int* lists = (const int*)(st + L.off_lists) + bhk * L.K * L.n;
     const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + bhk * L.n;
 
@@ -200,16 +291,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
         s_prev[0] = 0;
         for (int g = 0; g < L.K; ++g) {
             if (!((gq >> g) & 1u)) continue;
-            const int* lg = lists + (size_t)g * L.n;
-            int lo = 0, hi = counts[g];           // first entry >= lo_w
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (lg[mid] < lo_w) lo = mid + 1; else hi = mid;
-            }
             s_beg[nseg] = run;
             s_grp[nseg] = g;
             s_prev[nseg] = prev;
-            run += lo;
+            run += wptr[g];                       // list entries below the window (kept by the route kernel)
             prev |= (1u << g);
             ++nseg;
         }
@@ -225,64 +310,74 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
         for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
         return;
     }
+    // resolve the whole chunk at once: list entry -> position -> (mask check); all loads independent
+    const int nk = min(vtotal - v0, DEC_CHUNK);
+    for (int i = tid; i < DEC_CHUNK; i += 256) {
+        int j = -1;
+        if (i < nk) {
+            const int v = v0 + i;
+            int sgi = 0;
+            while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
+            if (sgi == 0) {
+                j = lo_w + v;
+            } else {
+                j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
+                const uint32_t pv = s_prev[sgi];
+                if (pv != 0u && (mk[j] & pv) != 0u) j = -1;           // already taken from an earlier group
+            }
+        }
+        s_j[i] = j;
+    }
+    __syncthreads();
 
-    float qv[8];
-    dec_load8(q_new + (size_t)bhq * D + sub * 8, qv);
+    Raw8<T> qr;
+    qr.load(q_new + (size_t)bhq * D + sub * 8);
     float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = 0.f;
-    float m = -INFINITY, l = 0.f;
+    float m = -INFINITY, l = 0.f;                 // running max in log2 units, running sum
     int cnt = 0;
-    const float scale = L.scale, cap = L.softcap;
+    const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
     const T* kbase = kc + bhk * L.n * D + sub * 8;
     const T* vbase = vc + bhk * L.n * D + sub * 8;
 
-    const int vend = min(vtotal, v0 + DEC_CHUNK);
-    // this wavefront takes keys v0 + wave*SLOTS*DEC_U*i ... in rounds of SLOTS*DEC_U keys, 4 wavefronts interleaved
-    for (int vb = v0 + wave * (SLOTS * DEC_U); vb < vend; vb += 4 * SLOTS * DEC_U) {
-        int jpos[DEC_U];
+    // rounds of SLOTS*U keys per wavefront, the 4 wavefronts interleaved; one softmax update per round
+    for (int r0 = wave * (SLOTS * U); r0 < nk; r0 += 4 * SLOTS * U) {
+        int jpos[U];
+        Raw8<T> kr[U], vr[U];
 #pragma unroll
-        for (int u = 0; u < DEC_U; ++u) {
-            const int v = vb + u * SLOTS + slot;
-            int j = -1;
-            if (v < vend) {
-                int sgi = 0;
-                while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
-                if (sgi == 0) {
-                    j = lo_w + v;
-                } else {
-                    j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
-                    const uint32_t pv = s_prev[sgi];
-                    if (pv != 0u && (mk[j] & pv) != 0u) j = -1;       // already taken from an earlier group
-                }
-            }
-            jpos[u] = j;
-        }
-        float kx[DEC_U][8], vx[DEC_U][8];
-#pragma unroll
-        for (int u = 0; u < DEC_U; ++u) {
+        for (int u = 0; u < U; ++u) {
+            jpos[u] = s_j[r0 + u * SLOTS + slot];                     // r0 + U*SLOTS <= DEC_CHUNK: in bounds
             const int j = max(jpos[u], 0);
-            dec_load8(kbase + (size_t)j * D, kx[u]);
-            dec_load8(vbase + (size_t)j * D, vx[u]);
+            kr[u].load(kbase + (size_t)j * D);
+            vr[u].load(vbase + (size_t)j * D);
         }
+        float xs[U];
+        float mx = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < DEC_U; ++u) {
-            float dot = 0.f;
+        for (int u = 0; u < U; ++u) {
+            const float dot = slice_sum<LPK>(slice_dot(qr, kr[u]));
+            float x = dot * sl2;
+            if (cap > 0.f) x = cap * DEC_LOG2E * tanhf(dot * L.scale / cap);
+            xs[u] = (jpos[u] < 0) ? -INFINITY : x;
+            mx = fmaxf(mx, xs[u]);
+            cnt += (jpos[u] < 0) ? 0 : 1;
+        }
+        const float m_new = fmaxf(m, mx);
+        if (m_new == -INFINITY) continue;         // nothing attended so far (uniform over the slice)
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);        // m = -inf: 0
+        m = m_new;
+        l *= alpha;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dot = fmaf(qv[e], kx[u][e], dot);
+        for (int e = 0; e < 8; ++e) o[e] *= alpha;
 #pragma unroll
-            for (int off = 1; off < LPK; off <<= 1) dot += __shfl_xor(dot, off, 64);
-            if (jpos[u] < 0) continue;            // uniform over the LPK lanes of the slice
-            float x = dot * scale;
-            if (cap > 0.f) x = cap * tanhf(x / cap);
-            const float m_new = fmaxf(m, x);
-            const float alpha = expf(m - m_new);  // m = -inf: 0
-            const float p = expf(x - m_new);
-            l = l * alpha + p;
-            m = m_new;
+        for (int u = 0; u < U; ++u) {
+            const float pr = __builtin_amdgcn_exp2f(xs[u] - m_new);   // skipped keys: exp2(-inf) = 0
+            float vx[8];
+            vr[u].unpack(vx);
+            l += pr;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = o[e] * alpha + p * vx[u][e];
-            ++cnt;
+            for (int e = 0; e < 8; ++e) o[e] = fmaf(pr, vx[e], o[e]);
         }
     }
     // every (wavefront, slot) holds a partial softmax over its keys: fold them through LDS
@@ -301,7 +396,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
         for (int w2 = 0; w2 < 4; ++w2)
             for (int s2 = 0; s2 < SLOTS; ++s2) {
                 const float ms = s_red[w2][s2][D];
-                const float wgt = (ms == -INFINITY) ? 0.f : expf(ms - mx);
+                const float wgt = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - mx);
                 acc += wgt * s_red[w2][s2][tid];
                 lsum += wgt * s_red[w2][s2][D + 1];
                 csum += s_red[w2][s2][D + 2];
@@ -312,30 +407,51 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
 }
 
 // ---------------------------------------------------------------- step 3: merge of the chunks
+// One work-group per (batch, query head).  A chunk's partial is read by D/4 threads (4 components each);
+// the 256 / (D/4) groups of threads take the chunks round-robin, then fold through LDS.
 template <typename T, int D>
-__global__ __launch_bounds__(D) void decode_merge_kernel(DecodeLayout L, int nchunks, const float* __restrict__ part,
-                                                         T* __restrict__ out, float* __restrict__ lse,
-                                                         int32_t* __restrict__ row_pairs)
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int nchunks, const float* __restrict__ part,
+                                                           T* __restrict__ out, float* __restrict__ lse,
+                                                           int32_t* __restrict__ row_pairs)
 {
     constexpr int PW = D + 4;
-    const int t = threadIdx.x, bhq = blockIdx.x;
+    constexpr int TPG = D / 4;                    // threads per group
+    constexpr int NG = 256 / TPG;
+    __shared__ float s_w[4];
+    __shared__ float s_acc[NG][D + 4];
+    const int tid = threadIdx.x, t = tid % TPG, grp = tid / TPG, bhq = blockIdx.x;
     const float* p0 = part + (size_t)bhq * L.max_chunks * PW;
     float mx = -INFINITY;
-    for (int c = 0; c < nchunks; ++c) mx = fmaxf(mx, p0[(size_t)c * PW + D]);
-    float acc = 0.f, lsum = 0.f, csum = 0.f;
-    for (int c = 0; c < nchunks; ++c) {
+    for (int c = tid; c < nchunks; c += 256) mx = fmaxf(mx, p0[(size_t)c * PW + D]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    if ((tid & 63) == 0) s_w[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(s_w[0], s_w[1]), fmaxf(s_w[2], s_w[3]));
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lsum = 0.f, csum = 0.f;
+    for (int c = grp; c < nchunks; c += NG) {
         const float* p = p0 + (size_t)c * PW;
-        const float ms = p[D];
-        if (ms == -INFINITY) continue;
-        const float wgt = expf(ms - mx);
-        acc += wgt * p[t];
-        lsum += wgt * p[D + 1];
-        csum += p[D + 2];
+        const float4 tail = *(const float4*)(p + D);                  // max (log2 units), sum, count, unused
+        if (tail.x == -INFINITY) continue;
+        const float4 ov = *(const float4*)(p + 4 * t);
+        const float wgt = __builtin_amdgcn_exp2f(tail.x - mx);
+        acc.x = fmaf(wgt, ov.x, acc.x); acc.y = fmaf(wgt, ov.y, acc.y);
+        acc.z = fmaf(wgt, ov.z, acc.z); acc.w = fmaf(wgt, ov.w, acc.w);
+        lsum = fmaf(wgt, tail.y, lsum);
+        csum += tail.z;
     }
-    out[(size_t)bhq * D + t] = dec_from_f32<T>(lsum > 0.f ? acc / lsum : 0.f);
-    if (t == 0) {
-        if (lse) lse[bhq] = mx + logf(lsum);
-        if (row_pairs) row_pairs[bhq] = (int32_t)(csum + 0.5f);
+    *(float4*)(&s_acc[grp][4 * t]) = acc;
+    if (t == 0) { s_acc[grp][D] = lsum; s_acc[grp][D + 1] = csum; }
+    __syncthreads();
+    if (tid < D) {
+        float a = 0.f, ls = 0.f, cs = 0.f;
+        for (int g2 = 0; g2 < NG; ++g2) { a += s_acc[g2][tid]; ls += s_acc[g2][D]; cs += s_acc[g2][D + 1]; }
+        out[(size_t)bhq * D + tid] = dec_from_f32<T>(ls > 0.f ? a / ls : 0.f);
+        if (tid == 0) {
+            if (lse) lse[bhq] = (mx + __builtin_amdgcn_logf(ls)) * (1.f / DEC_LOG2E);
+            if (row_pairs) row_pairs[bhq] = (int32_t)(cs + 0.5f);
+        }
     }
 }
 
@@ -345,7 +461,7 @@ hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* k
                                  hipStream_t s)
 {
     // counts start at zero even when nothing is cached yet (a fill kernel, not a memset: callers may capture this)
-    const int ncount = L.B * L.Hkv * L.K;
+    const int ncount = (int)((L.off_wp - L.off_counts) / 4) + L.B * L.Hkv * L.K;      // counts, padding, window pointers
     hipLaunchKernelGGL(decode_zero_kernel, dim3((ncount + 255) / 256), dim3(256), 0, s, (int*)(st + L.off_counts), ncount);
     if (n_ctx == 0) return hipGetLastError();
     dim3 g1((n_ctx + 255) / 256, L.B * L.Hkv);
@@ -372,12 +488,12 @@ static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int po
     if (L.d == 64) {
         hipLaunchKernelGGL((decode_attn_kernel<T, 64>), grid, dim3(256), 0, s, L, hm, pos, (const T*)q_new, (const T*)kc,
                            (const T*)vc, (const char*)st, part);
-        hipLaunchKernelGGL((decode_merge_kernel<T, 64>), dim3(L.B * L.Hq), dim3(64), 0, s, L, nchunks, part, (T*)out, lse,
+        hipLaunchKernelGGL((decode_merge_kernel<T, 64>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nchunks, part, (T*)out, lse,
                            row_pairs);
     } else {
         hipLaunchKernelGGL((decode_attn_kernel<T, 128>), grid, dim3(256), 0, s, L, hm, pos, (const T*)q_new, (const T*)kc,
                            (const T*)vc, (const char*)st, part);
-        hipLaunchKernelGGL((decode_merge_kernel<T, 128>), dim3(L.B * L.Hq), dim3(128), 0, s, L, nchunks, part, (T*)out, lse,
+        hipLaunchKernelGGL((decode_merge_kernel<T, 128>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nchunks, part, (T*)out, lse,
                            row_pairs);
     }
     return hipGetLastError();

@@ -86,7 +86,7 @@ struct RouteLayout {
 };
 
 // Shapes and state offsets of the incremental (one token per step) path.
-constexpr int DEC_CHUNK = 1024;   // keys of the concatenated key sequence per work-group of the decode attention
+constexpr int DEC_CHUNK = 256;    // keys of the concatenated key sequence per work-group of the decode attention
 struct DecodeLayout {
     int B, Hq, Hkv, n, d;      // n = capacity of the caches
     int K, topk, window;
@@ -96,6 +96,7 @@ struct DecodeLayout {
     size_t off_mk;             // [B,Hkv,n] uint32 membership of the cached keys
     size_t off_lists;          // [B,Hkv,K,n] int32 positions of every group, ascending
     size_t off_counts;         // [B,Hkv,K] int32 list lengths
+    size_t off_wp;             // [B,Hkv,K] int32 list entries below the current step's window
     size_t off_mq;             // [B,Hq] uint32 membership of the current queries
     size_t off_part;           // [B,Hq,max_chunks,d+4] fp32 partial (o, max, sum, count) per chunk
     size_t total;
