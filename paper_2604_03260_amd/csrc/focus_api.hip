@@ -207,6 +207,8 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     L->K = p->K; L->topk = p->topk; L->window = p->window; L->dtype = p->dtype;
     L->scale = (p->scale > 0.0f) ? p->scale : (float)(1.0 / std::sqrt((double)p->d));
     L->softcap = p->softcap;
+    // longest concatenated key sequence: the window plus list prefixes, which together hold at most topk * n
+    // entries (every key sits in exactly topk lists)
     const int64_t vmax = (int64_t)std::min(p->window, p->n) + (int64_t)p->topk * (int64_t)p->n;
     L->max_chunks = (int)((vmax + DEC_CHUNK - 1) / DEC_CHUNK);
     for (int h = 0; h < p->Hq; ++h)

@@ -16,6 +16,7 @@
 //      chunks of DEC_CHUNK keys, one work-group each, with an online softmax per 8-component slice;
 //   3. merges the chunks' partial (o, max, sum) by their log-sum-exp weights (App. D "Merge", n-ary).
 #include "focus_internal.h"
+#include <algorithm>
 
 namespace focus {
 
@@ -406,6 +407,208 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     }
 }
 
+// ---------------------------------------------------------------- step 2, grouped-query form
+// The G query heads of one KV head read the same K and V rows, so one work-group serves all of them:
+// the key sequence is the window plus the list prefixes of the UNION of the heads' groups (a key is
+// taken from the first of those groups it belongs to), every key carries the set of heads that attend
+// it (window: all; list key: the heads whose groups meet the key's), and each K/V row is loaded once
+// for G softmaxes.  Keys skipped by the dedup are squeezed out of the chunk before the arithmetic.
+// Requires the default head map (query heads hk*G .. hk*G+G-1 belong to KV head hk).
+template <typename T, int D, int G>
+__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, int pos, const T* __restrict__ q_new,
+                                                              const T* __restrict__ kc, const T* __restrict__ vc,
+                                                              const char* __restrict__ st, float* __restrict__ part)
+{
+    constexpr int LPK = D / 8;
+    constexpr int SLOTS = 64 / LPK;
+    constexpr int PW = D + 4;
+    constexpr int U = (G <= 2 && sizeof(T) == 2) ? 8 : 4;
+    __shared__ int s_beg[34];
+    __shared__ int s_grp[33];
+    __shared__ uint32_t s_prev[33];
+    __shared__ int s_nseg;
+    __shared__ int s_j[DEC_CHUNK + SLOTS * U];    // cache rows of the chunk's keys, squeezed; padded with -1
+    __shared__ uint8_t s_hb[DEC_CHUNK + SLOTS * U];   // which of the G heads attend the key
+    __shared__ int s_wcnt[4];
+    __shared__ float s_red[4][SLOTS][PW];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slot = lane / LPK, sub = lane % LPK;
+    const int chunk = blockIdx.x;
+    const size_t bhk = blockIdx.y;
+    const int b = (int)(bhk / L.Hkv), hk = (int)(bhk % L.Hkv);
+    const size_t bhq0 = (size_t)b * L.Hq + (size_t)hk * G;
+    const int lo_w = max(0, pos - L.window + 1);
+    uint32_t gq[G];
+    uint32_t gu = 0;
+#pragma unroll
+    for (int i = 0; i < G; ++i) { gq[i] = ((const uint32_t*)(st + L.off_mq))[bhq0 + i]; gu |= gq[i]; }
+    const int* wptr = (const int*)(st + L.off_wp) + bhk * L.K;
+    const int* lists = (const int*)(st + L.off_lists) + bhk * L.K * L.n;
+    const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + bhk * L.n;
+
+    if (tid == 0) {
+        int nseg = 1, run = pos - lo_w + 1;
+        uint32_t prev = 0;
+        s_beg[0] = 0; s_grp[0] = -1; s_prev[0] = 0;
+        for (int g = 0; g < L.K; ++g) {
+            if (!((gu >> g) & 1u)) continue;
+            s_beg[nseg] = run; s_grp[nseg] = g; s_prev[nseg] = prev;
+            run += wptr[g];
+            prev |= (1u << g);
+            ++nseg;
+        }
+        s_beg[nseg] = run;
+        s_nseg = nseg;
+    }
+    __syncthreads();
+    const int nseg = s_nseg;
+    const int vtotal = s_beg[nseg];
+    const int v0 = chunk * DEC_CHUNK;
+    if (v0 >= vtotal) {
+        for (int i = 0; i < G; ++i) {
+            float* mypart = part + ((bhq0 + i) * L.max_chunks + chunk) * PW;
+            for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
+        }
+        return;
+    }
+    // resolve one key per thread, then squeeze the skipped ones out (stable: wave ballots + wave offsets)
+    {
+        const int nk0 = min(vtotal - v0, DEC_CHUNK);
+        int j = -1;
+        uint32_t hb = 0;
+        if (tid < nk0) {
+            const int v = v0 + tid;
+            int sgi = 0;
+            while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
+            if (sgi == 0) {
+                j = lo_w + v;
+                hb = (1u << G) - 1u;
+            } else {
+                j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
+                const uint32_t mkj = mk[j];
+                if ((mkj & s_prev[sgi]) != 0u) {
+                    j = -1;                                           // already taken from an earlier group
+                } else {
+#pragma unroll
+                    for (int i = 0; i < G; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
+                }
+            }
+        }
+        const unsigned long long bal = __ballot(j >= 0);
+        if (lane == 0) s_wcnt[wave] = __popcll(bal);
+        for (int i = tid; i < DEC_CHUNK + SLOTS * U; i += 256) s_j[i] = -1;
+        __syncthreads();
+        int before = 0;
+        for (int w2 = 0; w2 < wave; ++w2) before += s_wcnt[w2];
+        if (j >= 0) {
+            const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+            const int dst = before + __popcll(bal & lt);
+            s_j[dst] = j;
+            s_hb[dst] = (uint8_t)hb;
+        }
+        __syncthreads();
+    }
+    const int nk = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
+
+    Raw8<T> qr[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) qr[i].load(q_new + (bhq0 + i) * D + sub * 8);
+    float o[G][8], m[G], l[G];
+    int cnt[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        m[i] = -INFINITY; l[i] = 0.f; cnt[i] = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
+    }
+    const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
+    const T* kbase = kc + bhk * L.n * D + sub * 8;
+    const T* vbase = vc + bhk * L.n * D + sub * 8;
+
+    for (int r0 = wave * (SLOTS * U); r0 < nk; r0 += 4 * SLOTS * U) {
+        int jpos[U];
+        uint32_t hbs[U];
+        Raw8<T> kr[U], vr[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            jpos[u] = s_j[r0 + u * SLOTS + slot];                     // the array is padded by one round of -1
+            hbs[u] = (jpos[u] >= 0) ? (uint32_t)s_hb[r0 + u * SLOTS + slot] : 0u;
+            const int j = max(jpos[u], 0);
+            kr[u].load(kbase + (size_t)j * D);
+            vr[u].load(vbase + (size_t)j * D);
+        }
+        float vx[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) vr[u].unpack(vx[u]);
+        uint32_t hb_or = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) hb_or |= hbs[u];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            // a list segment holds the keys of one group: with few groups per key most heads want none of
+            // the keys of a round, and the whole wavefront skips them
+            if (!__any((hb_or >> i) & 1u)) continue;
+            float xs[U];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float dot = slice_sum<LPK>(slice_dot(qr[i], kr[u]));
+                float x = dot * sl2;
+                if (cap > 0.f) x = cap * DEC_LOG2E * tanhf(dot * L.scale / cap);
+                const bool on = (hbs[u] >> i) & 1u;
+                xs[u] = on ? x : -INFINITY;
+                mx = fmaxf(mx, xs[u]);
+                cnt[i] += on ? 1 : 0;
+            }
+            const float m_new = fmaxf(m[i], mx);
+            if (m_new != -INFINITY) {
+                const float alpha = __builtin_amdgcn_exp2f(m[i] - m_new);
+                m[i] = m_new;
+                l[i] *= alpha;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[i][e] *= alpha;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float pr = __builtin_amdgcn_exp2f(xs[u] - m_new);
+                    l[i] += pr;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[i][e] = fmaf(pr, vx[u][e], o[i][e]);
+                }
+            }
+        }
+    }
+    // fold the (wavefront, slot) partials of one head at a time through LDS
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        if (i > 0) __syncthreads();
+        {
+            float* r = s_red[wave][slot];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) r[sub * 8 + e] = o[i][e];
+            if (sub == 0) { r[D] = m[i]; r[D + 1] = l[i]; r[D + 2] = (float)cnt[i]; }
+        }
+        __syncthreads();
+        if (tid < D) {
+            float mx = -INFINITY;
+            for (int w2 = 0; w2 < 4; ++w2)
+                for (int s2 = 0; s2 < SLOTS; ++s2) mx = fmaxf(mx, s_red[w2][s2][D]);
+            float acc = 0.f, lsum = 0.f, csum = 0.f;
+            for (int w2 = 0; w2 < 4; ++w2)
+                for (int s2 = 0; s2 < SLOTS; ++s2) {
+                    const float ms = s_red[w2][s2][D];
+                    const float wgt = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - mx);
+                    acc += wgt * s_red[w2][s2][tid];
+                    lsum += wgt * s_red[w2][s2][D + 1];
+                    csum += s_red[w2][s2][D + 2];
+                }
+            float* mypart = part + ((bhq0 + i) * L.max_chunks + chunk) * PW;
+            mypart[tid] = acc;
+            if (tid == 0) { mypart[D] = mx; mypart[D + 1] = lsum; mypart[D + 2] = csum; mypart[D + 3] = 0.f; }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- step 3: merge of the chunks
 // One work-group per (batch, query head).  A chunk's partial is read by D/4 threads (4 components each);
 // the 256 / (D/4) groups of threads take the chunks round-robin, then fold through LDS.
@@ -473,6 +676,33 @@ hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* k
     return hipGetLastError();
 }
 
+template <typename T, int D>
+static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int pos, const T* q_new, const T* kc, const T* vc,
+                                char* st, T* out, float* lse, int32_t* row_pairs, hipStream_t s)
+{
+    float* part = (float*)(st + L.off_part);
+    // grouped-query form when query heads hk*G .. hk*G+G-1 share KV head hk (the default map)
+    const int G = (L.Hq % L.Hkv == 0) ? L.Hq / L.Hkv : 0;
+    bool grouped = (G == 1 || G == 2 || G == 4 || G == 8);
+    for (int h = 0; grouped && h < L.Hq; ++h) grouped = hm.kv[h] == h / G;
+    // upper bound of the concatenated key sequence known on the host: the window plus list prefixes that hold
+    // at most topk * pos entries together (every cached key sits in exactly topk lists), for one head's groups
+    // as for the union of several heads' groups
+    const long vmax = (long)std::min(L.window, pos + 1) + (long)L.topk * (long)pos;
+    const int nchunks = (int)std::min((long)L.max_chunks, (vmax + DEC_CHUNK - 1) / DEC_CHUNK);
+    if (grouped) {
+        dim3 grid(nchunks, L.B * L.Hkv);
+#define FOCUS_DEC_GQA(G_) hipLaunchKernelGGL((decode_attn_gqa_kernel<T, D, G_>), grid, dim3(256), 0, s, L, pos, q_new, kc, vc, (const char*)st, part)
+        if (G == 1) FOCUS_DEC_GQA(1); else if (G == 2) FOCUS_DEC_GQA(2); else if (G == 4) FOCUS_DEC_GQA(4); else FOCUS_DEC_GQA(8);
+#undef FOCUS_DEC_GQA
+    } else {
+        hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3(nchunks, L.B * L.Hq), dim3(256), 0, s, L, hm, pos, q_new, kc, vc,
+                           (const char*)st, part);
+    }
+    hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nchunks, part, out, lse, row_pairs);
+    return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
                                 const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out,
@@ -480,23 +710,9 @@ static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int po
 {
     hipLaunchKernelGGL(decode_route_kernel<T>, dim3(L.Hq + L.Hkv, L.B), dim3(64), 0, s, L, hm, pos, (const T*)q_new,
                        (const T*)k_new, (const T*)v_new, cents, (T*)kc, (T*)vc, st);
-    // upper bound of the concatenated key sequence known on the host: the window plus topk lists of at most pos entries
-    const long vmax = (long)min(L.window, pos + 1) + (long)L.topk * (long)pos;
-    const int nchunks = (int)min((long)L.max_chunks, (vmax + DEC_CHUNK - 1) / DEC_CHUNK);
-    float* part = (float*)(st + L.off_part);
-    dim3 grid(nchunks, L.B * L.Hq);
-    if (L.d == 64) {
-        hipLaunchKernelGGL((decode_attn_kernel<T, 64>), grid, dim3(256), 0, s, L, hm, pos, (const T*)q_new, (const T*)kc,
-                           (const T*)vc, (const char*)st, part);
-        hipLaunchKernelGGL((decode_merge_kernel<T, 64>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nchunks, part, (T*)out, lse,
-                           row_pairs);
-    } else {
-        hipLaunchKernelGGL((decode_attn_kernel<T, 128>), grid, dim3(256), 0, s, L, hm, pos, (const T*)q_new, (const T*)kc,
-                           (const T*)vc, (const char*)st, part);
-        hipLaunchKernelGGL((decode_merge_kernel<T, 128>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nchunks, part, (T*)out, lse,
-                           row_pairs);
-    }
-    return hipGetLastError();
+    if (L.d == 64)
+        return decode_step_d<T, 64>(L, hm, pos, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s);
+    return decode_step_d<T, 128>(L, hm, pos, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s);
 }
 
 hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,

@@ -70,6 +70,9 @@ CASES = [
     (1, 2, 2, 700, 64, "f32", 32, 4, 5, 0.0, 690, 10),           # C(32,4) classes: beyond the prefill path's limit
     (1, 4, 4, 2500, 128, "bf16", 4, 3, 3000, 0.0, 2495, 5),      # window wider than the sequence
     (1, 2, 2, 520, 64, "bf16", 1, 1, 4, 0.0, 515, 5),
+    (1, 8, 1, 600, 64, "bf16", 8, 2, 16, 0.0, 590, 10),         # 8 query heads on one KV head
+    (2, 16, 2, 900, 128, "f32", 6, 2, 30, 0.0, 880, 8),
+    (1, 6, 2, 400, 64, "bf16", 4, 2, 10, 0.0, 390, 10),          # 3 query heads per KV head: per-head kernel
 ]
 
 
