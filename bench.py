@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-router", action="store_true")
     ap.add_argument("--no-two-call", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of q (known size) so a counter run can be calibrated")
@@ -220,6 +221,56 @@ def main():
             "max_abs_diff_vs_fused": float((out.float() - out_focus.float()).abs().max().item()),
         }
         del part_out, part_lse
+
+    # incremental inference: one token per sequence against the cached K/V of this workload (memory-bound)
+    if not args.no_decode:
+        dsteps = 32
+        n0 = wl.n - dsteps
+        state = focus.alloc_decode_state(p)
+        kc, vc = k.clone(), v.clone()
+        focus.focus_decode_prefill(p, n0, kc, cents, state)
+        qs = [q[:, :, i].contiguous() for i in range(n0, wl.n)]
+        ks = [k[:, :, i].contiguous() for i in range(n0, wl.n)]
+        vs = [v[:, :, i].contiguous() for i in range(n0, wl.n)]
+        dout = torch.empty_like(qs[0])
+        drp = torch.empty((wl.B, wl.Hq), dtype=torch.int32, device="cuda")
+        for s in range(4):                               # warm-up steps (they also advance the cache)
+            focus.focus_decode_step(p, n0 + s, qs[s], ks[s], vs[s], cents, kc, vc, state, dout, None, drp)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(dsteps - 4 + 1)]
+        for s in range(4, dsteps):
+            ev[s - 4].record()
+            focus.focus_decode_step(p, n0 + s, qs[s], ks[s], vs[s], cents, kc, vc, state, dout, None, drp)
+        ev[dsteps - 4].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(dsteps - 4))
+        t_dec = ts[len(ts) // 2]
+        # rows of K and V the last step had to read: per KV head the union over its query heads of
+        # {window} + {keys whose group set meets the head's}; membership read back from the state
+        dviews = focus.focus_decode_state_views(p, state)
+        mk_t, mq_t = dviews["mk"], dviews["mq"]
+        Gq = wl.Hq // wl.Hkv
+        gu = torch.zeros((wl.B, wl.Hkv), dtype=torch.int32, device="cuda")
+        for g_ in range(Gq):
+            gu |= mq_t.view(wl.B, wl.Hkv, Gq)[:, :, g_]
+        pos_last = wl.n - 1
+        jj = torch.arange(wl.n, device="cuda")
+        att = ((mk_t & gu[:, :, None]) != 0) | (jj[None, None, :] > pos_last - wl.window)
+        unique_rows = int(att.sum().item())
+        elem = 2 if wl.dtype == "bf16" else 4
+        dec_bytes = 2.0 * unique_rows * wl.d * elem
+        per_head_rows = int(drp.to(torch.int64).sum().item())
+        result["decode"] = {
+            "what": "focus_decode_step at context n (route + append + attention + merge), median of %d steps" % (dsteps - 4),
+            "ms_per_step": t_dec, "tokens_per_s": wl.B / (t_dec * 1e-3),
+            "attended_keys_all_heads": per_head_rows,
+            "roofline": {"bound": "hbm", "kernel": "decode_attn (whole step timed)", "achieved": dec_bytes / (t_dec * 1e-3) / 1e9,
+                         "peak": 8000.0, "unit": "GB/s", "frac": dec_bytes / (t_dec * 1e-3) / 1e9 / 8000.0, "traffic": None,
+                         "note": "algorithmic bytes = K and V rows of the keys at least one query head of the KV head "
+                                 "attends, read once (%d rows, %.1f MB); per-head reads would be %.1f MB"
+                                 % (unique_rows, dec_bytes / 1e6, 2.0 * per_head_rows * wl.d * elem / 1e6)},
+        }
+        del state, kc, vc, qs, ks, vs
 
     mq_host = mk_host = None
     if not args.no_cpu_baseline:       # the router leg below reuses the workspace: keep the per-head membership

@@ -188,6 +188,13 @@ focus_status focus_decode_step(const focus_params *p, int32_t pos, const void *q
                                void *k_cache, void *v_cache, void *state, size_t state_bytes,
                                void *out, float *lse, int32_t *row_pairs, void *stream);
 
+/* Device pointers INTO the decode state for parity checks (any may be NULL): mk [B,Hkv,n] uint32
+ * masks of the cached keys, lists [B,Hkv,K,n] int32 (the first counts[b,h,g] entries of a list are
+ * its positions, ascending), counts [B,Hkv,K] int32, mq [B,Hq] uint32 masks of the last step's queries. */
+focus_status focus_decode_state_views(const focus_params *p, void *state, const uint32_t **mk,
+                                      const int32_t **lists, const int32_t **counts,
+                                      const uint32_t **mq);
+
 /* Device pointers INTO the workspace for parity checks; valid until the
  * workspace is overwritten.  Any output pointer may be NULL.
  *   mq [B,Hq,n], mk [B,Hkv,n]                   uint32 membership masks

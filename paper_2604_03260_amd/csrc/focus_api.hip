@@ -460,6 +460,22 @@ focus_status focus_decode_step(const focus_params* p, int32_t pos, const void* q
     return FOCUS_OK;
 }
 
+focus_status focus_decode_state_views(const focus_params* p, void* state, const uint32_t** mk, const int32_t** lists,
+                                      const int32_t** counts, const uint32_t** mq)
+{
+    focus::DecodeLayout L;
+    focus::HeadMap hm;
+    focus_status st = make_decode_layout(p, &L, &hm);
+    if (st != FOCUS_OK) return st;
+    if (!state) return fail(FOCUS_EINVAL, "state is NULL");
+    char* s = (char*)state;
+    if (mk) *mk = (const uint32_t*)(s + L.off_mk);
+    if (lists) *lists = (const int32_t*)(s + L.off_lists);
+    if (counts) *counts = (const int32_t*)(s + L.off_counts);
+    if (mq) *mq = (const uint32_t*)(s + L.off_mq);
+    return FOCUS_OK;
+}
+
 focus_status focus_workspace_views(const focus_params* p, void* workspace, const uint32_t** mq,
                                    const uint32_t** mk, const int32_t** q_group_counts,
                                    const int32_t** k_group_counts, const int32_t** q_group_lists,

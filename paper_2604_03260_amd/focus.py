@@ -3,7 +3,7 @@
 The functions mirror include/focus.h one to one (focus_workspace_size,
 focus_assign, focus_attn_fwd, focus_workspace_views, focus_route_workspace_size,
 focus_route, focus_assign_tokens, focus_attn_fwd_set, focus_attn_merge, focus_attn_fwd_two_call,
-focus_decode_state_size, focus_decode_prefill, focus_decode_step, focus_last_error, focus_version).  Tensors are torch CUDA tensors used purely as device buffers;
+focus_decode_state_size, focus_decode_prefill, focus_decode_step, focus_decode_state_views, focus_last_error, focus_version).  Tensors are torch CUDA tensors used purely as device buffers;
 the calls are enqueued on torch's current stream.  There is no CPU fallback: a
 missing library is an error.
 """
@@ -22,6 +22,7 @@ EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_work
            "focus_route_workspace_size", "focus_route", "focus_assign_tokens",
            "focus_attn_fwd_set", "focus_attn_merge", "focus_attn_fwd_two_call",
            "focus_decode_state_size", "focus_decode_prefill", "focus_decode_step",
+           "focus_decode_state_views",
            "focus_last_error", "focus_version")
 
 
@@ -86,6 +87,8 @@ def load_library():
     lib.focus_decode_prefill.restype = ctypes.c_int
     lib.focus_decode_step.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
     lib.focus_decode_step.restype = ctypes.c_int
+    lib.focus_decode_state_views.argtypes = [pp, vp] + [ctypes.POINTER(vp)] * 4
+    lib.focus_decode_state_views.restype = ctypes.c_int
     rp = ctypes.POINTER(FocusRouteParams)
     lib.focus_route_workspace_size.argtypes = [rp, ctypes.POINTER(sz)]
     lib.focus_route_workspace_size.restype = ctypes.c_int
@@ -197,6 +200,24 @@ def focus_decode_step(p, pos, q_new, k_new, v_new, centroids, k_cache, v_cache, 
                                             _ptr(centroids), _ptr(k_cache), _ptr(v_cache), _ptr(state),
                                             state.numel() * state.element_size(), _ptr(out), _ptr(lse),
                                             _ptr(row_pairs), _stream()))
+
+
+def focus_decode_state_views(p, state):
+    """Returns dict of torch int32 tensors aliasing the decode state (no copies)."""
+    ptrs = [ctypes.c_void_p(0) for _ in range(4)]
+    _check(load_library().focus_decode_state_views(ctypes.byref(p), _ptr(state), *[ctypes.byref(x) for x in ptrs]))
+    base = state.data_ptr()
+    raw = state.view(torch.uint8).reshape(-1)
+
+    def view(ptr, shape):
+        count = 1
+        for x in shape:
+            count *= x
+        off = ptr.value - base
+        return raw[off:off + 4 * count].view(torch.int32).view(*shape)
+    B, Hq, Hkv, n, K = p.B, p.Hq, p.Hkv, p.n, p.K
+    return {"mk": view(ptrs[0], (B, Hkv, n)), "lists": view(ptrs[1], (B, Hkv, K, n)),
+            "counts": view(ptrs[2], (B, Hkv, K)), "mq": view(ptrs[3], (B, Hq))}
 
 
 def make_route_params(B, n, d_model, d_g, K, topk, dtype="bf16", sinkhorn_iters=10, tau=0.1):

@@ -90,16 +90,11 @@ def test_decode_state_matches_oracle_lists():
     n0, steps = 600, 300
     res = run_decode(wl, inp, n0, steps)
     mk = check_decode(wl, inp, res, n0, steps)
-    # state layout (as documented in focus.h): masks [B,Hkv,n], lists [B,Hkv,K,n], counts [B,Hkv,K] at the start
-    st = res["state"]
-    BHk = wl.B * wl.Hkv
-    off = 0
-    got_mk = st[off:off + BHk * wl.n * 4].view(torch.int32).cpu().numpy().view(np.uint32).reshape(wl.B, wl.Hkv, wl.n)
+    views = focus.focus_decode_state_views(res["params"], res["state"])
+    got_mk = views["mk"].cpu().numpy().view(np.uint32)
     assert np.array_equal(got_mk, mk)
-    off = ((BHk * wl.n * 4 + 255) // 256) * 256
-    lists = st[off:off + BHk * wl.K * wl.n * 4].view(torch.int32).cpu().numpy().reshape(wl.B, wl.Hkv, wl.K, wl.n)
-    off += ((BHk * wl.K * wl.n * 4 + 255) // 256) * 256
-    counts = st[off:off + BHk * wl.K * 4].view(torch.int32).cpu().numpy().reshape(wl.B, wl.Hkv, wl.K)
+    lists = views["lists"].cpu().numpy()
+    counts = views["counts"].cpu().numpy()
     for b in range(wl.B):
         for h in range(wl.Hkv):
             for g in range(wl.K):
