@@ -257,7 +257,7 @@ __device__ inline float slice_dot(const Raw8<float>& q, const Raw8<float>& k)
 constexpr float DEC_LOG2E = 1.4426950408889634f;
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos, const T* __restrict__ q_new,
+__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos, int span, const T* __restrict__ q_new,
                                                           const T* __restrict__ kc, const T* __restrict__ vc,
                                                           const char* __restrict__ st, float* __restrict__ part)
 {
@@ -305,12 +305,27 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     __syncthreads();
     const int nseg = s_nseg;
     const int vtotal = s_beg[nseg];
-    const int v0 = chunk * DEC_CHUNK;
     float* mypart = part + ((size_t)bhq * L.max_chunks + chunk) * PW;
-    if (v0 >= vtotal) {                           // nothing in this chunk
+    if (chunk * span * DEC_CHUNK >= vtotal) {     // nothing for this work-group
         for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
         return;
     }
+    Raw8<T> qr;
+    qr.load(q_new + (size_t)bhq * D + sub * 8);
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+    float m = -INFINITY, l = 0.f;                 // running max in log2 units, running sum
+    int cnt = 0;
+    const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
+    const T* kbase = kc + bhk * L.n * D + sub * 8;
+    const T* vbase = vc + bhk * L.n * D + sub * 8;
+
+    // rounds of SLOTS*U keys per wavefront, the 4 wavefronts interleaved; one softmax update per round
+    for (int cc = 0; cc < span; ++cc) {
+    const int v0 = (chunk * span + cc) * DEC_CHUNK;
+    if (v0 >= vtotal) break;                      // uniform over the work-group
+    if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
     // resolve the whole chunk at once: list entry -> position -> (mask check); all loads independent
     const int nk = min(vtotal - v0, DEC_CHUNK);
     for (int i = tid; i < DEC_CHUNK; i += 256) {
@@ -331,18 +346,6 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     }
     __syncthreads();
 
-    Raw8<T> qr;
-    qr.load(q_new + (size_t)bhq * D + sub * 8);
-    float o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = 0.f;
-    float m = -INFINITY, l = 0.f;                 // running max in log2 units, running sum
-    int cnt = 0;
-    const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
-    const T* kbase = kc + bhk * L.n * D + sub * 8;
-    const T* vbase = vc + bhk * L.n * D + sub * 8;
-
-    // rounds of SLOTS*U keys per wavefront, the 4 wavefronts interleaved; one softmax update per round
     for (int r0 = wave * (SLOTS * U); r0 < nk; r0 += 4 * SLOTS * U) {
         int jpos[U];
         Raw8<T> kr[U], vr[U];
@@ -381,6 +384,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
             for (int e = 0; e < 8; ++e) o[e] = fmaf(pr, vx[e], o[e]);
         }
     }
+    }   // chunks of the span
     // every (wavefront, slot) holds a partial softmax over its keys: fold them through LDS
     {
         float* r = s_red[wave][slot];
@@ -415,7 +419,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
 // for G softmaxes.  Keys skipped by the dedup are squeezed out of the chunk before the arithmetic.
 // Requires the default head map (query heads hk*G .. hk*G+G-1 belong to KV head hk).
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, int pos, const T* __restrict__ q_new,
+__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, int pos, int span, const T* __restrict__ q_new,
                                                               const T* __restrict__ kc, const T* __restrict__ vc,
                                                               const char* __restrict__ st, float* __restrict__ part)
 {
@@ -464,14 +468,33 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     __syncthreads();
     const int nseg = s_nseg;
     const int vtotal = s_beg[nseg];
-    const int v0 = chunk * DEC_CHUNK;
-    if (v0 >= vtotal) {
+    // this work-group walks `span` consecutive chunks of the sequence and leaves one partial per head
+    if (chunk * span * DEC_CHUNK >= vtotal) {
         for (int i = 0; i < G; ++i) {
             float* mypart = part + ((bhq0 + i) * L.max_chunks + chunk) * PW;
             for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
         }
         return;
     }
+    Raw8<T> qr[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) qr[i].load(q_new + (bhq0 + i) * D + sub * 8);
+    float o[G][8], m[G], l[G];
+    int cnt[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        m[i] = -INFINITY; l[i] = 0.f; cnt[i] = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
+    }
+    const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
+    const T* kbase = kc + bhk * L.n * D + sub * 8;
+    const T* vbase = vc + bhk * L.n * D + sub * 8;
+
+    for (int cc = 0; cc < span; ++cc) {
+    const int v0 = (chunk * span + cc) * DEC_CHUNK;
+    if (v0 >= vtotal) break;                      // uniform over the work-group
+    if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
     // resolve one key per thread, then squeeze the skipped ones out (stable: wave ballots + wave offsets)
     {
         const int nk0 = min(vtotal - v0, DEC_CHUNK);
@@ -510,21 +533,6 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
         __syncthreads();
     }
     const int nk = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-
-    Raw8<T> qr[G];
-#pragma unroll
-    for (int i = 0; i < G; ++i) qr[i].load(q_new + (bhq0 + i) * D + sub * 8);
-    float o[G][8], m[G], l[G];
-    int cnt[G];
-#pragma unroll
-    for (int i = 0; i < G; ++i) {
-        m[i] = -INFINITY; l[i] = 0.f; cnt[i] = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
-    }
-    const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
-    const T* kbase = kc + bhk * L.n * D + sub * 8;
-    const T* vbase = vc + bhk * L.n * D + sub * 8;
 
     for (int r0 = wave * (SLOTS * U); r0 < nk; r0 += 4 * SLOTS * U) {
         int jpos[U];
@@ -578,6 +586,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
             }
         }
     }
+    }   // chunks of the span
     // fold the (wavefront, slot) partials of one head at a time through LDS
 #pragma unroll
     for (int i = 0; i < G; ++i) {
@@ -690,16 +699,20 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     // as for the union of several heads' groups
     const long vmax = (long)std::min(L.window, pos + 1) + (long)L.topk * (long)pos;
     const int nchunks = (int)std::min((long)L.max_chunks, (vmax + DEC_CHUNK - 1) / DEC_CHUNK);
+    // a work-group walks `span` chunks and leaves one partial: at most about 384 partials per head, so the merge
+    // stays short at any context length
+    const int span = (nchunks + 383) / 384;
+    const int nparts = (nchunks + span - 1) / span;
     if (grouped) {
-        dim3 grid(nchunks, L.B * L.Hkv);
-#define FOCUS_DEC_GQA(G_) hipLaunchKernelGGL((decode_attn_gqa_kernel<T, D, G_>), grid, dim3(256), 0, s, L, pos, q_new, kc, vc, (const char*)st, part)
+        dim3 grid(nparts, L.B * L.Hkv);
+#define FOCUS_DEC_GQA(G_) hipLaunchKernelGGL((decode_attn_gqa_kernel<T, D, G_>), grid, dim3(256), 0, s, L, pos, span, q_new, kc, vc, (const char*)st, part)
         if (G == 1) FOCUS_DEC_GQA(1); else if (G == 2) FOCUS_DEC_GQA(2); else if (G == 4) FOCUS_DEC_GQA(4); else FOCUS_DEC_GQA(8);
 #undef FOCUS_DEC_GQA
     } else {
-        hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3(nchunks, L.B * L.Hq), dim3(256), 0, s, L, hm, pos, q_new, kc, vc,
-                           (const char*)st, part);
+        hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3(nparts, L.B * L.Hq), dim3(256), 0, s, L, hm, pos, span, q_new, kc,
+                           vc, (const char*)st, part);
     }
-    hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nchunks, part, out, lse, row_pairs);
+    hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nparts, part, out, lse, row_pairs);
     return hipGetLastError();
 }
 

@@ -73,6 +73,8 @@ CASES = [
     (1, 8, 1, 600, 64, "bf16", 8, 2, 16, 0.0, 590, 10),         # 8 query heads on one KV head
     (2, 16, 2, 900, 128, "f32", 6, 2, 30, 0.0, 880, 8),
     (1, 6, 2, 400, 64, "bf16", 4, 2, 10, 0.0, 390, 10),          # 3 query heads per KV head: per-head kernel
+    (1, 2, 1, 60000, 64, "bf16", 4, 2, 300, 0.0, 59996, 4),      # long context: several chunks per work-group
+    (1, 3, 1, 60000, 64, "bf16", 4, 2, 300, 0.0, 59997, 3),      # ... in the per-head kernel
 ]
 
 
