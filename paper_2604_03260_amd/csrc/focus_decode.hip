@@ -73,27 +73,39 @@ __global__ void decode_zero_kernel(int* __restrict__ p, int count)
 }
 
 // ---------------------------------------------------------------- prefill of the cache state
-// membership of the cached keys 0 .. n_ctx-1: one thread per key, fp64 scores in index order
-template <typename T>
+// membership of the cached keys 0 .. n_ctx-1: one thread per key, fp64 scores in index order;
+// KMAX = K rounded up, so that the scores stay in registers
+template <typename T, int KMAX>
 __global__ __launch_bounds__(256) void decode_prefill_score_kernel(DecodeLayout L, int n_ctx, const T* __restrict__ kc,
                                                                    const float* __restrict__ cents, char* __restrict__ st)
 {
     const int j = blockIdx.x * 256 + threadIdx.x;
     const int bhk = blockIdx.y, hk = bhk % L.Hkv;
     if (j >= n_ctx) return;
+    const int K = L.K;
     const T* row = kc + ((size_t)bhk * L.n + j) * L.d;
-    const float* c = cents + (size_t)hk * L.K * L.d;
-    double s[32];
-    for (int g = 0; g < L.K; ++g) s[g] = 0.0;
-    for (int t = 0; t < L.d; ++t) {
-        const double x = (double)dec_to_f32<T>(row[t]);
-        for (int g = 0; g < L.K; ++g) s[g] = fma(x, (double)c[(size_t)g * L.d + t], s[g]);
+    const float* c = cents + (size_t)hk * K * L.d;        // wave-uniform: scalar loads
+    double s[KMAX];
+#pragma unroll
+    for (int g = 0; g < KMAX; ++g) s[g] = 0.0;
+    for (int t0 = 0; t0 < L.d; t0 += 8) {            // 16-byte (bf16) or 32-byte (fp32) pieces of the row, index order kept
+        float xv[8];
+        dec_load8(row + t0, xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const double x = (double)xv[e];
+#pragma unroll
+            for (int g = 0; g < KMAX; ++g)
+                if (g < K) s[g] = fma(x, (double)c[(size_t)g * L.d + t0 + e], s[g]);
+        }
     }
     uint32_t m = 0;
-    for (int g = 0; g < L.K; ++g) {
+#pragma unroll
+    for (int g = 0; g < KMAX; ++g) {
         int beaten = 0;
-        for (int o = 0; o < L.K; ++o) beaten += (o != g && (s[o] > s[g] || (s[o] == s[g] && o < g))) ? 1 : 0;
-        if (beaten < L.topk) m |= (1u << g);
+#pragma unroll
+        for (int o = 0; o < KMAX; ++o) beaten += (o < K && o != g && (s[o] > s[g] || (s[o] == s[g] && o < g))) ? 1 : 0;
+        if (g < K && beaten < L.topk) m |= (1u << g);
     }
     ((uint32_t*)(st + L.off_mk))[(size_t)bhk * L.n + j] = m;
 }
@@ -677,10 +689,15 @@ hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* k
     hipLaunchKernelGGL(decode_zero_kernel, dim3((ncount + 255) / 256), dim3(256), 0, s, (int*)(st + L.off_counts), ncount);
     if (n_ctx == 0) return hipGetLastError();
     dim3 g1((n_ctx + 255) / 256, L.B * L.Hkv);
-    if (L.dtype == 0)
-        hipLaunchKernelGGL(decode_prefill_score_kernel<float>, g1, dim3(256), 0, s, L, n_ctx, (const float*)kc, cents, st);
-    else
-        hipLaunchKernelGGL(decode_prefill_score_kernel<uint16_t>, g1, dim3(256), 0, s, L, n_ctx, (const uint16_t*)kc, cents, st);
+#define FOCUS_DEC_SCORE(T_, KM_) hipLaunchKernelGGL((decode_prefill_score_kernel<T_, KM_>), g1, dim3(256), 0, s, L, n_ctx, (const T_*)kc, cents, st)
+    if (L.dtype == 0) {
+        if (L.K <= 4) FOCUS_DEC_SCORE(float, 4); else if (L.K <= 8) FOCUS_DEC_SCORE(float, 8);
+        else if (L.K <= 16) FOCUS_DEC_SCORE(float, 16); else FOCUS_DEC_SCORE(float, 32);
+    } else {
+        if (L.K <= 4) FOCUS_DEC_SCORE(uint16_t, 4); else if (L.K <= 8) FOCUS_DEC_SCORE(uint16_t, 8);
+        else if (L.K <= 16) FOCUS_DEC_SCORE(uint16_t, 16); else FOCUS_DEC_SCORE(uint16_t, 32);
+    }
+#undef FOCUS_DEC_SCORE
     hipLaunchKernelGGL(decode_prefill_lists_kernel, dim3(L.K, L.B * L.Hkv), dim3(256), 0, s, L, n_ctx, st);
     return hipGetLastError();
 }
