@@ -34,5 +34,18 @@ def build_library(verbose=False):
     return LIB
 
 
+def build_probes(verbose=False):
+    """Stand-alone measurement programs under csrc/probes (not part of the library)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "_build", "issue_rates")
+    os.makedirs(os.path.dirname(out), exist_ok=True)
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-w", "-o", out, os.path.join(CSRC, "probes", "issue_rates.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probes(verbose=True))
