@@ -49,10 +49,11 @@ typedef enum {
     FOCUS_EHIP = -4           /* a HIP call failed (launch error text kept)    */
 } focus_status;
 
-typedef enum { FOCUS_F32 = 0, FOCUS_BF16 = 1 } focus_dtype;
+typedef enum { FOCUS_F32 = 0, FOCUS_BF16 = 1, FOCUS_F16 = 2 } focus_dtype;   /* F16 = IEEE binary16 */
 
 typedef struct {
-    int32_t B, Hq, Hkv, n, d;  /* d in {64,128}; Hq % Hkv == 0 unless head_map   */
+    int32_t B, Hq, Hkv, n, d;  /* d in {64,80,96,128,256}; Hq % Hkv == 0 unless
+                                  head_map                                       */
     int32_t K, topk;           /* 1 <= topk <= K <= 32 groups per KV head        */
     int32_t window;            /* >= 1 keys including the query itself; a window
                                   >= n means plain causal attention              */

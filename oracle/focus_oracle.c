@@ -43,7 +43,7 @@ typedef struct {
     int32_t B, Hq, Hkv, n, d;
     int32_t K, topk, window;
     int32_t causal;
-    int32_t dtype;            /* 0 = fp32, 1 = bf16 (raw uint16 storage) */
+    int32_t dtype;            /* 0 = fp32, 1 = bf16, 2 = IEEE binary16 (both as raw uint16 storage) */
     double scale;             /* 0 -> 1/sqrt(d) */
     double softcap;           /* 0 -> off */
     const int32_t *head_map;  /* [Hq] -> kv head, or NULL */
@@ -53,6 +53,15 @@ static double widen(const void *base, int dtype, int64_t idx)
 {
     if (dtype == 0) {
         return (double)((const float *)base)[idx];
+    } else if (dtype == 2) {
+        /* IEEE 754 binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        const uint16_t h = ((const uint16_t *)base)[idx];
+        const int e = (h >> 10) & 31, m = h & 1023;
+        double v;
+        if (e == 0) v = ldexp((double)m, -24);
+        else if (e == 31) v = m ? NAN : INFINITY;
+        else v = ldexp((double)(1024 + m), e - 25);
+        return (h >> 15) ? -v : v;
     } else {
         uint32_t bits = ((uint32_t)((const uint16_t *)base)[idx]) << 16;
         float f;
@@ -73,7 +82,7 @@ static int check_params(const oracle_params *p)
     if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->n < 1 || p->d < 1) return -1;
     if (p->K < 1 || p->K > 32 || p->topk < 1 || p->topk > p->K) return -1;
     if (p->window < 1) return -1;
-    if (p->dtype != 0 && p->dtype != 1) return -1;
+    if (p->dtype < 0 || p->dtype > 2) return -1;
     if (!p->head_map && (p->Hq % p->Hkv) != 0) return -1;
     if (p->head_map)
         for (int h = 0; h < p->Hq; ++h)
@@ -440,7 +449,7 @@ int focus_oracle_num_threads(void)
  * unchanged, and exp cannot overflow); Sinkhorn runs per batch element over its
  * n tokens; ties in the top-k go to the smaller group index.
  *
- * hidden [B,n,dm] in dtype (0 fp32, 1 bf16 bits); wg [dm,dg] fp32; cent [K,dg] fp32.
+ * hidden [B,n,dm] in dtype (0 fp32, 1 bf16 bits, 2 binary16 bits); wg [dm,dg] fp32; cent [K,dg] fp32.
  * z_out [B,n,dg], g_out [B,n,K] nullable fp64; masks [B,n] (bit g = member).
  */
 int focus_oracle_route(int32_t B, int32_t n, int32_t dm, int32_t dg, int32_t K, int32_t topk,
@@ -449,7 +458,7 @@ int focus_oracle_route(int32_t B, int32_t n, int32_t dm, int32_t dg, int32_t K, 
 {
     if (B < 1 || n < 1 || dm < 1 || dg < 1 || K < 1 || K > 32 || topk < 1 || topk > K) return -1;
     if (!(tau > 0.0) || iters < 0 || !hidden || !wg || !cent || !masks) return -1;
-    if (dtype != 0 && dtype != 1) return -1;
+    if (dtype < 0 || dtype > 2) return -1;
     double *Q = (double *)malloc(sizeof(double) * (size_t)n * K);
     if (!Q) return -2;
     for (int b = 0; b < B; ++b) {

@@ -57,6 +57,9 @@ def num_threads():
     return int(_load().focus_oracle_num_threads())
 
 
+DTYPES = {"f32": 0, "bf16": 1, "f16": 2}      # 16-bit types travel as uint16 bit patterns
+
+
 def _ptr(a):
     return ctypes.c_void_p(a.ctypes.data) if a is not None else ctypes.c_void_p(0)
 
@@ -75,7 +78,7 @@ class Problem:
 
     def _c(self):
         p = _Params(self.B, self.Hq, self.Hkv, self.n, self.d, self.K, self.topk, self.window,
-                    1 if self.causal else 0, {"f32": 0, "bf16": 1}[self.dtype],
+                    1 if self.causal else 0, DTYPES[self.dtype],
                     self.scale, self.softcap,
                     self.head_map.ctypes.data if self.head_map is not None else None)
         return p
@@ -215,7 +218,7 @@ def route(hidden, wg, cent, topk, tau=0.1, iters=10, dtype="f32", want_soft=Fals
     g = np.empty((B, n, K), dtype=np.float64) if want_soft else None
     _rc(lib.focus_oracle_route(ctypes.c_int32(B), ctypes.c_int32(n), ctypes.c_int32(dm), ctypes.c_int32(dg),
                                ctypes.c_int32(K), ctypes.c_int32(topk),
-                               ctypes.c_int32({"f32": 0, "bf16": 1}[dtype]), _ptr(hidden), _ptr(wg), _ptr(cent),
+                               ctypes.c_int32(DTYPES[dtype]), _ptr(hidden), _ptr(wg), _ptr(cent),
                                ctypes.c_double(tau), ctypes.c_int32(iters), _ptr(z), _ptr(g), _ptr(masks)),
         "route")
     if want_soft:

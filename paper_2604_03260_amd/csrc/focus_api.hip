@@ -31,7 +31,7 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     if (!p) return fail(FOCUS_EINVAL, "params is NULL");
     if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->n < 1)
         return fail(FOCUS_EINVAL, "B, Hq, Hkv, n must be >= 1 (got %d %d %d %d)", p->B, p->Hq, p->Hkv, p->n);
-    if (p->dtype != FOCUS_F32 && p->dtype != FOCUS_BF16)
+    if (p->dtype != FOCUS_F32 && p->dtype != FOCUS_BF16 && p->dtype != FOCUS_F16)
         return fail(FOCUS_EINVAL, "unknown dtype %d", p->dtype);
     if (p->K < 1 || p->K > 32) return fail(FOCUS_EINVAL, "K must be in [1,32] (got %d)", p->K);
     if (p->topk < 1 || p->topk > p->K)
@@ -52,7 +52,8 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     }
     // valid, but no kernel in this build
     if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "non-causal attention is not built");
-    if (p->d != 64 && p->d != 128) return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64 or 128)", p->d);
+    if (p->d != 64 && p->d != 80 && p->d != 96 && p->d != 128 && p->d != 256)
+        return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64, 80, 96, 128 or 256)", p->d);
     if (p->Hq > MAX_HQ || p->Hkv > MAX_HQ)
         return fail(FOCUS_EUNSUPPORTED, "more than %d heads is not built", MAX_HQ);
     if (p->n > (1 << 24)) return fail(FOCUS_EUNSUPPORTED, "n above 2^24 is not built");
@@ -83,7 +84,8 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->nblk = (p->n + SB - 1) / SB;
     // bf16 at long n: 256-row tiles (8 wavefronts share every K/V tile: half the L2->LDS traffic per FLOP,
     // which is what bounds the kernel once a KV head's K/V no longer sits in L2/MALL)
-    L->BQ = (p->dtype == FOCUS_BF16 && p->n >= LONG_N) ? 256 : BQ_VECTOR;
+    L->dp = (p->d <= 64) ? 64 : (p->d <= 128) ? 128 : 256;
+    L->BQ = (p->dtype != FOCUS_F32 && p->n >= LONG_N && p->d <= 128) ? 256 : BQ_VECTOR;
     L->NT = (p->n + L->BQ - 1) / L->BQ + L->NC;
     L->NQP = L->NT * L->BQ;
     L->NKP = ((p->n + KT - 1) / KT + L->NC) * KT;
@@ -114,13 +116,13 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->off_qco = take(BHq * (L->NC + 1) * 4);
     L->off_kco = take(BHk * (L->NC + 1) * 4);
     L->off_clsmask = take((size_t)L->NC * 4);
-    L->off_cent64 = take((size_t)p->Hkv * p->d * 32 * 8);
+    L->off_cent64 = take((size_t)p->Hkv * (((size_t)p->d * L->elem + 127) / 128 * (128 / L->elem)) * 32 * 8);
     L->off_qperm = take(BHq * L->NQP * 4);
     L->off_kpos = take(BHk * L->NKP * 4);
     L->off_jobs = take(BHq * L->NT * 4);
-    if (p->dtype == FOCUS_BF16) {
-        L->off_kc = take(BHk * L->NKP * (size_t)p->d * 2);
-        L->off_vt = take(BHk * L->NKP * (size_t)p->d * 2);
+    if (p->dtype != FOCUS_F32) {
+        L->off_kc = take(BHk * L->NKP * (size_t)L->dp * 2);
+        L->off_vt = take(BHk * L->NKP * (size_t)L->dp * 2);
     } else {
         L->off_kc = L->off_vt = off;
     }
@@ -281,7 +283,7 @@ focus_status attn_launch(const focus_params* p, int pair_set, const void* q, con
     if (st != FOCUS_OK) return st;
     L.pair_set = pair_set;
     hipError_t e;
-    if (L.dtype == FOCUS_BF16)
+    if (L.dtype != FOCUS_F32)
         e = focus::launch_attn_mfma(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
     else
         e = focus::launch_attn_simple(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
@@ -310,7 +312,7 @@ focus_status focus_attn_merge(int64_t rows, int32_t d, int32_t dtype, const void
                               const void* out_b, const float* lse_b, void* out, float* lse, void* stream)
 {
     if (rows < 0 || d < 8 || d % 8 != 0) return fail(FOCUS_EINVAL, "rows must be >= 0 and d a positive multiple of 8");
-    if (dtype != FOCUS_F32 && dtype != FOCUS_BF16) return fail(FOCUS_EINVAL, "unknown dtype %d", dtype);
+    if (dtype != FOCUS_F32 && dtype != FOCUS_BF16 && dtype != FOCUS_F16) return fail(FOCUS_EINVAL, "unknown dtype %d", dtype);
     if (!out_a || !lse_a || !out_b || !lse_b || !out) return fail(FOCUS_EINVAL, "partial outputs, their lse and out must not be NULL");
     if (misaligned16(out_a) || misaligned16(out_b) || misaligned16(out))
         return fail(FOCUS_EINVAL, "out_a, out_b and out must be 16-byte aligned");

@@ -18,6 +18,7 @@
 //                and of the per-group index lists.
 #include "focus_internal.h"
 #include <hip/hip_bf16.h>
+#include <type_traits>
 
 namespace focus {
 
@@ -70,13 +71,14 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     constexpr int EPC = 16 / sizeof(T);                              // elements per 16-byte chunk
     constexpr int CPR = ROW_CHUNK_BYTES / 16;                        // chunks per staged row = loads per thread
     const int row_bytes = d * (int)sizeof(T);
-    const int phases = row_bytes / ROW_CHUNK_BYTES;
+    const int phases = (row_bytes + ROW_CHUNK_BYTES - 1) / ROW_CHUNK_BYTES;   // the last one may be partly past the row
+    const int dcent = phases * (ROW_CHUNK_BYTES / (int)sizeof(T));              // rows of the (zero-padded) centroid table
     const int nb_here = min(NBW, L.nblk - blk0);
     const int total_steps = nb_here * phases;                        // (block, 128-byte column phase) pairs
 
     // centroids of this KV head as fp64 [d][KMAX]: a wave-uniform, read-only table -> scalar loads,
     // the values feed v_fma_f64 straight from SGPRs
-    const double* __restrict__ cd = cent64 + (size_t)hk * d * KMAX;
+    const double* __restrict__ cd = cent64 + (size_t)hk * dcent * KMAX;
     for (int e = tid; e < MAX_CLASSES; e += SB) s_hist_c[e] = 0;
     if (tid < 32) s_hist_g[tid] = 0;
 
@@ -101,7 +103,8 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
             const int cid_ = tid + i * SB;                                                           \
             const int r_ = cid_ / CPR, cc_ = cid_ % CPR;                                             \
             const u32x4 z_ = {0u, 0u, 0u, 0u};                                                       \
-            st[i] = (r_ < rows_) ? *(const u32x4*)(g_ + (size_t)r_ * row_bytes + cc_ * 16) : z_;     \
+            const bool in_ = r_ < rows_ && ph_ * ROW_CHUNK_BYTES + cc_ * 16 < row_bytes;                 \
+            st[i] = in_ ? *(const u32x4*)(g_ + (size_t)r_ * row_bytes + cc_ * 16) : z_;              \
         }                                                                                            \
     } while (0)
 
@@ -124,6 +127,12 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
             if constexpr (sizeof(T) == 4) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) xv[e] = (double)__uint_as_float(val[e]);
+            } else if constexpr (std::is_same<T, f16_bits>::value) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    xv[2 * e] = (double)f16_bits_to_f32((uint16_t)(val[e] & 0xffffu));
+                    xv[2 * e + 1] = (double)f16_bits_to_f32((uint16_t)(val[e] >> 16));
+                }
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -182,14 +191,14 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
 #undef FOCUS_SCORE_LOAD
 }
 
-// centroids fp32 [Hkv][K][d] -> fp64 [Hkv][d][KMAX] (zero-padded groups)
+// centroids fp32 [Hkv][K][d] -> fp64 [Hkv][dcent][KMAX] (zero-padded groups, zero rows from d to dcent)
 __global__ void cent_to_f64_kernel(const float* __restrict__ cents, double* __restrict__ out, int Hkv, int K, int d,
-                                   int kmax)
+                                   int dcent, int kmax)
 {
-    const int total = Hkv * d * kmax;
+    const int total = Hkv * dcent * kmax;
     for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
-        const int g = e % kmax, t = (e / kmax) % d, hk = e / (kmax * d);
-        out[e] = (g < K) ? (double)cents[((size_t)hk * K + g) * d + t] : 0.0;
+        const int g = e % kmax, t = (e / kmax) % dcent, hk = e / (kmax * dcent);
+        out[e] = (g < K && t < d) ? (double)cents[((size_t)hk * K + g) * d + t] : 0.0;
     }
 }
 
@@ -483,7 +492,7 @@ hipError_t launch_bucketing(const Layout& L, const void* k, char* ws, hipStream_
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (L.dtype == 1) return launch_gather_k(L, k, ws, st);   // class-ordered key copy for the MFMA kernel
+    if (L.dtype != 0) return launch_gather_k(L, k, ws, st);   // class-ordered key copy for the MFMA kernel
     return hipSuccess;
 }
 
@@ -496,12 +505,17 @@ hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, cons
     launch_pad_fills(L, ws, st);
     {
         const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
+        const int row_bytes = L.d * L.elem;
+        const int dcent = (row_bytes + ROW_CHUNK_BYTES - 1) / ROW_CHUNK_BYTES * (ROW_CHUNK_BYTES / L.elem);
         hipLaunchKernelGGL(cent_to_f64_kernel, dim3(64), dim3(256), 0, st, centroids, (double*)(ws + L.off_cent64),
-                           L.Hkv, L.K, L.d, kmax);
+                           L.Hkv, L.K, L.d, dcent, kmax);
     }
     if (L.dtype == 0) {
         if ((e = launch_score<float>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
         if ((e = launch_score<float>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
+    } else if (L.dtype == 2) {
+        if ((e = launch_score<f16_bits>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
+        if ((e = launch_score<f16_bits>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
     } else {
         if ((e = launch_score<uint16_t>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
         if ((e = launch_score<uint16_t>(L, hm, k, 0, ws, st)) != hipSuccess) return e;

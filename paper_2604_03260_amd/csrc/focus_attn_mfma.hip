@@ -1,5 +1,5 @@
 // Block-sparse flash-style attention forward on the gfx950 matrix cores
-// (bf16 in, fp32 accumulate): App. D Eq. 3 generalised to top-k sets, exact
+// (bf16 or fp16 in, fp32 accumulate): App. D Eq. 3 generalised to top-k sets, exact
 // softmax (Sec. 1), every allowed pair visited once under ONE online softmax.
 //
 // Data layout (built by the two gather kernels below, class order = tokens
@@ -8,6 +8,9 @@
 //   Kc [B*Hkv][NKP][D]            keys, row-major: a key tile is one contiguous block
 //   Vt [B*Hkv][NKP/KT][D][KT]     values, transposed per key tile (KT = 64 keys), the 16 keys of
 //                                 every 16-key group stored in MFMA k-slot order
+// D is the head dim rounded up to 64, 128 or 256 (zero columns / rows past it); the kernel runs
+// KS = d/16 k-steps of Q K^T and DB = ceil(d/32) row blocks of O^T, so a head dim of 80 or 96
+// pays for its own products only.
 // One work-group = MFMA_WAVES wavefronts = one query tile of 32*MFMA_WAVES rows of one class;
 // each wavefront owns 32 query rows.  The scores are computed transposed,
 // S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K rows from LDS, B = Q rows held
@@ -43,7 +46,26 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 f16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// the two 16-bit element types: vector types, the 32x32x16 product and the 2-term dot product
+template <bool F16> struct Half;
+template <> struct Half<false> {
+    typedef __bf16 T;
+    typedef bf16x8 V8;
+    typedef bf16x2 V2;
+    static __device__ inline f32x16 mfma(V8 a, V8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+    static __device__ inline float dot2(V2 a, V2 b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
+};
+template <> struct Half<true> {
+    typedef _Float16 T;
+    typedef f16x8 V8;
+    typedef f16x2 V2;
+    static __device__ inline f32x16 mfma(V8 a, V8 b, f32x16 c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+    static __device__ inline float dot2(V2 a, V2 b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
+};
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NTHR = 256;
@@ -58,16 +80,17 @@ __host__ __device__ constexpr int slot_to_key16(int p16) { return 8 * ((p16 % 8)
 template <int D>
 __global__ __launch_bounds__(NTHR) void gather_k_kernel(Layout L, const uint16_t* __restrict__ k, char* __restrict__ ws)
 {
-    constexpr int CPR = D / 8;                       // 16-byte chunks per row
+    constexpr int CPR = D / 8;                       // 16-byte chunks per row of the copy
+    const int cin = L.d / 8;                         // ... and of a source row (d <= D)
     const int tile = blockIdx.x, bhk = blockIdx.y, tid = threadIdx.x;
     const int* kpos = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP + (size_t)tile * KT;
     uint4* dst = (uint4*)(ws + L.off_kc) + ((size_t)bhk * L.NKP + (size_t)tile * KT) * CPR;
-    const uint4* src = (const uint4*)k + (size_t)bhk * L.n * CPR;
+    const uint4* src = (const uint4*)k + (size_t)bhk * L.n * cin;
     for (int id = tid; id < KT * CPR; id += NTHR) {
         const int row = id / CPR, ch = id % CPR;
         const int kp = kpos[row];
         uint4 val = make_uint4(0, 0, 0, 0);
-        if (kp != KPOS_PAD) val = src[(size_t)kp * CPR + ch];
+        if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * cin + ch];
         dst[id] = val;
     }
 }
@@ -78,14 +101,15 @@ __global__ __launch_bounds__(NTHR) void gather_vt_kernel(Layout L, const uint16_
     constexpr int CPR = D / 8;
     constexpr int RS = D + 2;                        // padded LDS row stride in elements
     __shared__ uint16_t s_v[KT * RS];
+    const int cin = L.d / 8;
     const int tile = blockIdx.x, bhk = blockIdx.y, tid = threadIdx.x;
     const int* kpos = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP + (size_t)tile * KT;
-    const uint4* src = (const uint4*)v + (size_t)bhk * L.n * CPR;
+    const uint4* src = (const uint4*)v + (size_t)bhk * L.n * cin;
     for (int id = tid; id < KT * CPR; id += NTHR) {
         const int row = id / CPR, ch = id % CPR;
         const int kp = kpos[row];
         uint4 val = make_uint4(0, 0, 0, 0);
-        if (kp != KPOS_PAD) val = src[(size_t)kp * CPR + ch];
+        if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * cin + ch];
         uint32_t* d32 = (uint32_t*)(s_v + row * RS + ch * 8);   // RS even -> 4-byte aligned
         d32[0] = val.x; d32[1] = val.y; d32[2] = val.z; d32[3] = val.w;
     }
@@ -111,7 +135,7 @@ __global__ __launch_bounds__(NTHR) void gather_vt_kernel(Layout L, const uint16_
 template <int ROW_BYTES>
 __device__ inline int swz(int row, int ch)
 {
-    if constexpr (ROW_BYTES == 256) return ch ^ (row & 15);
+    if constexpr (ROW_BYTES >= 256) return ch ^ (row & 15);     // 256- and 512-byte rows: low 4 bits of the chunk
     else return ch ^ ((row >> 1) & 7);
 }
 
@@ -142,40 +166,50 @@ __device__ inline void dma16(const void* sbase, unsigned voff, unsigned lds_addr
 __device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)p; }
 
 // 16-byte LDS read whose completion the compiler does not track (see F4_WAIT_OPERANDS)
-__device__ inline bf16x8 lds_read16_async(unsigned addr)
+template <typename V8>
+__device__ inline V8 lds_read16_async(unsigned addr)
 {
-    bf16x8 r;
+    V8 r;
     asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr));
     return r;
 }
-__device__ inline void wait_lds_operands(bf16x8 (&a)[8])
+// s_waitcnt lgkmcnt(0) tied to every register of an operand array (N = 4..16 registers of 16 bytes)
+template <typename V8, int N>
+__device__ inline void wait_lds_operands(V8 (&a)[N])
 {
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]));
-}
-__device__ inline void wait_lds_operands(bf16x8 (&a)[4])
-{
+    static_assert(N >= 4, "operand arrays hold at least four registers");
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+#pragma unroll
+    for (int i = 4; i < N; ++i) asm volatile("" : "+v"(a[i]));
 }
-__device__ inline void pin_operands(bf16x8 (&a)[8])
+template <typename V8, int N>
+__device__ inline void pin_operands(V8 (&a)[N])
 {
-    asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]));
-}
-__device__ inline void pin_operands(bf16x8 (&a)[4])
-{
-    asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(a[i]));
 }
 
-template <int D, int MFMA_WAVES, bool SOFTCAP, bool PAIRS>
-__global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_kernel(Layout L, HeadMap hm, int default_map,
-                                                             const uint16_t* __restrict__ q,
-                                                             const char* __restrict__ ws, uint16_t* __restrict__ out,
-                                                             float* __restrict__ lse, int32_t* __restrict__ row_pairs)
+// D: row length of the class-ordered copies (64, 128, 256); KS: MFMAs of one QK^T unit = d / 16;
+// DB: 32-row blocks of O^T = ceil(d / 32).  With 512-byte key rows the operands of a phase alone
+// take 128 registers, so that shape runs one wavefront per SIMD with the full register file.
+template <int D, int KS, int DB, int MFMA_WAVES, bool SOFTCAP, bool PAIRS, bool F16>
+__global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) void attn_mfma_kernel(
+    Layout L, HeadMap hm, int default_map, const uint16_t* __restrict__ q, const char* __restrict__ ws,
+    uint16_t* __restrict__ out, float* __restrict__ lse, int32_t* __restrict__ row_pairs)
 {
+    typedef Half<F16> HT;
+    typedef typename HT::T elem_t;
+    typedef typename HT::V8 V8;
+    typedef typename HT::V2 V2;
     __shared__ Smem<D> S;
-    constexpr int KS = D / 16;          // MFMAs of one QK^T unit
-    constexpr int DB = D / 32;          // 32-row blocks of O^T
-    constexpr int NPV = DB * 2;         // MFMAs of one PV unit
+    static_assert(KS * 16 <= D && DB * 32 <= D, "the products stay inside the copied rows");
+    // With 512-byte key rows the operands of a whole phase would not fit the vector registers next to
+    // Q, so that shape fetches and multiplies them in two halves (HV = 2); the others in one go.
+    constexpr int HV = (D == 256) ? 2 : 1;
+    constexpr int KSH = KS / HV;        // Q K^T MFMAs per half
+    constexpr int DBH = DB / HV;        // O^T row blocks per half
+    constexpr int NPVH = DBH * 2;       // P V MFMAs per half
+    static_assert(KS % HV == 0 && DB % HV == 0, "halves are equal");
     constexpr int TILE_BYTES = KT * D * 2;      // bytes of a K tile and of a V^T tile
     constexpr int NW = TILE_BYTES / 1024 / MFMA_WAVES;   // 1-KB wave loads per wavefront and tile
     constexpr int ATHR = 64 * MFMA_WAVES;                // threads of the work-group
@@ -208,13 +242,13 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     const int i_lo = S.plan.i_lo;
     const int total = S.plan.total;
     const int w = L.window;
+    const int d = L.d;                  // row length of q and out
     if (total == 0) {
         // Only a launch restricted to one of the two pair sets can leave a tile without keys
         // (the whole mask always holds the diagonal): its rows are empty, out = 0 and lse = -inf.
         if (rvalid) {
-            uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * D + hh * (D / 2);
-#pragma unroll
-            for (int e = 0; e < D / 2; e += 4) *(uint2*)(orow + e) = make_uint2(0u, 0u);
+            uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * d + hh * (d / 2);
+            for (int e = 0; e < d / 2; e += 4) *(uint2*)(orow + e) = make_uint2(0u, 0u);
             if (hh == 0) {
                 if (lse) lse[(size_t)bhq * L.n + qpos] = -INFINITY;
                 if constexpr (PAIRS) row_pairs[(size_t)bhq * L.n + qpos] = 0;
@@ -223,12 +257,12 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
         return;
     }
 
-    bf16x8 qreg[KS];
+    V8 qreg[KS];
     {
-        const bf16x8* qrow = (const bf16x8*)(q + ((size_t)bhq * L.n + (rvalid ? qpos : 0)) * D);
-        bf16x8 zero;
+        const V8* qrow = (const V8*)(q + ((size_t)bhq * L.n + (rvalid ? qpos : 0)) * d);
+        V8 zero;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.f;
+        for (int e = 0; e < 8; ++e) zero[e] = (elem_t)0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qreg[ks] = rvalid ? qrow[2 * ks + hh] : zero;
     }
@@ -252,14 +286,25 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     // per-lane source offsets of the swizzled DMA: wave `wave` fills the 1-KB LDS blocks wave + 4*i
     // of a tile; block j holds rows 4j..4j+3 (256-byte rows) or 8j..8j+7 (128-byte rows), and the
     // swizzle key of a row depends only on (j mod 4) = wave, so one offset serves every i.
-    unsigned voff_k, voff_v;
+    // With 512-byte rows a block holds 2 rows and the key alternates between a wave's consecutive
+    // blocks (4 wavefronts: 8 rows apart), so even and odd loads get an offset each.
+    unsigned voff_k[2], voff_v;
     {
         const int r128 = wave * 8 + lane / 8;                         // 128-byte rows
         const unsigned off128 = (unsigned)((r128 * 8 + ((lane % 8) ^ ((wave & 1) * 4 + lane / 16))) * 16);
-        const int r256 = wave * 4 + lane / 16;                        // 256-byte rows
-        const unsigned off256 = (unsigned)((r256 * 16 + ((lane % 16) ^ (r256 & 15))) * 16);
-        voff_k = (D == 128) ? off256 : off128;
         voff_v = off128;
+        if constexpr (D == 256) {
+#pragma unroll
+            for (int par = 0; par < 2; ++par) {
+                const int r512 = (wave + MFMA_WAVES * par) * 2 + lane / 32;   // 512-byte rows
+                voff_k[par] = (unsigned)((r512 * 32 + ((lane % 32) ^ (r512 & 15))) * 16);
+            }
+        } else {
+            const int r256 = wave * 4 + lane / 16;                    // 256-byte rows
+            const unsigned off256 = (unsigned)((r256 * 16 + ((lane % 16) ^ (r256 & 15))) * 16);
+            voff_k[0] = (D == 128) ? off256 : off128;
+            voff_k[1] = voff_k[0] + 1024u * MFMA_WAVES;
+        }
     }
     const unsigned lds_k0 = lds_addr_of(&S.k[0][0]), lds_v0 = lds_addr_of(&S.vt[0][0]);
     const unsigned lds_kp0 = lds_addr_of(&S.kpos[0][0]);
@@ -268,7 +313,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     do {                                                                                             \
         const char* src_ = kc_base + (size_t)(TILE) * TILE_BYTES;                                    \
         _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
-            dma16(src_ + i * (1024 * MFMA_WAVES), voff_k, lds_k0 + (STAGE) * TILE_BYTES + (wave + MFMA_WAVES * i) * 1024); \
+            dma16(src_ + (i >> 1) * (2048 * MFMA_WAVES), voff_k[i & 1], lds_k0 + (STAGE) * TILE_BYTES + (wave + MFMA_WAVES * i) * 1024); \
     } while (0)
 #define F4_DMA_V(TILE, STAGE)                                                                        \
     do {                                                                                             \
@@ -286,16 +331,16 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     // LDS operand reads of one unit, issued as inline asm so that they stay where they are written
     // and are NOT waited for at once: the vector work that follows runs while they are in flight,
     // and F4_WAIT_OPERANDS() (s_waitcnt lgkmcnt(0), tied to every operand register) precedes the MFMAs.
-#define F4_READ_K(DST, KST, U)                                                                       \
-    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                              \
+#define F4_READ_K(DST, KST, U, HALF)                                                                 \
+    _Pragma("unroll") for (int ks = 0; ks < KSH; ++ks) {                                             \
         const int row_ = (U) * 32 + n32;                                                             \
-        DST[ks] = lds_read16_async(lds_k0 + (KST) * TILE_BYTES + row_ * (D * 2) + swz<D * 2>(row_, 2 * ks + hh) * 16); \
+        DST[ks] = lds_read16_async<V8>(lds_k0 + (KST) * TILE_BYTES + row_ * (D * 2) + swz<D * 2>(row_, 2 * ((HALF) * KSH + ks) + hh) * 16); \
     }
-#define F4_READ_V(DST, VST, U)                                                                       \
-    _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                \
+#define F4_READ_V(DST, VST, U, HALF)                                                                 \
+    _Pragma("unroll") for (int db = 0; db < DBH; ++db)                                               \
         _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {                                           \
-            const int row_ = db * 32 + n32;                                                          \
-            DST[db * 2 + s2] = lds_read16_async(lds_v0 + (VST) * TILE_BYTES + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
+            const int row_ = ((HALF) * DBH + db) * 32 + n32;                                         \
+            DST[db * 2 + s2] = lds_read16_async<V8>(lds_v0 + (VST) * TILE_BYTES + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
         }
 #define F4_WAIT_OPERANDS()                                                                           \
     wait_lds_operands(ak);                                                                           \
@@ -344,19 +389,22 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     }
     __syncthreads();
     f32x16 s0, s1;
-    bf16x8 p0[2], p1[2];
-    bf16x2 ones2;
-    ones2[0] = (__bf16)1.0f;
-    ones2[1] = (__bf16)1.0f;
-    bf16x8 ak[KS], av[NPV];
+    V8 p0[2], p1[2];
+    V2 ones2;
+    ones2[0] = (elem_t)1.0f;
+    ones2[1] = (elem_t)1.0f;
+    V8 ak[KSH], av[NPVH];
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { p1[0][e] = (__bf16)0.f; p1[1][e] = (__bf16)0.f; p0[0][e] = (__bf16)0.f; p0[1][e] = (__bf16)0.f; }
-    F4_READ_K(ak, 0, 0)
-    wait_lds_operands(ak);
+    for (int e = 0; e < 8; ++e) { p1[0][e] = (elem_t)0.f; p1[1][e] = (elem_t)0.f; p0[0][e] = (elem_t)0.f; p0[1][e] = (elem_t)0.f; }
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], s0, 0, 0, 0);
+    for (int half = 0; half < HV; ++half) {
+        F4_READ_K(ak, 0, 0, half)
+        wait_lds_operands(ak);
+#pragma unroll
+        for (int ks = 0; ks < KSH; ++ks) s0 = HT::mfma(ak[ks], qreg[half * KSH + ks], s0);
+    }
 
     // softmax step on one unit's scores: SIN (f32x16, consumed) -> POUT (2 x bf16x8), split in two parts.
     // PPEND: probabilities of the previous unit whose PV product has not been issued yet.
@@ -395,8 +443,8 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
                 _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][r] *= alpha_;                       \
             /* probabilities still waiting for their PV product were taken against the old reference */ \
             _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
-                PPEND[0][e] = (__bf16)((float)PPEND[0][e] * alpha_);                                     \
-                PPEND[1][e] = (__bf16)((float)PPEND[1][e] * alpha_);                                     \
+                PPEND[0][e] = (elem_t)((float)PPEND[0][e] * alpha_);                                     \
+                PPEND[1][e] = (elem_t)((float)PPEND[1][e] * alpha_);                                     \
             }                                                                                            \
         }                                                                                                \
     }
@@ -407,23 +455,23 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
         _Pragma("unroll") for (int r = 0; r < 16; r += 2) {                                              \
             const float a0_ = SOFTCAP ? (SIN[r] - m_use_) : fmaf(SIN[r], sl2, -m_use_);                  \
             const float a1_ = SOFTCAP ? (SIN[r + 1] - m_use_) : fmaf(SIN[r + 1], sl2, -m_use_);          \
-            bf16x2 pr_;                                                                                  \
-            pr_[0] = (__bf16)__builtin_amdgcn_exp2f(a0_);                                                \
-            pr_[1] = (__bf16)__builtin_amdgcn_exp2f(a1_);                                                \
+            V2 pr_;                                                                                      \
+            pr_[0] = (elem_t)__builtin_amdgcn_exp2f(a0_);                                                \
+            pr_[1] = (elem_t)__builtin_amdgcn_exp2f(a1_);                                                \
             /* the row sum adds the ROUNDED probabilities, the same numbers the PV product uses */      \
-            psum_ = __builtin_amdgcn_fdot2_f32_bf16(pr_, ones2, psum_, false);                           \
+            psum_ = HT::dot2(pr_, ones2, psum_);                                                         \
             POUT[r / 8][r % 8] = pr_[0];                                                                 \
             POUT[r / 8][r % 8 + 1] = pr_[1];                                                             \
         }                                                                                                \
         l_run += psum_;                                                                                  \
     }
-    // the MFMAs of a phase: PV with pending probabilities PP, then the QK^T unit into SOUT
-#define F4_MFMAS(PP, SOUT)                                                                               \
-    _Pragma("unroll") for (int i = 0; i < NPV; ++i)                                                      \
-        o[i / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], PP[i % 2], o[i / 2], 0, 0, 0);         \
-    _Pragma("unroll") for (int r = 0; r < 16; ++r) SOUT[r] = 0.f;                                        \
-    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                                    \
-        SOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], qreg[ks], SOUT, 0, 0, 0);
+    // the MFMAs of (one half of) a phase: PV with pending probabilities PP, then the QK^T unit into SOUT
+#define F4_MFMAS(PP, SOUT, HALF)                                                                         \
+    _Pragma("unroll") for (int i = 0; i < NPVH; ++i)                                                     \
+        o[(HALF) * DBH + i / 2] = HT::mfma(av[i], PP[i % 2], o[(HALF) * DBH + i / 2]);                   \
+    if ((HALF) == 0) { _Pragma("unroll") for (int r = 0; r < 16; ++r) SOUT[r] = 0.f; }                   \
+    _Pragma("unroll") for (int ks = 0; ks < KSH; ++ks)                                                   \
+        SOUT = HT::mfma(ak[ks], qreg[(HALF) * KSH + ks], SOUT);
     // keeps values computed / loaded where they are written in the source (no sinking past a branch)
 #define F4_PIN2(P_) asm volatile("" : "+v"(P_[0]), "+v"(P_[1]))
     int kb_cur = 0;                                          // kpos buffer of tile t (t mod 3)
@@ -437,12 +485,20 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
         const int tl2 = (int)(pk2 & TILE_MASK);                                                          \
         const int kb_nn = (kb_cur >= 1) ? kb_cur - 1 : 2;    /* (t+2) mod 3 */                           \
         /* phase A: VALU softmax(S0) -> P0 ; MFMA O += V(t-1,u1) P1 and S1 = K(t,u1) Q^T */              \
-        F4_READ_V(av, sn, 1)                                                                             \
-        F4_READ_K(ak, sc, 1)                                                                             \
+        F4_READ_V(av, sn, 1, 0)                                                                          \
+        F4_READ_K(ak, sc, 1, 0)                                                                          \
         F4_SOFTMAX_PRE(s0, 0, kb_cur, p1)                                                                \
         F4_WAIT_OPERANDS()                                                                               \
-        F4_MFMAS(p1, s1)                                                                                 \
+        F4_MFMAS(p1, s1, 0)                                                                              \
+        if constexpr (HV == 2) {                                                                         \
+            F4_READ_V(av, sn, 1, 1)                                                                      \
+            F4_READ_K(ak, sc, 1, 1)                                                                      \
+        }                                                                                                \
         F4_SOFTMAX_EXP(s0, p0)                                                                           \
+        if constexpr (HV == 2) {                                                                         \
+            F4_WAIT_OPERANDS()                                                                           \
+            F4_MFMAS(p1, s1, 1)                                                                          \
+        }                                                                                                \
         __builtin_amdgcn_iglp_opt(3);                                                                    \
         F4_PIN2(p0);                                                                                     \
         /* one barrier per tile: all are done with K(t), V(t-1); K(t+1), V(t) have landed */             \
@@ -452,12 +508,20 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
         F4_DMA_V(tl1, sn);                                                                               \
         F4_DMA_KPOS(tl2, kb_nn);                                                                         \
         /* phase B: VALU softmax(S1) -> P1 ; MFMA O += V(t,u0) P0 and S0 = K(t+1,u0) Q^T */              \
-        F4_READ_V(av, sc, 0)                                                                             \
-        F4_READ_K(ak, sn, 0)                                                                             \
+        F4_READ_V(av, sc, 0, 0)                                                                          \
+        F4_READ_K(ak, sn, 0, 0)                                                                          \
         F4_SOFTMAX_PRE(s1, 1, kb_cur, p0)                                                                \
         F4_WAIT_OPERANDS()                                                                               \
-        F4_MFMAS(p0, s0)                                                                                 \
+        F4_MFMAS(p0, s0, 0)                                                                              \
+        if constexpr (HV == 2) {                                                                         \
+            F4_READ_V(av, sc, 0, 1)                                                                      \
+            F4_READ_K(ak, sn, 0, 1)                                                                      \
+        }                                                                                                \
         F4_SOFTMAX_EXP(s1, p1)                                                                           \
+        if constexpr (HV == 2) {                                                                         \
+            F4_WAIT_OPERANDS()                                                                           \
+            F4_MFMAS(p0, s0, 1)                                                                          \
+        }                                                                                                \
         __builtin_amdgcn_iglp_opt(3);                                                                    \
         F4_PIN2(p1);                                                                                     \
         kb_cur = (kb_cur == 2) ? 0 : kb_cur + 1;                                                         \
@@ -472,11 +536,14 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     // ---- drain: O += V(T-1,u1) P1 (V(T-1) was complete before the last barrier)
     {
         const int sl = (total - 1) & 1;
-        F4_READ_V(av, sl, 1)
-        wait_lds_operands(av);
 #pragma unroll
-        for (int i = 0; i < NPV; ++i)
-            o[i / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], p1[i % 2], o[i / 2], 0, 0, 0);
+        for (int half = 0; half < HV; ++half) {
+            F4_READ_V(av, sl, 1, half)
+            wait_lds_operands(av);
+#pragma unroll
+            for (int i = 0; i < NPVH; ++i)
+                o[half * DBH + i / 2] = HT::mfma(av[i], p1[i % 2], o[half * DBH + i / 2]);
+        }
     }
     F4_WAIT_DMA();                                           // nothing may still be writing LDS when the block ends
 #undef F4_DMA_K
@@ -496,14 +563,15 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     if constexpr (PAIRS) npairs += __shfl_xor(npairs, 32, 64);
     if (!rvalid) return;
     const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;      // an empty row (restricted pair set): out = 0, lse = -inf
-    uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * D;
+    uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * d;
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
             const int dcol = db * 32 + 8 * r4 + 4 * hh;
-            __bf16 e0 = (__bf16)(o[db][r4 * 4 + 0] * inv), e1 = (__bf16)(o[db][r4 * 4 + 1] * inv);
-            __bf16 e2 = (__bf16)(o[db][r4 * 4 + 2] * inv), e3 = (__bf16)(o[db][r4 * 4 + 3] * inv);
+            if (DB * 32 > KS * 16 && dcol >= d) continue;        // rows of O^T past a head dim that is no multiple of 32
+            elem_t e0 = (elem_t)(o[db][r4 * 4 + 0] * inv), e1 = (elem_t)(o[db][r4 * 4 + 1] * inv);
+            elem_t e2 = (elem_t)(o[db][r4 * 4 + 2] * inv), e3 = (elem_t)(o[db][r4 * 4 + 3] * inv);
             uint16_t u0, u1, u2, u3;
             __builtin_memcpy(&u0, &e0, 2); __builtin_memcpy(&u1, &e1, 2);
             __builtin_memcpy(&u2, &e2, 2); __builtin_memcpy(&u3, &e3, 2);
@@ -519,38 +587,45 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, 8 / MFMA_WAVES) void attn_mfma_ker
     }
 }
 
-template <int D, int WAVES, bool SOFTCAP, bool PAIRS>
+template <int D, int KS, int DB, int WAVES, bool SOFTCAP, bool PAIRS, bool F16>
 hipError_t launch_one(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
                       float* lse, int32_t* row_pairs, hipStream_t st)
 {
     const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
-    hipLaunchKernelGGL((attn_mfma_kernel<D, WAVES, SOFTCAP, PAIRS>), dim3(grid), dim3(64 * WAVES), 0, st, L, hm,
-                       default_map, (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16>), dim3(grid), dim3(64 * WAVES), 0, st,
+                       L, hm, default_map, (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
     return hipGetLastError();
 }
 
-template <int D, int WAVES>
+template <int D, int KS, int DB, int WAVES, bool F16>
 hipError_t launch_w(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
                     float* lse, int32_t* row_pairs, hipStream_t st)
 {
     const bool sc = L.softcap > 0.f, pairs = row_pairs != nullptr;
     if (sc) {
-        return pairs ? launch_one<D, WAVES, true, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-                     : launch_one<D, WAVES, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+        return pairs ? launch_one<D, KS, DB, WAVES, true, true, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                     : launch_one<D, KS, DB, WAVES, true, false, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
     }
-    return pairs ? launch_one<D, WAVES, false, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-                 : launch_one<D, WAVES, false, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    return pairs ? launch_one<D, KS, DB, WAVES, false, true, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                 : launch_one<D, KS, DB, WAVES, false, false, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
 }
 
-template <int D>
+template <int D, int KS, int DB>
 hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const void* q, const void* v, char* ws,
                     void* out, float* lse, int32_t* row_pairs, hipStream_t st)
 {
     dim3 ggrid(L.NKP / KT, L.B * L.Hkv);
     hipLaunchKernelGGL(gather_vt_kernel<D>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)v, ws);
+    const bool f16 = L.dtype == 2;
     // the query tile size fixed by focus_assign selects the work-group shape: 4 or 8 wavefronts
-    if (L.BQ == 256) return launch_w<D, 8>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
-    return launch_w<D, 4>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    if constexpr (D != 256) {
+        if (L.BQ == 256)
+            return f16 ? launch_w<D, KS, DB, 8, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                       : launch_w<D, KS, DB, 8, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    }
+    if (L.BQ != 128) return hipErrorInvalidValue;
+    return f16 ? launch_w<D, KS, DB, 4, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+               : launch_w<D, KS, DB, 4, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
 }
 
 }  // namespace
@@ -559,10 +634,12 @@ hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const v
 hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t st)
 {
     dim3 ggrid(L.NKP / KT, L.B * L.Hkv);
-    if (L.d == 64)
+    if (L.dp == 64)
         hipLaunchKernelGGL(gather_k_kernel<64>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)k, ws);
-    else
+    else if (L.dp == 128)
         hipLaunchKernelGGL(gather_k_kernel<128>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)k, ws);
+    else
+        hipLaunchKernelGGL(gather_k_kernel<256>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)k, ws);
     return hipGetLastError();
 }
 
@@ -577,8 +654,14 @@ hipError_t launch_attn_mfma(const Layout& L, const HeadMap& hm, const void* q, c
         for (int h = 0; h < L.Hq; ++h)
             if (hm.kv[h] != h / G) default_map = 0;
     if ((size_t)L.NT * L.B * L.Hq > 0x7fffffffull) return hipErrorInvalidValue;
-    if (L.d == 64) return launch_d<64>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
-    return launch_d<128>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
+    switch (L.d) {
+        case 64: return launch_d<64, 4, 2>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
+        case 80: return launch_d<128, 5, 3>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
+        case 96: return launch_d<128, 6, 3>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
+        case 128: return launch_d<128, 8, 4>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
+        case 256: return launch_d<256, 16, 8>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace focus

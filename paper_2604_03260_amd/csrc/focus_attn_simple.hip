@@ -3,9 +3,9 @@
 //
 // One work-group owns one query tile (<= L.BQ queries of one membership class) and
 // handles it in passes of BQ_VECTOR rows.
-// A row is shared by d/32 adjacent lanes, each holding 32 of the d components
-// of q and of the output accumulator.  Keys and values are gathered 32 at a
-// time through the class-ordered position array into LDS as fp32; the allowed
+// A row is shared by D/32 adjacent lanes (D = head dim rounded up to 64, 128 or 256, zeros past d),
+// each holding 32 of the components of q and of the output accumulator.  Keys and values are gathered
+// SUB at a time through the class-ordered position array into LDS as fp32; the allowed
 // set is App. D Eq. 3 with top-k sets and the softmax is exact (Sec. 1), kept
 // online per 32-key step.
 #include "focus_internal.h"
@@ -15,11 +15,10 @@ namespace focus {
 
 namespace {
 
-constexpr int SUB = 32;   // keys per inner step
-
 template <typename T> __device__ inline float to_f32(T v);
 template <> __device__ inline float to_f32<float>(float v) { return v; }
 template <> __device__ inline float to_f32<uint16_t>(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+template <> __device__ inline float to_f32<f16_bits>(f16_bits v) { return f16_bits_to_f32(v.v); }
 
 __device__ inline uint16_t f32_to_bf16_rne(float f)
 {
@@ -31,8 +30,10 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
 template <typename T> __device__ inline T from_f32(float v);
 template <> __device__ inline float from_f32<float>(float v) { return v; }
 template <> __device__ inline uint16_t from_f32<uint16_t>(float v) { return f32_to_bf16_rne(v); }
+template <> __device__ inline f16_bits from_f32<f16_bits>(float v) { return f16_bits{f32_to_f16_bits(v)}; }
 
-template <typename T, int D>
+// SUB: keys per inner step (the fp32 staging of a step's keys and values fills 2 * SUB * D * 4 bytes of LDS)
+template <typename T, int D, int SUB>
 __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layout L, HeadMap hm, const T* __restrict__ q,
                                                                     const T* __restrict__ k, const T* __restrict__ v,
                                                                     const char* __restrict__ ws, T* __restrict__ out,
@@ -59,13 +60,14 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
     const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
     const int qpos = rvalid ? qperm[P.row0 + row] : -1;
     const int* kpos_all = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP;
-    const T* kbase = k + (size_t)bhk * L.n * D;
-    const T* vbase = v + (size_t)bhk * L.n * D;
+    const int d = L.d;
+    const T* kbase = k + (size_t)bhk * L.n * d;
+    const T* vbase = v + (size_t)bhk * L.n * d;
 
     float qv[32], o[32];
 #pragma unroll
     for (int e = 0; e < 32; ++e) {
-        qv[e] = rvalid ? to_f32<T>(q[((size_t)bhq * L.n + qpos) * D + part * 32 + e]) : 0.f;
+        qv[e] = (rvalid && part * 32 + e < d) ? to_f32<T>(q[((size_t)bhq * L.n + qpos) * d + part * 32 + e]) : 0.f;
         o[e] = 0.f;
     }
     float m = -INFINITY, l = 0.f;
@@ -85,9 +87,9 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
             for (int e = tid; e < SUB * D; e += NTHR) {
                 const int kk = e / D, t = e % D;
                 const int kp = kpos_all[r0 + kk];
-                const bool real = kp != KPOS_PAD;
-                s_k[e] = real ? to_f32<T>(kbase[(size_t)kp * D + t]) : 0.f;
-                s_v[e] = real ? to_f32<T>(vbase[(size_t)kp * D + t]) : 0.f;
+                const bool real = kp != KPOS_PAD && t < d;
+                s_k[e] = real ? to_f32<T>(kbase[(size_t)kp * d + t]) : 0.f;
+                s_v[e] = real ? to_f32<T>(vbase[(size_t)kp * d + t]) : 0.f;
             }
             __syncthreads();
             float s[SUB];
@@ -132,9 +134,10 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
     }
     if (rvalid) {
     const float inv = (l > 0.f) ? 1.f / l : 0.f;     // empty row (launch restricted to one pair set): out = 0, lse = -inf
-    T* orow = out + ((size_t)bhq * L.n + qpos) * D + part * 32;
+    T* orow = out + ((size_t)bhq * L.n + qpos) * d + part * 32;
 #pragma unroll
-    for (int e = 0; e < 32; ++e) orow[e] = from_f32<T>(o[e] * inv);
+    for (int e = 0; e < 32; ++e)
+        if (part * 32 + e < d) orow[e] = from_f32<T>(o[e] * inv);
     if (part == 0) {
         if (lse) lse[(size_t)bhq * L.n + qpos] = m + logf(l);
         if (row_pairs) row_pairs[(size_t)bhq * L.n + qpos] = npairs;
@@ -158,6 +161,25 @@ __device__ inline void load8(const uint16_t* p, float (&x)[8])
         x[2 * e] = __uint_as_float(w[e] << 16);
         x[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
     }
+}
+__device__ inline void load8(const f16_bits* p, float (&x)[8])
+{
+    const uint4 u = *(const uint4*)p;
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = f16_bits_to_f32((uint16_t)(w[e] & 0xffffu));
+        x[2 * e + 1] = f16_bits_to_f32((uint16_t)(w[e] >> 16));
+    }
+}
+__device__ inline void store8(f16_bits* p, const float (&y)[8])
+{
+    uint4 u;
+    u.x = f32_to_f16_bits(y[0]) | ((uint32_t)f32_to_f16_bits(y[1]) << 16);
+    u.y = f32_to_f16_bits(y[2]) | ((uint32_t)f32_to_f16_bits(y[3]) << 16);
+    u.z = f32_to_f16_bits(y[4]) | ((uint32_t)f32_to_f16_bits(y[5]) << 16);
+    u.w = f32_to_f16_bits(y[6]) | ((uint32_t)f32_to_f16_bits(y[7]) << 16);
+    *(uint4*)p = u;
 }
 __device__ inline void store8(float* p, const float (&y)[8])
 {
@@ -221,6 +243,9 @@ hipError_t launch_attn_merge(size_t rows, int d, int dtype, const void* oa, cons
     if (dtype == 0)
         hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(grid), dim3(256), 0, st, rows, d, (const float*)oa, la,
                            (const float*)ob, lb, (float*)out, lse);
+    else if (dtype == 2)
+        hipLaunchKernelGGL(attn_merge_kernel<f16_bits>, dim3(grid), dim3(256), 0, st, rows, d, (const f16_bits*)oa, la,
+                           (const f16_bits*)ob, lb, (f16_bits*)out, lse);
     else
         hipLaunchKernelGGL(attn_merge_kernel<uint16_t>, dim3(grid), dim3(256), 0, st, rows, d, (const uint16_t*)oa, la,
                            (const uint16_t*)ob, lb, (uint16_t*)out, lse);
@@ -231,14 +256,19 @@ hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q,
                               char* ws, void* out, float* lse, int32_t* row_pairs, hipStream_t st)
 {
     dim3 grid(L.NT, L.B * L.Hq);
-#define FOCUS_LAUNCH_SIMPLE(T, D)                                                                      \
-    hipLaunchKernelGGL((attn_simple_kernel<T, D>), grid, dim3(BQ_VECTOR*(D / 32)), 0, st, L, hm, (const T*)q, \
+#define FOCUS_LAUNCH_SIMPLE(T, D, SUB)                                                                 \
+    hipLaunchKernelGGL((attn_simple_kernel<T, D, SUB>), grid, dim3(BQ_VECTOR*(D / 32)), 0, st, L, hm, (const T*)q, \
                        (const T*)k, (const T*)v, (const char*)ws, (T*)out, lse, row_pairs)
-    if (L.dtype == 0) {
-        if (L.d == 64) FOCUS_LAUNCH_SIMPLE(float, 64); else FOCUS_LAUNCH_SIMPLE(float, 128);
-    } else {
-        if (L.d == 64) FOCUS_LAUNCH_SIMPLE(uint16_t, 64); else FOCUS_LAUNCH_SIMPLE(uint16_t, 128);
-    }
+#define FOCUS_LAUNCH_SIMPLE_T(T)                                                                       \
+    do {                                                                                               \
+        if (L.dp == 64) FOCUS_LAUNCH_SIMPLE(T, 64, 32);                                                \
+        else if (L.dp == 128) FOCUS_LAUNCH_SIMPLE(T, 128, 32);                                         \
+        else FOCUS_LAUNCH_SIMPLE(T, 256, 16);                                                          \
+    } while (0)
+    if (L.dtype == 0) FOCUS_LAUNCH_SIMPLE_T(float);
+    else if (L.dtype == 2) FOCUS_LAUNCH_SIMPLE_T(f16_bits);
+    else FOCUS_LAUNCH_SIMPLE_T(uint16_t);
+#undef FOCUS_LAUNCH_SIMPLE_T
 #undef FOCUS_LAUNCH_SIMPLE
     return hipGetLastError();
 }

@@ -15,6 +15,22 @@ constexpr int MAX_CLASSES = 256;
 constexpr int MAX_HQ = 256;
 constexpr int KPOS_PAD = 0x7fffffff;  // position stored in padded key slots: never <= a query position
 
+// Element types as the kernels see them: float, uint16_t for a bfloat16 bit pattern, f16_bits for an IEEE half.
+struct f16_bits { uint16_t v; };
+__device__ inline float f16_bits_to_f32(uint16_t b)
+{
+    _Float16 h;
+    __builtin_memcpy(&h, &b, 2);
+    return (float)h;
+}
+__device__ inline uint16_t f32_to_f16_bits(float f)
+{
+    const _Float16 h = (_Float16)f;                     // round to nearest even
+    uint16_t b;
+    __builtin_memcpy(&b, &h, 2);
+    return b;
+}
+
 struct HeadMap {               // query head -> KV head, passed by value to kernels
     uint8_t kv[MAX_HQ];
 };
@@ -24,9 +40,10 @@ struct HeadMap {               // query head -> KV head, passed by value to kern
 struct Layout {
     int B, Hq, Hkv, n, d;
     int K, topk, window;
-    int dtype;                 // 0 fp32, 1 bf16
+    int dtype;                 // 0 fp32, 1 bf16, 2 fp16
     int elem;                  // bytes per element
-    int BQ;                    // query rows per attention tile (128; 256 for bf16 at n >= LONG_N)
+    int dp;                    // row length of the class-ordered K / V^T copies: d rounded up to 64, 128 or 256
+    int BQ;                    // query rows per attention tile (128; 256 for 16-bit types at n >= LONG_N, d <= 128)
     int NC;                    // number of membership classes (1 in dense mode)
     int dense;                 // every causal pair allowed: one class, no masks beyond causal
     int pair_set;              // which pairs a launch attends: 0 the whole mask, 1 only pairs that share a group
@@ -48,12 +65,13 @@ struct Layout {
     size_t off_qcc, off_kcc;           // class counts [.,NC]
     size_t off_qco, off_kco;           // padded class offsets [.,NC+1]
     size_t off_clsmask;                // group bit mask of each class [NC]
-    size_t off_cent64;                 // centroids as fp64 [Hkv][d][KMAX], KMAX = K rounded up to 4/8/16/32
+    size_t off_cent64;                 // centroids as fp64 [Hkv][d rounded up to whole 128-byte row chunks][KMAX],
+                                       // KMAX = K rounded up to 4/8/16/32
     size_t off_qperm;                  // [B,Hq,NQP] positions in class order, -1 in pads
     size_t off_kpos;                   // [B,Hkv,NKP] positions in class order, KPOS_PAD in pads
     size_t off_jobs;                   // [B,Hq,NT] (class << 24 | tile) heaviest first, -1 unused
-    size_t off_kc;                     // [B,Hkv,NKP,d] keys in class order (bf16 path)
-    size_t off_vt;                     // [B,Hkv,NKP/KT,d,KT] values, transposed per key tile (bf16 path)
+    size_t off_kc;                     // [B,Hkv,NKP,dp] keys in class order (16-bit types)
+    size_t off_vt;                     // [B,Hkv,NKP/KT,dp,KT] values, transposed per key tile (16-bit types)
     size_t total;
 };
 

@@ -16,7 +16,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfocus.so")
 
 FOCUS_OK, FOCUS_EINVAL, FOCUS_EUNSUPPORTED, FOCUS_EWORKSPACE, FOCUS_EHIP = 0, -1, -2, -3, -4
-FOCUS_F32, FOCUS_BF16 = 0, 1
+FOCUS_F32, FOCUS_BF16, FOCUS_F16 = 0, 1, 2
+DTYPES = {"f32": FOCUS_F32, "bf16": FOCUS_BF16, "f16": FOCUS_F16}
+TORCH_DTYPE_CODES = {torch.float32: FOCUS_F32, torch.bfloat16: FOCUS_BF16, torch.float16: FOCUS_F16}
 
 EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_workspace_views",
            "focus_route_workspace_size", "focus_route", "focus_assign_tokens",
@@ -113,7 +115,7 @@ def make_params(B, Hq, Hkv, n, d, K, topk, window, causal=True, dtype="bf16", sc
         keep = (ctypes.c_int32 * len(head_map))(*[int(x) for x in head_map])
         hm = ctypes.cast(keep, ctypes.POINTER(ctypes.c_int32))
     p = FocusParams(B, Hq, Hkv, n, d, K, topk, window, 1 if causal else 0,
-                    {"f32": FOCUS_F32, "bf16": FOCUS_BF16}[dtype], scale, softcap, hm)
+                    DTYPES[dtype], scale, softcap, hm)
     p._keep = keep
     return p
 
@@ -168,7 +170,7 @@ def focus_attn_fwd_set(p, pair_set, q, k, v, workspace, out, lse=None, row_pairs
 def focus_attn_merge(out_a, lse_a, out_b, lse_b, out, lse=None):
     d = out_a.shape[-1]
     rows = out_a.numel() // d
-    dtype = FOCUS_F32 if out_a.dtype == torch.float32 else FOCUS_BF16
+    dtype = TORCH_DTYPE_CODES[out_a.dtype]
     _check(load_library().focus_attn_merge(rows, d, dtype, _ptr(out_a), _ptr(lse_a), _ptr(out_b), _ptr(lse_b),
                                            _ptr(out), _ptr(lse), _stream()))
 
@@ -221,7 +223,7 @@ def focus_decode_state_views(p, state):
 
 
 def make_route_params(B, n, d_model, d_g, K, topk, dtype="bf16", sinkhorn_iters=10, tau=0.1):
-    return FocusRouteParams(B, n, d_model, d_g, K, topk, {"f32": FOCUS_F32, "bf16": FOCUS_BF16}[dtype],
+    return FocusRouteParams(B, n, d_model, d_g, K, topk, DTYPES[dtype],
                             sinkhorn_iters, tau)
 
 

@@ -21,6 +21,8 @@ from dataclasses import dataclass, replace
 import numpy as np
 import torch
 
+TORCH_DTYPES = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+
 
 @dataclass(frozen=True)
 class Workload:
@@ -31,7 +33,7 @@ class Workload:
     Hkv: int
     n: int
     d: int
-    dtype: str          # "f32" | "bf16"
+    dtype: str          # "f32" | "bf16" | "f16"
     K: int
     topk: int
     window: int
@@ -83,7 +85,7 @@ def _draw_tensor(wl, H, tensor_id, device, z, out_dtype):
 def make_inputs(wl, device="cpu"):
     """Returns dict(q, k, v, centroids) of torch tensors on `device`."""
     device = torch.device(device)
-    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    tdt = TORCH_DTYPES[wl.dtype]
     base = 1000 * wl.config_id
     z = None
     if wl.mixture > 0:
@@ -111,7 +113,7 @@ def make_router_inputs(wl, device="cpu", d_model=None, d_g=ROUTER_DG):
     router-centroids=9 router-means=10; the mixture configs add the same per-token cluster
     mean (cluster ids as for q, k, v) in hidden space."""
     device = torch.device(device)
-    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    tdt = TORCH_DTYPES[wl.dtype]
     base = 1000 * wl.config_id
     dm = d_model if d_model is not None else wl.Hq * wl.d
     g = _gen(device, base + 7)
@@ -161,8 +163,8 @@ def sample_rows(wl, count, device="cpu"):
 
 
 def to_host_bits(t):
-    """Torch tensor -> numpy array the oracle accepts (fp32, or uint16 bf16 bit patterns)."""
+    """Torch tensor -> numpy array the oracle accepts (fp32, or uint16 bit patterns of bf16 / fp16)."""
     t = t.detach().cpu().contiguous()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16)
     return t.numpy()

@@ -6,8 +6,10 @@ import torch
 from oracle import focus_oracle as fo
 from paper_2604_03260_amd import focus, workloads
 
-# stated tolerances of the benchmark spec: bf16 max-abs 2e-2 / mean-abs 2e-3, fp32 1e-5
-TOL = {"bf16": dict(out_max=2e-2, out_mean=2e-3, lse=1e-2), "f32": dict(out_max=1e-5, out_mean=1e-6, lse=1e-5)}
+# stated tolerances of the benchmark spec: bf16 max-abs 2e-2 / mean-abs 2e-3, fp32 1e-5; fp16 (three more
+# fraction bits than bf16 in the inputs' storage, the rounded probabilities and the output) a fifth of bf16's
+TOL = {"bf16": dict(out_max=2e-2, out_mean=2e-3, lse=1e-2), "f32": dict(out_max=1e-5, out_mean=1e-6, lse=1e-5),
+       "f16": dict(out_max=4e-3, out_mean=4e-4, lse=2e-3)}
 
 
 def params_of(wl, head_map=None, scale=0.0):

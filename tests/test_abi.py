@@ -53,7 +53,11 @@ def status_of(**kw):
     (dict(head_map=[0, 1, 2, 0]), focus.FOCUS_EINVAL),
     (dict(scale=-1.0), focus.FOCUS_EINVAL),
     (dict(softcap=float("nan")), focus.FOCUS_EINVAL),
-    (dict(d=80), focus.FOCUS_EUNSUPPORTED),
+    (dict(d=80), focus.FOCUS_OK),
+    (dict(d=96, dtype="f16"), focus.FOCUS_OK),
+    (dict(d=256, dtype="f32"), focus.FOCUS_OK),
+    (dict(d=112), focus.FOCUS_EUNSUPPORTED),
+    (dict(d=512), focus.FOCUS_EUNSUPPORTED),
     (dict(causal=False), focus.FOCUS_EUNSUPPORTED),
     (dict(K=32, topk=8), focus.FOCUS_EUNSUPPORTED),
     (dict(K=32, topk=1), focus.FOCUS_OK),

@@ -47,6 +47,21 @@ SMALL_CASES = [
     small("softcap_bf16", n=900, softcap=50.0, dtype="bf16", d=128, K=8, topk=2, mixture=8),
     small("batch_mha", B=3, Hq=3, Hkv=3, n=400, dtype="bf16"),
     small("gqa8", Hq=8, Hkv=1, n=700, dtype="bf16", d=128),
+    # head dims beyond 64 / 128: 80 and 96 run inside 128-wide copies, 256 has its own shape
+    small("d80_bf16", n=777, dtype="bf16", d=80),
+    small("d96_bf16", n=900, dtype="bf16", d=96, K=8, topk=2, window=50, mixture=8),
+    small("d256_bf16", n=1000, dtype="bf16", d=256, window=100),
+    small("d256_bf16_softcap_k8", n=700, dtype="bf16", d=256, K=8, topk=1, window=64, softcap=30.0, Hq=6, Hkv=2),
+    small("d80_f32", n=500, d=80),
+    small("d96_f32", n=500, d=96, K=8, topk=3, window=16),
+    small("d256_f32", n=300, d=256, Hq=2, Hkv=1),
+    # IEEE half precision
+    small("f16_d64", n=777, dtype="f16"),
+    small("f16_d128_k8", n=1400, dtype="f16", d=128, K=8, topk=2, window=64, mixture=8),
+    small("f16_d96_softcap", n=640, dtype="f16", d=96, softcap=20.0),
+    small("f16_d256", n=600, dtype="f16", d=256, Hq=2, Hkv=2),
+    small("f16_dense", n=520, dtype="f16", d=128, K=4, topk=4),
+    small("f16_two_tokens", n=2, dtype="f16", d=80),
 ]
 
 
@@ -110,9 +125,10 @@ def test_deterministic_bytes():
         assert torch.equal(a["views"][key], b["views"][key]), key
 
 
-def test_vector_and_matrix_core_kernels_agree():
-    # bf16 through both attention kernels on the same workspace
-    wl = small("two_kernels", n=3000, dtype="bf16", d=128, K=4, topk=2, window=300, Hq=4, Hkv=1)
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 256), ("f16", 80)])
+def test_vector_and_matrix_core_kernels_agree(dtype, d):
+    # 16-bit inputs through both attention kernels on the same workspace
+    wl = small("two_kernels", n=3000, dtype=dtype, d=d, K=4, topk=2, window=300, Hq=4, Hkv=1)
     inp = workloads.make_inputs(wl, "cuda")
     a = harness.run_gpu(wl, inp)
     b = harness.run_gpu(wl, inp, vector=True)
@@ -203,10 +219,11 @@ def test_cfg5_full_sampled_rows_and_group_pair_counts():
     say("cfg5 allowed fraction", float(allowed.sum()) / (wl.Hq * (wl.n * (wl.n + 1) // 2)))
 
 
-def test_long_sequence_uses_256_row_tiles():
-    # n >= 2^18 switches the bf16 kernel to 8-wavefront work-groups (256-row query tiles); the vector
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f16", 96)])
+def test_long_sequence_uses_256_row_tiles(dtype, d):
+    # n >= 2^18 switches the 16-bit kernel to 8-wavefront work-groups (256-row query tiles); the vector
     # kernel then walks each tile in two passes.  Ragged n so the last tiles are partial.
-    wl = small("long_n", n=262144 + 77, Hq=2, Hkv=1, d=64, dtype="bf16", K=4, topk=2, window=2048)
+    wl = small("long_n", n=262144 + 77, Hq=2, Hkv=1, d=d, dtype=dtype, K=4, topk=2, window=2048)
     inp = workloads.make_inputs(wl, "cuda")
     res = harness.run_gpu(wl, inp)
     mq, mk = harness.check_assign(wl, inp, res)

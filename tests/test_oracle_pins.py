@@ -391,3 +391,31 @@ def test_window_holds_exactly_w_keys():
     for i in range(n):
         lo = max(0, i - w + 1)
         np.testing.assert_allclose(out[i], v[0, 0, lo:i + 1].astype(np.float64).mean(axis=0), atol=1e-14)
+
+
+def test_half_precision_storage_is_ieee_binary16():
+    # Every one of the 65536 bit patterns, read by the oracle (score against the centroid [1.0] with
+    # d = 1 is the stored value itself) and by numpy's float16: zeros, subnormals, normals, infinities, NaNs.
+    bits = np.arange(65536, dtype=np.uint16).reshape(1, 1, 65536, 1)
+    pb = fo.Problem(1, 1, 1, 65536, 1, 1, 1, 1, dtype="f16")
+    got = fo.scores(pb, np.ascontiguousarray(bits), np.ones((1, 1, 1), dtype=np.float32), True).reshape(-1)
+    want = bits.reshape(-1).view(np.float16).astype(np.float64)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok], want[ok])                  # (-0 scores as +0: equal as numbers)
+
+
+def test_half_precision_attention_matches_the_widened_inputs():
+    # the same values handed over as fp16 bits and as fp32 give the same rows
+    rng = np.random.default_rng(5)
+    B, Hq, Hkv, n, d, K, topk, w = 1, 2, 1, 40, 8, 4, 2, 5
+    q, k, v = (rng.standard_normal((B, H, n, d)).astype(np.float16) for H in (Hq, Hkv, Hkv))
+    c = rng.standard_normal((Hkv, K, d)).astype(np.float32)
+    outs = []
+    for dtype, conv in (("f16", lambda a: np.ascontiguousarray(a.view(np.uint16))), ("f32", lambda a: a.astype(np.float32))):
+        pb = fo.Problem(B, Hq, Hkv, n, d, K, topk, w, dtype=dtype)
+        mq = fo.membership(pb, conv(q), c, True)
+        mk = fo.membership(pb, conv(k), c, False)
+        outs.append(fo.attn_rows(pb, conv(q), conv(k), conv(v), mq, mk))
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
