@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--no-router", action="store_true")
     ap.add_argument("--no-two-call", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-wider", action="store_true", help="skip the half-precision / other-head-dim variants of cfg3")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of q (known size) so a counter run can be calibrated")
@@ -114,7 +115,8 @@ def main():
     out = torch.empty_like(q)          # later runs (dense mode) must not overwrite the checked output
     tflops_step = useful_flop / (ms_step * 1e-3) / 1e12
     tflops_attn = useful_flop / (ms_attn * 1e-3) / 1e12
-    peak = BF16_MFMA_PEAK_TFLOPS if wl.dtype == "bf16" else FP32_VECTOR_PEAK_TFLOPS
+    half = wl.dtype in ("bf16", "f16")          # both 16-bit types run on the matrix cores at the same peak
+    peak = BF16_MFMA_PEAK_TFLOPS if half else FP32_VECTOR_PEAK_TFLOPS
 
     result = {
         "metric": "useful TFLOP/s of Focus attention fwd (assign + attention, 4*d FLOP per allowed pair)",
@@ -140,8 +142,8 @@ def main():
         "largest_group_fraction": dominance,
         "pct_of_peak_step": 100.0 * tflops_step / peak,
         "roofline": {
-            "bound": "mfma" if wl.dtype == "bf16" else "alu",
-            "kernel": "attn_mfma_kernel" if wl.dtype == "bf16" else "attn_simple_kernel",
+            "bound": "mfma" if half else "alu",
+            "kernel": "attn_mfma_kernel" if half else "attn_simple_kernel",
             "achieved": tflops_attn,
             "peak": peak,
             "unit": "TFLOP/s",
@@ -162,9 +164,10 @@ def main():
         result["speedup_vs_dense_step"] = ms_step_d / ms_step
         del wsd
 
-    # context: the GPT-2 124M shape (short sequences), same step, reported beside the headline workload
-    if wl.name == "cfg3" and not args.no_dense:
-        w2 = workloads.CONFIGS["cfg2"]
+    # context: other shapes through the same step (assign + attention), reported beside the headline workload:
+    # the GPT-2 124M shape (short sequences), and the headline shape in half precision and at other head dims
+    # (query heads scaled so that Hq*d stays 4096)
+    def quick(w2, label, nrep):
         i2 = workloads.make_inputs(w2, "cuda")
         p2 = focus.make_params(w2.B, w2.Hq, w2.Hkv, w2.n, w2.d, w2.K, w2.topk, w2.window, causal=True,
                                dtype=w2.dtype, softcap=w2.softcap)
@@ -176,20 +179,29 @@ def main():
         torch.cuda.synchronize()
         allowed2 = int(rp2.to(torch.int64).sum().item())
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        n2 = 20
         ev[0].record()
-        for _ in range(n2):
+        for _ in range(nrep):
             focus.focus_assign(p2, i2["q"], i2["k"], i2["centroids"], ws2)
             focus.focus_attn_fwd(p2, i2["q"], i2["k"], i2["v"], ws2, o2, None, None)
         ev[1].record()
         torch.cuda.synchronize()
-        ms2 = ev[0].elapsed_time(ev[1]) / n2
-        result["other_workloads"] = {"cfg2": {
-            "workload": "cfg2: B=8 H=12 n=4096 d=64 K=4 topk=2 window=256 bf16 (4-cluster mixture)",
-            "ms_per_step": ms2, "tokens_per_s": w2.B * w2.n / (ms2 * 1e-3),
-            "useful_tflops_step": 4.0 * w2.d * allowed2 / (ms2 * 1e-3) / 1e12,
-            "allowed_fraction": allowed2 / (w2.B * w2.Hq * (w2.n * (w2.n + 1) // 2))}}
-        del i2, ws2, o2, rp2
+        ms2 = ev[0].elapsed_time(ev[1]) / nrep
+        return {"workload": label, "ms_per_step": ms2, "tokens_per_s": w2.B * w2.n / (ms2 * 1e-3),
+                "useful_tflops_step": 4.0 * w2.d * allowed2 / (ms2 * 1e-3) / 1e12,
+                "allowed_fraction": allowed2 / (w2.B * w2.Hq * (w2.n * (w2.n + 1) // 2))}
+
+    if wl.name == "cfg3" and not args.no_dense:
+        result["other_workloads"] = {"cfg2": quick(
+            workloads.CONFIGS["cfg2"], "cfg2: B=8 H=12 n=4096 d=64 K=4 topk=2 window=256 bf16 (4-cluster mixture)", 20)}
+    if wl.name == "cfg3" and not args.no_wider:
+        from dataclasses import replace
+        wider = result.setdefault("other_workloads", {})
+        for tag, kw in (("cfg3_f16", dict(dtype="f16")), ("cfg3_d256", dict(d=256, Hq=16, Hkv=4)),
+                        ("cfg3_d96", dict(d=96, Hq=40, Hkv=8)), ("cfg3_d80", dict(d=80, Hq=48, Hkv=8)),
+                        ("cfg3_d64", dict(d=64, Hq=64, Hkv=16))):
+            w2 = replace(wl, name=tag, **kw)
+            wider[tag] = quick(w2, "%s: B=%d Hq=%d Hkv=%d n=%d d=%d K=%d topk=%d window=%d %s" % (
+                tag, w2.B, w2.Hq, w2.Hkv, w2.n, w2.d, w2.K, w2.topk, w2.window, w2.dtype), 5)
 
     # the paper's own evaluation order (App. D): the set of pairs that share a group, the set of window pairs
     # that share none, one softmax each, merged through their log-sum-exp -- built from the same kernels, on

@@ -55,9 +55,11 @@ typedef struct {
     int32_t B, Hq, Hkv, n, d;  /* d in {64,80,96,128,256}; Hq % Hkv == 0 unless
                                   head_map                                       */
     int32_t K, topk;           /* 1 <= topk <= K <= 32 groups per KV head        */
-    int32_t window;            /* >= 1 keys including the query itself; a window
-                                  >= n means plain causal attention              */
-    int32_t causal;            /* 1; causal = 0 is FOCUS_EUNSUPPORTED            */
+    int32_t window;            /* w >= 1: the local keys of query i are i-w < j <= i
+                                  (w keys including the query itself) when causal,
+                                  |i-j| < w when not; w >= n means plain attention */
+    int32_t causal;            /* 1: keys j <= i only; 0: keys on both sides (the
+                                  incremental path takes 1 only)                 */
     int32_t dtype;             /* focus_dtype of q, k, v, out                    */
     float scale;               /* logit scale, 0 selects 1/sqrt(d) (Sec. 2)      */
     float softcap;             /* 0 = off, else logit = softcap*tanh(scale*q.k/softcap),

@@ -51,7 +51,6 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
         return fail(FOCUS_EINVAL, "Hq (%d) is not a multiple of Hkv (%d) and no head_map given", p->Hq, p->Hkv);
     }
     // valid, but no kernel in this build
-    if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "non-causal attention is not built");
     if (p->d != 64 && p->d != 80 && p->d != 96 && p->d != 128 && p->d != 256)
         return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64, 80, 96, 128 or 256)", p->d);
     if (p->Hq > MAX_HQ || p->Hkv > MAX_HQ)
@@ -62,7 +61,8 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
 
     memset(L, 0, sizeof(*L));
     L->B = p->B; L->Hq = p->Hq; L->Hkv = p->Hkv; L->n = p->n; L->d = p->d;
-    L->K = p->K; L->topk = p->topk; L->window = p->window;
+    L->K = p->K; L->topk = p->topk; L->window = std::min(p->window, p->n);
+    L->causal = p->causal;
     L->dtype = p->dtype;
     L->elem = (p->dtype == FOCUS_F32) ? 4 : 2;
     L->scale = (p->scale > 0.0f) ? p->scale : (float)(1.0 / std::sqrt((double)p->d));
@@ -198,7 +198,7 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     } else if (p->Hq % p->Hkv != 0) {
         return fail(FOCUS_EINVAL, "Hq (%d) is not a multiple of Hkv (%d) and no head_map given", p->Hq, p->Hkv);
     }
-    if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "non-causal attention is not built");
+    if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "the incremental path is causal (one new token at the end)");
     if (p->d != 64 && p->d != 128) return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64 or 128)", p->d);
     if (p->Hq > MAX_HQ || p->Hkv > MAX_HQ) return fail(FOCUS_EUNSUPPORTED, "more than %d heads is not built", MAX_HQ);
     if (p->n > (1 << 24)) return fail(FOCUS_EUNSUPPORTED, "n above 2^24 is not built");

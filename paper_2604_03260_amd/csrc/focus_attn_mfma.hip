@@ -243,6 +243,13 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     const int total = S.plan.total;
     const int w = L.window;
     const int d = L.d;                  // row length of q and out
+    // The allowed test of a key at position kp is one unsigned compare, (unsigned)(qadj - kp) < wlim:
+    //   causal:      qadj = qpos;  wlim = 2^31 for a class that shares a group (0 <= qpos - kp), else w;
+    //   non-causal:  shares a group: qadj = qpos + 2^30, wlim = 2^31 (any real key; pads sit at INT_MAX);
+    //                otherwise |qpos - kp| < w: qadj = qpos + w - 1, wlim = 2w - 1.
+    const int qadj_inter = L.causal ? qpos : qpos + (1 << 30);
+    const int qadj_local = L.causal ? qpos : qpos + w - 1;
+    const unsigned wlim_local = L.causal ? (unsigned)w : (unsigned)(2 * w - 1);
     if (total == 0) {
         // Only a launch restricted to one of the two pair sets can leave a tile without keys
         // (the whole mask always holds the diagonal): its rows are empty, out = 0 and lse = -inf.
@@ -420,8 +427,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
             const int4 kp4_ = *(const int4*)(&S.kpos[KPB][(U) * 32 + 8 * r4 + 4 * hh]);                  \
             const int kp_[4] = {kp4_.x, kp4_.y, kp4_.z, kp4_.w};                                         \
             _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                              \
-                /* 0 <= qpos - kpos < wlim in one unsigned compare; pads (INT_MAX) and qpos = -1 fail */ \
-                const bool ok_ = (unsigned)(qpos - kp_[e]) < wlim;                                       \
+                const bool ok_ = (unsigned)(qadj - kp_[e]) < wlim;                                       \
                 SIN[r4 * 4 + e] = ok_ ? SIN[r4 * 4 + e] : -INFINITY;                                     \
                 if constexpr (PAIRS) npairs += ok_ ? 1 : 0;                                              \
             }                                                                                            \
@@ -479,7 +485,9 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
 #define F4_TILE(SC)                                                                                      \
     {                                                                                                    \
         const int sc = (SC), sn = (SC) ^ 1;                                                              \
-        const unsigned wlim = ((pk0 >> 30) & 1u) ? 0x80000000u : (unsigned)w;   /* causal only / window */ \
+        const bool shares_ = ((pk0 >> 30) & 1u) != 0;        /* the key class shares a group with the rows */ \
+        const unsigned wlim = shares_ ? 0x80000000u : wlim_local;                                        \
+        const int qadj = shares_ ? qadj_inter : qadj_local;                                              \
         const bool interior = (pk0 >> 31) != 0;                                                          \
         const int tl1 = (int)(pk1 & TILE_MASK);                                                          \
         const int tl2 = (int)(pk2 & TILE_MASK);                                                          \

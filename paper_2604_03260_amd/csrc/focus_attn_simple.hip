@@ -105,7 +105,9 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
                 float x = dot * scale;
                 if (cap > 0.f) x = cap * tanhf(x / cap);
                 const int kp = s_kpos[kk];
-                const bool ok = rvalid && kp <= qpos && (inter || kp > qpos - w);
+                const int dlt = qpos - kp;               // pads sit at INT_MAX
+                const bool ok = rvalid && kp != KPOS_PAD &&
+                                (L.causal ? (dlt >= 0 && (inter || dlt < w)) : (inter || (dlt < w && -dlt < w)));
                 s[kk] = ok ? x : -INFINITY;
                 npairs += ok ? 1 : 0;
                 mx = fmaxf(mx, s[kk]);

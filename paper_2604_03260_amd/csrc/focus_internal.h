@@ -39,7 +39,8 @@ struct HeadMap {               // query head -> KV head, passed by value to kern
 // workspace (byte offsets from its base, all multiples of 256).
 struct Layout {
     int B, Hq, Hkv, n, d;
-    int K, topk, window;
+    int K, topk, window;       // window clamped to n
+    int causal;                // 1: keys j <= i, local = i-w < j <= i; 0: every j, local = |i-j| < w
     int dtype;                 // 0 fp32, 1 bf16, 2 fp16
     int elem;                  // bytes per element
     int dp;                    // row length of the class-ordered K / V^T copies: d rounded up to 64, 128 or 256

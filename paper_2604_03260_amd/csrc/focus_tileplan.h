@@ -4,8 +4,9 @@
 // ascending.  Keys are partitioned by class too, so every allowed pair of
 // App. D Eq. 3 (with top-k sets) is met exactly once:
 //   - key class shares a group with the query class: all its keys up to the
-//     tile's last query position (causal prefix);
-//   - otherwise: only its keys inside the union of the rows' local windows.
+//     tile's last query position (causal prefix), or all its keys (non-causal);
+//   - otherwise: only its keys inside the union of the rows' local windows
+//     (i-w < j <= i causal, |i-j| < w non-causal).
 // Per-element causal/window checks on positions finish the job inside a tile.
 // A launch may be restricted to one of the two disjoint parts (App. D): the classes that share
 // a group (set A) or the window spans of those that share none (set B); a tile may then have nothing to visit.
@@ -42,7 +43,8 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
     const int nvalid = min(L.BQ, qcc[c] - t * L.BQ);
     const int i_lo = qperm[row0];
     const int i_hi = qperm[row0 + nvalid - 1];
-    const int x_hi = i_hi + 1;                              // keys with position < x_hi are causal for the tile
+    // keys with position < x_hi are causal for the tile / not beyond every window (non-causal)
+    const int x_hi = L.causal ? i_hi + 1 : min(L.n, i_hi + L.window);
     const int x_lo = max(0, i_lo - L.window + 1);           // keys with position < x_lo are outside every window
     const uint8_t* kcls = (const uint8_t*)(ws + L.off_kcls) + (size_t)bhk * ((size_t)L.nblk * SB);
     const int bh_i = x_hi / SB, bl_i = x_lo / SB;
@@ -67,8 +69,9 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
         int a = 0, b = 0;
         if (inter) {
             if (L.pair_set != 2) {                         // set B skips the classes that share a group
+                const int upto = L.causal ? pre_hi : kbc[(size_t)L.nblk * NC + c2];   // non-causal: the whole class
                 a = koff / KT;
-                b = (koff + pre_hi + KT - 1) / KT;
+                b = (koff + upto + KT - 1) / KT;
             }
         } else if (L.pair_set != 1) {                      // set A skips the classes that share none
             int pre_lo = kbc[(size_t)bl_i * NC + c2];
@@ -84,7 +87,11 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
         // Tiles that need no per-element test, from prefix counts at sort-block boundaries (conservative):
         // keys before the sort block that holds i_lo+1 sit at positions <= i_lo (causal for every row);
         // for a class without a common group they must also lie above i_hi - window for every row.
-        const int cnt_below = kbc[(size_t)((i_lo + 1) / SB) * NC + c2];
+        // Non-causal: for a class with a common group every tile without pads; otherwise the keys must lie
+        // below i_lo + window for every row instead of at or below i_lo.
+        const int safe_end = L.causal ? i_lo + 1 : min(L.n, i_lo + L.window);
+        const int cnt_below = (!L.causal && (inter || safe_end >= L.n)) ? kbc[(size_t)L.nblk * NC + c2]
+                                                                        : kbc[(size_t)(safe_end / SB) * NC + c2];
         int ib = a, ie = a;
         if (inter) {
             ie = a + min(b - a, cnt_below / KT);

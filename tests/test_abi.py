@@ -58,7 +58,7 @@ def status_of(**kw):
     (dict(d=256, dtype="f32"), focus.FOCUS_OK),
     (dict(d=112), focus.FOCUS_EUNSUPPORTED),
     (dict(d=512), focus.FOCUS_EUNSUPPORTED),
-    (dict(causal=False), focus.FOCUS_EUNSUPPORTED),
+    (dict(causal=False), focus.FOCUS_OK),
     (dict(K=32, topk=8), focus.FOCUS_EUNSUPPORTED),
     (dict(K=32, topk=1), focus.FOCUS_OK),
     (dict(K=32, topk=20), focus.FOCUS_OK),          # 2k > K: plain causal attention, one class

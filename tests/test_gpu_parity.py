@@ -62,6 +62,17 @@ SMALL_CASES = [
     small("f16_d256", n=600, dtype="f16", d=256, Hq=2, Hkv=2),
     small("f16_dense", n=520, dtype="f16", d=128, K=4, topk=4),
     small("f16_two_tokens", n=2, dtype="f16", d=80),
+    # keys on both sides of the query: local = |i-j| < w
+    small("noncausal_f32", n=777, causal=False),
+    small("noncausal_bf16", n=1000, causal=False, dtype="bf16", d=128, window=100),
+    small("noncausal_k8_top1", n=1500, causal=False, K=8, topk=1, window=70, dtype="bf16", d=128, Hq=8, Hkv=2, mixture=8),
+    small("noncausal_k8_top2_f16", n=1300, causal=False, K=8, topk=2, window=33, dtype="f16", d=96),
+    small("noncausal_window_one", n=300, causal=False, window=1, topk=1),
+    small("noncausal_dense_window", n=520, causal=False, window=520, dtype="bf16"),
+    small("noncausal_dense_groups", n=700, causal=False, K=4, topk=3, dtype="bf16", d=256),
+    small("noncausal_tile_multiple", n=512, causal=False, window=64, dtype="bf16"),
+    small("noncausal_softcap", n=640, causal=False, softcap=5.0, dtype="bf16", d=80),
+    small("noncausal_one_token", n=1, causal=False, dtype="bf16"),
 ]
 
 
@@ -112,6 +123,21 @@ def test_disjoint_roles_only_window_survives():
     harness.check_attn(wl, inp, res, mq, mk, tol=dict(out_max=1e-4, out_mean=1e-5, lse=1e-3))
     want = np.minimum(np.arange(wl.n) + 1, wl.window)
     assert np.array_equal(res["row_pairs"].cpu().numpy()[0, 0], want)
+
+
+def test_noncausal_mid_size_sampled_rows():
+    # windows that span several sort blocks on both sides: tiles without any per-element test exist
+    wl = small("noncausal_mid", n=20000 + 37, causal=False, K=4, topk=2, window=1500, dtype="bf16", d=128, Hq=4, Hkv=2)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    rows = workloads.sample_rows(wl, 1024)
+    say("noncausal_mid", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    harness.check_pair_totals(wl, res, mq, mk)
+    vec = harness.run_gpu(wl, inp, vector=True)
+    assert torch.equal(res["row_pairs"], vec["row_pairs"])
+    diff = (res["out"].float() - vec["out"].float()).abs()
+    assert diff.max().item() <= 2e-2 and diff.mean().item() <= 2e-3
 
 
 def test_deterministic_bytes():

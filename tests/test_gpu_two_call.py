@@ -75,12 +75,19 @@ CASES = [
     (1, 2, 1, 513, 64, "f32", 8, 3, 1, 0.0),
     (1, 2, 2, 260, 128, "bf16", 1, 1, 8, 0.0),         # one group: B is empty everywhere
     (1, 2, 2, 3, 64, "bf16", 4, 1, 2, 0.0),
+    (1, 4, 2, 800, 96, "f16", 4, 2, 50, 0.0),          # half precision, a head dim inside 128-wide copies
+    (1, 2, 1, 600, 256, "bf16", 8, 1, 30, 0.0),
+    (1, 4, 2, 900, 128, "bf16", 4, 1, 40, 0.0, False), # keys on both sides of the query
+    (1, 2, 2, 500, 64, "f32", 8, 2, 9, 0.0, False),
 ]
 
 
-@pytest.mark.parametrize("B,Hq,Hkv,n,d,dtype,K,topk,w,cap", CASES)
-def test_sets_merge_and_two_call_small(B, Hq, Hkv, n, d, dtype, K, topk, w, cap):
-    wl = workloads.Workload("t", 70 + K + topk, B, Hq, Hkv, n, d, dtype, K, topk, w, softcap=cap, mixture=3)
+@pytest.mark.parametrize("case", CASES, ids=[str(i) for i in range(len(CASES))])
+def test_sets_merge_and_two_call_small(case):
+    B, Hq, Hkv, n, d, dtype, K, topk, w, cap = case[:10]
+    causal = case[10] if len(case) > 10 else True
+    wl = workloads.Workload("t", 70 + K + topk, B, Hq, Hkv, n, d, dtype, K, topk, w, causal=causal, softcap=cap,
+                            mixture=3)
     inp = workloads.make_inputs(wl, "cuda")
     res = run_sets(wl, inp)
     mq, mk = harness.oracle_membership(wl, inp)
