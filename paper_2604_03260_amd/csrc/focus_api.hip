@@ -77,15 +77,27 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
             c = c * (uint64_t)(p->K - kk + i) / (uint64_t)i;
             if (c > (uint64_t)MAX_CLASSES) break;
         }
-        if (c > (uint64_t)MAX_CLASSES)
-            return fail(FOCUS_EUNSUPPORTED, "C(K=%d, topk=%d) membership classes exceed %d", p->K, p->topk, MAX_CLASSES);
         L->NC = (int)c;
+        L->S = p->K;
+        if (c > (uint64_t)MAX_CLASSES) {
+            // too many exact classes: fold the groups onto the largest number S of super-groups whose sets of
+            // 1..topk members still fit the class tables
+            L->coarse = 1;
+            int best = 1, best_nc = 1;
+            for (int S = 1; S <= p->K; ++S) {
+                uint64_t tot = 0;
+                for (int j = 1; j <= std::min(kk, S); ++j) tot += focus::binom_u32(S, j);
+                if (tot <= (uint64_t)MAX_CLASSES) { best = S; best_nc = (int)tot; }
+            }
+            L->S = best;
+            L->NC = best_nc;
+        }
     }
     L->nblk = (p->n + SB - 1) / SB;
     // bf16 at long n: 256-row tiles (8 wavefronts share every K/V tile: half the L2->LDS traffic per FLOP,
     // which is what bounds the kernel once a KV head's K/V no longer sits in L2/MALL)
     L->dp = (p->d <= 64) ? 64 : (p->d <= 128) ? 128 : 256;
-    L->BQ = (p->dtype != FOCUS_F32 && p->n >= LONG_N && p->d <= 128) ? 256 : BQ_VECTOR;
+    L->BQ = (p->dtype != FOCUS_F32 && p->n >= LONG_N && p->d <= 128 && !L->coarse) ? 256 : BQ_VECTOR;
     L->NT = (p->n + L->BQ - 1) / L->BQ + L->NC;
     L->NQP = L->NT * L->BQ;
     L->NKP = ((p->n + KT - 1) / KT + L->NC) * KT;
@@ -119,6 +131,7 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->off_cent64 = take((size_t)p->Hkv * (((size_t)p->d * L->elem + 127) / 128 * (128 / L->elem)) * 32 * 8);
     L->off_qperm = take(BHq * L->NQP * 4);
     L->off_kpos = take(BHk * L->NKP * 4);
+    L->off_kmsk = L->coarse ? take(BHk * L->NKP * 4) : off;
     L->off_jobs = take(BHq * L->NT * 4);
     if (p->dtype != FOCUS_F32) {
         L->off_kc = take(BHk * L->NKP * (size_t)L->dp * 2);
@@ -151,7 +164,8 @@ focus_status make_route_layout(const focus_route_params* rp, focus::RouteLayout*
     if (rp->K < 1 || rp->K > 32) return fail(FOCUS_EINVAL, "K must be in [1,32] (got %d)", rp->K);
     if (rp->topk < 1 || rp->topk > rp->K)
         return fail(FOCUS_EINVAL, "topk must be in [1,K] (got %d, K=%d)", rp->topk, rp->K);
-    if (rp->dtype != FOCUS_F32 && rp->dtype != FOCUS_BF16) return fail(FOCUS_EINVAL, "unknown dtype %d", rp->dtype);
+    if (rp->dtype != FOCUS_F32 && rp->dtype != FOCUS_BF16 && rp->dtype != FOCUS_F16)
+        return fail(FOCUS_EINVAL, "unknown dtype %d", rp->dtype);
     if (rp->sinkhorn_iters < 0) return fail(FOCUS_EINVAL, "sinkhorn_iters must be >= 0");
     if (!(rp->tau > 0.0) || !std::isfinite(rp->tau)) return fail(FOCUS_EINVAL, "tau must be finite and > 0");
     if (rp->d_model % 8 != 0) return fail(FOCUS_EUNSUPPORTED, "d_model %d is not a multiple of 8", rp->d_model);
@@ -275,6 +289,9 @@ focus_status attn_launch(const focus_params* p, int pair_set, const void* q, con
     if (pair_set != 0 && p->window >= p->n && 2 * p->topk <= p->K)
         return fail(FOCUS_EUNSUPPORTED, "the two-set decomposition is not built for window >= n "
                                         "(every causal pair is local: one launch over the whole mask is the answer)");
+    if (pair_set != 0 && L.coarse)
+        return fail(FOCUS_EUNSUPPORTED, "the two-set decomposition is not built for C(K=%d, topk=%d) > %d classes",
+                    p->K, p->topk, focus::MAX_CLASSES);
     if (!q || !k || !v || !out) return fail(FOCUS_EINVAL, "q, k, v and out must not be NULL");
     if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(out))
         return fail(FOCUS_EINVAL, "q, k, v and out must be 16-byte aligned");

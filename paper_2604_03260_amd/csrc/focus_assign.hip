@@ -169,7 +169,9 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
         for (int g = 0; g < KMAX; ++g) acc[g] = 0.0;
         // class = colex rank of the membership set among all topk-subsets
         int cls = 0;
-        if (!L.dense) {
+        if (L.coarse) {
+            cls = class_of_mask(mask, 0, 1, L.S);
+        } else if (!L.dense) {
             int j = 0;
             for (int g = 0; g < K; ++g)
                 if ((mask >> g) & 1u) { ++j; cls += (int)g_binom.v[g * 33 + j]; }
@@ -291,9 +293,17 @@ __global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int is_query,
             if (L.dense) {
                 m = 0xffffffffu;
             } else {
+                // exact classes: topk-subsets of the K groups in colex order; coarse classes: sets of
+                // 1..topk of the S super-groups, by size, then colex
                 uint32_t r = (uint32_t)c;
-                int g = K - 1;
-                for (int j = L.topk; j >= 1; --j) {
+                int size = L.topk, top = K - 1;
+                if (L.coarse) {
+                    size = 1;
+                    while (r >= binom_u32(L.S, size)) { r -= binom_u32(L.S, size); ++size; }
+                    top = L.S - 1;
+                }
+                int g = top;
+                for (int j = size; j >= 1; --j) {
                     while (binom_u32(g, j) > r) --g;      // largest g with C(g,j) <= r
                     m |= (1u << g);
                     r -= binom_u32(g, j);
@@ -319,7 +329,7 @@ __global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int is_query,
                 j += min(s_nt[c2], s);
                 if (c2 < c && s_nt[c2] > s) ++j;
             }
-            jobs[j] = (c << 24) | t;
+            jobs[j] = (int)(((unsigned)c << 24) | (unsigned)t);   // t < 2^17: never the unused marker -1
         }
     }
 }
@@ -378,10 +388,12 @@ __global__ __launch_bounds__(SB) void scatter_kernel(Layout L, int is_query, cha
         int before = 0;
         for (int w = 0; w < wave; ++w) before += s_wc[w][cls];
         const int dest = co[cls] + bc[cls] + before + rank_c;
-        if (is_query)
+        if (is_query) {
             ((int*)(ws + L.off_qperm))[(size_t)bh * L.NQP + dest] = pos;
-        else
+        } else {
             ((int*)(ws + L.off_kpos))[(size_t)bh * L.NKP + dest] = pos;
+            if (L.coarse) ((uint32_t*)(ws + L.off_kmsk))[(size_t)bh * L.NKP + dest] = mask;
+        }
     }
     // group lists: position-ascending because ranks follow the position order
     int* lists = (int*)(ws + (is_query ? L.off_qgl : L.off_kgl)) + (size_t)bh * L.topk * n;
@@ -423,7 +435,9 @@ __global__ __launch_bounds__(SB) void token_classes_kernel(Layout L, const uint3
             mask = (L.topk == 32) ? 0xffffffffu : ((1u << L.topk) - 1u);
             if (invalid_count) atomicAdd(invalid_count, 1);
         }
-        if (!L.dense) {
+        if (L.coarse) {
+            cls = class_of_mask(mask, 0, 1, L.S);
+        } else if (!L.dense) {
             int j = 0;
             for (int g = 0; g < K; ++g)
                 if ((mask >> g) & 1u) { ++j; cls += (int)g_binom.v[g * 33 + j]; }
@@ -479,6 +493,7 @@ void launch_pad_fills(const Layout& L, char* ws, hipStream_t st)
     const int gq = (int)min((size_t)8192, (nq + 255) / 256), gk = (int)min((size_t)8192, (nk + 255) / 256);
     hipLaunchKernelGGL(fill_i32_kernel, dim3(gq), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, -1);
     hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kpos), nk, KPOS_PAD);
+    if (L.coarse) hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kmsk), nk, 0);
 }
 
 // from masks, class ids and block histograms to the class-ordered arrays, group lists and job lists

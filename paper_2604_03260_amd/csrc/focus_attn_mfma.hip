@@ -139,12 +139,13 @@ __device__ inline int swz(int row, int ch)
     else return ch ^ ((row >> 1) & 7);
 }
 
-template <int D>
+template <int D, bool COARSE>
 struct Smem {
     TilePlan plan;
     __attribute__((aligned(16))) int kpos[3][KT];
-    __attribute__((aligned(16))) char k[2][KT * D * 2];     // [stage][key][D] bf16, chunks swizzled
-    __attribute__((aligned(16))) char vt[2][D * KT * 2];    // [stage][d][KT] bf16, chunks swizzled
+    __attribute__((aligned(16))) char k[2][KT * D * 2];     // [stage][key][D] 16-bit elements, chunks swizzled
+    __attribute__((aligned(16))) char vt[2][D * KT * 2];    // [stage][d][KT] 16-bit elements, chunks swizzled
+    __attribute__((aligned(16))) unsigned kmsk[COARSE ? 3 * KT : 4];   // membership masks of the keys (coarse classes)
 };
 
 // max of the two half-waves (lane l and lane l^32 hold the same query row)
@@ -192,7 +193,9 @@ __device__ inline void pin_operands(V8 (&a)[N])
 // D: row length of the class-ordered copies (64, 128, 256); KS: MFMAs of one QK^T unit = d / 16;
 // DB: 32-row blocks of O^T = ceil(d / 32).  With 512-byte key rows the operands of a phase alone
 // take 128 registers, so that shape runs one wavefront per SIMD with the full register file.
-template <int D, int KS, int DB, int MFMA_WAVES, bool SOFTCAP, bool PAIRS, bool F16>
+// COARSE: membership classes are sets of super-groups; a key class that shares one with the rows' class
+// may or may not share a real group, so its pairs are tested against the two membership masks.
+template <int D, int KS, int DB, int MFMA_WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE>
 __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) void attn_mfma_kernel(
     Layout L, HeadMap hm, int default_map, const uint16_t* __restrict__ q, const char* __restrict__ ws,
     uint16_t* __restrict__ out, float* __restrict__ lse, int32_t* __restrict__ row_pairs)
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     typedef typename HT::T elem_t;
     typedef typename HT::V8 V8;
     typedef typename HT::V2 V2;
-    __shared__ Smem<D> S;
+    __shared__ Smem<D, COARSE> S;
     static_assert(KS * 16 <= D && DB * 32 <= D, "the products stay inside the copied rows");
     // With 512-byte key rows the operands of a whole phase would not fit the vector registers next to
     // Q, so that shape fetches and multiplies them in two halves (HV = 2); the others in one go.
@@ -247,6 +250,8 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     //   causal:      qadj = qpos;  wlim = 2^31 for a class that shares a group (0 <= qpos - kp), else w;
     //   non-causal:  shares a group: qadj = qpos + 2^30, wlim = 2^31 (any real key; pads sit at INT_MAX);
     //                otherwise |qpos - kp| < w: qadj = qpos + w - 1, wlim = 2w - 1.
+    unsigned mq_row = 0u;
+    if constexpr (COARSE) mq_row = rvalid ? ((const unsigned*)(ws + L.off_mq))[(size_t)bhq * L.n + qpos] : 0u;
     const int qadj_inter = L.causal ? qpos : qpos + (1 << 30);
     const int qadj_local = L.causal ? qpos : qpos + w - 1;
     const unsigned wlim_local = L.causal ? (unsigned)w : (unsigned)(2 * w - 1);
@@ -289,6 +294,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     const char* kc_base = ws + L.off_kc + (size_t)bhk * L.NKP * (D * 2);
     const char* vt_base = ws + L.off_vt + (size_t)bhk * L.NKP * (D * 2);
     const char* kpos_base = ws + L.off_kpos + (size_t)bhk * L.NKP * 4;
+    const char* kmsk_base = ws + L.off_kmsk + (size_t)bhk * L.NKP * 4;
 
     // per-lane source offsets of the swizzled DMA: wave `wave` fills the 1-KB LDS blocks wave + 4*i
     // of a tile; block j holds rows 4j..4j+3 (256-byte rows) or 8j..8j+7 (128-byte rows), and the
@@ -315,6 +321,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     }
     const unsigned lds_k0 = lds_addr_of(&S.k[0][0]), lds_v0 = lds_addr_of(&S.vt[0][0]);
     const unsigned lds_kp0 = lds_addr_of(&S.kpos[0][0]);
+    const unsigned lds_km0 = lds_addr_of(&S.kmsk[0]);
 
 #define F4_DMA_K(TILE, STAGE)                                                                        \
     do {                                                                                             \
@@ -330,8 +337,11 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     } while (0)
 #define F4_DMA_KPOS(TILE, BUF)                                                                       \
     do {                                                                                             \
-        if (wave == 0 && lane < KT / 4)                                                              \
+        if (wave == 0 && lane < KT / 4) {                                                            \
             dma16(kpos_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_kp0 + (BUF) * (KT * 4)); \
+            if constexpr (COARSE)                                                                    \
+                dma16(kmsk_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_km0 + (BUF) * (KT * 4)); \
+        }                                                                                            \
     } while (0)
 #define F4_WAIT_DMA() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
 
@@ -426,8 +436,18 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
         _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4) {                                               \
             const int4 kp4_ = *(const int4*)(&S.kpos[KPB][(U) * 32 + 8 * r4 + 4 * hh]);                  \
             const int kp_[4] = {kp4_.x, kp4_.y, kp4_.z, kp4_.w};                                         \
+            unsigned km_[4] = {0u, 0u, 0u, 0u};                                                          \
+            if constexpr (COARSE) {                                                                      \
+                const uint4 km4_ = *(const uint4*)(&S.kmsk[(KPB) * KT + (U) * 32 + 8 * r4 + 4 * hh]);    \
+                km_[0] = km4_.x; km_[1] = km4_.y; km_[2] = km4_.z; km_[3] = km4_.w;                      \
+            }                                                                                            \
             _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                              \
-                const bool ok_ = (unsigned)(qadj - kp_[e]) < wlim;                                       \
+                bool ok_ = (unsigned)(qadj - kp_[e]) < wlim;                                             \
+                if constexpr (COARSE) {                                                                  \
+                    /* a common super-group only: the pair needs a common group or the window */        \
+                    if (shares_)                                                                         \
+                        ok_ = ok_ && ((mq_row & km_[e]) != 0u || (unsigned)(qadj_local - kp_[e]) < wlim_local); \
+                }                                                                                        \
                 SIN[r4 * 4 + e] = ok_ ? SIN[r4 * 4 + e] : -INFINITY;                                     \
                 if constexpr (PAIRS) npairs += ok_ ? 1 : 0;                                              \
             }                                                                                            \
@@ -595,27 +615,27 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     }
 }
 
-template <int D, int KS, int DB, int WAVES, bool SOFTCAP, bool PAIRS, bool F16>
+template <int D, int KS, int DB, int WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE>
 hipError_t launch_one(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
                       float* lse, int32_t* row_pairs, hipStream_t st)
 {
     const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
-    hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16>), dim3(grid), dim3(64 * WAVES), 0, st,
+    hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16, COARSE>), dim3(grid), dim3(64 * WAVES), 0, st,
                        L, hm, default_map, (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
     return hipGetLastError();
 }
 
-template <int D, int KS, int DB, int WAVES, bool F16>
+template <int D, int KS, int DB, int WAVES, bool F16, bool COARSE>
 hipError_t launch_w(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
                     float* lse, int32_t* row_pairs, hipStream_t st)
 {
     const bool sc = L.softcap > 0.f, pairs = row_pairs != nullptr;
     if (sc) {
-        return pairs ? launch_one<D, KS, DB, WAVES, true, true, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-                     : launch_one<D, KS, DB, WAVES, true, false, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+        return pairs ? launch_one<D, KS, DB, WAVES, true, true, F16, COARSE>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                     : launch_one<D, KS, DB, WAVES, true, false, F16, COARSE>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
     }
-    return pairs ? launch_one<D, KS, DB, WAVES, false, true, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-                 : launch_one<D, KS, DB, WAVES, false, false, F16>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    return pairs ? launch_one<D, KS, DB, WAVES, false, true, F16, COARSE>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                 : launch_one<D, KS, DB, WAVES, false, false, F16, COARSE>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
 }
 
 template <int D, int KS, int DB>
@@ -628,12 +648,15 @@ hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const v
     // the query tile size fixed by focus_assign selects the work-group shape: 4 or 8 wavefronts
     if constexpr (D != 256) {
         if (L.BQ == 256)
-            return f16 ? launch_w<D, KS, DB, 8, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-                       : launch_w<D, KS, DB, 8, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+            return f16 ? launch_w<D, KS, DB, 8, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                       : launch_w<D, KS, DB, 8, false, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
     }
     if (L.BQ != 128) return hipErrorInvalidValue;
-    return f16 ? launch_w<D, KS, DB, 4, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
-               : launch_w<D, KS, DB, 4, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    if (L.coarse)                        // coarse classes always use 128-row tiles
+        return f16 ? launch_w<D, KS, DB, 4, true, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+                   : launch_w<D, KS, DB, 4, false, true>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
+    return f16 ? launch_w<D, KS, DB, 4, true, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st)
+               : launch_w<D, KS, DB, 4, false, false>(L, hm, default_map, q, ws, out, lse, row_pairs, st);
 }
 
 }  // namespace

@@ -59,6 +59,8 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
     const bool rvalid = row < P.nvalid;
     const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
     const int qpos = rvalid ? qperm[P.row0 + row] : -1;
+    const uint32_t mq_row = rvalid ? ((const uint32_t*)(ws + L.off_mq))[(size_t)bhq * L.n + qpos] : 0u;
+    const uint32_t* mk_all = (const uint32_t*)(ws + L.off_mk) + (size_t)bhk * L.n;
     const int* kpos_all = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP;
     const int d = L.d;
     const T* kbase = k + (size_t)bhk * L.n * d;
@@ -106,8 +108,10 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
                 if (cap > 0.f) x = cap * tanhf(x / cap);
                 const int kp = s_kpos[kk];
                 const int dlt = qpos - kp;               // pads sit at INT_MAX
+                bool share = inter;                      // exact classes: a common group is a class property
+                if (L.coarse && inter && kp != KPOS_PAD) share = (mq_row & mk_all[kp]) != 0u;
                 const bool ok = rvalid && kp != KPOS_PAD &&
-                                (L.causal ? (dlt >= 0 && (inter || dlt < w)) : (inter || (dlt < w && -dlt < w)));
+                                (L.causal ? (dlt >= 0 && (share || dlt < w)) : (share || (dlt < w && -dlt < w)));
                 s[kk] = ok ? x : -INFINITY;
                 npairs += ok ? 1 : 0;
                 mx = fmaxf(mx, s[kk]);

@@ -47,6 +47,8 @@ struct Layout {
     int BQ;                    // query rows per attention tile (128; 256 for 16-bit types at n >= LONG_N, d <= 128)
     int NC;                    // number of membership classes (1 in dense mode)
     int dense;                 // every causal pair allowed: one class, no masks beyond causal
+    int coarse;                // C(K,topk) exceeds MAX_CLASSES: classes are sets of S super-groups (group g folds
+    int S;                     // onto g % S), a superset test; the kernels then test the real masks per pair
     int pair_set;              // which pairs a launch attends: 0 the whole mask, 1 only pairs that share a group
                                // (set A of App. D), 2 only window pairs that share none (set B)
     int nblk;                  // ceil(n / SB)
@@ -70,6 +72,7 @@ struct Layout {
                                        // KMAX = K rounded up to 4/8/16/32
     size_t off_qperm;                  // [B,Hq,NQP] positions in class order, -1 in pads
     size_t off_kpos;                   // [B,Hkv,NKP] positions in class order, KPOS_PAD in pads
+    size_t off_kmsk;                   // [B,Hkv,NKP] membership masks in class order, 0 in pads (coarse classes only)
     size_t off_jobs;                   // [B,Hq,NT] (class << 24 | tile) heaviest first, -1 unused
     size_t off_kc;                     // [B,Hkv,NKP,dp] keys in class order (16-bit types)
     size_t off_vt;                     // [B,Hkv,NKP/KT,dp,KT] values, transposed per key tile (16-bit types)
@@ -84,6 +87,36 @@ __host__ __device__ inline uint32_t binom_u32(int a, int b)
     uint64_t r = 1;
     for (int i = 1; i <= b; ++i) r = r * (uint64_t)(a - b + i) / (uint64_t)i;
     return (uint32_t)r;
+}
+
+// Coarse classes: the S-bit set of super-groups a membership mask folds onto
+__host__ __device__ inline uint32_t fold_groups(uint32_t mask, int S)
+{
+    uint32_t r = 0;
+    while (mask) {
+        const int g = __builtin_ctz(mask);
+        r |= 1u << (g % S);
+        mask &= mask - 1;
+    }
+    return r;
+}
+
+// Class id of a membership mask.  Exact classes: the colex rank of the topk-subset of the K groups.
+// Coarse classes: the folded set has 1..topk members; sets are ordered by size, then colex.
+__host__ __device__ inline int class_of_mask(uint32_t mask, int dense, int coarse, int S)
+{
+    if (dense) return 0;
+    uint32_t m = coarse ? fold_groups(mask, S) : mask;
+    int j = 0, cls = 0;
+    while (m) {
+        const int g = __builtin_ctz(m);
+        ++j;
+        cls += (int)binom_u32(g, j);
+        m &= m - 1;
+    }
+    if (coarse)
+        for (int t = 1; t < j; ++t) cls += (int)binom_u32(S, t);
+    return cls;
 }
 
 // Shapes and workspace offsets of the router (focus_route).

@@ -4,7 +4,7 @@
 //   or Q = exp(S / tau) followed by N rounds of {columns / their sum over the sequence's tokens,
 //   rows / their sum over the groups}; the top-k entries of a row become the token's membership.
 //
-// Everything is fp64.  The projection adds exact products (fp32 x bf16/fp32 fits in fp64) in a
+// Everything is fp64.  The projection adds exact products (fp32 x bf16/fp16/fp32 fits in fp64) in a
 // fixed order -- 64 consecutive hidden components in index order, the chunk sums in chunk order --
 // so z, S and, without Sinkhorn, the membership are reproducible bit for bit.
 //
@@ -23,6 +23,7 @@
 //                     rows and leaves its own partial sums for the next pass.  The last pass writes
 //                     the masks (ties to the smaller group index) and, if asked, the soft assignment.
 #include "focus_internal.h"
+#include <type_traits>
 
 namespace focus {
 
@@ -138,6 +139,12 @@ __global__ __launch_bounds__(64 * NW) void route_project_kernel(RouteLayout R, c
             if constexpr (sizeof(T) == 4) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) xv[e] = (double)__uint_as_float(val[e]);
+            } else if constexpr (std::is_same<T, f16_bits>::value) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    xv[2 * e] = (double)f16_bits_to_f32((uint16_t)(val[e] & 0xffffu));
+                    xv[2 * e + 1] = (double)f16_bits_to_f32((uint16_t)(val[e] >> 16));
+                }
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -341,6 +348,7 @@ hipError_t launch_route(const RouteLayout& R, const void* hidden, const float* w
                        (double*)(ws + R.off_w64), nw);
     hipLaunchKernelGGL(to_f64_kernel, dim3(1), dim3(256), 0, st, cent, (double*)(ws + R.off_c64), nc);
     if (R.dtype == 0) e = launch_project<float>(R, hidden, ws, masks, soft, st);
+    else if (R.dtype == 2) e = launch_project<f16_bits>(R, hidden, ws, masks, soft, st);
     else e = launch_project<uint16_t>(R, hidden, ws, masks, soft, st);
     if (e != hipSuccess) return e;
     if (R.iters == 0) return hipSuccess;

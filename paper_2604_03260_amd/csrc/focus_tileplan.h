@@ -34,8 +34,8 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int NC = L.NC;
     const int jv = ((const int*)(ws + L.off_jobs))[(size_t)bhq * L.NT + job];
-    if (jv < 0) return false;
-    const int c = jv >> 24, t = jv & 0xffffff;
+    if (jv == -1) return false;                             // class ids reach 255: the word is unsigned but for -1
+    const int c = (int)((unsigned)jv >> 24), t = jv & 0xffffff;
     const int* qco = (const int*)(ws + L.off_qco) + (size_t)bhq * (NC + 1);
     const int* qcc = (const int*)(ws + L.off_qcc) + (size_t)bhq * NC;
     const int* qperm = (const int*)(ws + L.off_qperm) + (size_t)bhq * L.NQP;
@@ -94,7 +94,8 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
                                                                         : kbc[(size_t)(safe_end / SB) * NC + c2];
         int ib = a, ie = a;
         if (inter) {
-            ie = a + min(b - a, cnt_below / KT);
+            // coarse classes only promise a common super-group: every pair is tested against the real masks
+            if (!L.coarse) ie = a + min(b - a, cnt_below / KT);
         } else if (b > a) {
             const int x_in = i_hi - L.window + 1;
             const int lo_blk = (x_in <= 0) ? 0 : min(L.nblk, (x_in + SB - 1) / SB);

@@ -59,7 +59,7 @@ def status_of(**kw):
     (dict(d=112), focus.FOCUS_EUNSUPPORTED),
     (dict(d=512), focus.FOCUS_EUNSUPPORTED),
     (dict(causal=False), focus.FOCUS_OK),
-    (dict(K=32, topk=8), focus.FOCUS_EUNSUPPORTED),
+    (dict(K=32, topk=8), focus.FOCUS_OK),           # more than 256 membership sets: classes of super-groups
     (dict(K=32, topk=1), focus.FOCUS_OK),
     (dict(K=32, topk=20), focus.FOCUS_OK),          # 2k > K: plain causal attention, one class
 ])
@@ -181,11 +181,14 @@ def test_decode_argument_errors_before_any_launch():
     lib = focus.load_library()
     vp = ctypes.c_void_p
     fake = vp(0x1000)
-    p = focus.make_params(1, 4, 2, 4096, 128, 32, 4, 64)           # C(32,4) classes: fine for decode
+    p = focus.make_params(1, 4, 2, 4096, 128, 32, 4, 64)           # C(32,4) membership sets
     need = focus.focus_decode_state_size(p)
     assert need > 0 and need % 256 == 0
     st = lib.focus_workspace_size(ctypes.byref(p), ctypes.byref(ctypes.c_size_t(0)))
-    assert st == focus.FOCUS_EUNSUPPORTED                           # ... but not for the class-bucketed prefill path
+    assert st == focus.FOCUS_OK                                     # the prefill path folds them onto super-groups ...
+    st = lib.focus_attn_fwd_set(ctypes.byref(p), focus.FOCUS_PAIRS_SHARED, fake, fake, fake, fake,
+                                ctypes.c_size_t(1 << 40), fake, vp(0), vp(0), vp(0))
+    assert st == focus.FOCUS_EUNSUPPORTED                           # ... but then has no two-set decomposition
     assert lib.focus_decode_prefill(ctypes.byref(p), -1, fake, fake, fake, need, vp(0)) == focus.FOCUS_EINVAL
     assert lib.focus_decode_prefill(ctypes.byref(p), 4097, fake, fake, fake, need, vp(0)) == focus.FOCUS_EINVAL
     assert lib.focus_decode_prefill(ctypes.byref(p), 10, vp(0), fake, fake, need, vp(0)) == focus.FOCUS_EINVAL

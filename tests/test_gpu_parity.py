@@ -38,6 +38,7 @@ SMALL_CASES = [
     small("k16_top1", n=900, K=16, topk=1, window=16, dtype="bf16"),
     small("k32_top1", n=700, K=32, topk=1, window=8),
     small("k5_top2", n=640, K=5, topk=2, window=20, dtype="bf16"),
+    small("k12_top3_220_classes", n=2000, K=12, topk=3, window=30, dtype="bf16"),   # class ids above 127
     small("k2_top1", n=1100, K=2, topk=1, window=50, dtype="bf16", d=128),
     small("dense_window", n=700, window=700),
     small("dense_k1", n=700, K=1, topk=1, window=4, dtype="bf16"),
@@ -73,6 +74,13 @@ SMALL_CASES = [
     small("noncausal_tile_multiple", n=512, causal=False, window=64, dtype="bf16"),
     small("noncausal_softcap", n=640, causal=False, softcap=5.0, dtype="bf16", d=80),
     small("noncausal_one_token", n=1, causal=False, dtype="bf16"),
+    # more than 256 membership classes: classes of super-groups, pairs tested against the real masks
+    small("k32_top2_coarse", n=1500, K=32, topk=2, window=40, dtype="bf16", d=128),
+    small("k16_top3_coarse_f32", n=700, K=16, topk=3, window=16),
+    small("k16_top4_coarse_f16", n=1200, K=16, topk=4, window=25, dtype="f16", d=96, mixture=8),
+    small("k32_top5_coarse", n=900, K=32, topk=5, window=10, dtype="bf16"),
+    small("k32_top2_coarse_noncausal", n=1100, K=32, topk=2, window=30, causal=False, dtype="bf16", d=128),
+    small("k32_top3_coarse_d256_softcap", n=800, K=32, topk=3, window=20, dtype="bf16", d=256, softcap=20.0),
 ]
 
 
@@ -133,6 +141,21 @@ def test_noncausal_mid_size_sampled_rows():
     mq, mk = harness.check_assign(wl, inp, res)
     rows = workloads.sample_rows(wl, 1024)
     say("noncausal_mid", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    harness.check_pair_totals(wl, res, mq, mk)
+    vec = harness.run_gpu(wl, inp, vector=True)
+    assert torch.equal(res["row_pairs"], vec["row_pairs"])
+    diff = (res["out"].float() - vec["out"].float()).abs()
+    assert diff.max().item() <= 2e-2 and diff.mean().item() <= 2e-3
+
+
+def test_coarse_classes_mid_size_sampled_rows():
+    # K = 32, top-2: 496 membership sets fold onto 22 super-groups (253 classes)
+    wl = small("coarse_mid", n=20000 + 11, K=32, topk=2, window=1024, dtype="bf16", d=128, Hq=4, Hkv=2, mixture=8)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    rows = workloads.sample_rows(wl, 1024)
+    say("coarse_mid", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
     harness.check_pair_totals(wl, res, mq, mk)
     vec = harness.run_gpu(wl, inp, vector=True)
     assert torch.equal(res["row_pairs"], vec["row_pairs"])

@@ -76,6 +76,8 @@ SMALL = [
     (1, 5000, 128, 32, 16, 3, "bf16", 3),
     (3, 130, 64, 64, 32, 4, "f32", 2),
     (1, 1, 64, 16, 4, 2, "bf16", 10),
+    (2, 600, 136, 16, 8, 2, "f16", 10),
+    (1, 900, 768, 32, 32, 2, "f16", 0),
     (1, 70000, 64, 16, 8, 2, "bf16", 10),      # more than 256 tokens per Sinkhorn work-group
 ]
 
@@ -109,12 +111,15 @@ def test_route_temperature_and_ties():
     assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("name,n", [("cfg1", None), ("cfg2", 1024), ("cfg3", 2048), ("cfg4a", 3000), ("cfg4b", 1500)])
+@pytest.mark.parametrize("name,n", [("cfg1", None), ("cfg2", 1024), ("cfg3", 2048), ("cfg4a", 3000), ("cfg4b", 1500),
+                                    ("cfg3_k32_top2", 1800), ("cfg2_f16_d80_noncausal", 1200)])
 def test_routed_attention_matches_oracle(name, n):
     """route -> assign_tokens -> attention, every row against the oracle fed the oracle's own routing."""
-    base = workloads.CONFIGS[name]
+    extra = {"cfg3_k32_top2": dict(K=32, topk=2),                      # classes of super-groups
+             "cfg2_f16_d80_noncausal": dict(dtype="f16", d=80, causal=False)}.get(name, {})
+    base = workloads.CONFIGS[name.split("_")[0]]
     wl = base if n is None else base.scaled(n=n, B=min(base.B, 2), Hq=min(base.Hq, 8), Hkv=min(base.Hkv, 2),
-                                            window=max(8, base.window * n // base.n))
+                                            window=max(8, base.window * n // base.n), **extra)
     inp = workloads.make_inputs(wl, "cuda")
     rin = workloads.make_router_inputs(wl, "cuda", d_model=256)
     tm = check_route(wl, rin, 10)
