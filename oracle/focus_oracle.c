@@ -15,6 +15,7 @@
  *     least one group; nearby pairs always attend.
  *   - App. D, Eq. 3: the hard-assignment mask, causal AND (same group OR local).
  *   - Sec. 1: the softmax over the allowed pairs is exact (no renormalisation).
+ *   - Sec. 2, Eq. 2: the soft-gated attention of training (focus_oracle_soft_rows).
  *
  * Readings taken where the paper is silent or the benchmark spec binds
  * differently (all restated in the design notes of the repository):
@@ -289,6 +290,88 @@ static int attn_rows_impl(const oracle_params *p, int pair_set, const void *q, c
             }
         }
         free(allowed); free(x); free(qi);
+    }
+    return bad ? -1 : 0;
+}
+
+/* Sec. 2 Eq. 2, the soft-gated attention of training: every causal pair is computed,
+ *   s_ij = scale * (q_i . k_j) * gate_ij,
+ *   gate_ij = 1                               for local pairs (i-w < j <= i),
+ *           = sigmoid(lambda * g_i . g_j)     for the others,
+ * followed by the exact softmax over j <= i and the product with V.  g [B,n,K] fp32 is the soft
+ * assignment of every token of the layer (one per token, the same for all heads).  The equation is
+ * taken literally: a gate of sigmoid(0) = 1/2 halves a logit, it does not remove the pair.
+ * rows / out / lse as in attn_rows_impl; probs (nullable) [nrows,n].  causal only, no softcap. */
+int focus_oracle_soft_rows(const oracle_params *p, double lambda, const float *g, const void *q,
+                           const void *k, const void *v, int64_t nrows, const int32_t *rows,
+                           double *out, double *lse, double *probs)
+{
+    if (check_params(p) || !g || !q || !k || !v || !out) return -1;
+    if (!p->causal || p->softcap != 0.0) return -2;
+    const int n = p->n, d = p->d, Hq = p->Hq, Hkv = p->Hkv, w = p->window, K = p->K;
+    const double scale = (p->scale != 0.0) ? p->scale : 1.0 / sqrt((double)d);
+    if (!rows && nrows != (int64_t)p->B * Hq * n) return -1;
+    int bad = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc(sizeof(double) * (size_t)n);
+        double *qi = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!x || !qi) {
+#pragma omp atomic write
+            bad = 1;
+        } else {
+#pragma omp for schedule(dynamic, 4)
+            for (int64_t r = 0; r < nrows; ++r) {
+                int b, h, i;
+                if (rows) {
+                    b = rows[3 * r]; h = rows[3 * r + 1]; i = rows[3 * r + 2];
+                } else {
+                    i = (int)(r % n); h = (int)((r / n) % Hq); b = (int)(r / ((int64_t)n * Hq));
+                }
+                if (b < 0 || b >= p->B || h < 0 || h >= Hq || i < 0 || i >= n) {
+#pragma omp atomic write
+                    bad = 1;
+                    continue;
+                }
+                const int hk = kv_of(p, h);
+                const int64_t qrow = ((int64_t)b * Hq + h) * n + i;
+                const int64_t kbase = ((int64_t)b * Hkv + hk) * n;
+                const float *gi = g + ((int64_t)b * n + i) * K;
+                for (int t = 0; t < d; ++t) qi[t] = widen(q, p->dtype, qrow * d + t);
+                double mx = -INFINITY;
+                for (int j = 0; j <= i; ++j) {
+                    double dot = 0.0;
+                    for (int t = 0; t < d; ++t)
+                        dot += qi[t] * widen(k, p->dtype, (kbase + j) * d + t);
+                    double gate = 1.0;
+                    if (j <= i - w) {                         /* not local */
+                        const float *gj = g + ((int64_t)b * n + j) * K;
+                        double aff = 0.0;
+                        for (int c = 0; c < K; ++c) aff += (double)gi[c] * (double)gj[c];
+                        gate = 1.0 / (1.0 + exp(-lambda * aff));
+                    }
+                    x[j] = scale * dot * gate;
+                    if (x[j] > mx) mx = x[j];
+                }
+                double sum = 0.0;
+                for (int j = 0; j <= i; ++j) {
+                    x[j] = exp(x[j] - mx);
+                    sum += x[j];
+                }
+                double *o = out + r * d;
+                for (int t = 0; t < d; ++t) o[t] = 0.0;
+                if (probs)
+                    for (int j = 0; j < n; ++j) probs[r * n + j] = 0.0;
+                for (int j = 0; j <= i; ++j) {
+                    double pj = x[j] / sum;
+                    if (probs) probs[r * n + j] = pj;
+                    for (int t = 0; t < d; ++t)
+                        o[t] += pj * widen(v, p->dtype, (kbase + j) * d + t);
+                }
+                if (lse) lse[r] = mx + log(sum);
+            }
+        }
+        free(x); free(qi);
     }
     return bad ? -1 : 0;
 }

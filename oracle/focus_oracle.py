@@ -173,6 +173,34 @@ def attn_rows(pb, q, k, v, mq, mk, rows=None, want_probs=False, pair_set="all"):
     return out, lse, pairs
 
 
+def soft_rows(pb, lam, g, q, k, v, rows=None, want_probs=False):
+    """Sec. 2 Eq. 2 (soft-gated attention of training).  g [B,n,K] float32, lam the gate's slope.
+    rows as in attn_rows.  Returns out [nrows,d] f64, lse [nrows] f64 (and probs [nrows,n])."""
+    pb._check_tensor(q, pb.Hq)
+    pb._check_tensor(k, pb.Hkv)
+    pb._check_tensor(v, pb.Hkv)
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    assert g.shape == (pb.B, pb.n, pb.K), g.shape
+    if rows is None:
+        nrows = pb.B * pb.Hq * pb.n
+        rows_arr = None
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 3)
+        nrows = rows_arr.shape[0]
+    out = np.empty((nrows, pb.d), dtype=np.float64)
+    lse = np.empty((nrows,), dtype=np.float64)
+    probs = np.zeros((nrows, pb.n), dtype=np.float64) if want_probs else None
+    p = pb._c()
+    lib = _load()
+    lib.focus_oracle_soft_rows.restype = ctypes.c_int
+    _rc(lib.focus_oracle_soft_rows(ctypes.byref(p), ctypes.c_double(float(lam)), _ptr(g), _ptr(q), _ptr(k), _ptr(v),
+                                   ctypes.c_int64(nrows), _ptr(rows_arr), _ptr(out), _ptr(lse), _ptr(probs)),
+        "soft_rows")
+    if want_probs:
+        return out, lse, probs
+    return out, lse
+
+
 def merge(oa, la, ob, lb):
     """App. D merge of two disjoint partial attentions: returns (out [nrows,d], lse [nrows])."""
     lib = _load()
