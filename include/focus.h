@@ -90,6 +90,22 @@ focus_status focus_attn_fwd(const focus_params *p, const void *q, const void *k,
                             const void *v, void *workspace, size_t workspace_bytes,
                             void *out, float *lse, int32_t *row_pairs, void *stream);
 
+/* ---- the soft-gated attention of training (Sec. 2 Eq. 2) ----
+ *
+ * Every causal pair is computed: logit_ij = scale * q_i.k_j * gate_ij with gate_ij = 1 inside the
+ * window (i-w < j <= i) and sigmoid(lambda * g_i.g_j) outside, exact softmax over j <= i, times V.
+ * The equation is taken as printed: a gate of sigmoid(0) = 1/2 halves a logit, it removes no pair.
+ * g [B,n,K] fp32 DEVICE: the soft assignment of every token of the layer (the same for all heads;
+ * focus_route's `soft` output rounded to fp32, or any other); lambda finite.  p->K is the width of g,
+ * p->topk is not used (give 1), p->causal must be 1 and p->softcap 0 (else FOCUS_EUNSUPPORTED).
+ * One call does everything (no focus_assign): the workspace of focus_soft_workspace_size(p) bytes is
+ * scratch (position-ordered copies of K, V and g).  out [B,Hq,n,d] in p->dtype, lse (nullable)
+ * [B,Hq,n] fp32.  Forward only. */
+focus_status focus_soft_workspace_size(const focus_params *p, size_t *bytes);
+focus_status focus_attn_soft_fwd(const focus_params *p, float lambda, const float *g,
+                                 const void *q, const void *k, const void *v, void *workspace,
+                                 size_t workspace_bytes, void *out, float *lse, void *stream);
+
 /* ---- the per-layer router in front of the attention (Sec. 2 Eq. 1 and the Sinkhorn recipe) ----
  *
  * The paper routes once per layer: a token's hidden state h_i is projected by W_g (d_model x d_g),

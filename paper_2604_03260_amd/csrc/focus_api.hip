@@ -25,7 +25,8 @@ focus_status fail(focus_status st, const char* fmt, ...)
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Validates the params and derives the workspace layout and the head map.
-focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap* hm)
+// soft: the layout of the soft-gated attention (one class in position order whatever K, topk and the window are).
+focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap* hm, bool soft = false)
 {
     using namespace focus;
     if (!p) return fail(FOCUS_EINVAL, "params is NULL");
@@ -67,7 +68,8 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->elem = (p->dtype == FOCUS_F32) ? 4 : 2;
     L->scale = (p->scale > 0.0f) ? p->scale : (float)(1.0 / std::sqrt((double)p->d));
     L->softcap = p->softcap;
-    L->dense = (p->window >= p->n || 2 * p->topk > p->K) ? 1 : 0;
+    L->soft = soft ? 1 : 0;
+    L->dense = (soft || p->window >= p->n || 2 * p->topk > p->K) ? 1 : 0;
     if (L->dense) {
         L->NC = 1;
     } else {
@@ -97,7 +99,7 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     // bf16 at long n: 256-row tiles (8 wavefronts share every K/V tile: half the L2->LDS traffic per FLOP,
     // which is what bounds the kernel once a KV head's K/V no longer sits in L2/MALL)
     L->dp = (p->d <= 64) ? 64 : (p->d <= 128) ? 128 : 256;
-    L->BQ = (p->dtype != FOCUS_F32 && p->n >= LONG_N && p->d <= 128 && !L->coarse) ? 256 : BQ_VECTOR;
+    L->BQ = (p->dtype != FOCUS_F32 && p->n >= LONG_N && p->d <= 128 && !L->coarse && !soft) ? 256 : BQ_VECTOR;
     L->NT = (p->n + L->BQ - 1) / L->BQ + L->NC;
     L->NQP = L->NT * L->BQ;
     L->NKP = ((p->n + KT - 1) / KT + L->NC) * KT;
@@ -133,6 +135,7 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->off_kpos = take(BHk * L->NKP * 4);
     L->off_kmsk = L->coarse ? take(BHk * L->NKP * 4) : off;
     L->off_jobs = take(BHq * L->NT * 4);
+    L->off_gk = (soft && p->dtype != FOCUS_F32) ? take((size_t)p->B * L->NKP * 128) : off;
     if (p->dtype != FOCUS_F32) {
         L->off_kc = take(BHk * L->NKP * (size_t)L->dp * 2);
         L->off_vt = take(BHk * L->NKP * (size_t)L->dp * 2);
@@ -301,9 +304,9 @@ focus_status attn_launch(const focus_params* p, int pair_set, const void* q, con
     L.pair_set = pair_set;
     hipError_t e;
     if (L.dtype != FOCUS_F32)
-        e = focus::launch_attn_mfma(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
+        e = focus::launch_attn_mfma(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
     else
-        e = focus::launch_attn_simple(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
+        e = focus::launch_attn_simple(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
     if (e != hipSuccess) return fail(FOCUS_EHIP, "%s: %s", who, hipGetErrorString(e));
     return FOCUS_OK;
 }
@@ -377,10 +380,83 @@ focus_status focus_attn_fwd_vector(const focus_params* p, const void* q, const v
     if (!q || !k || !v || !out) return fail(FOCUS_EINVAL, "q, k, v and out must not be NULL");
     st = check_ws(L, workspace, workspace_bytes);
     if (st != FOCUS_OK) return st;
-    hipError_t e = focus::launch_attn_simple(L, hm, q, k, v, (char*)workspace, out, lse, row_pairs,
+    hipError_t e = focus::launch_attn_simple(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs,
                                              (hipStream_t)stream);
     if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_fwd_vector: %s", hipGetErrorString(e));
     return FOCUS_OK;
+}
+
+namespace {
+
+focus_status soft_checks(const focus_params* p)
+{
+    if (p && p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "the soft-gated attention is causal (Sec. 2 Eq. 2)");
+    if (p && p->softcap != 0.0f) return fail(FOCUS_EUNSUPPORTED, "the soft-gated attention takes no softcap");
+    if (p && p->d == 256 && p->dtype != FOCUS_F32)
+        return fail(FOCUS_EUNSUPPORTED, "the soft-gated attention is not built for head dim 256 in 16-bit types");
+    return FOCUS_OK;
+}
+
+focus_status soft_launch(const focus_params* p, float lambda, const float* g, const void* q, const void* k,
+                         const void* v, void* workspace, size_t workspace_bytes, void* out, float* lse, void* stream,
+                         bool vector)
+{
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = soft_checks(p);
+    if (st != FOCUS_OK) return st;
+    st = make_layout(p, &L, &hm, true);
+    if (st != FOCUS_OK) return st;
+    if (!std::isfinite(lambda)) return fail(FOCUS_EINVAL, "lambda must be finite");
+    if (!g || !q || !k || !v || !out) return fail(FOCUS_EINVAL, "g, q, k, v and out must not be NULL");
+    if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(out))
+        return fail(FOCUS_EINVAL, "q, k, v and out must be 16-byte aligned");
+    if (out == q || out == k || out == v) return fail(FOCUS_EINVAL, "out must not alias an input");
+    st = check_ws(L, workspace, workspace_bytes);
+    if (st != FOCUS_OK) return st;
+    L.gate_slope = (float)(-(double)lambda * 1.4426950408889634);
+    hipStream_t s = (hipStream_t)stream;
+    // one class holding every token, in position order: the bucketing with a constant membership
+    hipError_t e = focus::launch_assign_tokens(L, nullptr, k, (char*)workspace, nullptr, s);
+    if (e == hipSuccess && L.dtype != FOCUS_F32 && !vector) e = focus::launch_soft_gather_g(L, g, (char*)workspace, s);
+    if (e == hipSuccess) {
+        if (L.dtype != FOCUS_F32 && !vector)
+            e = focus::launch_attn_mfma(L, hm, q, k, v, g, (char*)workspace, out, lse, nullptr, s);
+        else
+            e = focus::launch_attn_simple(L, hm, q, k, v, g, (char*)workspace, out, lse, nullptr, s);
+    }
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_soft_fwd: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
+}  // namespace
+
+focus_status focus_soft_workspace_size(const focus_params* p, size_t* bytes)
+{
+    if (!bytes) return fail(FOCUS_EINVAL, "bytes is NULL");
+    focus::Layout L;
+    focus::HeadMap hm;
+    focus_status st = soft_checks(p);
+    if (st != FOCUS_OK) return st;
+    st = make_layout(p, &L, &hm, true);
+    if (st != FOCUS_OK) return st;
+    *bytes = L.total;
+    return FOCUS_OK;
+}
+
+focus_status focus_attn_soft_fwd(const focus_params* p, float lambda, const float* g, const void* q, const void* k,
+                                 const void* v, void* workspace, size_t workspace_bytes, void* out, float* lse,
+                                 void* stream)
+{
+    return soft_launch(p, lambda, g, q, k, v, workspace, workspace_bytes, out, lse, stream, false);
+}
+
+// The same through the fp32 vector kernel (cross-check of the MFMA kernel in tests; not in the public header).
+focus_status focus_attn_soft_fwd_vector(const focus_params* p, float lambda, const float* g, const void* q,
+                                        const void* k, const void* v, void* workspace, size_t workspace_bytes,
+                                        void* out, float* lse, void* stream)
+{
+    return soft_launch(p, lambda, g, q, k, v, workspace, workspace_bytes, out, lse, stream, true);
 }
 
 focus_status focus_route_workspace_size(const focus_route_params* rp, size_t* bytes)

@@ -429,7 +429,8 @@ __global__ __launch_bounds__(SB) void token_classes_kernel(Layout L, const uint3
     uint32_t mask = 0;
     int cls = 0;
     if (pos < n) {
-        mask = token_masks[(size_t)b * n + pos];
+        // no masks given: every token in the first topk groups (callers that need one class in position order)
+        mask = token_masks ? token_masks[(size_t)b * n + pos] : ((L.topk == 32) ? 0xffffffffu : ((1u << L.topk) - 1u));
         const uint32_t allowed = (K == 32) ? 0xffffffffu : ((1u << K) - 1u);
         if ((mask & ~allowed) != 0u || __popc(mask) != L.topk) {
             mask = (L.topk == 32) ? 0xffffffffu : ((1u << L.topk) - 1u);

@@ -39,6 +39,7 @@
 //    row sum adds the bf16-rounded probabilities (v_dot2), the numbers PV uses.
 #include "focus_internal.h"
 #include "focus_tileplan.h"
+#include <algorithm>
 
 namespace focus {
 
@@ -139,13 +140,16 @@ __device__ inline int swz(int row, int ch)
     else return ch ^ ((row >> 1) & 7);
 }
 
-template <int D, bool COARSE>
+constexpr int GROW = 128;     // bytes of a key's soft assignment in LDS: bf16 high parts of 32 groups, then the low parts
+
+template <int D, bool COARSE, bool SOFT>
 struct Smem {
     TilePlan plan;
     __attribute__((aligned(16))) int kpos[3][KT];
     __attribute__((aligned(16))) char k[2][KT * D * 2];     // [stage][key][D] 16-bit elements, chunks swizzled
     __attribute__((aligned(16))) char vt[2][D * KT * 2];    // [stage][d][KT] 16-bit elements, chunks swizzled
     __attribute__((aligned(16))) unsigned kmsk[COARSE ? 3 * KT : 4];   // membership masks of the keys (coarse classes)
+    __attribute__((aligned(16))) char gk[SOFT ? 2 * KT * GROW : 16];   // [stage][key][GROW] soft assignments of the keys
 };
 
 // max of the two half-waves (lane l and lane l^32 hold the same query row)
@@ -195,16 +199,22 @@ __device__ inline void pin_operands(V8 (&a)[N])
 // take 128 registers, so that shape runs one wavefront per SIMD with the full register file.
 // COARSE: membership classes are sets of super-groups; a key class that shares one with the rows' class
 // may or may not share a real group, so its pairs are tested against the two membership masks.
-template <int D, int KS, int DB, int MFMA_WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE>
-__global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) void attn_mfma_kernel(
-    Layout L, HeadMap hm, int default_map, const uint16_t* __restrict__ q, const char* __restrict__ ws,
-    uint16_t* __restrict__ out, float* __restrict__ lse, int32_t* __restrict__ row_pairs)
+// SOFT: Sec. 2 Eq. 2, the attention of training: one class in position order, every causal pair computed; the
+// score of a pair outside the window is multiplied by sigmoid(lambda * g_i . g_j).  The affinities come off the
+// matrix cores next to the scores: G^T = g_K g_Q^T with both sides split into bf16 high and low parts (three
+// products per 16 groups), the query side pre-multiplied by -lambda*log2(e) so that the gate is 1/(1 + 2^G).
+// Runs one wavefront per SIMD (two more accumulators and the operands of G do not fit 256 registers).
+template <int D, int KS, int DB, int MFMA_WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE, bool SOFT>
+__global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_WAVES) void attn_mfma_kernel(
+    Layout L, HeadMap hm, int default_map, const uint16_t* __restrict__ q, const float* __restrict__ g,
+    const char* __restrict__ ws, uint16_t* __restrict__ out, float* __restrict__ lse,
+    int32_t* __restrict__ row_pairs)
 {
     typedef Half<F16> HT;
     typedef typename HT::T elem_t;
     typedef typename HT::V8 V8;
     typedef typename HT::V2 V2;
-    __shared__ Smem<D, COARSE> S;
+    __shared__ Smem<D, COARSE, SOFT> S;
     static_assert(KS * 16 <= D && DB * 32 <= D, "the products stay inside the copied rows");
     // With 512-byte key rows the operands of a whole phase would not fit the vector registers next to
     // Q, so that shape fetches and multiplies them in two halves (HV = 2); the others in one go.
@@ -279,6 +289,23 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
         for (int ks = 0; ks < KS; ++ks) qreg[ks] = rvalid ? qrow[2 * ks + hh] : zero;
     }
 
+    // soft gate: this row's assignment times -lambda*log2(e), as bf16 high and low parts in B-operand order
+    bf16x8 gqh[2], gql[2];
+    const bool kg2 = L.K > 16;          // a second k-step of 16 groups
+    if constexpr (SOFT) {
+        const float* grow = g + ((size_t)b * L.n + (rvalid ? qpos : 0)) * L.K;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int c = ks * 16 + hh * 8 + e;
+                const float x = (rvalid && c < L.K) ? grow[c] * L.gate_slope : 0.f;
+                const __bf16 hi = (__bf16)x;
+                gqh[ks][e] = hi;
+                gql[ks][e] = (__bf16)(x - (float)hi);
+            }
+    }
+
     f32x16 o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -295,6 +322,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     const char* vt_base = ws + L.off_vt + (size_t)bhk * L.NKP * (D * 2);
     const char* kpos_base = ws + L.off_kpos + (size_t)bhk * L.NKP * 4;
     const char* kmsk_base = ws + L.off_kmsk + (size_t)bhk * L.NKP * 4;
+    const char* gk_base = ws + L.off_gk + (size_t)b * L.NKP * GROW;
 
     // per-lane source offsets of the swizzled DMA: wave `wave` fills the 1-KB LDS blocks wave + 4*i
     // of a tile; block j holds rows 4j..4j+3 (256-byte rows) or 8j..8j+7 (128-byte rows), and the
@@ -322,12 +350,18 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     const unsigned lds_k0 = lds_addr_of(&S.k[0][0]), lds_v0 = lds_addr_of(&S.vt[0][0]);
     const unsigned lds_kp0 = lds_addr_of(&S.kpos[0][0]);
     const unsigned lds_km0 = lds_addr_of(&S.kmsk[0]);
+    const unsigned lds_g0 = lds_addr_of(&S.gk[0]);
 
 #define F4_DMA_K(TILE, STAGE)                                                                        \
     do {                                                                                             \
         const char* src_ = kc_base + (size_t)(TILE) * TILE_BYTES;                                    \
         _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
             dma16(src_ + (i >> 1) * (2048 * MFMA_WAVES), voff_k[i & 1], lds_k0 + (STAGE) * TILE_BYTES + (wave + MFMA_WAVES * i) * 1024); \
+        if constexpr (SOFT) {            /* the keys' soft assignments travel with the key tile */          \
+            const char* gsrc_ = gk_base + (size_t)(TILE) * (KT * GROW);                              \
+            _Pragma("unroll") for (int i = 0; i < KT * GROW / 1024 / MFMA_WAVES; ++i)                 \
+                dma16(gsrc_ + (wave + MFMA_WAVES * i) * 1024, (unsigned)lane * 16, lds_g0 + (STAGE) * (KT * GROW) + (wave + MFMA_WAVES * i) * 1024); \
+        }                                                                                            \
     } while (0)
 #define F4_DMA_V(TILE, STAGE)                                                                        \
     do {                                                                                             \
@@ -359,9 +393,31 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
             const int row_ = ((HALF) * DBH + db) * 32 + n32;                                         \
             DST[db * 2 + s2] = lds_read16_async<V8>(lds_v0 + (VST) * TILE_BYTES + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
         }
+    // soft gate: high parts of the two k-steps, then the low parts, of the 32 keys of unit U
+#define F4_READ_G(KST, U)                                                                            \
+    if constexpr (SOFT) {                                                                            \
+        _Pragma("unroll") for (int c = 0; c < 4; ++c) {                                              \
+            const int row_ = (U) * 32 + n32;                                                         \
+            ag[c] = lds_read16_async<bf16x8>(lds_g0 + (KST) * (KT * GROW) + row_ * GROW + ((((c >> 1) * 4 + (c & 1) * 2 + hh) ^ (row_ & 7)) * 16)); \
+        }                                                                                            \
+    }
 #define F4_WAIT_OPERANDS()                                                                           \
     wait_lds_operands(ak);                                                                           \
-    pin_operands(av);
+    pin_operands(av);                                                                                \
+    if constexpr (SOFT) pin_operands(ag);
+    // G^T of one unit: (high x high) + (high x low) + (low x high) per k-step of 16 groups
+#define F4_GATE_MFMAS(GOUT)                                                                          \
+    if constexpr (SOFT) {                                                                            \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) GOUT[r] = 0.f;                                \
+        GOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag[0], gqh[0], GOUT, 0, 0, 0);                \
+        GOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag[0], gql[0], GOUT, 0, 0, 0);                \
+        GOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag[2], gqh[0], GOUT, 0, 0, 0);                \
+        if (kg2) {                                                                                   \
+            GOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag[1], gqh[1], GOUT, 0, 0, 0);            \
+            GOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag[1], gql[1], GOUT, 0, 0, 0);            \
+            GOUT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag[3], gqh[1], GOUT, 0, 0, 0);            \
+        }                                                                                            \
+    }
 
     // Scalar walk over the tile sequence (class by class).  A tile travels as one packed word:
     // bits 0..29 tile index, bit 30 "class shares a group" flag, bit 31 "no mask needed" flag.
@@ -411,28 +467,51 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     ones2[0] = (elem_t)1.0f;
     ones2[1] = (elem_t)1.0f;
     V8 ak[KSH], av[NPVH];
+    bf16x8 ag[4];
+    f32x16 g0acc, g1acc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; g0acc[r] = 0.f; g1acc[r] = 0.f; }
 #pragma unroll
     for (int e = 0; e < 8; ++e) { p1[0][e] = (elem_t)0.f; p1[1][e] = (elem_t)0.f; p0[0][e] = (elem_t)0.f; p0[1][e] = (elem_t)0.f; }
 #pragma unroll
     for (int half = 0; half < HV; ++half) {
         F4_READ_K(ak, 0, 0, half)
+        if (half == 0) { F4_READ_G(0, 0) }
         wait_lds_operands(ak);
+        if constexpr (SOFT) pin_operands(ag);
 #pragma unroll
         for (int ks = 0; ks < KSH; ++ks) s0 = HT::mfma(ak[ks], qreg[half * KSH + ks], s0);
+        if (half == 0) { F4_GATE_MFMAS(g0acc) }
     }
 
     // softmax step on one unit's scores: SIN (f32x16, consumed) -> POUT (2 x bf16x8), split in two parts.
     // PPEND: probabilities of the previous unit whose PV product has not been issued yet.
-#define F4_SOFTMAX_PRE(SIN, U, KPB, PPEND)                                                               \
+#define F4_SOFTMAX_PRE(SIN, U, KPB, PPEND, GIN)                                                          \
+    if constexpr (SOFT) {                                                                                \
+        /* Eq. 2: score * (local ? 1 : sigmoid(lambda g_i.g_j)), then the causal mask (pads sit at INT_MAX) */ \
+        if (far_) {                      /* the whole tile lies before every row's window: gate only */  \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r)                                               \
+                SIN[r] *= __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(GIN[r]));                   \
+        } else                                                                                           \
+        _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4) {                                               \
+            const int4 kp4_ = *(const int4*)(&S.kpos[KPB][(U) * 32 + 8 * r4 + 4 * hh]);                  \
+            const int kp_[4] = {kp4_.x, kp4_.y, kp4_.z, kp4_.w};                                         \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                              \
+                const unsigned dlt_ = (unsigned)(qpos - kp_[e]);                                         \
+                const float gate_ = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(GIN[r4 * 4 + e])); \
+                const float sg_ = SIN[r4 * 4 + e] * ((dlt_ < (unsigned)w) ? 1.f : gate_);                \
+                SIN[r4 * 4 + e] = (dlt_ < 0x80000000u) ? sg_ : -INFINITY;                                \
+            }                                                                                            \
+        }                                                                                                \
+    } else                                                                                               \
     if constexpr (SOFTCAP) {                                                                             \
         _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                 \
             const float e2_ = __builtin_amdgcn_exp2f(SIN[r] * two_over_cap_l2);                          \
             SIN[r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2_);                           \
         }                                                                                                \
     }                                                                                                    \
-    if (!interior) {                                                                                     \
+    if (SOFT) {                          /* masked above */                                              \
+    } else if (!interior) {                                                                              \
         _Pragma("unroll") for (int r4 = 0; r4 < 4; ++r4) {                                               \
             const int4 kp4_ = *(const int4*)(&S.kpos[KPB][(U) * 32 + 8 * r4 + 4 * hh]);                  \
             const int kp_[4] = {kp4_.x, kp4_.y, kp4_.z, kp4_.w};                                         \
@@ -492,7 +571,8 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
         l_run += psum_;                                                                                  \
     }
     // the MFMAs of (one half of) a phase: PV with pending probabilities PP, then the QK^T unit into SOUT
-#define F4_MFMAS(PP, SOUT, HALF)                                                                         \
+#define F4_MFMAS(PP, SOUT, HALF, GOUT)                                                                   \
+    if ((HALF) == 0) { F4_GATE_MFMAS(GOUT) }                                                             \
     _Pragma("unroll") for (int i = 0; i < NPVH; ++i)                                                     \
         o[(HALF) * DBH + i / 2] = HT::mfma(av[i], PP[i % 2], o[(HALF) * DBH + i / 2]);                   \
     if ((HALF) == 0) { _Pragma("unroll") for (int r = 0; r < 16; ++r) SOUT[r] = 0.f; }                   \
@@ -509,15 +589,18 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
         const unsigned wlim = shares_ ? 0x80000000u : wlim_local;                                        \
         const int qadj = shares_ ? qadj_inter : qadj_local;                                              \
         const bool interior = (pk0 >> 31) != 0;                                                          \
+        /* soft gate, position order: keys of this tile all at or below i_lo - w (and real, and causal) */ \
+        const bool far_ = SOFT && interior && ((int)(pk0 & TILE_MASK) * KT + KT - 1 + w <= i_lo);        \
         const int tl1 = (int)(pk1 & TILE_MASK);                                                          \
         const int tl2 = (int)(pk2 & TILE_MASK);                                                          \
         const int kb_nn = (kb_cur >= 1) ? kb_cur - 1 : 2;    /* (t+2) mod 3 */                           \
         /* phase A: VALU softmax(S0) -> P0 ; MFMA O += V(t-1,u1) P1 and S1 = K(t,u1) Q^T */              \
         F4_READ_V(av, sn, 1, 0)                                                                          \
         F4_READ_K(ak, sc, 1, 0)                                                                          \
-        F4_SOFTMAX_PRE(s0, 0, kb_cur, p1)                                                                \
+        F4_READ_G(sc, 1)                                                                                 \
+        F4_SOFTMAX_PRE(s0, 0, kb_cur, p1, g0acc)                                                         \
         F4_WAIT_OPERANDS()                                                                               \
-        F4_MFMAS(p1, s1, 0)                                                                              \
+        F4_MFMAS(p1, s1, 0, g1acc)                                                                       \
         if constexpr (HV == 2) {                                                                         \
             F4_READ_V(av, sn, 1, 1)                                                                      \
             F4_READ_K(ak, sc, 1, 1)                                                                      \
@@ -525,7 +608,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
         F4_SOFTMAX_EXP(s0, p0)                                                                           \
         if constexpr (HV == 2) {                                                                         \
             F4_WAIT_OPERANDS()                                                                           \
-            F4_MFMAS(p1, s1, 1)                                                                          \
+            F4_MFMAS(p1, s1, 1, g1acc)                                                                   \
         }                                                                                                \
         __builtin_amdgcn_iglp_opt(3);                                                                    \
         F4_PIN2(p0);                                                                                     \
@@ -538,9 +621,10 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
         /* phase B: VALU softmax(S1) -> P1 ; MFMA O += V(t,u0) P0 and S0 = K(t+1,u0) Q^T */              \
         F4_READ_V(av, sc, 0, 0)                                                                          \
         F4_READ_K(ak, sn, 0, 0)                                                                          \
-        F4_SOFTMAX_PRE(s1, 1, kb_cur, p0)                                                                \
+        F4_READ_G(sn, 0)                                                                                 \
+        F4_SOFTMAX_PRE(s1, 1, kb_cur, p0, g1acc)                                                         \
         F4_WAIT_OPERANDS()                                                                               \
-        F4_MFMAS(p0, s0, 0)                                                                              \
+        F4_MFMAS(p0, s0, 0, g0acc)                                                                       \
         if constexpr (HV == 2) {                                                                         \
             F4_READ_V(av, sc, 0, 1)                                                                      \
             F4_READ_K(ak, sn, 0, 1)                                                                      \
@@ -548,7 +632,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
         F4_SOFTMAX_EXP(s1, p1)                                                                           \
         if constexpr (HV == 2) {                                                                         \
             F4_WAIT_OPERANDS()                                                                           \
-            F4_MFMAS(p0, s0, 1)                                                                          \
+            F4_MFMAS(p0, s0, 1, g0acc)                                                                   \
         }                                                                                                \
         __builtin_amdgcn_iglp_opt(3);                                                                    \
         F4_PIN2(p1);                                                                                     \
@@ -585,6 +669,8 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
 #undef F4_MFMAS
 #undef F4_PIN2
 #undef F4_WAIT_OPERANDS
+#undef F4_READ_G
+#undef F4_GATE_MFMAS
 
     // ---- epilogue
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -615,13 +701,14 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256) ? 1 : 8 / MFMA_WAVES) v
     }
 }
 
-template <int D, int KS, int DB, int WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE>
+template <int D, int KS, int DB, int WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE, bool SOFT = false>
 hipError_t launch_one(const Layout& L, const HeadMap& hm, int default_map, const void* q, char* ws, void* out,
-                      float* lse, int32_t* row_pairs, hipStream_t st)
+                      float* lse, int32_t* row_pairs, hipStream_t st, const float* g = nullptr)
 {
     const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
-    hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16, COARSE>), dim3(grid), dim3(64 * WAVES), 0, st,
-                       L, hm, default_map, (const uint16_t*)q, (const char*)ws, (uint16_t*)out, lse, row_pairs);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16, COARSE, SOFT>), dim3(grid),
+                       dim3(64 * WAVES), 0, st, L, hm, default_map, (const uint16_t*)q, g, (const char*)ws,
+                       (uint16_t*)out, lse, row_pairs);
     return hipGetLastError();
 }
 
@@ -639,12 +726,20 @@ hipError_t launch_w(const Layout& L, const HeadMap& hm, int default_map, const v
 }
 
 template <int D, int KS, int DB>
-hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const void* q, const void* v, char* ws,
-                    void* out, float* lse, int32_t* row_pairs, hipStream_t st)
+hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const void* q, const void* v, const float* g,
+                    char* ws, void* out, float* lse, int32_t* row_pairs, hipStream_t st)
 {
     dim3 ggrid(L.NKP / KT, L.B * L.Hkv);
     hipLaunchKernelGGL(gather_vt_kernel<D>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)v, ws);
     const bool f16 = L.dtype == 2;
+    if (L.soft) {                        // 128-row tiles, no softcap, no pair counts (a row i attends i + 1 keys)
+        if (L.BQ != 128 || !g || row_pairs || L.softcap > 0.f) return hipErrorInvalidValue;
+        // 512-byte key rows plus the gate's accumulators and operands do not fit the register file
+        if constexpr (D == 256) return hipErrorInvalidValue;
+        else
+        return f16 ? launch_one<D, KS, DB, 4, false, false, true, false, true>(L, hm, default_map, q, ws, out, lse, nullptr, st, g)
+                   : launch_one<D, KS, DB, 4, false, false, false, false, true>(L, hm, default_map, q, ws, out, lse, nullptr, st, g);
+    }
     // the query tile size fixed by focus_assign selects the work-group shape: 4 or 8 wavefronts
     if constexpr (D != 256) {
         if (L.BQ == 256)
@@ -674,8 +769,42 @@ hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t
     return hipGetLastError();
 }
 
+// the soft assignments of the key positions as the matrix cores read them (see Layout::off_gk)
+__global__ __launch_bounds__(256) void soft_gather_g_kernel(Layout L, const float* __restrict__ g, char* __restrict__ ws)
+{
+    const size_t total = (size_t)L.B * L.NKP * 8;         // 16-byte chunks: 4 of high parts, 4 of low parts per key
+    for (size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x; id < total; id += (size_t)gridDim.x * blockDim.x) {
+        const int c8 = (int)(id % 8);
+        const size_t slot = (id / 8) % L.NKP;             // one class in position order: slot = position, pads after n
+        const size_t b = id / 8 / L.NKP;
+        const int part = c8 / 4, e0 = (c8 % 4) * 8;
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int c = e0 + e;
+            const float x = (slot < (size_t)L.n && c < L.K) ? g[(b * L.n + slot) * L.K + c] : 0.f;
+            const __bf16 hi = (__bf16)x;
+            const __bf16 val = part ? (__bf16)(x - (float)hi) : hi;
+            __builtin_memcpy(&h[e], &val, 2);
+        }
+        uint4 u;
+        u.x = h[0] | ((uint32_t)h[1] << 16); u.y = h[2] | ((uint32_t)h[3] << 16);
+        u.z = h[4] | ((uint32_t)h[5] << 16); u.w = h[6] | ((uint32_t)h[7] << 16);
+        // chunks swizzled inside a key's 128 bytes so that 8 consecutive keys spread over the LDS banks
+        *(uint4*)(ws + L.off_gk + (b * L.NKP + slot) * GROW + (size_t)((c8 ^ (int)(slot & 7)) * 16)) = u;
+    }
+}
+
+hipError_t launch_soft_gather_g(const Layout& L, const float* g, char* ws, hipStream_t st)
+{
+    const size_t total = (size_t)L.B * L.NKP * 8;
+    const unsigned grid = (unsigned)std::min<size_t>(8192, (total + 255) / 256);
+    hipLaunchKernelGGL(soft_gather_g_kernel, dim3(grid), dim3(256), 0, st, L, g, ws);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_mfma(const Layout& L, const HeadMap& hm, const void* q, const void* k, const void* v,
-                            char* ws, void* out, float* lse, int32_t* row_pairs, hipStream_t st)
+                            const float* g, char* ws, void* out, float* lse, int32_t* row_pairs, hipStream_t st)
 {
     (void)k;
     int default_map = 1;
@@ -686,11 +815,11 @@ hipError_t launch_attn_mfma(const Layout& L, const HeadMap& hm, const void* q, c
             if (hm.kv[h] != h / G) default_map = 0;
     if ((size_t)L.NT * L.B * L.Hq > 0x7fffffffull) return hipErrorInvalidValue;
     switch (L.d) {
-        case 64: return launch_d<64, 4, 2>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
-        case 80: return launch_d<128, 5, 3>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
-        case 96: return launch_d<128, 6, 3>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
-        case 128: return launch_d<128, 8, 4>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
-        case 256: return launch_d<256, 16, 8>(L, hm, default_map, q, v, ws, out, lse, row_pairs, st);
+        case 64: return launch_d<64, 4, 2>(L, hm, default_map, q, v, g, ws, out, lse, row_pairs, st);
+        case 80: return launch_d<128, 5, 3>(L, hm, default_map, q, v, g, ws, out, lse, row_pairs, st);
+        case 96: return launch_d<128, 6, 3>(L, hm, default_map, q, v, g, ws, out, lse, row_pairs, st);
+        case 128: return launch_d<128, 8, 4>(L, hm, default_map, q, v, g, ws, out, lse, row_pairs, st);
+        case 256: return launch_d<256, 16, 8>(L, hm, default_map, q, v, g, ws, out, lse, row_pairs, st);
         default: return hipErrorInvalidValue;
     }
 }

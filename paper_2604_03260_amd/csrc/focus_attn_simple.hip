@@ -36,6 +36,7 @@ template <> __device__ inline f16_bits from_f32<f16_bits>(float v) { return f16_
 template <typename T, int D, int SUB>
 __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layout L, HeadMap hm, const T* __restrict__ q,
                                                                     const T* __restrict__ k, const T* __restrict__ v,
+                                                                    const float* __restrict__ g,
                                                                     const char* __restrict__ ws, T* __restrict__ out,
                                                                     float* __restrict__ lse,
                                                                     int32_t* __restrict__ row_pairs)
@@ -108,6 +109,22 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
                 if (cap > 0.f) x = cap * tanhf(x / cap);
                 const int kp = s_kpos[kk];
                 const int dlt = qpos - kp;               // pads sit at INT_MAX
+                if (L.soft) {
+                    // Sec. 2 Eq. 2: every causal pair; outside the window the score is scaled by
+                    // sigmoid(lambda * g_i . g_j) = 1 / (1 + 2^(gate_slope * g_i . g_j))
+                    const bool okc = rvalid && kp != KPOS_PAD && dlt >= 0;
+                    if (okc && dlt >= w) {
+                        const float* gi = g + ((size_t)b * L.n + qpos) * L.K;
+                        const float* gj = g + ((size_t)b * L.n + kp) * L.K;
+                        float aff = 0.f;
+                        for (int c = 0; c < L.K; ++c) aff = fmaf(gi[c], gj[c], aff);
+                        x *= 1.f / (1.f + exp2f(L.gate_slope * aff));
+                    }
+                    s[kk] = okc ? x : -INFINITY;
+                    npairs += okc ? 1 : 0;
+                    mx = fmaxf(mx, s[kk]);
+                    continue;
+                }
                 bool share = inter;                      // exact classes: a common group is a class property
                 if (L.coarse && inter && kp != KPOS_PAD) share = (mq_row & mk_all[kp]) != 0u;
                 const bool ok = rvalid && kp != KPOS_PAD &&
@@ -259,12 +276,12 @@ hipError_t launch_attn_merge(size_t rows, int d, int dtype, const void* oa, cons
 }
 
 hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q, const void* k, const void* v,
-                              char* ws, void* out, float* lse, int32_t* row_pairs, hipStream_t st)
+                              const float* g, char* ws, void* out, float* lse, int32_t* row_pairs, hipStream_t st)
 {
     dim3 grid(L.NT, L.B * L.Hq);
 #define FOCUS_LAUNCH_SIMPLE(T, D, SUB)                                                                 \
     hipLaunchKernelGGL((attn_simple_kernel<T, D, SUB>), grid, dim3(BQ_VECTOR*(D / 32)), 0, st, L, hm, (const T*)q, \
-                       (const T*)k, (const T*)v, (const char*)ws, (T*)out, lse, row_pairs)
+                       (const T*)k, (const T*)v, g, (const char*)ws, (T*)out, lse, row_pairs)
 #define FOCUS_LAUNCH_SIMPLE_T(T)                                                                       \
     do {                                                                                               \
         if (L.dp == 64) FOCUS_LAUNCH_SIMPLE(T, 64, 32);                                                \

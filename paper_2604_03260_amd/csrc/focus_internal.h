@@ -47,6 +47,8 @@ struct Layout {
     int BQ;                    // query rows per attention tile (128; 256 for 16-bit types at n >= LONG_N, d <= 128)
     int NC;                    // number of membership classes (1 in dense mode)
     int dense;                 // every causal pair allowed: one class, no masks beyond causal
+    int soft;                  // Sec. 2 Eq. 2: every causal pair, the logit of a pair outside the window scaled by
+    float gate_slope;          // sigmoid(lambda * g_i . g_j); gate_slope = -lambda * log2(e).  One class, position order.
     int coarse;                // C(K,topk) exceeds MAX_CLASSES: classes are sets of S super-groups (group g folds
     int S;                     // onto g % S), a superset test; the kernels then test the real masks per pair
     int pair_set;              // which pairs a launch attends: 0 the whole mask, 1 only pairs that share a group
@@ -74,6 +76,8 @@ struct Layout {
     size_t off_kpos;                   // [B,Hkv,NKP] positions in class order, KPOS_PAD in pads
     size_t off_kmsk;                   // [B,Hkv,NKP] membership masks in class order, 0 in pads (coarse classes only)
     size_t off_jobs;                   // [B,Hq,NT] (class << 24 | tile) heaviest first, -1 unused
+    size_t off_gk;                     // [B,NKP,2,32] bf16: the soft assignment of every key position as bf16 high and
+                                       // low parts, groups padded to 32, chunks swizzled per key (soft gate, 16-bit types)
     size_t off_kc;                     // [B,Hkv,NKP,dp] keys in class order (16-bit types)
     size_t off_vt;                     // [B,Hkv,NKP/KT,dp,KT] values, transposed per key tile (16-bit types)
     size_t total;
@@ -167,12 +171,13 @@ hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, cons
                          const float* centroids, char* ws, hipStream_t st);
 hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t st);
 hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q, const void* k,
-                              const void* v, char* ws, void* out, float* lse, int32_t* row_pairs,
+                              const void* v, const float* g, char* ws, void* out, float* lse, int32_t* row_pairs,
                               hipStream_t st);
+hipError_t launch_soft_gather_g(const Layout& L, const float* g, char* ws, hipStream_t st);
 hipError_t launch_attn_merge(size_t rows, int d, int dtype, const void* oa, const float* la, const void* ob,
                              const float* lb, void* out, float* lse, hipStream_t st);
 hipError_t launch_attn_mfma(const Layout& L, const HeadMap& hm, const void* q, const void* k,
-                            const void* v, char* ws, void* out, float* lse, int32_t* row_pairs,
+                            const void* v, const float* g, char* ws, void* out, float* lse, int32_t* row_pairs,
                             hipStream_t st);
 
 }  // namespace focus

@@ -25,6 +25,7 @@ EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_work
            "focus_attn_fwd_set", "focus_attn_merge", "focus_attn_fwd_two_call",
            "focus_decode_state_size", "focus_decode_prefill", "focus_decode_step",
            "focus_decode_state_views",
+           "focus_soft_workspace_size", "focus_attn_soft_fwd",
            "focus_last_error", "focus_version")
 
 
@@ -83,6 +84,11 @@ def load_library():
     lib.focus_attn_merge.restype = ctypes.c_int
     lib.focus_attn_fwd_two_call.argtypes = [pp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp]
     lib.focus_attn_fwd_two_call.restype = ctypes.c_int
+    lib.focus_soft_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
+    lib.focus_soft_workspace_size.restype = ctypes.c_int
+    for fn in (lib.focus_attn_soft_fwd, lib.focus_attn_soft_fwd_vector):
+        fn.argtypes = [pp, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+        fn.restype = ctypes.c_int
     lib.focus_decode_state_size.argtypes = [pp, ctypes.POINTER(sz)]
     lib.focus_decode_state_size.restype = ctypes.c_int
     lib.focus_decode_prefill.argtypes = [pp, ctypes.c_int32, vp, vp, vp, sz, vp]
@@ -159,6 +165,25 @@ def focus_attn_fwd(p, q, k, v, workspace, out, lse=None, row_pairs=None, vector=
 
 
 FOCUS_PAIRS_ALL, FOCUS_PAIRS_SHARED, FOCUS_PAIRS_CROSS_LOCAL = 0, 1, 2
+
+
+def focus_soft_workspace_size(p):
+    out = ctypes.c_size_t(0)
+    _check(load_library().focus_soft_workspace_size(ctypes.byref(p), ctypes.byref(out)))
+    return out.value
+
+
+def alloc_soft_workspace(p, device="cuda"):
+    nbytes = focus_soft_workspace_size(p)
+    return torch.empty(((nbytes + 255) // 256) * 256, dtype=torch.uint8, device=device)
+
+
+def focus_attn_soft_fwd(p, lam, g, q, k, v, workspace, out, lse=None, vector=False):
+    """Sec. 2 Eq. 2: g [B,n,K] float32 on the device, lam the slope of the gate."""
+    assert g.dtype == torch.float32 and g.is_contiguous()
+    fn = load_library().focus_attn_soft_fwd_vector if vector else load_library().focus_attn_soft_fwd
+    _check(fn(ctypes.byref(p), float(lam), _ptr(g), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
+              workspace.numel() * workspace.element_size(), _ptr(out), _ptr(lse), _stream()))
 
 
 def focus_attn_fwd_set(p, pair_set, q, k, v, workspace, out, lse=None, row_pairs=None):
