@@ -39,6 +39,7 @@ def main():
     ap.add_argument("--no-router", action="store_true")
     ap.add_argument("--no-two-call", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-soft", action="store_true", help="skip the soft-gated training attention leg")
     ap.add_argument("--no-wider", action="store_true", help="skip the half-precision / other-head-dim variants of cfg3")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calib-copy", action="store_true",
@@ -233,6 +234,33 @@ def main():
             "max_abs_diff_vs_fused": float((out.float() - out_focus.float()).abs().max().item()),
         }
         del part_out, part_lse
+
+    # the soft-gated attention of training (Sec. 2 Eq. 2) on the same q, k, v: every causal pair, gate from
+    # seeded soft assignments (a softmax of N(0, 4^2) scores per token), slope 8
+    if not args.no_soft and wl.softcap == 0.0 and not (wl.d == 256 and half):
+        ps = focus.make_params(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.K, 1, wl.window, causal=True, dtype=wl.dtype)
+        wss = focus.alloc_soft_workspace(ps)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1000 * wl.config_id + 11)
+        gsoft = torch.softmax(torch.randn((wl.B, wl.n, wl.K), generator=gen, device="cuda") * 4.0, dim=-1).contiguous()
+        focus.focus_attn_soft_fwd(ps, 8.0, gsoft, q, k, v, wss, out)
+        torch.cuda.synchronize()
+        nsoft = max(2, steps // 4)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(nsoft):
+            focus.focus_attn_soft_fwd(ps, 8.0, gsoft, q, k, v, wss, out)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms_soft = ev[0].elapsed_time(ev[1]) / nsoft
+        tf_soft = 4.0 * wl.d * causal_pairs / (ms_soft * 1e-3) / 1e12
+        result["soft_gate"] = {
+            "what": "focus_attn_soft_fwd (Sec. 2 Eq. 2, forward only): staging + attention over every causal pair",
+            "ms": ms_soft, "tflops_qk_pv": tf_soft,
+            "roofline": {"bound": "mfma" if half else "alu", "kernel": "attn_mfma_kernel (soft gate)" if half else "attn_simple_kernel",
+                         "achieved": tf_soft, "peak": peak, "unit": "TFLOP/s", "frac": tf_soft / peak, "traffic": None,
+                         "note": "4*d FLOP per causal pair; the affinity products (3 or 6 MFMAs per 32 keys) are not counted"}}
+        del wss, gsoft
 
     # incremental inference: one token per sequence against the cached K/V of this workload (memory-bound)
     if not args.no_decode:
