@@ -202,7 +202,7 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     if (!p) return fail(FOCUS_EINVAL, "params is NULL");
     if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->n < 1)
         return fail(FOCUS_EINVAL, "B, Hq, Hkv, n must be >= 1 (got %d %d %d %d)", p->B, p->Hq, p->Hkv, p->n);
-    if (p->dtype != FOCUS_F32 && p->dtype != FOCUS_BF16) return fail(FOCUS_EINVAL, "unknown dtype %d", p->dtype);
+    if (p->dtype != FOCUS_F32 && p->dtype != FOCUS_BF16 && p->dtype != FOCUS_F16) return fail(FOCUS_EINVAL, "unknown dtype %d", p->dtype);
     if (p->K < 1 || p->K > 32) return fail(FOCUS_EINVAL, "K must be in [1,32] (got %d)", p->K);
     if (p->topk < 1 || p->topk > p->K) return fail(FOCUS_EINVAL, "topk must be in [1,K] (got %d, K=%d)", p->topk, p->K);
     if (p->window < 1) return fail(FOCUS_EINVAL, "window must be >= 1 (got %d)", p->window);
@@ -216,7 +216,8 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
         return fail(FOCUS_EINVAL, "Hq (%d) is not a multiple of Hkv (%d) and no head_map given", p->Hq, p->Hkv);
     }
     if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "the incremental path is causal (one new token at the end)");
-    if (p->d != 64 && p->d != 128) return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64 or 128)", p->d);
+    if (p->d != 64 && p->d != 80 && p->d != 96 && p->d != 128 && p->d != 256)
+        return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64, 80, 96, 128 or 256)", p->d);
     if (p->Hq > MAX_HQ || p->Hkv > MAX_HQ) return fail(FOCUS_EUNSUPPORTED, "more than %d heads is not built", MAX_HQ);
     if (p->n > (1 << 24)) return fail(FOCUS_EUNSUPPORTED, "n above 2^24 is not built");
     if ((int64_t)p->B * p->Hq > 65535 || (int64_t)p->B * p->Hkv > 65535)

@@ -25,6 +25,7 @@ namespace {
 template <typename T> __device__ inline float dec_to_f32(T v);
 template <> __device__ inline float dec_to_f32<float>(float v) { return v; }
 template <> __device__ inline float dec_to_f32<uint16_t>(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+template <> __device__ inline float dec_to_f32<f16_bits>(f16_bits v) { return f16_bits_to_f32(v.v); }
 
 __device__ inline uint16_t dec_bf16_rne(float f)
 {
@@ -36,6 +37,7 @@ __device__ inline uint16_t dec_bf16_rne(float f)
 template <typename T> __device__ inline T dec_from_f32(float v);
 template <> __device__ inline float dec_from_f32<float>(float v) { return v; }
 template <> __device__ inline uint16_t dec_from_f32<uint16_t>(float v) { return dec_bf16_rne(v); }
+template <> __device__ inline f16_bits dec_from_f32<f16_bits>(float v) { return f16_bits{f32_to_f16_bits(v)}; }
 
 // 8 consecutive components as fp32
 __device__ inline void dec_load8(const float* p, float (&x)[8])
@@ -51,6 +53,17 @@ __device__ inline void dec_load8(const uint16_t* p, float (&x)[8])
     for (int e = 0; e < 4; ++e) {
         x[2 * e] = __uint_as_float(w[e] << 16);
         x[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+}
+
+__device__ inline void dec_load8(const f16_bits* p, float (&x)[8])
+{
+    const uint4 u = *(const uint4*)p;
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = f16_bits_to_f32((uint16_t)(w[e] & 0xffffu));
+        x[2 * e + 1] = f16_bits_to_f32((uint16_t)(w[e] >> 16));
     }
 }
 
@@ -159,8 +172,8 @@ __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMa
                                                           const float* __restrict__ cents, T* __restrict__ kc,
                                                           T* __restrict__ vc, char* __restrict__ st)
 {
-    __shared__ float s_x[128];
-    __shared__ float s_c[32 * 129];               // row stride d + 1: the K lanes read K different rows
+    __shared__ float s_x[256];
+    __shared__ float s_c[32 * 257];               // row stride d + 1: the K lanes read K different rows
     const int lane = threadIdx.x;
     const int b = blockIdx.y, hh = blockIdx.x;
     const bool is_q = hh < L.Hq;
@@ -214,6 +227,7 @@ template <typename T> struct Raw8;
 template <> struct Raw8<uint16_t> {
     uint4 u;
     __device__ inline void load(const uint16_t* p) { u = *(const uint4*)p; }
+    __device__ inline void zero() { u = make_uint4(0u, 0u, 0u, 0u); }
     __device__ inline void unpack(float (&x)[8]) const
     {
         const uint32_t w[4] = {u.x, u.y, u.z, u.w};
@@ -224,25 +238,45 @@ template <> struct Raw8<uint16_t> {
         }
     }
 };
+template <> struct Raw8<f16_bits> {
+    uint4 u;
+    __device__ inline void load(const f16_bits* p) { u = *(const uint4*)p; }
+    __device__ inline void zero() { u = make_uint4(0u, 0u, 0u, 0u); }
+    __device__ inline void unpack(float (&x)[8]) const
+    {
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[2 * e] = f16_bits_to_f32((uint16_t)(w[e] & 0xffffu));
+            x[2 * e + 1] = f16_bits_to_f32((uint16_t)(w[e] >> 16));
+        }
+    }
+};
 template <> struct Raw8<float> {
     float4 a, b;
     __device__ inline void load(const float* p) { a = *(const float4*)p; b = *(const float4*)(p + 4); }
+    __device__ inline void zero() { a = make_float4(0.f, 0.f, 0.f, 0.f); b = a; }
     __device__ inline void unpack(float (&x)[8]) const
     {
         x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
     }
 };
 
-// sum over the LPK (8 or 16) adjacent lanes that share a key, by DPP lane permutations (no LDS):
-// xor 1, xor 2 inside quads, then mirror inside 8 lanes, then mirror inside the 16-lane row
+// lanes that share one key: a power of two covering d / 8 slices of 8 components (the lanes past d / 8 hold zeros)
+__host__ __device__ constexpr int lanes_per_key(int d) { return d <= 64 ? 8 : d <= 128 ? 16 : 32; }
+
+// sum over the LPK (8, 16 or 32) adjacent lanes that share a key, by DPP lane permutations (no LDS):
+// xor 1, xor 2 inside quads, then mirror inside 8 lanes, then mirror inside the 16-lane row; two rows
+// meet through a lane exchange
 template <int LPK>
 __device__ inline float slice_sum(float x)
 {
     x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
     x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
     x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));   // row_half_mirror
-    if constexpr (LPK == 16)
+    if constexpr (LPK >= 16)
         x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false));  // row_mirror
+    if constexpr (LPK == 32) x += __shfl_xor(x, 16, 64);
     return x;
 }
 
@@ -256,6 +290,16 @@ __device__ inline float slice_dot(const Raw8<uint16_t>& q, const Raw8<uint16_t>&
     d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, q.u.y), __builtin_bit_cast(dec_bf16x2, k.u.y), d, false);
     d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, q.u.z), __builtin_bit_cast(dec_bf16x2, k.u.z), d, false);
     d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, q.u.w), __builtin_bit_cast(dec_bf16x2, k.u.w), d, false);
+    return d;
+}
+typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 dec_f16x2;
+__device__ inline float slice_dot(const Raw8<f16_bits>& q, const Raw8<f16_bits>& k)
+{
+    float d = 0.f;
+    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(dec_f16x2, q.u.x), __builtin_bit_cast(dec_f16x2, k.u.x), d, false);
+    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(dec_f16x2, q.u.y), __builtin_bit_cast(dec_f16x2, k.u.y), d, false);
+    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(dec_f16x2, q.u.z), __builtin_bit_cast(dec_f16x2, k.u.z), d, false);
+    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(dec_f16x2, q.u.w), __builtin_bit_cast(dec_f16x2, k.u.w), d, false);
     return d;
 }
 __device__ inline float slice_dot(const Raw8<float>& q, const Raw8<float>& k)
@@ -273,7 +317,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
                                                           const T* __restrict__ kc, const T* __restrict__ vc,
                                                           const char* __restrict__ st, float* __restrict__ part)
 {
-    constexpr int LPK = D / 8;                    // lanes that share one key (8 components each)
+    constexpr int LPK = lanes_per_key(D);         // lanes that share one key (8 components each)
+    constexpr int ACT = D / 8;                    // ... of which this many hold components (all, unless d is 80 or 96)
     constexpr int SLOTS = 64 / LPK;               // keys a wavefront handles side by side
     constexpr int PW = D + 4;                     // floats of one partial: o[D], max (log2 units), sum, count
     constexpr int U = sizeof(T) == 2 ? 8 : 4;     // keys in flight per slice: U K rows and U V rows loaded before use
@@ -322,8 +367,9 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
         for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
         return;
     }
+    const bool act = (ACT == LPK) || sub < ACT;
     Raw8<T> qr;
-    qr.load(q_new + (size_t)bhq * D + sub * 8);
+    if (act) qr.load(q_new + (size_t)bhq * D + sub * 8); else qr.zero();
     float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = 0.f;
@@ -365,8 +411,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
         for (int u = 0; u < U; ++u) {
             jpos[u] = s_j[r0 + u * SLOTS + slot];                     // r0 + U*SLOTS <= DEC_CHUNK: in bounds
             const int j = max(jpos[u], 0);
-            kr[u].load(kbase + (size_t)j * D);
-            vr[u].load(vbase + (size_t)j * D);
+            if (act) { kr[u].load(kbase + (size_t)j * D); vr[u].load(vbase + (size_t)j * D); }
+            else { kr[u].zero(); vr[u].zero(); }
         }
         float xs[U];
         float mx = -INFINITY;
@@ -400,8 +446,10 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     // every (wavefront, slot) holds a partial softmax over its keys: fold them through LDS
     {
         float* r = s_red[wave][slot];
+        if (act) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) r[sub * 8 + e] = o[e];
+            for (int e = 0; e < 8; ++e) r[sub * 8 + e] = o[e];
+        }
         if (sub == 0) { r[D] = m; r[D + 1] = l; r[D + 2] = (float)cnt; }
     }
     __syncthreads();
@@ -435,7 +483,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
                                                               const T* __restrict__ kc, const T* __restrict__ vc,
                                                               const char* __restrict__ st, float* __restrict__ part)
 {
-    constexpr int LPK = D / 8;
+    constexpr int LPK = lanes_per_key(D);
+    constexpr int ACT = D / 8;
     constexpr int SLOTS = 64 / LPK;
     constexpr int PW = D + 4;
     constexpr int U = (G <= 2 && sizeof(T) == 2) ? 8 : 4;
@@ -488,9 +537,12 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
         }
         return;
     }
+    const bool act = (ACT == LPK) || sub < ACT;
     Raw8<T> qr[G];
 #pragma unroll
-    for (int i = 0; i < G; ++i) qr[i].load(q_new + (bhq0 + i) * D + sub * 8);
+    for (int i = 0; i < G; ++i) {
+        if (act) qr[i].load(q_new + (bhq0 + i) * D + sub * 8); else qr[i].zero();
+    }
     float o[G][8], m[G], l[G];
     int cnt[G];
 #pragma unroll
@@ -555,8 +607,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
             jpos[u] = s_j[r0 + u * SLOTS + slot];                     // the array is padded by one round of -1
             hbs[u] = (jpos[u] >= 0) ? (uint32_t)s_hb[r0 + u * SLOTS + slot] : 0u;
             const int j = max(jpos[u], 0);
-            kr[u].load(kbase + (size_t)j * D);
-            vr[u].load(vbase + (size_t)j * D);
+            if (act) { kr[u].load(kbase + (size_t)j * D); vr[u].load(vbase + (size_t)j * D); }
+            else { kr[u].zero(); vr[u].zero(); }
         }
         float vx[U][8];
 #pragma unroll
@@ -605,8 +657,10 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
         if (i > 0) __syncthreads();
         {
             float* r = s_red[wave][slot];
+            if (act) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) r[sub * 8 + e] = o[i][e];
+                for (int e = 0; e < 8; ++e) r[sub * 8 + e] = o[i][e];
+            }
             if (sub == 0) { r[D] = m[i]; r[D + 1] = l[i]; r[D + 2] = (float)cnt[i]; }
         }
         __syncthreads();
@@ -640,7 +694,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int n
 {
     constexpr int PW = D + 4;
     constexpr int TPG = D / 4;                    // threads per group
-    constexpr int NG = 256 / TPG;
+    constexpr int NG = 256 / TPG;                 // whole groups; the threads past NG * TPG (d = 80, 96) only help with the max
     __shared__ float s_w[4];
     __shared__ float s_acc[NG][D + 4];
     const int tid = threadIdx.x, t = tid % TPG, grp = tid / TPG, bhq = blockIdx.x;
@@ -654,7 +708,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int n
     mx = fmaxf(fmaxf(s_w[0], s_w[1]), fmaxf(s_w[2], s_w[3]));
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float lsum = 0.f, csum = 0.f;
-    for (int c = grp; c < nchunks; c += NG) {
+    for (int c = grp; grp < NG && c < nchunks; c += NG) {
         const float* p = p0 + (size_t)c * PW;
         const float4 tail = *(const float4*)(p + D);                  // max (log2 units), sum, count, unused
         if (tail.x == -INFINITY) continue;
@@ -665,8 +719,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int n
         lsum = fmaf(wgt, tail.y, lsum);
         csum += tail.z;
     }
-    *(float4*)(&s_acc[grp][4 * t]) = acc;
-    if (t == 0) { s_acc[grp][D] = lsum; s_acc[grp][D + 1] = csum; }
+    if (grp < NG) {
+        *(float4*)(&s_acc[grp][4 * t]) = acc;
+        if (t == 0) { s_acc[grp][D] = lsum; s_acc[grp][D + 1] = csum; }
+    }
     __syncthreads();
     if (tid < D) {
         float a = 0.f, ls = 0.f, cs = 0.f;
@@ -693,6 +749,9 @@ hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* k
     if (L.dtype == 0) {
         if (L.K <= 4) FOCUS_DEC_SCORE(float, 4); else if (L.K <= 8) FOCUS_DEC_SCORE(float, 8);
         else if (L.K <= 16) FOCUS_DEC_SCORE(float, 16); else FOCUS_DEC_SCORE(float, 32);
+    } else if (L.dtype == 2) {
+        if (L.K <= 4) FOCUS_DEC_SCORE(f16_bits, 4); else if (L.K <= 8) FOCUS_DEC_SCORE(f16_bits, 8);
+        else if (L.K <= 16) FOCUS_DEC_SCORE(f16_bits, 16); else FOCUS_DEC_SCORE(f16_bits, 32);
     } else {
         if (L.K <= 4) FOCUS_DEC_SCORE(uint16_t, 4); else if (L.K <= 8) FOCUS_DEC_SCORE(uint16_t, 8);
         else if (L.K <= 16) FOCUS_DEC_SCORE(uint16_t, 16); else FOCUS_DEC_SCORE(uint16_t, 32);
@@ -740,9 +799,16 @@ static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int po
 {
     hipLaunchKernelGGL(decode_route_kernel<T>, dim3(L.Hq + L.Hkv, L.B), dim3(64), 0, s, L, hm, pos, (const T*)q_new,
                        (const T*)k_new, (const T*)v_new, cents, (T*)kc, (T*)vc, st);
-    if (L.d == 64)
-        return decode_step_d<T, 64>(L, hm, pos, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s);
-    return decode_step_d<T, 128>(L, hm, pos, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s);
+#define FOCUS_DEC_D(D_) decode_step_d<T, D_>(L, hm, pos, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s)
+    switch (L.d) {
+        case 64: return FOCUS_DEC_D(64);
+        case 80: return FOCUS_DEC_D(80);
+        case 96: return FOCUS_DEC_D(96);
+        case 128: return FOCUS_DEC_D(128);
+        case 256: return FOCUS_DEC_D(256);
+        default: return hipErrorInvalidValue;
+    }
+#undef FOCUS_DEC_D
 }
 
 hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
@@ -751,6 +817,8 @@ hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos,
 {
     if (L.dtype == 0)
         return decode_step_t<float>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+    if (L.dtype == 2)
+        return decode_step_t<f16_bits>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
     return decode_step_t<uint16_t>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
 }
 

@@ -199,5 +199,13 @@ def test_decode_argument_errors_before_any_launch():
     assert lib.focus_decode_step(ctypes.byref(p), -1, *args, fake, need, fake, vp(0), vp(0), vp(0)) == focus.FOCUS_EINVAL
     assert lib.focus_decode_step(ctypes.byref(p), 5, *args, fake, need - 1, fake, vp(0), vp(0), vp(0)) == focus.FOCUS_EWORKSPACE
     assert lib.focus_decode_step(ctypes.byref(p), 5, *args, fake, need, vp(0), vp(0), vp(0), vp(0)) == focus.FOCUS_EINVAL
-    bad = focus.make_params(1, 4, 2, 4096, 96, 4, 2, 64)
+    bad = focus.make_params(1, 4, 2, 4096, 112, 4, 2, 64)                 # a head dim outside {64, 80, 96, 128, 256}
     assert lib.focus_decode_state_size(ctypes.byref(bad), ctypes.byref(ctypes.c_size_t(0))) == focus.FOCUS_EUNSUPPORTED
+
+
+def test_decode_takes_the_causal_mask_only():
+    p = focus.make_params(1, 4, 2, 4096, 128, 4, 2, 64, causal=False)
+    with pytest.raises(focus.FocusError) as e:
+        focus.focus_decode_state_size(p)
+    assert e.value.status == focus.FOCUS_EUNSUPPORTED
+    assert focus.focus_decode_state_size(focus.make_params(1, 4, 2, 4096, 80, 4, 2, 64, dtype="f16")) > 0
