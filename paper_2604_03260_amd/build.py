@@ -1,6 +1,8 @@
 """Builds libfocus.so (HIP, gfx950) in-tree next to this file."""
 import os
+import re
 import subprocess
+import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -12,6 +14,31 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp
          "-Wno-unused-result", "-Wno-unused-command-line-argument"]
 
 
+# The attention kernel reads its LDS operands with inline ds_read whose completion the compiler does not track
+# (one s_waitcnt before the matrix products).  A register spilled between such a read and its wait would be
+# stored before the data has arrived, so a build in which any instantiation of that kernel spills is refused.
+NO_SPILL_SOURCE = "focus_attn_mfma.hip"
+NO_SPILL_KERNEL = "attn_mfma_kernel"
+
+
+def check_no_spills(remarks):
+    """remarks: the compiler's -Rpass-analysis=kernel-resource-usage output.  Returns the number of kernels seen."""
+    seen = 0
+    for block in remarks.split("Function Name:")[1:]:
+        name = block.split()[0]
+        if NO_SPILL_KERNEL not in name:
+            continue
+        seen += 1
+        m = re.search(r"VGPRs Spill:\s*(\d+)", block)
+        s = re.search(r"ScratchSize \[bytes/lane\]:\s*(\d+)", block)
+        if m is None or int(m.group(1)) != 0 or (s is not None and int(s.group(1)) != 0):
+            raise RuntimeError("%s spills registers (%s): its untracked LDS reads are unsafe, see build.py"
+                               % (name, m.group(0) if m else "no report"))
+    if seen == 0:
+        raise RuntimeError("no resource report for %s: cannot check for spills" % NO_SPILL_KERNEL)
+    return seen
+
+
 def build_library(verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
@@ -20,12 +47,26 @@ def build_library(verbose=False):
     for s in SOURCES:
         o = os.path.join(HERE, "_build", s.replace(".hip", ".o"))
         cmd = [hipcc] + [f for f in FLAGS if f != "-shared"] + ["-c", os.path.join(CSRC, s), "-o", o]
+        err = None
+        if s == NO_SPILL_SOURCE:
+            cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
+            err = open(os.path.join(HERE, "_build", "resource_usage.txt"), "w")
         if verbose:
             print(" ".join(cmd), flush=True)
-        procs.append((subprocess.Popen(cmd), cmd))
+        procs.append((subprocess.Popen(cmd, stderr=err), cmd, err))
         objs.append(o)
-    for p, cmd in procs:
-        if p.wait() != 0:
+    for p, cmd, err in procs:
+        rc = p.wait()
+        if err is not None:
+            err.close()
+            remarks = open(err.name).read()
+            if rc != 0:
+                sys.stderr.write(remarks[-4000:])
+            else:
+                n = check_no_spills(remarks)
+                if verbose:
+                    print("%d instantiations of %s, none spills" % (n, NO_SPILL_KERNEL), flush=True)
+        if rc != 0:
             raise RuntimeError("compile failed: " + " ".join(cmd))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:

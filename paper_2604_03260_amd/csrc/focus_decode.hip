@@ -708,16 +708,26 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int n
     mx = fmaxf(fmaxf(s_w[0], s_w[1]), fmaxf(s_w[2], s_w[3]));
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float lsum = 0.f, csum = 0.f;
-    for (int c = grp; grp < NG && c < nchunks; c += NG) {
-        const float* p = p0 + (size_t)c * PW;
-        const float4 tail = *(const float4*)(p + D);                  // max (log2 units), sum, count, unused
-        if (tail.x == -INFINITY) continue;
-        const float4 ov = *(const float4*)(p + 4 * t);
-        const float wgt = __builtin_amdgcn_exp2f(tail.x - mx);
-        acc.x = fmaf(wgt, ov.x, acc.x); acc.y = fmaf(wgt, ov.y, acc.y);
-        acc.z = fmaf(wgt, ov.z, acc.z); acc.w = fmaf(wgt, ov.w, acc.w);
-        lsum = fmaf(wgt, tail.y, lsum);
-        csum += tail.z;
+    // four partials in flight per group of threads: the loop is a chain of dependent L2 round trips otherwise
+    constexpr int MU = 4;
+    for (int c0 = grp; grp < NG && c0 < nchunks; c0 += NG * MU) {
+        float4 tail[MU], ov[MU];
+#pragma unroll
+        for (int u = 0; u < MU; ++u) {
+            const int c = min(c0 + u * NG, nchunks - 1);              // clamped loads, weighed zero below
+            const float* p = p0 + (size_t)c * PW;
+            tail[u] = *(const float4*)(p + D);                        // max (log2 units), sum, count, unused
+            ov[u] = *(const float4*)(p + 4 * t);
+        }
+#pragma unroll
+        for (int u = 0; u < MU; ++u) {
+            if (c0 + u * NG >= nchunks || tail[u].x == -INFINITY) continue;
+            const float wgt = __builtin_amdgcn_exp2f(tail[u].x - mx);
+            acc.x = fmaf(wgt, ov[u].x, acc.x); acc.y = fmaf(wgt, ov[u].y, acc.y);
+            acc.z = fmaf(wgt, ov[u].z, acc.z); acc.w = fmaf(wgt, ov[u].w, acc.w);
+            lsum = fmaf(wgt, tail[u].y, lsum);
+            csum += tail[u].z;
+        }
     }
     if (grp < NG) {
         *(float4*)(&s_acc[grp][4 * t]) = acc;
