@@ -225,6 +225,31 @@ def test_cfg3_full_sampled_rows():
     harness.check_pair_totals(wl, res, mq, mk)
 
 
+CFG3_VARIANTS = {
+    # the shapes bench.py times beside the headline workload (query heads scaled so that Hq*d = 4096) ...
+    "f16": dict(dtype="f16"),
+    "d256": dict(d=256, Hq=16, Hkv=4),
+    "d96": dict(d=96, Hq=40, Hkv=8),
+    "d80": dict(d=80, Hq=48, Hkv=8),
+    "d64": dict(d=64, Hq=64, Hkv=16),
+    # ... and the other two extensions of the parameter space at the same size
+    "noncausal": dict(causal=False),
+    "k32_top2_coarse": dict(K=32, topk=2),
+}
+
+
+@pytest.mark.parametrize("tag", list(CFG3_VARIANTS))
+def test_cfg3_variants_full_sampled_rows(tag):
+    from dataclasses import replace
+    wl = replace(CONFIGS["cfg3"], name="cfg3_" + tag, **CFG3_VARIANTS[tag])
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    rows = workloads.sample_rows(wl, 768)
+    say(wl.name, harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+    harness.check_pair_totals(wl, res, mq, mk)
+
+
 @pytest.mark.parametrize("name", ["cfg4a", "cfg4b"])
 def test_cfg4_full_sampled_rows(name):
     wl = CONFIGS[name]

@@ -112,6 +112,16 @@ def test_soft_gate_matrix_core_and_vector_kernels_agree_mid_size():
     assert (lse - lse_v).abs().max().item() <= 1e-2
 
 
+def test_soft_gate_full_size_sampled_rows():
+    # the shape and inputs of bench.py's soft_gate leg (cfg3's q, k, v; seeded soft assignments; slope 8)
+    wl = workloads.CONFIGS["cfg3"]
+    inp = workloads.make_inputs(wl, "cuda")
+    g = soft_assignment(wl, "cuda")
+    out, lse = run_soft(wl, inp, g, 8.0)
+    rows = workloads.sample_rows(wl, 512)
+    say("cfg3 soft gate", check_soft(wl, inp, g, 8.0, out, lse, rows=rows))
+
+
 def test_soft_gate_with_the_router_output():
     # the router's Sinkhorn-normalised soft assignment (fp64) rounded to fp32 feeds the gate
     wl = case("routed", n=1500, d=128, K=4, window=64, Hq=8, Hkv=2)
