@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2604_03260_amd import workloads
+from paper_2604_03260_amd import focus, workloads
 from paper_2604_03260_amd.workloads import CONFIGS, Workload
 from tests import harness
 
@@ -161,6 +161,24 @@ def test_coarse_classes_mid_size_sampled_rows():
     assert torch.equal(res["row_pairs"], vec["row_pairs"])
     diff = (res["out"].float() - vec["out"].float()).abs()
     assert diff.max().item() <= 2e-2 and diff.mean().item() <= 2e-3
+
+
+def test_assign_at_the_maximum_sequence_length():
+    # n = 2^24, the largest the library takes: membership, counts and lists bit-exact (65536 sort blocks,
+    # 32-bit positions, 64-bit byte offsets); the attention itself would run for a minute and is not launched
+    wl = small("max_n", n=1 << 24, Hq=1, Hkv=1, d=64, dtype="bf16", K=4, topk=2, window=4096)
+    inp = workloads.make_inputs(wl, "cuda")
+    p = harness.params_of(wl)
+    ws = focus.alloc_workspace(p)
+    focus.focus_assign(p, inp["q"], inp["k"], inp["centroids"], ws)
+    torch.cuda.synchronize()
+    res = dict(views=focus.focus_workspace_views(p, ws))
+    say("max_n assigned; checking against the oracle")
+    harness.check_assign(wl, inp, res)
+    p1 = focus.make_params(1, 1, 1, (1 << 24) + 1, 64, 4, 2, 4096)
+    with pytest.raises(focus.FocusError) as e:
+        focus.focus_workspace_size(p1)
+    assert e.value.status == focus.FOCUS_EUNSUPPORTED
 
 
 def test_deterministic_bytes():
