@@ -21,8 +21,8 @@ struct TilePlan {
     uint8_t inter[MAX_CLASSES];
     int ibeg[MAX_CLASSES];     // tiles [ibeg, iend) of the class need no per-element causal/window test
     int iend[MAX_CLASSES];
-    uint8_t blk_hi[SB];        // class ids of the sort block holding the upper bound
-    uint8_t blk_lo[SB];        // ... and the lower bound of the window span
+    int cnt_hi[MAX_CLASSES];   // keys of every class in the part of a sort block below the upper bound
+    int cnt_lo[MAX_CLASSES];   // ... and below the lower bound of the window span
     int cls, tile, row0, nvalid, i_lo, i_hi, total;
 };
 
@@ -49,12 +49,16 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
     const uint8_t* kcls = (const uint8_t*)(ws + L.off_kcls) + (size_t)bhk * ((size_t)L.nblk * SB);
     const int bh_i = x_hi / SB, bl_i = x_lo / SB;
     const int part_hi = x_hi % SB, part_lo = x_lo % SB;
-    for (int e = tid; e < SB; e += nthr) {
-        P.blk_hi[e] = (e < part_hi) ? kcls[(size_t)bh_i * SB + e] : 0;
-        P.blk_lo[e] = (e < part_lo) ? kcls[(size_t)bl_i * SB + e] : 0;
-    }
+    // The prefix counts at sort-block boundaries come from the assign pass; the partial blocks are
+    // counted here, all threads at once into a class histogram (integer atomics in LDS).
+    for (int c2 = tid; c2 < NC; c2 += nthr) { P.cnt_hi[c2] = 0; P.cnt_lo[c2] = 0; }
     if (tid == 0) {
         P.cls = c; P.tile = t; P.row0 = row0; P.nvalid = nvalid; P.i_lo = i_lo; P.i_hi = i_hi;
+    }
+    __syncthreads();
+    for (int e = tid; e < SB; e += nthr) {
+        if (e < part_hi) atomicAdd(&P.cnt_hi[kcls[(size_t)bh_i * SB + e]], 1);
+        if (e < part_lo) atomicAdd(&P.cnt_lo[kcls[(size_t)bl_i * SB + e]], 1);
     }
     __syncthreads();
     const int* kbc = (const int*)(ws + L.off_kbc) + (size_t)bhk * (L.nblk + 1) * NC;
@@ -62,8 +66,7 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
     const uint32_t* clsmask = (const uint32_t*)(ws + L.off_clsmask);
     const uint32_t mymask = clsmask[c];
     for (int c2 = tid; c2 < NC; c2 += nthr) {
-        int pre_hi = kbc[(size_t)bh_i * NC + c2];
-        for (int e = 0; e < part_hi; ++e) pre_hi += (P.blk_hi[e] == c2) ? 1 : 0;
+        const int pre_hi = kbc[(size_t)bh_i * NC + c2] + P.cnt_hi[c2];
         const bool inter = (clsmask[c2] & mymask) != 0;
         const int koff = kco[c2];
         int a = 0, b = 0;
@@ -74,8 +77,7 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
                 b = (koff + upto + KT - 1) / KT;
             }
         } else if (L.pair_set != 1) {                      // set A skips the classes that share none
-            int pre_lo = kbc[(size_t)bl_i * NC + c2];
-            for (int e = 0; e < part_lo; ++e) pre_lo += (P.blk_lo[e] == c2) ? 1 : 0;
+            const int pre_lo = kbc[(size_t)bl_i * NC + c2] + P.cnt_lo[c2];
             if (pre_hi > pre_lo) {
                 a = (koff + pre_lo) / KT;
                 b = (koff + pre_hi + KT - 1) / KT;
