@@ -100,7 +100,7 @@ focus_status focus_attn_fwd(const focus_params *p, const void *q, const void *k,
  * p->topk is not used (give 1), p->causal must be 1 and p->softcap 0 (else FOCUS_EUNSUPPORTED).
  * One call does everything (no focus_assign): the workspace of focus_soft_workspace_size(p) bytes is
  * scratch (position-ordered copies of K, V and g).  out [B,Hq,n,d] in p->dtype, lse (nullable)
- * [B,Hq,n] fp32.  Forward only. */
+ * [B,Hq,n] fp32.  Forward only.  d = 256 runs on the vector ALUs in every dtype (slow). */
 focus_status focus_soft_workspace_size(const focus_params *p, size_t *bytes);
 focus_status focus_attn_soft_fwd(const focus_params *p, float lambda, const float *g,
                                  const void *q, const void *k, const void *v, void *workspace,

@@ -393,8 +393,6 @@ focus_status soft_checks(const focus_params* p)
 {
     if (p && p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "the soft-gated attention is causal (Sec. 2 Eq. 2)");
     if (p && p->softcap != 0.0f) return fail(FOCUS_EUNSUPPORTED, "the soft-gated attention takes no softcap");
-    if (p && p->d == 256 && p->dtype != FOCUS_F32)
-        return fail(FOCUS_EUNSUPPORTED, "the soft-gated attention is not built for head dim 256 in 16-bit types");
     return FOCUS_OK;
 }
 
@@ -416,6 +414,9 @@ focus_status soft_launch(const focus_params* p, float lambda, const float* g, co
     st = check_ws(L, workspace, workspace_bytes);
     if (st != FOCUS_OK) return st;
     L.gate_slope = (float)(-(double)lambda * 1.4426950408889634);
+    // head dim 256 in a 16-bit type: the gate's accumulators and operands do not fit the register file next to
+    // 512-byte key rows, so that shape goes through the vector kernel (correct, slow)
+    if (p->d == 256) vector = true;
     hipStream_t s = (hipStream_t)stream;
     // one class holding every token, in position order: the bucketing with a constant membership
     hipError_t e = focus::launch_assign_tokens(L, nullptr, k, (char*)workspace, nullptr, s);

@@ -68,6 +68,7 @@ CASES = [
     (case("bf16_d80_k32", n=700, d=80, K=32, window=16, Hq=2, Hkv=2), 12.0),       # two k-steps of groups
     (case("f32_d64", n=500, dtype="f32", K=4, window=24), 6.0),
     (case("f32_d256_k2", n=300, d=256, dtype="f32", K=2, window=8, Hq=2, Hkv=1), 2.0),
+    (case("bf16_d256_vector_path", n=400, d=256, K=4, window=20, Hq=2, Hkv=1), 6.0),   # 16-bit d = 256: vector kernel
     (case("lambda_zero", n=520, d=128), 0.0),                                      # every distant logit halved
     (case("negative_slope", n=640, d=64, K=8), -7.0),
     (case("window_covers", n=300, d=128, window=300), 9.0),                        # plain causal attention
@@ -143,10 +144,6 @@ def test_soft_gate_refusals():
         focus.focus_soft_workspace_size(p)
     assert e.value.status == focus.FOCUS_EUNSUPPORTED
     p = focus.make_params(1, 2, 2, 256, 64, 4, 1, 16, softcap=30.0)
-    with pytest.raises(focus.FocusError) as e:
-        focus.focus_soft_workspace_size(p)
-    assert e.value.status == focus.FOCUS_EUNSUPPORTED
-    p = focus.make_params(1, 2, 2, 256, 256, 4, 1, 16, dtype="bf16")
     with pytest.raises(focus.FocusError) as e:
         focus.focus_soft_workspace_size(p)
     assert e.value.status == focus.FOCUS_EUNSUPPORTED
