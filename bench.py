@@ -285,6 +285,29 @@ def main():
         torch.cuda.synchronize()
         ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(dsteps - 4))
         t_dec = ts[len(ts) // 2]
+        # the same steps replayed from ONE captured HIP graph (position in device memory, advanced inside the
+        # graph): what a generation loop pays per token without per-step launch work on the host
+        focus.focus_decode_prefill(p, n0, kc, cents, state)          # lists back to n0; the caches keep their rows
+        posd = torch.full((1,), n0, dtype=torch.int32, device="cuda")
+        qb, kb, vb = qs[0].clone(), ks[0].clone(), vs[0].clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        dgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(dgraph, stream=side):
+            focus.focus_decode_step_at(p, posd, qb, kb, vb, cents, kc, vc, state, dout, None, drp)
+            posd.add_(1)
+        for s in range(4):                               # warm-up replays
+            qb.copy_(qs[s]); kb.copy_(ks[s]); vb.copy_(vs[s])
+            dgraph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for s in range(4, dsteps):                       # the whole loop enqueued, as a generation loop would
+            qb.copy_(qs[s]); kb.copy_(ks[s]); vb.copy_(vs[s])
+            dgraph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t_dec_graph = e0.elapsed_time(e1) / (dsteps - 4)
         # rows of K and V the last step had to read: per KV head the union over its query heads of
         # {window} + {keys whose group set meets the head's}; membership read back from the state
         dviews = focus.focus_decode_state_views(p, state)
@@ -303,6 +326,7 @@ def main():
         result["decode"] = {
             "what": "focus_decode_step at context n (route + append + attention + merge), median of %d steps" % (dsteps - 4),
             "ms_per_step": t_dec, "tokens_per_s": wl.B / (t_dec * 1e-3),
+            "ms_per_token_graph_loop": t_dec_graph,      # three input copies + one graph replay per token, enqueued back to back
             "attended_keys_all_heads": per_head_rows,
             "roofline": {"bound": "hbm", "kernel": "decode_attn (whole step timed)", "achieved": dec_bytes / (t_dec * 1e-3) / 1e9,
                          "peak": 8000.0, "unit": "GB/s", "frac": dec_bytes / (t_dec * 1e-3) / 1e9 / 8000.0, "traffic": None,

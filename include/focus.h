@@ -207,6 +207,17 @@ focus_status focus_decode_step(const focus_params *p, int32_t pos, const void *q
                                void *k_cache, void *v_cache, void *state, size_t state_bytes,
                                void *out, float *lse, int32_t *row_pairs, void *stream);
 
+/* The same step with the position read from DEVICE memory by the kernels when they run: a HIP graph
+ * captured once around this call serves every step of a generation loop (the caller writes the new
+ * token's q, k, v into the captured buffers and advances *pos_dev on the device between replays).
+ * The launch shapes are those of the last position the caches can hold; work-groups past the real
+ * sequence exit at once.  A position outside [0, n) cannot be checked on the host: the step then
+ * does nothing (caches, state and outputs untouched). */
+focus_status focus_decode_step_at(const focus_params *p, const int32_t *pos_dev, const void *q_new,
+                                  const void *k_new, const void *v_new, const float *centroids,
+                                  void *k_cache, void *v_cache, void *state, size_t state_bytes,
+                                  void *out, float *lse, int32_t *row_pairs, void *stream);
+
 /* Device pointers INTO the decode state for parity checks (any may be NULL): mk [B,Hkv,n] uint32
  * masks of the cached keys, lists [B,Hkv,K,n] int32 (the first counts[b,h,g] entries of a list are
  * its positions, ascending), counts [B,Hkv,K] int32, mq [B,Hq] uint32 masks of the last step's queries. */

@@ -167,7 +167,8 @@ __global__ __launch_bounds__(256) void decode_prefill_lists_kernel(DecodeLayout 
 // The vector and the K centroid rows are staged in LDS first, so the fp64 chain of lane g (group g,
 // components in index order) runs from LDS instead of waiting for a global load per component.
 template <typename T>
-__global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMap hm, int pos, const T* __restrict__ q_new,
+__global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMap hm, int pos_arg, const int* __restrict__ pos_dev,
+                                                          const T* __restrict__ q_new,
                                                           const T* __restrict__ k_new, const T* __restrict__ v_new,
                                                           const float* __restrict__ cents, T* __restrict__ kc,
                                                           T* __restrict__ vc, char* __restrict__ st)
@@ -175,6 +176,10 @@ __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMa
     __shared__ float s_x[256];
     __shared__ float s_c[32 * 257];               // row stride d + 1: the K lanes read K different rows
     const int lane = threadIdx.x;
+    // the position comes from the launch, or from device memory when a captured graph serves every step;
+    // a position outside the caches does nothing (the host could not check it)
+    const int pos = pos_dev ? *pos_dev : pos_arg;
+    if (pos < 0 || pos >= L.n) return;
     const int b = blockIdx.y, hh = blockIdx.x;
     const bool is_q = hh < L.Hq;
     const int h = is_q ? hh : hh - L.Hq;
@@ -313,7 +318,8 @@ __device__ inline float slice_dot(const Raw8<float>& q, const Raw8<float>& k)
 constexpr float DEC_LOG2E = 1.4426950408889634f;
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos, int span, const T* __restrict__ q_new,
+__global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos_arg, const int* __restrict__ pos_dev, int span,
+                                                          const T* __restrict__ q_new,
                                                           const T* __restrict__ kc, const T* __restrict__ vc,
                                                           const char* __restrict__ st, float* __restrict__ part)
 {
@@ -329,6 +335,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     __shared__ int s_j[DEC_CHUNK];                // cache row of every key of the chunk, -1 = skipped
     __shared__ float s_red[4][SLOTS][PW];
 
+    const int pos = pos_dev ? *pos_dev : pos_arg;
+    if (pos < 0 || pos >= L.n) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane / LPK, sub = lane % LPK;
     const int chunk = blockIdx.x, bhq = blockIdx.y;
@@ -479,7 +487,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
 // for G softmaxes.  Keys skipped by the dedup are squeezed out of the chunk before the arithmetic.
 // Requires the default head map (query heads hk*G .. hk*G+G-1 belong to KV head hk).
 template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, int pos, int span, const T* __restrict__ q_new,
+__global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, int pos_arg, const int* __restrict__ pos_dev, int span,
+                                                              const T* __restrict__ q_new,
                                                               const T* __restrict__ kc, const T* __restrict__ vc,
                                                               const char* __restrict__ st, float* __restrict__ part)
 {
@@ -497,6 +506,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     __shared__ int s_wcnt[4];
     __shared__ float s_red[4][SLOTS][PW];
 
+    const int pos = pos_dev ? *pos_dev : pos_arg;
+    if (pos < 0 || pos >= L.n) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane / LPK, sub = lane % LPK;
     const int chunk = blockIdx.x;
@@ -688,7 +699,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
 // One work-group per (batch, query head).  A chunk's partial is read by D/4 threads (4 components each);
 // the 256 / (D/4) groups of threads take the chunks round-robin, then fold through LDS.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int nchunks, const float* __restrict__ part,
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int pos_arg, const int* __restrict__ pos_dev, int nchunks,
+                                                           const float* __restrict__ part,
                                                            T* __restrict__ out, float* __restrict__ lse,
                                                            int32_t* __restrict__ row_pairs)
 {
@@ -697,6 +709,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int n
     constexpr int NG = 256 / TPG;                 // whole groups; the threads past NG * TPG (d = 80, 96) only help with the max
     __shared__ float s_w[4];
     __shared__ float s_acc[NG][D + 4];
+    const int pos = pos_dev ? *pos_dev : pos_arg;
+    if (pos < 0 || pos >= L.n) return;                // the other kernels of the step did nothing either
     const int tid = threadIdx.x, t = tid % TPG, grp = tid / TPG, bhq = blockIdx.x;
     const float* p0 = part + (size_t)bhq * L.max_chunks * PW;
     float mx = -INFINITY;
@@ -772,7 +786,7 @@ hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* k
 }
 
 template <typename T, int D>
-static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int pos, const T* q_new, const T* kc, const T* vc,
+static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int pos, const int* pos_dev, const T* q_new, const T* kc, const T* vc,
                                 char* st, T* out, float* lse, int32_t* row_pairs, hipStream_t s)
 {
     float* part = (float*)(st + L.off_part);
@@ -783,6 +797,9 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     // upper bound of the concatenated key sequence known on the host: the window plus list prefixes that hold
     // at most topk * pos entries together (every cached key sits in exactly topk lists), for one head's groups
     // as for the union of several heads' groups
+    // (with the position in device memory: the bound of the last position the caches can hold; work-groups
+    // past the real sequence leave an empty partial)
+    if (pos_dev) pos = L.n - 1;
     const long vmax = (long)std::min(L.window, pos + 1) + (long)L.topk * (long)pos;
     const int nchunks = (int)std::min((long)L.max_chunks, (vmax + DEC_CHUNK - 1) / DEC_CHUNK);
     // a work-group walks `span` chunks and leaves one partial: at most about 384 partials per head, so the merge
@@ -791,25 +808,26 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     const int nparts = (nchunks + span - 1) / span;
     if (grouped) {
         dim3 grid(nparts, L.B * L.Hkv);
-#define FOCUS_DEC_GQA(G_) hipLaunchKernelGGL((decode_attn_gqa_kernel<T, D, G_>), grid, dim3(256), 0, s, L, pos, span, q_new, kc, vc, (const char*)st, part)
+#define FOCUS_DEC_GQA(G_) hipLaunchKernelGGL((decode_attn_gqa_kernel<T, D, G_>), grid, dim3(256), 0, s, L, pos, pos_dev, span, q_new, kc, vc, (const char*)st, part)
         if (G == 1) FOCUS_DEC_GQA(1); else if (G == 2) FOCUS_DEC_GQA(2); else if (G == 4) FOCUS_DEC_GQA(4); else FOCUS_DEC_GQA(8);
 #undef FOCUS_DEC_GQA
     } else {
-        hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3(nparts, L.B * L.Hq), dim3(256), 0, s, L, hm, pos, span, q_new, kc,
-                           vc, (const char*)st, part);
+        hipLaunchKernelGGL((decode_attn_kernel<T, D>), dim3(nparts, L.B * L.Hq), dim3(256), 0, s, L, hm, pos, pos_dev, span,
+                           q_new, kc, vc, (const char*)st, part);
     }
-    hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(L.B * L.Hq), dim3(256), 0, s, L, nparts, part, out, lse, row_pairs);
+    hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(L.B * L.Hq), dim3(256), 0, s, L, pos, pos_dev, nparts, part, out, lse,
+                       row_pairs);
     return hipGetLastError();
 }
 
 template <typename T>
-static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
+static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int pos, const int* pos_dev, const void* q_new, const void* k_new,
                                 const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out,
                                 float* lse, int32_t* row_pairs, hipStream_t s)
 {
-    hipLaunchKernelGGL(decode_route_kernel<T>, dim3(L.Hq + L.Hkv, L.B), dim3(64), 0, s, L, hm, pos, (const T*)q_new,
+    hipLaunchKernelGGL(decode_route_kernel<T>, dim3(L.Hq + L.Hkv, L.B), dim3(64), 0, s, L, hm, pos, pos_dev, (const T*)q_new,
                        (const T*)k_new, (const T*)v_new, cents, (T*)kc, (T*)vc, st);
-#define FOCUS_DEC_D(D_) decode_step_d<T, D_>(L, hm, pos, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s)
+#define FOCUS_DEC_D(D_) decode_step_d<T, D_>(L, hm, pos, pos_dev, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s)
     switch (L.d) {
         case 64: return FOCUS_DEC_D(64);
         case 80: return FOCUS_DEC_D(80);
@@ -821,15 +839,15 @@ static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int po
 #undef FOCUS_DEC_D
 }
 
-hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
+hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const int* pos_dev, const void* q_new, const void* k_new,
                               const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out, float* lse,
                               int32_t* row_pairs, hipStream_t s)
 {
     if (L.dtype == 0)
-        return decode_step_t<float>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+        return decode_step_t<float>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
     if (L.dtype == 2)
-        return decode_step_t<f16_bits>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
-    return decode_step_t<uint16_t>(L, hm, pos, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+        return decode_step_t<f16_bits>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+    return decode_step_t<uint16_t>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
 }
 
 }  // namespace focus

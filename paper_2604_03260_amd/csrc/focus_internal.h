@@ -160,7 +160,7 @@ struct DecodeLayout {
 
 hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* kc, const float* cents, char* st,
                                  hipStream_t s);
-hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const void* q_new, const void* k_new,
+hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const int* pos_dev, const void* q_new, const void* k_new,
                               const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out, float* lse,
                               int32_t* row_pairs, hipStream_t s);
 hipError_t launch_route(const RouteLayout& R, const void* hidden, const float* wg, const float* cent, char* ws,

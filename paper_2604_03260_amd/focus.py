@@ -24,7 +24,7 @@ EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_work
            "focus_route_workspace_size", "focus_route", "focus_assign_tokens",
            "focus_attn_fwd_set", "focus_attn_merge", "focus_attn_fwd_two_call",
            "focus_decode_state_size", "focus_decode_prefill", "focus_decode_step",
-           "focus_decode_state_views",
+           "focus_decode_state_views", "focus_decode_step_at",
            "focus_soft_workspace_size", "focus_attn_soft_fwd",
            "focus_last_error", "focus_version")
 
@@ -95,6 +95,8 @@ def load_library():
     lib.focus_decode_prefill.restype = ctypes.c_int
     lib.focus_decode_step.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
     lib.focus_decode_step.restype = ctypes.c_int
+    lib.focus_decode_step_at.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.focus_decode_step_at.restype = ctypes.c_int
     lib.focus_decode_state_views.argtypes = [pp, vp] + [ctypes.POINTER(vp)] * 4
     lib.focus_decode_state_views.restype = ctypes.c_int
     rp = ctypes.POINTER(FocusRouteParams)
@@ -227,6 +229,16 @@ def focus_decode_step(p, pos, q_new, k_new, v_new, centroids, k_cache, v_cache, 
                                             _ptr(centroids), _ptr(k_cache), _ptr(v_cache), _ptr(state),
                                             state.numel() * state.element_size(), _ptr(out), _ptr(lse),
                                             _ptr(row_pairs), _stream()))
+
+
+def focus_decode_step_at(p, pos_dev, q_new, k_new, v_new, centroids, k_cache, v_cache, state, out, lse=None,
+                         row_pairs=None):
+    """The step with the position in device memory (an int32 tensor of one element): capturable once."""
+    assert pos_dev.dtype == torch.int32 and pos_dev.is_cuda
+    _check(load_library().focus_decode_step_at(ctypes.byref(p), _ptr(pos_dev), _ptr(q_new), _ptr(k_new), _ptr(v_new),
+                                               _ptr(centroids), _ptr(k_cache), _ptr(v_cache), _ptr(state),
+                                               state.numel() * state.element_size(), _ptr(out), _ptr(lse),
+                                               _ptr(row_pairs), _stream()))
 
 
 def focus_decode_state_views(p, state):

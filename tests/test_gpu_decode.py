@@ -135,3 +135,77 @@ def test_decode_agrees_with_prefill_kernel_long_context():
     assert torch.equal(res["row_pairs"], full["row_pairs"][:, :, n0:])
     assert (res["lse"] - full["lse"][:, :, n0:]).abs().max().item() <= 1e-2
     check_decode(wl, inp, res, n0, steps)
+
+
+@pytest.mark.parametrize("kw", [dict(Hq=8, Hkv=2, d=128, dtype="bf16", K=4, topk=2),
+                                dict(Hq=3, Hkv=1, d=96, dtype="f16", K=8, topk=2),
+                                dict(Hq=4, Hkv=4, d=64, dtype="f32", K=4, topk=1)])
+def test_decode_step_with_the_position_on_the_device_replays_from_one_graph(kw):
+    # A generation loop as a serving stack would run it: one HIP graph captured around focus_decode_step_at,
+    # replayed once per token; the new token's q, k, v are written into the captured buffers and the position
+    # advances on the device.  Every step is checked against the oracle, the state against the host-position path.
+    wl = workloads.Workload("dec_graph", 45, 2, kw["Hq"], kw["Hkv"], 1300, kw["d"], kw["dtype"], kw["K"], kw["topk"], 48)
+    n0, steps = 1200, 40
+    inp = workloads.make_inputs(wl, "cuda")
+    p = harness.params_of(wl)
+    state = focus.alloc_decode_state(p)
+    kc = torch.zeros_like(inp["k"]); vc = torch.zeros_like(inp["v"])
+    kc[:, :, :n0] = inp["k"][:, :, :n0]; vc[:, :, :n0] = inp["v"][:, :, :n0]
+    focus.focus_decode_prefill(p, n0, kc, inp["centroids"], state)
+    q_new = inp["q"][:, :, n0].contiguous(); k_new = inp["k"][:, :, n0].contiguous(); v_new = inp["v"][:, :, n0].contiguous()
+    out = torch.empty_like(q_new)
+    lse = torch.empty((wl.B, wl.Hq), dtype=torch.float32, device="cuda")
+    rp = torch.empty((wl.B, wl.Hq), dtype=torch.int32, device="cuda")
+    pos = torch.full((1,), n0, dtype=torch.int32, device="cuda")
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        focus.focus_decode_step_at(p, pos, q_new, k_new, v_new, inp["centroids"], kc, vc, state, out, lse, rp)
+        pos.add_(1)                                   # the position advances inside the graph
+    outs, lses, pairs = [], [], []
+    for i in range(n0, n0 + steps):
+        q_new.copy_(inp["q"][:, :, i]); k_new.copy_(inp["k"][:, :, i]); v_new.copy_(inp["v"][:, :, i])
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        outs.append(out.clone()); lses.append(lse.clone()); pairs.append(rp.clone())
+    assert int(pos.item()) == n0 + steps
+    res = dict(out=torch.stack(outs, 2), lse=torch.stack(lses, 2), row_pairs=torch.stack(pairs, 2), kc=kc, vc=vc)
+    check_decode(wl, inp, res, n0, steps)
+    # the same steps with the position as a host argument: identical state, outputs equal up to the
+    # grouping of the partial sums (the launch shapes differ)
+    ref = run_decode(wl, inp, n0, steps)
+    va = focus.focus_decode_state_views(p, state)
+    vb = focus.focus_decode_state_views(ref["params"], ref["state"])
+    assert torch.equal(va["mk"][:, :, :n0 + steps], vb["mk"][:, :, :n0 + steps])
+    assert torch.equal(va["counts"], vb["counts"])
+    cnt = va["counts"].cpu().numpy()
+    la, lb = va["lists"].cpu().numpy(), vb["lists"].cpu().numpy()
+    for b in range(cnt.shape[0]):
+        for h in range(cnt.shape[1]):
+            for g in range(cnt.shape[2]):
+                assert np.array_equal(la[b, h, g, :cnt[b, h, g]], lb[b, h, g, :cnt[b, h, g]])
+    assert torch.equal(res["row_pairs"], ref["row_pairs"])
+    tol = harness.TOL[wl.dtype]
+    assert (res["out"].float() - ref["out"].float()).abs().max().item() <= tol["out_max"]
+
+
+def test_decode_step_with_a_device_position_outside_the_caches_does_nothing():
+    wl = workloads.Workload("dec_oob", 46, 1, 4, 2, 256, 64, "bf16", 4, 2, 16)
+    inp = workloads.make_inputs(wl, "cuda")
+    p = harness.params_of(wl)
+    state = focus.alloc_decode_state(p)
+    kc = inp["k"].clone(); vc = inp["v"].clone()
+    focus.focus_decode_prefill(p, 200, kc, inp["centroids"], state)
+    torch.cuda.synchronize()
+    before = (kc.clone(), vc.clone(), state.clone())
+    out = torch.full((wl.B, wl.Hq, wl.d), 7.0, dtype=torch.bfloat16, device="cuda")
+    for bad in (-1, 256, 1 << 30):
+        pos = torch.full((1,), bad, dtype=torch.int32, device="cuda")
+        focus.focus_decode_step_at(p, pos, inp["q"][:, :, 0].contiguous(), inp["k"][:, :, 0].contiguous(),
+                                   inp["v"][:, :, 0].contiguous(), inp["centroids"], kc, vc, state, out)
+        torch.cuda.synchronize()
+        assert torch.equal(kc, before[0]) and torch.equal(vc, before[1]) and torch.equal(state, before[2])
+        assert bool((out == 7.0).all())
