@@ -19,7 +19,8 @@
  *     the calling thread.
  *   - q, k, v, out, centroids, workspace, lse, row_pairs are DEVICE pointers of
  *     the current HIP device; `p` and p->head_map are HOST pointers.
- *   - q, out: [B,Hq,n,d]; k, v: [B,Hkv,n,d]; contiguous, d innermost, 16-byte
+ *   - q, out: [B,Hq,n,d]; k, v: [B,Hkv,n,d]; d innermost and contiguous, the other
+ *     three indices strided (focus_params), contiguous by default; 16-byte
  *     aligned.  centroids: [Hkv,K,d] fp32 (used as given, never renormalised).
  *   - The caller owns all buffers.  The library allocates no device memory and
  *     keeps no state between calls.  The workspace is caller-allocated,
@@ -67,6 +68,15 @@ typedef struct {
     const int32_t *head_map;   /* HOST [Hq] query head -> KV head (keys, values,
                                   key membership and centroids); NULL selects
                                   h / (Hq / Hkv)                                 */
+    /* Strides of q, of k and v (both the same) and of out, in ELEMENTS, for the batch, head and
+     * position index; the d components of a row are contiguous.  All three 0 selects the contiguous
+     * [B,H,n,d]; a [B,n,H,d] tensor is {n*H*d, d, H*d}.  Every stride must be a multiple of 16 bytes.
+     * The prefill path (focus_assign, focus_assign_tokens, focus_attn_fwd, focus_attn_fwd_set,
+     * focus_attn_soft_fwd) takes strides; the two-call convenience and the incremental path take
+     * contiguous tensors only (FOCUS_EUNSUPPORTED otherwise). */
+    int64_t q_strides[3];
+    int64_t kv_strides[3];
+    int64_t o_strides[3];
 } focus_params;
 
 /* Bytes of workspace the two calls need for these params.  Pure host code. */

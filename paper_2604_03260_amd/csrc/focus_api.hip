@@ -24,6 +24,19 @@ focus_status fail(focus_status st, const char* fmt, ...)
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// true when q, k/v and out are the contiguous [B,H,n,d] (strides all zero, or spelled out)
+bool contiguous_tensors(const focus_params* p)
+{
+    const int64_t* src[3] = {p->q_strides, p->kv_strides, p->o_strides};
+    const int heads[3] = {p->Hq, p->Hkv, p->Hq};
+    for (int t = 0; t < 3; ++t) {
+        if (src[t][0] == 0 && src[t][1] == 0 && src[t][2] == 0) continue;
+        if (src[t][0] != (int64_t)heads[t] * p->n * p->d || src[t][1] != (int64_t)p->n * p->d || src[t][2] != p->d)
+            return false;
+    }
+    return true;
+}
+
 // Validates the params and derives the workspace layout and the head map.
 // soft: the layout of the soft-gated attention (one class in position order whatever K, topk and the window are).
 focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap* hm, bool soft = false)
@@ -93,6 +106,29 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
             }
             L->S = best;
             L->NC = best_nc;
+        }
+    }
+    // strides: all zero = contiguous [B,H,n,d]; else positive, rows 16-byte aligned, inside int64
+    {
+        const int64_t* src[3] = {p->q_strides, p->kv_strides, p->o_strides};
+        long long* dst[3] = {L->qs, L->ks, L->os};
+        const int heads[3] = {p->Hq, p->Hkv, p->Hq};
+        const char* names[3] = {"q_strides", "kv_strides", "o_strides"};
+        const long long align = 16 / L->elem;
+        for (int t = 0; t < 3; ++t) {
+            if (src[t][0] == 0 && src[t][1] == 0 && src[t][2] == 0) {
+                dst[t][0] = (long long)heads[t] * p->n * p->d;
+                dst[t][1] = (long long)p->n * p->d;
+                dst[t][2] = p->d;
+                continue;
+            }
+            for (int e = 0; e < 3; ++e) {
+                if (src[t][e] <= 0 || src[t][e] % align != 0 || src[t][e] > ((int64_t)1 << 40))
+                    return fail(FOCUS_EINVAL, "%s[%d] = %lld must be positive and a multiple of %lld elements (16 bytes)",
+                                names[t], e, (long long)src[t][e], align);
+                dst[t][e] = src[t][e];
+            }
+            if (dst[t][2] < p->d) return fail(FOCUS_EINVAL, "%s[2] is smaller than d: rows overlap", names[t]);
         }
     }
     L->nblk = (p->n + SB - 1) / SB;
@@ -216,6 +252,8 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
         return fail(FOCUS_EINVAL, "Hq (%d) is not a multiple of Hkv (%d) and no head_map given", p->Hq, p->Hkv);
     }
     if (p->causal != 1) return fail(FOCUS_EUNSUPPORTED, "the incremental path is causal (one new token at the end)");
+    if (!contiguous_tensors(p))
+        return fail(FOCUS_EUNSUPPORTED, "the incremental path takes contiguous caches and rows (strides must be 0)");
     if (p->d != 64 && p->d != 80 && p->d != 96 && p->d != 128 && p->d != 256)
         return fail(FOCUS_EUNSUPPORTED, "head dim %d is not built (64, 80, 96, 128 or 256)", p->d);
     if (p->Hq > MAX_HQ || p->Hkv > MAX_HQ) return fail(FOCUS_EUNSUPPORTED, "more than %d heads is not built", MAX_HQ);
@@ -350,6 +388,9 @@ focus_status focus_attn_fwd_two_call(const focus_params* p, const void* q, const
 {
     if (!p) return fail(FOCUS_EINVAL, "params is NULL");
     if (!part_out || !part_lse) return fail(FOCUS_EINVAL, "part_out and part_lse must not be NULL");
+    if (!contiguous_tensors(p))
+        return fail(FOCUS_EUNSUPPORTED, "focus_attn_fwd_two_call takes contiguous tensors (use focus_attn_fwd_set and "
+                                        "focus_attn_merge on contiguous partial outputs, or the fused focus_attn_fwd)");
     if (misaligned16(part_out)) return fail(FOCUS_EINVAL, "part_out must be 16-byte aligned");
     const size_t rows = (size_t)p->B * (size_t)p->Hq * (size_t)p->n;
     const size_t elem = (p->dtype == FOCUS_F32) ? 4 : 2;

@@ -89,7 +89,10 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     uint32_t* masks = (uint32_t*)(ws + (is_query ? L.off_mq : L.off_mk));
     uint8_t* clsarr = (uint8_t*)(ws + (is_query ? L.off_qcls : L.off_kcls));
     const size_t cls_stride = is_query ? (size_t)n : (size_t)L.nblk * SB;
-    const char* xbase = (const char*)x + (size_t)bh * n * row_bytes;
+    // rows are row_bytes long; where they start comes from the strides of q (or of k)
+    const long long* xs = is_query ? L.qs : L.ks;
+    const size_t row_pitch = (size_t)xs[2] * sizeof(T);
+    const char* xbase = (const char*)x + ((size_t)(bh / H) * xs[0] + (size_t)h * xs[1]) * sizeof(T);
 
     // Register staging of the next step: its global loads fly while the current step is computed.
     // Coalesced: consecutive threads fetch consecutive 16-byte chunks of a 128-byte row segment.
@@ -98,13 +101,13 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     do {                                                                                             \
         const int bi_ = (STEP) / phases, ph_ = (STEP) % phases;                                      \
         const int rows_ = min(SB, n - (blk0 + bi_) * SB);                                            \
-        const char* g_ = xbase + (size_t)(blk0 + bi_) * SB * row_bytes + ph_ * ROW_CHUNK_BYTES;      \
+        const char* g_ = xbase + (size_t)(blk0 + bi_) * SB * row_pitch + ph_ * ROW_CHUNK_BYTES;      \
         _Pragma("unroll") for (int i = 0; i < CPR; ++i) {                                            \
             const int cid_ = tid + i * SB;                                                           \
             const int r_ = cid_ / CPR, cc_ = cid_ % CPR;                                             \
             const u32x4 z_ = {0u, 0u, 0u, 0u};                                                       \
             const bool in_ = r_ < rows_ && ph_ * ROW_CHUNK_BYTES + cc_ * 16 < row_bytes;                 \
-            st[i] = in_ ? *(const u32x4*)(g_ + (size_t)r_ * row_bytes + cc_ * 16) : z_;              \
+            st[i] = in_ ? *(const u32x4*)(g_ + (size_t)r_ * row_pitch + cc_ * 16) : z_;              \
         }                                                                                            \
     } while (0)
 

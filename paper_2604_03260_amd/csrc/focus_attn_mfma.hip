@@ -86,12 +86,14 @@ __global__ __launch_bounds__(NTHR) void gather_k_kernel(Layout L, const uint16_t
     const int tile = blockIdx.x, bhk = blockIdx.y, tid = threadIdx.x;
     const int* kpos = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP + (size_t)tile * KT;
     uint4* dst = (uint4*)(ws + L.off_kc) + ((size_t)bhk * L.NKP + (size_t)tile * KT) * CPR;
-    const uint4* src = (const uint4*)k + (size_t)bhk * L.n * cin;
+    // source rows through the strides of k (multiples of 8 elements = one 16-byte chunk)
+    const uint4* src = (const uint4*)k + ((size_t)(bhk / L.Hkv) * L.ks[0] + (size_t)(bhk % L.Hkv) * L.ks[1]) / 8;
+    const size_t pitch = (size_t)L.ks[2] / 8;
     for (int id = tid; id < KT * CPR; id += NTHR) {
         const int row = id / CPR, ch = id % CPR;
         const int kp = kpos[row];
         uint4 val = make_uint4(0, 0, 0, 0);
-        if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * cin + ch];
+        if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * pitch + ch];
         dst[id] = val;
     }
 }
@@ -105,12 +107,13 @@ __global__ __launch_bounds__(NTHR) void gather_vt_kernel(Layout L, const uint16_
     const int cin = L.d / 8;
     const int tile = blockIdx.x, bhk = blockIdx.y, tid = threadIdx.x;
     const int* kpos = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP + (size_t)tile * KT;
-    const uint4* src = (const uint4*)v + (size_t)bhk * L.n * cin;
+    const uint4* src = (const uint4*)v + ((size_t)(bhk / L.Hkv) * L.ks[0] + (size_t)(bhk % L.Hkv) * L.ks[1]) / 8;
+    const size_t pitch = (size_t)L.ks[2] / 8;
     for (int id = tid; id < KT * CPR; id += NTHR) {
         const int row = id / CPR, ch = id % CPR;
         const int kp = kpos[row];
         uint4 val = make_uint4(0, 0, 0, 0);
-        if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * cin + ch];
+        if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * pitch + ch];
         uint32_t* d32 = (uint32_t*)(s_v + row * RS + ch * 8);   // RS even -> 4-byte aligned
         d32[0] = val.x; d32[1] = val.y; d32[2] = val.z; d32[3] = val.w;
     }
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         // Only a launch restricted to one of the two pair sets can leave a tile without keys
         // (the whole mask always holds the diagonal): its rows are empty, out = 0 and lse = -inf.
         if (rvalid) {
-            uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * d + hh * (d / 2);
+            uint16_t* orow = out + (size_t)b * L.os[0] + (size_t)h * L.os[1] + (size_t)qpos * L.os[2] + hh * (d / 2);
             for (int e = 0; e < d / 2; e += 4) *(uint2*)(orow + e) = make_uint2(0u, 0u);
             if (hh == 0) {
                 if (lse) lse[(size_t)bhq * L.n + qpos] = -INFINITY;
@@ -281,7 +284,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
 
     V8 qreg[KS];
     {
-        const V8* qrow = (const V8*)(q + ((size_t)bhq * L.n + (rvalid ? qpos : 0)) * d);
+        const V8* qrow = (const V8*)(q + (size_t)b * L.qs[0] + (size_t)h * L.qs[1] + (size_t)(rvalid ? qpos : 0) * L.qs[2]);
         V8 zero;
 #pragma unroll
         for (int e = 0; e < 8; ++e) zero[e] = (elem_t)0.f;
@@ -677,7 +680,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     if constexpr (PAIRS) npairs += __shfl_xor(npairs, 32, 64);
     if (!rvalid) return;
     const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;      // an empty row (restricted pair set): out = 0, lse = -inf
-    uint16_t* orow = out + ((size_t)bhq * L.n + qpos) * d;
+    uint16_t* orow = out + (size_t)b * L.os[0] + (size_t)h * L.os[1] + (size_t)qpos * L.os[2];
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
 #pragma unroll

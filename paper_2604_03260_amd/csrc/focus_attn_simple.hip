@@ -64,13 +64,16 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
     const uint32_t* mk_all = (const uint32_t*)(ws + L.off_mk) + (size_t)bhk * L.n;
     const int* kpos_all = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP;
     const int d = L.d;
-    const T* kbase = k + (size_t)bhk * L.n * d;
-    const T* vbase = v + (size_t)bhk * L.n * d;
+    const size_t koff = (size_t)b * L.ks[0] + (size_t)hm.kv[h] * L.ks[1];
+    const T* kbase = k + koff;
+    const T* vbase = v + koff;
+    const size_t kpitch = (size_t)L.ks[2];
 
     float qv[32], o[32];
 #pragma unroll
     for (int e = 0; e < 32; ++e) {
-        qv[e] = (rvalid && part * 32 + e < d) ? to_f32<T>(q[((size_t)bhq * L.n + qpos) * d + part * 32 + e]) : 0.f;
+        qv[e] = (rvalid && part * 32 + e < d)
+                    ? to_f32<T>(q[(size_t)b * L.qs[0] + (size_t)h * L.qs[1] + (size_t)qpos * L.qs[2] + part * 32 + e]) : 0.f;
         o[e] = 0.f;
     }
     float m = -INFINITY, l = 0.f;
@@ -91,8 +94,8 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
                 const int kk = e / D, t = e % D;
                 const int kp = kpos_all[r0 + kk];
                 const bool real = kp != KPOS_PAD && t < d;
-                s_k[e] = real ? to_f32<T>(kbase[(size_t)kp * d + t]) : 0.f;
-                s_v[e] = real ? to_f32<T>(vbase[(size_t)kp * d + t]) : 0.f;
+                s_k[e] = real ? to_f32<T>(kbase[(size_t)kp * kpitch + t]) : 0.f;
+                s_v[e] = real ? to_f32<T>(vbase[(size_t)kp * kpitch + t]) : 0.f;
             }
             __syncthreads();
             float s[SUB];
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
     }
     if (rvalid) {
     const float inv = (l > 0.f) ? 1.f / l : 0.f;     // empty row (launch restricted to one pair set): out = 0, lse = -inf
-    T* orow = out + ((size_t)bhq * L.n + qpos) * d + part * 32;
+    T* orow = out + (size_t)b * L.os[0] + (size_t)h * L.os[1] + (size_t)qpos * L.os[2] + part * 32;
 #pragma unroll
     for (int e = 0; e < 32; ++e)
         if (part * 32 + e < d) orow[e] = from_f32<T>(o[e] * inv);

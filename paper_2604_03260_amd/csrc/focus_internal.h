@@ -60,6 +60,8 @@ struct Layout {
     float scale;
     float softcap;
 
+    long long qs[3], ks[3], os[3];     // strides of q, of k and v, of out in elements (batch, head, position)
+
     size_t off_mq, off_mk;
     size_t off_qgc, off_kgc;           // group counts
     size_t off_qgl, off_kgl;           // group lists

@@ -45,6 +45,7 @@ class FocusParams(ctypes.Structure):
         ("window", ctypes.c_int32), ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("scale", ctypes.c_float), ("softcap", ctypes.c_float),
         ("head_map", ctypes.POINTER(ctypes.c_int32)),
+        ("q_strides", ctypes.c_int64 * 3), ("kv_strides", ctypes.c_int64 * 3), ("o_strides", ctypes.c_int64 * 3),
     ]
 
 
@@ -114,16 +115,24 @@ def load_library():
     return lib
 
 
+def strides_of(t):
+    """(batch, head, position) strides in elements of a torch tensor indexed [B,H,n,d] (any view whose last
+    dimension is contiguous, e.g. x.view(B, n, H, d).permute(0, 2, 1, 3))."""
+    assert t.dim() == 4 and t.stride(3) == 1
+    return tuple(int(x) for x in t.stride()[:3])
+
+
 def make_params(B, Hq, Hkv, n, d, K, topk, window, causal=True, dtype="bf16", scale=0.0, softcap=0.0,
-                head_map=None):
-    """Returns (FocusParams, keepalive) -- keepalive owns the host head_map array."""
+                head_map=None, q_strides=None, kv_strides=None, o_strides=None):
+    """Returns FocusParams (it keeps the host head_map array alive).  Strides: None = contiguous [B,H,n,d]."""
     keep = None
     hm = None
     if head_map is not None:
         keep = (ctypes.c_int32 * len(head_map))(*[int(x) for x in head_map])
         hm = ctypes.cast(keep, ctypes.POINTER(ctypes.c_int32))
+    arr = lambda st: (ctypes.c_int64 * 3)(*(st if st is not None else (0, 0, 0)))
     p = FocusParams(B, Hq, Hkv, n, d, K, topk, window, 1 if causal else 0,
-                    DTYPES[dtype], scale, softcap, hm)
+                    DTYPES[dtype], scale, softcap, hm, arr(q_strides), arr(kv_strides), arr(o_strides))
     p._keep = keep
     return p
 

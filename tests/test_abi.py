@@ -209,3 +209,29 @@ def test_decode_takes_the_causal_mask_only():
         focus.focus_decode_state_size(p)
     assert e.value.status == focus.FOCUS_EUNSUPPORTED
     assert focus.focus_decode_state_size(focus.make_params(1, 4, 2, 4096, 80, 4, 2, 64, dtype="f16")) > 0
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(q_strides=(4 * 256 * 64, 256 * 64, 64)), focus.FOCUS_OK),            # the contiguous strides spelled out
+    (dict(q_strides=(256 * 8 * 64, 64, 8 * 64), kv_strides=(256 * 8 * 64, 64, 8 * 64), o_strides=(256 * 4 * 64, 64, 4 * 64)), focus.FOCUS_OK),
+    (dict(q_strides=(4 * 256 * 64, 256 * 64, 60)), focus.FOCUS_EINVAL),        # not a multiple of 16 bytes
+    (dict(kv_strides=(2 * 256 * 64, 256 * 64, 32)), focus.FOCUS_EINVAL),       # rows overlap
+    (dict(o_strides=(4 * 256 * 64, -64, 64)), focus.FOCUS_EINVAL),
+    (dict(o_strides=(0, 64, 4 * 64)), focus.FOCUS_EINVAL),                     # partly given
+])
+def test_stride_validation(kw, want):
+    st, info = status_of(**kw)
+    assert st == want, info
+
+
+def test_strides_are_refused_where_they_are_not_built():
+    strided = dict(q_strides=(256 * 8 * 64, 64, 8 * 64), kv_strides=(256 * 8 * 64, 64, 8 * 64), o_strides=(256 * 4 * 64, 64, 4 * 64))
+    p = focus.make_params(1, 4, 2, 256, 64, 4, 2, 16, **strided)
+    with pytest.raises(focus.FocusError) as e:
+        focus.focus_decode_state_size(p)
+    assert e.value.status == focus.FOCUS_EUNSUPPORTED
+    lib = focus.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    st = lib.focus_attn_fwd_two_call(ctypes.byref(p), fake, fake, fake, fake, ctypes.c_size_t(1 << 40), fake, fake, fake, fake,
+                                     ctypes.c_void_p(0))
+    assert st == focus.FOCUS_EUNSUPPORTED
