@@ -13,6 +13,7 @@ workload on this machine's host cores.
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -154,6 +155,19 @@ def main():
         },
         "paper_context": "paper reports 2.0x (K=4, top-2) and 8.6x (K=8, 1M tokens) over dense FlashAttention on H100-80GB",
     }
+
+    # the matrix-core rate this machine sustains in a register-only MFMA loop (the stand-alone probe the build
+    # leaves beside the library), as a second denominator next to the nominal peak
+    probe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_03260_amd", "_build", "issue_rates")
+    if half and os.path.exists(probe):
+        try:
+            got = subprocess.run([probe, "--mfma-peak"], capture_output=True, text=True, timeout=60)
+            measured_peak = float(got.stdout.strip().split()[-1])
+            result["measured_mfma_peak_tflops"] = measured_peak
+            result["pct_of_measured_mfma_peak_attn"] = 100.0 * tflops_attn / measured_peak
+        except Exception as exc:              # the probe is optional: its absence or failure changes no figure above
+            result["measured_mfma_peak_tflops"] = None
+            print("bench.py: MFMA peak probe failed: %r" % (exc,), file=sys.stderr)
 
     if not args.no_dense:
         pd, wsd = make(wl.n)

@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
+#include <string>
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
@@ -128,9 +129,27 @@ template <int CH> void run_f64(int w)
            cycles_per_group(ms, w, iters, 16));
 }
 
-int main()
+// `issue_rates --mfma-peak`: one line, the bf16 matrix-core rate of this machine in TFLOP/s from the register-only
+// loop of 32x32x16 MFMAs (8 independent accumulators, 2 wavefronts per SIMD), best of 5 launches.
+static int mfma_peak()
+{
+    const int w = 2, iters = 20000;
+    double best = 0.0;
+    for (int rep = 0; rep < 5; ++rep) {
+        const float ms = timed([](int g, int it) { hipLaunchKernelGGL((mfma_valu<0, 1, true>), dim3(g), dim3(256), 0, 0, g_f, it); },
+                               256 * w, iters);
+        // work-groups x wavefronts x iterations x 8 MFMAs x 2*32*32*16 FLOP
+        const double flop = 256.0 * w * 4.0 * iters * 8.0 * 32768.0;
+        best = flop / (ms * 1e-3) / 1e12 > best ? flop / (ms * 1e-3) / 1e12 : best;
+    }
+    printf("%.1f\n", best);
+    return 0;
+}
+
+int main(int argc, char** argv)
 {
     CHECK(hipMalloc(&g_f, 1024));
+    if (argc > 1 && std::string(argv[1]) == "--mfma-peak") return mfma_peak();
     CHECK(hipMalloc(&g_d, 1024));
     CHECK(hipMalloc(&g_w, 64 * 16 * 8));
     CHECK(hipMemset(g_w, 0, 64 * 16 * 8));
