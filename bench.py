@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--no-router", action="store_true")
     ap.add_argument("--no-two-call", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-sdpa", action="store_true", help="skip torch's own causal attention (outside sanity number)")
     ap.add_argument("--no-soft", action="store_true", help="skip the soft-gated training attention leg")
     ap.add_argument("--no-wider", action="store_true", help="skip the half-precision / other-head-dim variants of cfg3")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -178,6 +179,28 @@ def main():
         result["speedup_vs_dense_attn"] = ms_attn_d / ms_attn
         result["speedup_vs_dense_step"] = ms_step_d / ms_step
         del wsd
+        # an outside sanity number for the dense comparator: torch's own causal attention on the same tensors
+        # (harness only; never part of the library or of `value`)
+        if half and not args.no_sdpa:
+            try:
+                import torch.nn.functional as F
+                with torch.no_grad():
+                    for _ in range(2):
+                        o_sd = F.scaled_dot_product_attention(q, k, v, is_causal=True, enable_gqa=(wl.Hq != wl.Hkv))
+                    torch.cuda.synchronize()
+                    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                    nsd = max(2, steps // 4)
+                    ev[0].record()
+                    for _ in range(nsd):
+                        o_sd = F.scaled_dot_product_attention(q, k, v, is_causal=True, enable_gqa=(wl.Hq != wl.Hkv))
+                    ev[1].record()
+                    torch.cuda.synchronize()
+                ms_sd = ev[0].elapsed_time(ev[1]) / nsd
+                result["torch_sdpa_dense"] = {"ms": ms_sd, "tflops": 4.0 * wl.d * causal_pairs / (ms_sd * 1e-3) / 1e12,
+                                              "what": "torch.nn.functional.scaled_dot_product_attention, causal, same q/k/v"}
+                del o_sd
+            except Exception as exc:
+                print("bench.py: torch SDPA sanity run skipped: %r" % (exc,), file=sys.stderr)
 
     # context: other shapes through the same step (assign + attention), reported beside the headline workload:
     # the GPT-2 124M shape (short sequences), and the headline shape in half precision and at other head dims
