@@ -217,6 +217,19 @@ focus_status focus_decode_step(const focus_params *p, int32_t pos, const void *q
                                void *k_cache, void *v_cache, void *state, size_t state_bytes,
                                void *out, float *lse, int32_t *row_pairs, void *stream);
 
+/* The paper's per-layer routing in the incremental path: memberships are given per token (focus_route's
+ * masks; at inference without the Sinkhorn rounds, which need the whole sequence) instead of scored per head.
+ * focus_decode_prefill_tokens builds the state from token_masks [B, n_ctx] uint32 DEVICE (every KV head of a
+ * token takes the token's mask; k_cache is not read).  focus_decode_step_tokens takes the new token's mask,
+ * token_mask [B] uint32 DEVICE, for all its query heads and as its key.  A mask that is not a topk-subset of
+ * the K groups is replaced by the first topk groups.  Everything else as in focus_decode_step. */
+focus_status focus_decode_prefill_tokens(const focus_params *p, int32_t n_ctx, const uint32_t *token_masks,
+                                         void *state, size_t state_bytes, void *stream);
+focus_status focus_decode_step_tokens(const focus_params *p, int32_t pos, const uint32_t *token_mask,
+                                      const void *q_new, const void *k_new, const void *v_new,
+                                      void *k_cache, void *v_cache, void *state, size_t state_bytes,
+                                      void *out, float *lse, int32_t *row_pairs, void *stream);
+
 /* The same step with the position read from DEVICE memory by the kernels when they run: a HIP graph
  * captured once around this call serves every step of a generation loop (the caller writes the new
  * token's q, k, v into the captured buffers and advances *pos_dev on the device between replays).

@@ -559,56 +559,74 @@ focus_status focus_decode_state_size(const focus_params* p, size_t* bytes)
     return FOCUS_OK;
 }
 
-focus_status focus_decode_prefill(const focus_params* p, int32_t n_ctx, const void* k_cache, const float* centroids,
-                                  void* state, size_t state_bytes, void* stream)
+namespace {
+
+focus_status decode_prefill_common(const focus_params* p, int32_t n_ctx, const void* k_cache, const float* centroids,
+                                   const uint32_t* token_masks, void* state, size_t state_bytes, void* stream,
+                                   const char* who)
 {
     focus::DecodeLayout L;
     focus::HeadMap hm;
     focus_status st = make_decode_layout(p, &L, &hm);
     if (st != FOCUS_OK) return st;
     if (n_ctx < 0 || n_ctx > p->n) return fail(FOCUS_EINVAL, "n_ctx must be in [0, n] (got %d, n=%d)", n_ctx, p->n);
-    if (!k_cache || !centroids) return fail(FOCUS_EINVAL, "k_cache and centroids must not be NULL");
+    if (!token_masks && (!k_cache || !centroids)) return fail(FOCUS_EINVAL, "k_cache and centroids must not be NULL");
     if (!state) return fail(FOCUS_EINVAL, "state is NULL");
     if (((uintptr_t)state & 255) != 0) return fail(FOCUS_EWORKSPACE, "state is not 256-byte aligned");
     if (state_bytes < L.total) return fail(FOCUS_EWORKSPACE, "state has %zu bytes, %zu needed", state_bytes, L.total);
-    hipError_t e = focus::launch_decode_prefill(L, n_ctx, k_cache, centroids, (char*)state, (hipStream_t)stream);
-    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_decode_prefill: %s", hipGetErrorString(e));
+    hipError_t e = focus::launch_decode_prefill(L, n_ctx, k_cache, centroids, token_masks, (char*)state, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "%s: %s", who, hipGetErrorString(e));
     return FOCUS_OK;
 }
 
-namespace {
-
 focus_status decode_step_common(const focus_params* p, int32_t pos, const int32_t* pos_dev, const void* q_new,
-                                const void* k_new, const void* v_new, const float* centroids, void* k_cache,
-                                void* v_cache, void* state, size_t state_bytes, void* out, float* lse,
-                                int32_t* row_pairs, void* stream, const char* who)
+                                const void* k_new, const void* v_new, const float* centroids,
+                                const uint32_t* token_mask, void* k_cache, void* v_cache, void* state,
+                                size_t state_bytes, void* out, float* lse, int32_t* row_pairs, void* stream,
+                                const char* who)
 {
     focus::DecodeLayout L;
     focus::HeadMap hm;
     focus_status st = make_decode_layout(p, &L, &hm);
     if (st != FOCUS_OK) return st;
     if (!pos_dev && (pos < 0 || pos >= p->n)) return fail(FOCUS_EINVAL, "pos must be in [0, n) (got %d, n=%d)", pos, p->n);
-    if (!q_new || !k_new || !v_new || !centroids || !k_cache || !v_cache || !out)
-        return fail(FOCUS_EINVAL, "q_new, k_new, v_new, centroids, k_cache, v_cache and out must not be NULL");
+    if (!q_new || !k_new || !v_new || (!centroids && !token_mask) || !k_cache || !v_cache || !out)
+        return fail(FOCUS_EINVAL, "q_new, k_new, v_new, centroids (or the token mask), k_cache, v_cache and out must not be NULL");
     if (misaligned16(q_new) || misaligned16(k_cache) || misaligned16(v_cache))
         return fail(FOCUS_EINVAL, "q_new, k_cache and v_cache must be 16-byte aligned");
     if (!state) return fail(FOCUS_EINVAL, "state is NULL");
     if (((uintptr_t)state & 255) != 0) return fail(FOCUS_EWORKSPACE, "state is not 256-byte aligned");
     if (state_bytes < L.total) return fail(FOCUS_EWORKSPACE, "state has %zu bytes, %zu needed", state_bytes, L.total);
-    hipError_t e = focus::launch_decode_step(L, hm, pos, pos_dev, q_new, k_new, v_new, centroids, k_cache, v_cache,
-                                             (char*)state, out, lse, row_pairs, (hipStream_t)stream);
+    hipError_t e = focus::launch_decode_step(L, hm, pos, pos_dev, q_new, k_new, v_new, centroids, token_mask, k_cache,
+                                             v_cache, (char*)state, out, lse, row_pairs, (hipStream_t)stream);
     if (e != hipSuccess) return fail(FOCUS_EHIP, "%s: %s", who, hipGetErrorString(e));
     return FOCUS_OK;
 }
 
 }  // namespace
 
+focus_status focus_decode_prefill(const focus_params* p, int32_t n_ctx, const void* k_cache, const float* centroids,
+                                  void* state, size_t state_bytes, void* stream)
+{
+    return decode_prefill_common(p, n_ctx, k_cache, centroids, nullptr, state, state_bytes, stream, "focus_decode_prefill");
+}
+
+focus_status focus_decode_prefill_tokens(const focus_params* p, int32_t n_ctx, const uint32_t* token_masks, void* state,
+                                         size_t state_bytes, void* stream)
+{
+    if (!token_masks && n_ctx > 0) return fail(FOCUS_EINVAL, "token_masks is NULL");
+    static const uint32_t none = 0;                  // n_ctx = 0: nothing is read, any non-NULL pointer selects the path
+    return decode_prefill_common(p, n_ctx, nullptr, nullptr, token_masks ? token_masks : &none, state, state_bytes, stream,
+                                 "focus_decode_prefill_tokens");
+}
+
 focus_status focus_decode_step(const focus_params* p, int32_t pos, const void* q_new, const void* k_new,
                                const void* v_new, const float* centroids, void* k_cache, void* v_cache, void* state,
                                size_t state_bytes, void* out, float* lse, int32_t* row_pairs, void* stream)
 {
-    return decode_step_common(p, pos, nullptr, q_new, k_new, v_new, centroids, k_cache, v_cache, state, state_bytes,
-                              out, lse, row_pairs, stream, "focus_decode_step");
+    if (!centroids) return fail(FOCUS_EINVAL, "centroids is NULL");
+    return decode_step_common(p, pos, nullptr, q_new, k_new, v_new, centroids, nullptr, k_cache, v_cache, state,
+                              state_bytes, out, lse, row_pairs, stream, "focus_decode_step");
 }
 
 focus_status focus_decode_step_at(const focus_params* p, const int32_t* pos_dev, const void* q_new, const void* k_new,
@@ -617,8 +635,18 @@ focus_status focus_decode_step_at(const focus_params* p, const int32_t* pos_dev,
                                   void* stream)
 {
     if (!pos_dev) return fail(FOCUS_EINVAL, "pos_dev is NULL");
-    return decode_step_common(p, 0, pos_dev, q_new, k_new, v_new, centroids, k_cache, v_cache, state, state_bytes,
-                              out, lse, row_pairs, stream, "focus_decode_step_at");
+    if (!centroids) return fail(FOCUS_EINVAL, "centroids is NULL");
+    return decode_step_common(p, 0, pos_dev, q_new, k_new, v_new, centroids, nullptr, k_cache, v_cache, state,
+                              state_bytes, out, lse, row_pairs, stream, "focus_decode_step_at");
+}
+
+focus_status focus_decode_step_tokens(const focus_params* p, int32_t pos, const uint32_t* token_mask, const void* q_new,
+                                      const void* k_new, const void* v_new, void* k_cache, void* v_cache, void* state,
+                                      size_t state_bytes, void* out, float* lse, int32_t* row_pairs, void* stream)
+{
+    if (!token_mask) return fail(FOCUS_EINVAL, "token_mask is NULL");
+    return decode_step_common(p, pos, nullptr, q_new, k_new, v_new, nullptr, token_mask, k_cache, v_cache, state,
+                              state_bytes, out, lse, row_pairs, stream, "focus_decode_step_tokens");
 }
 
 focus_status focus_decode_state_views(const focus_params* p, void* state, const uint32_t** mk, const int32_t** lists,

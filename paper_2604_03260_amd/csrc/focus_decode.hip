@@ -79,6 +79,26 @@ __device__ inline uint32_t wave_topk_mask(double s, int lane, int K, int topk)
     return (uint32_t)member;
 }
 
+// A membership given from outside (the per-layer router) must be a topk-subset of the K groups: anything else
+// would break the "every key sits in exactly topk lists" bound of the step; it is replaced by the first topk groups.
+__device__ inline uint32_t decode_valid_mask(uint32_t m, int K, int topk)
+{
+    const uint32_t allowed = (K == 32) ? 0xffffffffu : ((1u << K) - 1u);
+    if ((m & ~allowed) != 0u || __popc(m) != topk) m = (topk == 32) ? 0xffffffffu : ((1u << topk) - 1u);
+    return m;
+}
+
+// membership of the cached keys from per-token masks [B, n_ctx]: every KV head of a token takes the token's mask
+__global__ __launch_bounds__(256) void decode_prefill_masks_kernel(DecodeLayout L, int n_ctx,
+                                                                   const uint32_t* __restrict__ token_masks,
+                                                                   char* __restrict__ st)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int bhk = blockIdx.y, b = bhk / L.Hkv;
+    if (j >= n_ctx) return;
+    ((uint32_t*)(st + L.off_mk))[(size_t)bhk * L.n + j] = decode_valid_mask(token_masks[(size_t)b * n_ctx + j], L.K, L.topk);
+}
+
 __global__ void decode_zero_kernel(int* __restrict__ p, int count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -170,7 +190,8 @@ template <typename T>
 __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMap hm, int pos_arg, const int* __restrict__ pos_dev,
                                                           const T* __restrict__ q_new,
                                                           const T* __restrict__ k_new, const T* __restrict__ v_new,
-                                                          const float* __restrict__ cents, T* __restrict__ kc,
+                                                          const float* __restrict__ cents,
+                                                          const uint32_t* __restrict__ token_mask, T* __restrict__ kc,
                                                           T* __restrict__ vc, char* __restrict__ st)
 {
     __shared__ float s_x[256];
@@ -186,16 +207,22 @@ __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMa
     const int hk = is_q ? hm.kv[h] : h;
     const int d = L.d;
     const T* x = is_q ? q_new + ((size_t)b * L.Hq + h) * d : k_new + ((size_t)b * L.Hkv + h) * d;
-    for (int t = lane; t < d; t += 64) s_x[t] = dec_to_f32<T>(x[t]);
-    const float* c = cents + (size_t)hk * L.K * d;
-    for (int e = lane; e < L.K * d; e += 64) s_c[(e / d) * (d + 1) + e % d] = c[e];
-    __syncthreads();
-    double s = 0.0;
-    if (lane < L.K) {
-        const float* cr = s_c + lane * (d + 1);
-        for (int t = 0; t < d; ++t) s = fma((double)s_x[t], (double)cr[t], s);
+    uint32_t mask;
+    if (token_mask) {
+        // the new token's membership comes from the per-layer router: the same for every head, as query and as key
+        mask = decode_valid_mask(token_mask[b], L.K, L.topk);
+    } else {
+        for (int t = lane; t < d; t += 64) s_x[t] = dec_to_f32<T>(x[t]);
+        const float* c = cents + (size_t)hk * L.K * d;
+        for (int e = lane; e < L.K * d; e += 64) s_c[(e / d) * (d + 1) + e % d] = c[e];
+        __syncthreads();
+        double s = 0.0;
+        if (lane < L.K) {
+            const float* cr = s_c + lane * (d + 1);
+            for (int t = 0; t < d; ++t) s = fma((double)s_x[t], (double)cr[t], s);
+        }
+        mask = wave_topk_mask(s, lane, L.K, L.topk);
     }
-    const uint32_t mask = wave_topk_mask(s, lane, L.K, L.topk);
     if (is_q) {
         if (lane == 0) ((uint32_t*)(st + L.off_mq))[(size_t)b * L.Hq + h] = mask;
         return;
@@ -761,14 +788,19 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int p
 
 }  // namespace
 
-hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* kc, const float* cents, char* st,
-                                 hipStream_t s)
+hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* kc, const float* cents,
+                                 const uint32_t* token_masks, char* st, hipStream_t s)
 {
     // counts start at zero even when nothing is cached yet (a fill kernel, not a memset: callers may capture this)
     const int ncount = (int)((L.off_wp - L.off_counts) / 4) + L.B * L.Hkv * L.K;      // counts, padding, window pointers
     hipLaunchKernelGGL(decode_zero_kernel, dim3((ncount + 255) / 256), dim3(256), 0, s, (int*)(st + L.off_counts), ncount);
     if (n_ctx == 0) return hipGetLastError();
     dim3 g1((n_ctx + 255) / 256, L.B * L.Hkv);
+    if (token_masks) {
+        hipLaunchKernelGGL(decode_prefill_masks_kernel, g1, dim3(256), 0, s, L, n_ctx, token_masks, st);
+        hipLaunchKernelGGL(decode_prefill_lists_kernel, dim3(L.K, L.B * L.Hkv), dim3(256), 0, s, L, n_ctx, st);
+        return hipGetLastError();
+    }
 #define FOCUS_DEC_SCORE(T_, KM_) hipLaunchKernelGGL((decode_prefill_score_kernel<T_, KM_>), g1, dim3(256), 0, s, L, n_ctx, (const T_*)kc, cents, st)
     if (L.dtype == 0) {
         if (L.K <= 4) FOCUS_DEC_SCORE(float, 4); else if (L.K <= 8) FOCUS_DEC_SCORE(float, 8);
@@ -822,11 +854,11 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
 
 template <typename T>
 static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int pos, const int* pos_dev, const void* q_new, const void* k_new,
-                                const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out,
+                                const void* v_new, const float* cents, const uint32_t* token_mask, void* kc, void* vc, char* st, void* out,
                                 float* lse, int32_t* row_pairs, hipStream_t s)
 {
     hipLaunchKernelGGL(decode_route_kernel<T>, dim3(L.Hq + L.Hkv, L.B), dim3(64), 0, s, L, hm, pos, pos_dev, (const T*)q_new,
-                       (const T*)k_new, (const T*)v_new, cents, (T*)kc, (T*)vc, st);
+                       (const T*)k_new, (const T*)v_new, cents, token_mask, (T*)kc, (T*)vc, st);
 #define FOCUS_DEC_D(D_) decode_step_d<T, D_>(L, hm, pos, pos_dev, (const T*)q_new, (const T*)kc, (const T*)vc, st, (T*)out, lse, row_pairs, s)
     switch (L.d) {
         case 64: return FOCUS_DEC_D(64);
@@ -840,14 +872,14 @@ static hipError_t decode_step_t(const DecodeLayout& L, const HeadMap& hm, int po
 }
 
 hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const int* pos_dev, const void* q_new, const void* k_new,
-                              const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out, float* lse,
+                              const void* v_new, const float* cents, const uint32_t* token_mask, void* kc, void* vc, char* st, void* out, float* lse,
                               int32_t* row_pairs, hipStream_t s)
 {
     if (L.dtype == 0)
-        return decode_step_t<float>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+        return decode_step_t<float>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, token_mask, kc, vc, st, out, lse, row_pairs, s);
     if (L.dtype == 2)
-        return decode_step_t<f16_bits>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
-    return decode_step_t<uint16_t>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, kc, vc, st, out, lse, row_pairs, s);
+        return decode_step_t<f16_bits>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, token_mask, kc, vc, st, out, lse, row_pairs, s);
+    return decode_step_t<uint16_t>(L, hm, pos, pos_dev, q_new, k_new, v_new, cents, token_mask, kc, vc, st, out, lse, row_pairs, s);
 }
 
 }  // namespace focus

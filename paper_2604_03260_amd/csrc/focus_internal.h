@@ -160,11 +160,12 @@ struct DecodeLayout {
     size_t total;
 };
 
-hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* kc, const float* cents, char* st,
-                                 hipStream_t s);
+// token_masks / token_mask non-NULL: memberships given per token (centroids unused) instead of scored per head
+hipError_t launch_decode_prefill(const DecodeLayout& L, int n_ctx, const void* kc, const float* cents,
+                                 const uint32_t* token_masks, char* st, hipStream_t s);
 hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos, const int* pos_dev, const void* q_new, const void* k_new,
-                              const void* v_new, const float* cents, void* kc, void* vc, char* st, void* out, float* lse,
-                              int32_t* row_pairs, hipStream_t s);
+                              const void* v_new, const float* cents, const uint32_t* token_mask, void* kc, void* vc, char* st,
+                              void* out, float* lse, int32_t* row_pairs, hipStream_t s);
 hipError_t launch_route(const RouteLayout& R, const void* hidden, const float* wg, const float* cent, char* ws,
                         uint32_t* masks, double* soft, hipStream_t st);
 hipError_t launch_assign_tokens(const Layout& L, const uint32_t* token_masks, const void* k, char* ws,

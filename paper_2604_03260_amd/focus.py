@@ -25,6 +25,7 @@ EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_work
            "focus_attn_fwd_set", "focus_attn_merge", "focus_attn_fwd_two_call",
            "focus_decode_state_size", "focus_decode_prefill", "focus_decode_step",
            "focus_decode_state_views", "focus_decode_step_at",
+           "focus_decode_prefill_tokens", "focus_decode_step_tokens",
            "focus_soft_workspace_size", "focus_attn_soft_fwd",
            "focus_last_error", "focus_version")
 
@@ -96,6 +97,10 @@ def load_library():
     lib.focus_decode_prefill.restype = ctypes.c_int
     lib.focus_decode_step.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
     lib.focus_decode_step.restype = ctypes.c_int
+    lib.focus_decode_prefill_tokens.argtypes = [pp, ctypes.c_int32, vp, vp, sz, vp]
+    lib.focus_decode_prefill_tokens.restype = ctypes.c_int
+    lib.focus_decode_step_tokens.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.focus_decode_step_tokens.restype = ctypes.c_int
     lib.focus_decode_step_at.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp]
     lib.focus_decode_step_at.restype = ctypes.c_int
     lib.focus_decode_state_views.argtypes = [pp, vp] + [ctypes.POINTER(vp)] * 4
@@ -238,6 +243,19 @@ def focus_decode_step(p, pos, q_new, k_new, v_new, centroids, k_cache, v_cache, 
                                             _ptr(centroids), _ptr(k_cache), _ptr(v_cache), _ptr(state),
                                             state.numel() * state.element_size(), _ptr(out), _ptr(lse),
                                             _ptr(row_pairs), _stream()))
+
+
+def focus_decode_prefill_tokens(p, n_ctx, token_masks, state):
+    _check(load_library().focus_decode_prefill_tokens(ctypes.byref(p), n_ctx, _ptr(token_masks), _ptr(state),
+                                                      state.numel() * state.element_size(), _stream()))
+
+
+def focus_decode_step_tokens(p, pos, token_mask, q_new, k_new, v_new, k_cache, v_cache, state, out, lse=None,
+                             row_pairs=None):
+    _check(load_library().focus_decode_step_tokens(ctypes.byref(p), pos, _ptr(token_mask), _ptr(q_new), _ptr(k_new),
+                                                   _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(state),
+                                                   state.numel() * state.element_size(), _ptr(out), _ptr(lse),
+                                                   _ptr(row_pairs), _stream()))
 
 
 def focus_decode_step_at(p, pos_dev, q_new, k_new, v_new, centroids, k_cache, v_cache, state, out, lse=None,

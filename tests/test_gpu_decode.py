@@ -209,3 +209,71 @@ def test_decode_step_with_a_device_position_outside_the_caches_does_nothing():
         torch.cuda.synchronize()
         assert torch.equal(kc, before[0]) and torch.equal(vc, before[1]) and torch.equal(state, before[2])
         assert bool((out == 7.0).all())
+
+
+@pytest.mark.parametrize("kw", [dict(Hq=8, Hkv=2, d=128, dtype="bf16", K=4, topk=2, n0=1188),
+                                dict(Hq=3, Hkv=1, d=64, dtype="f32", K=8, topk=1, n0=0),
+                                dict(Hq=4, Hkv=4, d=96, dtype="f16", K=32, topk=3, n0=1100)])
+def test_decode_with_memberships_from_the_router(kw):
+    # The paper's flow at inference: one routing per token from the layer's hidden state (no Sinkhorn rounds at
+    # decode time), the token's membership for all its heads as query and as key.  The state is built from the
+    # routed masks of the cached prefix, every step gets the new token's mask from focus_route on one token.
+    n, n0 = 1200, kw["n0"]
+    steps = 12 if n0 else 30
+    wl = workloads.Workload("dec_routed", 47, 2, kw["Hq"], kw["Hkv"], n if n0 else steps, kw["d"], kw["dtype"], kw["K"], kw["topk"], 40)
+    n = wl.n
+    inp = workloads.make_inputs(wl, "cuda")
+    rin = workloads.make_router_inputs(wl, "cuda", d_model=128)
+    m_ref = fo.route(workloads.to_host_bits(rin["hidden"]), rin["w_g"].cpu().numpy(), rin["router_centroids"].cpu().numpy(),
+                     wl.topk, tau=0.1, iters=0, dtype=wl.dtype)
+    # the prefix routed in one call, the new tokens one call each (n = 1 per sequence)
+    rp_all = focus.make_route_params(wl.B, n, 128, workloads.ROUTER_DG, wl.K, wl.topk, dtype=wl.dtype, sinkhorn_iters=0, tau=0.1)
+    masks_all = torch.empty((wl.B, n), dtype=torch.int32, device="cuda")
+    focus.focus_route(rp_all, rin["hidden"], rin["w_g"], rin["router_centroids"], focus.alloc_route_workspace(rp_all), masks_all)
+    assert np.array_equal(masks_all.cpu().numpy().view(np.uint32), m_ref)
+    rp_one = focus.make_route_params(wl.B, 1, 128, workloads.ROUTER_DG, wl.K, wl.topk, dtype=wl.dtype, sinkhorn_iters=0, tau=0.1)
+    rws_one = focus.alloc_route_workspace(rp_one)
+    p = harness.params_of(wl)
+    state = focus.alloc_decode_state(p)
+    kc = torch.zeros_like(inp["k"]); vc = torch.zeros_like(inp["v"])
+    kc[:, :, :n0] = inp["k"][:, :, :n0]; vc[:, :, :n0] = inp["v"][:, :, :n0]
+    focus.focus_decode_prefill_tokens(p, n0, masks_all[:, :n0].contiguous() if n0 else None, state)
+    outs, lses, pairs = [], [], []
+    for i in range(n0, n0 + steps):
+        tmask = torch.empty((wl.B, 1), dtype=torch.int32, device="cuda")
+        focus.focus_route(rp_one, rin["hidden"][:, i:i + 1].contiguous(), rin["w_g"], rin["router_centroids"], rws_one, tmask)
+        out = torch.full((wl.B, wl.Hq, wl.d), float("nan"), dtype=inp["q"].dtype, device="cuda")
+        lse = torch.empty((wl.B, wl.Hq), dtype=torch.float32, device="cuda")
+        rp = torch.empty((wl.B, wl.Hq), dtype=torch.int32, device="cuda")
+        focus.focus_decode_step_tokens(p, i, tmask, inp["q"][:, :, i].contiguous(), inp["k"][:, :, i].contiguous(),
+                                       inp["v"][:, :, i].contiguous(), kc, vc, state, out, lse, rp)
+        outs.append(out); lses.append(lse); pairs.append(rp)
+    torch.cuda.synchronize()
+    # oracle: the whole sequence with the routed membership broadcast to every head
+    pb = harness.problem_of(wl)
+    mq, mk = fo.broadcast_masks(pb, m_ref)
+    qh, kh, vh = (workloads.to_host_bits(inp[x]) for x in ("q", "k", "v"))
+    rows = np.array([(b, h, i) for b in range(wl.B) for h in range(wl.Hq) for i in range(n0, n0 + steps)], dtype=np.int32)
+    o_ref, l_ref, p_ref = fo.attn_rows(pb, qh, kh, vh, mq, mk, rows=rows)
+    o = torch.stack(outs, 2).float().cpu().numpy().astype(np.float64).reshape(-1, wl.d)
+    l = torch.stack(lses, 2).cpu().numpy().astype(np.float64).reshape(-1)
+    tol = harness.TOL[wl.dtype]
+    err = np.abs(o - o_ref)
+    assert np.isfinite(o).all() and err.max() <= tol["out_max"] and err.mean() <= tol["out_mean"], (err.max(), err.mean())
+    assert np.abs(l - l_ref).max() <= tol["lse"]
+    assert np.array_equal(torch.stack(pairs, 2).cpu().numpy().astype(np.int64).reshape(-1), p_ref)
+    views = focus.focus_decode_state_views(p, state)
+    n1 = n0 + steps
+    assert np.array_equal(views["mk"][:, :, :n1].cpu().numpy().view(np.uint32), mk[:, :, :n1])
+
+
+def test_decode_token_masks_that_are_no_topk_subset_are_replaced():
+    wl = workloads.Workload("dec_badmask", 48, 1, 2, 2, 64, 64, "bf16", 4, 2, 8)
+    inp = workloads.make_inputs(wl, "cuda")
+    p = harness.params_of(wl)
+    state = focus.alloc_decode_state(p)
+    bad = torch.tensor([[0b1111, 0b0001, 0b10000, 0b0110]], dtype=torch.int32, device="cuda")    # only the last is valid
+    focus.focus_decode_prefill_tokens(p, 4, bad, state)
+    torch.cuda.synchronize()
+    mk = focus.focus_decode_state_views(p, state)["mk"][:, :, :4].cpu().numpy()
+    assert (mk == np.array([0b0011, 0b0011, 0b0011, 0b0110])).all()
