@@ -331,9 +331,6 @@ focus_status attn_launch(const focus_params* p, int pair_set, const void* q, con
     if (pair_set != 0 && p->window >= p->n && 2 * p->topk <= p->K)
         return fail(FOCUS_EUNSUPPORTED, "the two-set decomposition is not built for window >= n "
                                         "(every causal pair is local: one launch over the whole mask is the answer)");
-    if (pair_set != 0 && L.coarse)
-        return fail(FOCUS_EUNSUPPORTED, "the two-set decomposition is not built for C(K=%d, topk=%d) > %d classes",
-                    p->K, p->topk, focus::MAX_CLASSES);
     if (!q || !k || !v || !out) return fail(FOCUS_EINVAL, "q, k, v and out must not be NULL");
     if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(out))
         return fail(FOCUS_EINVAL, "q, k, v and out must be 16-byte aligned");

@@ -526,9 +526,13 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
             _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                              \
                 bool ok_ = (unsigned)(qadj - kp_[e]) < wlim;                                             \
                 if constexpr (COARSE) {                                                                  \
-                    /* a common super-group only: the pair needs a common group or the window */        \
-                    if (shares_)                                                                         \
-                        ok_ = ok_ && ((mq_row & km_[e]) != 0u || (unsigned)(qadj_local - kp_[e]) < wlim_local); \
+                    /* a common super-group only: the pair needs a common group or the window; a launch */ \
+                    /* restricted to one pair set keeps the pairs with a common group, or the local rest */ \
+                    if (shares_) {                                                                       \
+                        const bool sh_ = (mq_row & km_[e]) != 0u;                                        \
+                        const bool loc_ = (unsigned)(qadj_local - kp_[e]) < wlim_local;                  \
+                        ok_ = ok_ && (L.pair_set == 1 ? sh_ : L.pair_set == 2 ? (loc_ && !sh_) : (sh_ || loc_)); \
+                    }                                                                                    \
                 }                                                                                        \
                 SIN[r4 * 4 + e] = ok_ ? SIN[r4 * 4 + e] : -INFINITY;                                     \
                 if constexpr (PAIRS) npairs += ok_ ? 1 : 0;                                              \

@@ -130,8 +130,12 @@ __global__ __launch_bounds__(BQ_VECTOR * (D / 32)) void attn_simple_kernel(Layou
                 }
                 bool share = inter;                      // exact classes: a common group is a class property
                 if (L.coarse && inter && kp != KPOS_PAD) share = (mq_row & mk_all[kp]) != 0u;
-                const bool ok = rvalid && kp != KPOS_PAD &&
-                                (L.causal ? (dlt >= 0 && (share || dlt < w)) : (share || (dlt < w && -dlt < w)));
+                const bool loc = L.causal ? (dlt >= 0 && dlt < w) : (dlt < w && -dlt < w);
+                const bool cz = L.causal ? dlt >= 0 : true;
+                bool pair_ok = cz && (share || loc);
+                // coarse classes that share a super-group hold pairs of both sets of a restricted launch
+                if (L.coarse && inter && L.pair_set != 0) pair_ok = (L.pair_set == 1) ? (cz && share) : (loc && !share);
+                const bool ok = rvalid && kp != KPOS_PAD && pair_ok;
                 s[kk] = ok ? x : -INFINITY;
                 npairs += ok ? 1 : 0;
                 mx = fmaxf(mx, s[kk]);

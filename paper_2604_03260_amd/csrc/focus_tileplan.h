@@ -70,7 +70,10 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
         const bool inter = (clsmask[c2] & mymask) != 0;
         const int koff = kco[c2];
         int a = 0, b = 0;
-        if (inter) {
+        // Coarse classes that share a super-group hold pairs of both sets: set B then visits their window span
+        // like a class that shares nothing, and the kernels sort the pairs out one by one.
+        const bool as_window = !inter || (L.coarse && L.pair_set == 2);
+        if (!as_window) {
             if (L.pair_set != 2) {                         // set B skips the classes that share a group
                 const int upto = L.causal ? pre_hi : kbc[(size_t)L.nblk * NC + c2];   // non-causal: the whole class
                 a = koff / KT;

@@ -185,10 +185,7 @@ def test_decode_argument_errors_before_any_launch():
     need = focus.focus_decode_state_size(p)
     assert need > 0 and need % 256 == 0
     st = lib.focus_workspace_size(ctypes.byref(p), ctypes.byref(ctypes.c_size_t(0)))
-    assert st == focus.FOCUS_OK                                     # the prefill path folds them onto super-groups ...
-    st = lib.focus_attn_fwd_set(ctypes.byref(p), focus.FOCUS_PAIRS_SHARED, fake, fake, fake, fake,
-                                ctypes.c_size_t(1 << 40), fake, vp(0), vp(0), vp(0))
-    assert st == focus.FOCUS_EUNSUPPORTED                           # ... but then has no two-set decomposition
+    assert st == focus.FOCUS_OK                                     # the prefill path folds them onto super-groups
     assert lib.focus_decode_prefill(ctypes.byref(p), -1, fake, fake, fake, need, vp(0)) == focus.FOCUS_EINVAL
     assert lib.focus_decode_prefill(ctypes.byref(p), 4097, fake, fake, fake, need, vp(0)) == focus.FOCUS_EINVAL
     assert lib.focus_decode_prefill(ctypes.byref(p), 10, vp(0), fake, fake, need, vp(0)) == focus.FOCUS_EINVAL

@@ -79,6 +79,9 @@ CASES = [
     (1, 2, 1, 600, 256, "bf16", 8, 1, 30, 0.0),
     (1, 4, 2, 900, 128, "bf16", 4, 1, 40, 0.0, False), # keys on both sides of the query
     (1, 2, 2, 500, 64, "f32", 8, 2, 9, 0.0, False),
+    (1, 4, 2, 1300, 128, "bf16", 32, 2, 40, 0.0),      # 496 membership sets on classes of super-groups
+    (1, 2, 2, 700, 64, "f32", 16, 3, 12, 0.0),
+    (1, 2, 1, 900, 96, "f16", 32, 2, 25, 0.0, False),  # ... non-causal
 ]
 
 
