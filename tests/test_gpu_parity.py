@@ -181,6 +181,45 @@ def test_assign_at_the_maximum_sequence_length():
     assert e.value.status == focus.FOCUS_EUNSUPPORTED
 
 
+def test_many_heads_and_many_sequences():
+    # the widest head count the head map holds, and a batch whose B*H runs into the thousands
+    for wl in (small("heads256", Hq=256, Hkv=32, n=300, d=64, dtype="bf16", window=16),
+               small("batch160", B=160, Hq=8, Hkv=2, n=200, d=128, dtype="bf16", K=8, topk=2, window=10)):
+        say("case", wl)
+        inp = workloads.make_inputs(wl, "cuda")
+        res = harness.run_gpu(wl, inp)
+        mq, mk = harness.check_assign(wl, inp, res)
+        rows = workloads.sample_rows(wl, 2048)
+        say(wl.name, harness.check_attn(wl, inp, res, mq, mk, rows=rows))
+        harness.check_pair_totals(wl, res, mq, mk)
+
+
+def test_two_streams_at_once():
+    # the library keeps no state between calls: two problems on two streams, each with its own workspace,
+    # give the bytes of the same calls made one after the other
+    wls = [small("s0", n=6000, dtype="bf16", d=128, K=4, topk=2, window=200, Hq=8, Hkv=2),
+           small("s1", n=5000, dtype="f16", d=64, K=8, topk=1, window=100, Hq=4, Hkv=4)]
+    inps = [workloads.make_inputs(w, "cuda") for w in wls]
+    refs = [harness.run_gpu(w, i) for w, i in zip(wls, inps)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    torch.cuda.synchronize()
+    for rep in range(3):
+        got = []
+        for w, i, st in zip(wls, inps, streams):
+            with torch.cuda.stream(st):
+                p = harness.params_of(w)
+                ws = focus.alloc_workspace(p)
+                out = torch.empty_like(i["q"])
+                lse = torch.empty((w.B, w.Hq, w.n), dtype=torch.float32, device="cuda")
+                focus.focus_assign(p, i["q"], i["k"], i["centroids"], ws)
+                focus.focus_attn_fwd(p, i["q"], i["k"], i["v"], ws, out, lse)
+                got.append((out, lse, ws))
+        torch.cuda.synchronize()
+        for (out, lse, _), ref in zip(got, refs):
+            assert torch.equal(out, ref["out"]) and torch.equal(lse, ref["lse"]), rep
+
+
 def test_deterministic_bytes():
     wl = small("determinism", n=1500, dtype="bf16", d=128, K=8, topk=2)
     inp = workloads.make_inputs(wl, "cuda")
