@@ -29,9 +29,10 @@
 //                          VALU  P1 = softmax-step(S1)
 //    The 16 LDS operands of a phase are read as one batch at its start.
 //  * K and V^T tiles are double-buffered in LDS and filled with
-//    global_load_lds_dwordx4: 64 lanes x 16 bytes land at M0 + lane*16, so the
-//    XOR swizzle is applied on the global side (each lane fetches the chunk that
-//    belongs in its LDS slot).  The loads of K(t+2), V(t+1) and the key positions
+//    global_load_lds_dwordx4: 64 lanes x 16 bytes land at M0 + lane*16.  LDS rows
+//    are 16 bytes longer than their data (bank-conflict-free operand reads whose
+//    chunk is an immediate offset), so each lane fetches the global chunk that
+//    belongs in its LDS slot.  The loads of K(t+2), V(t+1) and the key positions
 //    of tile t+2 are issued in the middle of tile t, right after the one barrier
 //    per tile, and waited for with s_waitcnt vmcnt(0) just before the next one.
 //  * The softmax reference max of a row only moves when the true max has drifted
@@ -40,6 +41,7 @@
 #include "focus_internal.h"
 #include "focus_tileplan.h"
 #include <algorithm>
+#include <type_traits>
 
 namespace focus {
 
@@ -136,21 +138,27 @@ __global__ __launch_bounds__(NTHR) void gather_vt_kernel(Layout L, const uint16_
 }
 
 // ---------------------------------------------------------------- attention
-template <int ROW_BYTES>
-__device__ inline int swz(int row, int ch)
-{
-    if constexpr (ROW_BYTES >= 256) return ch ^ (row & 15);     // 256- and 512-byte rows: low 4 bits of the chunk
-    else return ch ^ ((row >> 1) & 7);
-}
-
 constexpr int GROW = 128;     // bytes of a key's soft assignment in LDS: bf16 high parts of 32 groups, then the low parts
+
+// LDS rows of the K and V^T tiles are 16 bytes longer than their data: with pitches of 272 / 528 / 144 bytes
+// the 16 lanes of a ds_read_b128 group (16 consecutive rows, the same chunk) fall on 16 different bank
+// quads, and the chunk of a read is a compile-time byte offset: every operand read is
+// `ds_read_b128 v, vaddr offset:imm` with ONE per-lane address register per operand kind and no address
+// arithmetic in the loop.
+template <int D> struct TileGeom {
+    static constexpr int KROW = D * 2 + 16;             // pitch of a key row
+    static constexpr int VROW = KT * 2 + 16;            // pitch of a V^T row (KT keys)
+    static constexpr int K_LDS = KT * KROW;             // bytes of a K stage, a multiple of 1024
+    static constexpr int V_LDS = D * VROW;              // bytes of a V^T stage, a multiple of 1024
+    static_assert(K_LDS % 1024 == 0 && V_LDS % 1024 == 0, "stages are filled in 1-KB wave loads");
+};
 
 template <int D, bool COARSE, bool SOFT>
 struct Smem {
     TilePlan plan;
     __attribute__((aligned(16))) int kpos[3][KT];
-    __attribute__((aligned(16))) char k[2][KT * D * 2];     // [stage][key][D] 16-bit elements, chunks swizzled
-    __attribute__((aligned(16))) char vt[2][D * KT * 2];    // [stage][d][KT] 16-bit elements, chunks swizzled
+    __attribute__((aligned(16))) char k[2][TileGeom<D>::K_LDS];    // [stage][key][KROW] 16-bit elements
+    __attribute__((aligned(16))) char vt[2][TileGeom<D>::V_LDS];   // [stage][d][VROW] 16-bit elements
     __attribute__((aligned(16))) unsigned kmsk[COARSE ? 3 * KT : 4];   // membership masks of the keys (coarse classes)
     __attribute__((aligned(16))) char gk[SOFT ? 2 * KT * GROW : 16];   // [stage][key][GROW] soft assignments of the keys
 };
@@ -180,6 +188,24 @@ __device__ inline V8 lds_read16_async(unsigned addr)
     V8 r;
     asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr));
     return r;
+}
+// the same with a compile-time byte offset in the instruction
+template <typename V8, int OFF>
+__device__ inline V8 lds_read16_async_at(unsigned addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "ds offsets are 16 bits");
+    V8 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+// compile-time loop: f(std::integral_constant<int, I>) for I = 0 .. N-1
+template <int I, int N, typename F>
+__device__ inline void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
 }
 // s_waitcnt lgkmcnt(0) tied to every register of an operand array (N = 4..16 registers of 16 bytes)
 template <typename V8, int N>
@@ -226,8 +252,12 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     constexpr int DBH = DB / HV;        // O^T row blocks per half
     constexpr int NPVH = DBH * 2;       // P V MFMAs per half
     static_assert(KS % HV == 0 && DB % HV == 0, "halves are equal");
-    constexpr int TILE_BYTES = KT * D * 2;      // bytes of a K tile and of a V^T tile
-    constexpr int NW = TILE_BYTES / 1024 / MFMA_WAVES;   // 1-KB wave loads per wavefront and tile
+    constexpr int TILE_BYTES = KT * D * 2;      // bytes of a K tile and of a V^T tile in global memory
+    constexpr int KROW = TileGeom<D>::KROW, VROW = TileGeom<D>::VROW;
+    constexpr int K_LDS = TileGeom<D>::K_LDS, V_LDS = TileGeom<D>::V_LDS;
+    constexpr int NKB = K_LDS / 1024, NVB = V_LDS / 1024;             // 1-KB wave loads per stage
+    constexpr int NKI = (NKB + MFMA_WAVES - 1) / MFMA_WAVES;          // ... per wavefront (the last may be missing)
+    constexpr int NVI = (NVB + MFMA_WAVES - 1) / MFMA_WAVES;
     constexpr int ATHR = 64 * MFMA_WAVES;                // threads of the work-group
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -327,39 +357,34 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     const char* kmsk_base = ws + L.off_kmsk + (size_t)bhk * L.NKP * 4;
     const char* gk_base = ws + L.off_gk + (size_t)b * L.NKP * GROW;
 
-    // per-lane source offsets of the swizzled DMA: wave `wave` fills the 1-KB LDS blocks wave + 4*i
-    // of a tile; block j holds rows 4j..4j+3 (256-byte rows) or 8j..8j+7 (128-byte rows), and the
-    // swizzle key of a row depends only on (j mod 4) = wave, so one offset serves every i.
-    // With 512-byte rows a block holds 2 rows and the key alternates between a wave's consecutive
-    // blocks (4 wavefronts: 8 rows apart), so even and odd loads get an offset each.
-    unsigned voff_k[2], voff_v;
-    {
-        const int r128 = wave * 8 + lane / 8;                         // 128-byte rows
-        const unsigned off128 = (unsigned)((r128 * 8 + ((lane % 8) ^ ((wave & 1) * 4 + lane / 16))) * 16);
-        voff_v = off128;
-        if constexpr (D == 256) {
+    // per-lane source offsets of the DMA: wave `wave` fills the 1-KB LDS blocks wave + MFMA_WAVES * i of a
+    // stage; LDS byte o of a stage belongs to row o / pitch; its bytes past the row's data are padding and
+    // fetch the row's last chunk again
+    unsigned voff_k[NKI], voff_v[NVI];
 #pragma unroll
-            for (int par = 0; par < 2; ++par) {
-                const int r512 = (wave + MFMA_WAVES * par) * 2 + lane / 32;   // 512-byte rows
-                voff_k[par] = (unsigned)((r512 * 32 + ((lane % 32) ^ (r512 & 15))) * 16);
-            }
-        } else {
-            const int r256 = wave * 4 + lane / 16;                    // 256-byte rows
-            const unsigned off256 = (unsigned)((r256 * 16 + ((lane % 16) ^ (r256 & 15))) * 16);
-            voff_k[0] = (D == 128) ? off256 : off128;
-            voff_k[1] = voff_k[0] + 1024u * MFMA_WAVES;
-        }
+    for (int i = 0; i < NKI; ++i) {
+        const int o = (wave + MFMA_WAVES * i) * 1024 + lane * 16;
+        voff_k[i] = (unsigned)((o / KROW) * (D * 2) + min(o % KROW, D * 2 - 16));
+    }
+#pragma unroll
+    for (int i = 0; i < NVI; ++i) {
+        const int o = (wave + MFMA_WAVES * i) * 1024 + lane * 16;
+        voff_v[i] = (unsigned)((o / VROW) * (KT * 2) + min(o % VROW, KT * 2 - 16));
     }
     const unsigned lds_k0 = lds_addr_of(&S.k[0][0]), lds_v0 = lds_addr_of(&S.vt[0][0]);
     const unsigned lds_kp0 = lds_addr_of(&S.kpos[0][0]);
+    // one address register per operand kind: this lane's row of a unit / of a 32-row block, its half-wave's chunk
+    const unsigned ka_lane = lds_k0 + n32 * KROW + hh * 16;
+    const unsigned va_lane = lds_v0 + n32 * VROW + hh * 16;
     const unsigned lds_km0 = lds_addr_of(&S.kmsk[0]);
     const unsigned lds_g0 = lds_addr_of(&S.gk[0]);
 
 #define F4_DMA_K(TILE, STAGE)                                                                        \
     do {                                                                                             \
         const char* src_ = kc_base + (size_t)(TILE) * TILE_BYTES;                                    \
-        _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
-            dma16(src_ + (i >> 1) * (2048 * MFMA_WAVES), voff_k[i & 1], lds_k0 + (STAGE) * TILE_BYTES + (wave + MFMA_WAVES * i) * 1024); \
+        _Pragma("unroll") for (int i = 0; i < NKI; ++i)                                              \
+            if ((i + 1) * MFMA_WAVES <= NKB || wave + MFMA_WAVES * i < NKB)                          \
+                dma16(src_, voff_k[i], lds_k0 + (STAGE) * K_LDS + (wave + MFMA_WAVES * i) * 1024);   \
         if constexpr (SOFT) {            /* the keys' soft assignments travel with the key tile */          \
             const char* gsrc_ = gk_base + (size_t)(TILE) * (KT * GROW);                              \
             _Pragma("unroll") for (int i = 0; i < KT * GROW / 1024 / MFMA_WAVES; ++i)                 \
@@ -369,8 +394,9 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
 #define F4_DMA_V(TILE, STAGE)                                                                        \
     do {                                                                                             \
         const char* src_ = vt_base + (size_t)(TILE) * TILE_BYTES;                                    \
-        _Pragma("unroll") for (int i = 0; i < NW; ++i)                                               \
-            dma16(src_ + i * (1024 * MFMA_WAVES), voff_v, lds_v0 + (STAGE) * TILE_BYTES + (wave + MFMA_WAVES * i) * 1024); \
+        _Pragma("unroll") for (int i = 0; i < NVI; ++i)                                              \
+            if ((i + 1) * MFMA_WAVES <= NVB || wave + MFMA_WAVES * i < NVB)                          \
+                dma16(src_, voff_v[i], lds_v0 + (STAGE) * V_LDS + (wave + MFMA_WAVES * i) * 1024);   \
     } while (0)
 #define F4_DMA_KPOS(TILE, BUF)                                                                       \
     do {                                                                                             \
@@ -386,16 +412,19 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     // and are NOT waited for at once: the vector work that follows runs while they are in flight,
     // and F4_WAIT_OPERANDS() (s_waitcnt lgkmcnt(0), tied to every operand register) precedes the MFMAs.
 #define F4_READ_K(DST, KST, U, HALF)                                                                 \
-    _Pragma("unroll") for (int ks = 0; ks < KSH; ++ks) {                                             \
-        const int row_ = (U) * 32 + n32;                                                             \
-        DST[ks] = lds_read16_async<V8>(lds_k0 + (KST) * TILE_BYTES + row_ * (D * 2) + swz<D * 2>(row_, 2 * ((HALF) * KSH + ks) + hh) * 16); \
+    {                                                                                                \
+        const unsigned a_ = ka_lane + (KST) * K_LDS;                                                 \
+        static_for<0, KSH>([&](auto ks) {                                                            \
+            DST[ks] = lds_read16_async_at<V8, (U) * 32 * KROW + ((HALF) * KSH + ks) * 32>(a_);       \
+        });                                                                                          \
     }
 #define F4_READ_V(DST, VST, U, HALF)                                                                 \
-    _Pragma("unroll") for (int db = 0; db < DBH; ++db)                                               \
-        _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {                                           \
-            const int row_ = ((HALF) * DBH + db) * 32 + n32;                                         \
-            DST[db * 2 + s2] = lds_read16_async<V8>(lds_v0 + (VST) * TILE_BYTES + row_ * (KT * 2) + swz<KT * 2>(row_, (U) * 4 + s2 * 2 + hh) * 16); \
-        }
+    {                                                                                                \
+        const unsigned a_ = va_lane + (VST) * V_LDS;                                                 \
+        static_for<0, NPVH>([&](auto i2) {                                                           \
+            DST[i2] = lds_read16_async_at<V8, ((HALF) * DBH + i2 / 2) * 32 * VROW + (U) * 64 + (i2 % 2) * 32>(a_); \
+        });                                                                                          \
+    }
     // soft gate: high parts of the two k-steps, then the low parts, of the 32 keys of unit U
 #define F4_READ_G(KST, U)                                                                            \
     if constexpr (SOFT) {                                                                            \
@@ -460,7 +489,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         F4_DMA_KPOS(t0, 0);
         F4_DMA_KPOS(t1, 1);
         const u32x4 z4 = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < TILE_BYTES / 16; i += ATHR) *(u32x4*)(S.vt[1] + i * 16) = z4;
+        for (int i = tid; i < V_LDS / 16; i += ATHR) *(u32x4*)(S.vt[1] + i * 16) = z4;
         F4_WAIT_DMA();
     }
     __syncthreads();
@@ -476,15 +505,20 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; g0acc[r] = 0.f; g1acc[r] = 0.f; }
 #pragma unroll
     for (int e = 0; e < 8; ++e) { p1[0][e] = (elem_t)0.f; p1[1][e] = (elem_t)0.f; p0[0][e] = (elem_t)0.f; p0[1][e] = (elem_t)0.f; }
-#pragma unroll
-    for (int half = 0; half < HV; ++half) {
-        F4_READ_K(ak, 0, 0, half)
-        if (half == 0) { F4_READ_G(0, 0) }
+    {
+        F4_READ_K(ak, 0, 0, 0)
+        F4_READ_G(0, 0)
         wait_lds_operands(ak);
         if constexpr (SOFT) pin_operands(ag);
 #pragma unroll
-        for (int ks = 0; ks < KSH; ++ks) s0 = HT::mfma(ak[ks], qreg[half * KSH + ks], s0);
-        if (half == 0) { F4_GATE_MFMAS(g0acc) }
+        for (int ks = 0; ks < KSH; ++ks) s0 = HT::mfma(ak[ks], qreg[ks], s0);
+        F4_GATE_MFMAS(g0acc)
+    }
+    if constexpr (HV == 2) {
+        F4_READ_K(ak, 0, 0, 1)
+        wait_lds_operands(ak);
+#pragma unroll
+        for (int ks = 0; ks < KSH; ++ks) s0 = HT::mfma(ak[ks], qreg[KSH + ks], s0);
     }
 
     // softmax step on one unit's scores: SIN (f32x16, consumed) -> POUT (2 x bf16x8), split in two parts.
@@ -655,13 +689,17 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     // ---- drain: O += V(T-1,u1) P1 (V(T-1) was complete before the last barrier)
     {
         const int sl = (total - 1) & 1;
-#pragma unroll
-        for (int half = 0; half < HV; ++half) {
-            F4_READ_V(av, sl, 1, half)
+        {
+            F4_READ_V(av, sl, 1, 0)
             wait_lds_operands(av);
 #pragma unroll
-            for (int i = 0; i < NPVH; ++i)
-                o[half * DBH + i / 2] = HT::mfma(av[i], p1[i % 2], o[half * DBH + i / 2]);
+            for (int i = 0; i < NPVH; ++i) o[i / 2] = HT::mfma(av[i], p1[i % 2], o[i / 2]);
+        }
+        if constexpr (HV == 2) {
+            F4_READ_V(av, sl, 1, 1)
+            wait_lds_operands(av);
+#pragma unroll
+            for (int i = 0; i < NPVH; ++i) o[DBH + i / 2] = HT::mfma(av[i], p1[i % 2], o[DBH + i / 2]);
         }
     }
     F4_WAIT_DMA();                                           // nothing may still be writing LDS when the block ends
