@@ -162,10 +162,14 @@ def main():
     probe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_03260_amd", "_build", "issue_rates")
     if half and os.path.exists(probe):
         try:
-            got = subprocess.run([probe, "--mfma-peak"], capture_output=True, text=True, timeout=60)
-            measured_peak = float(got.stdout.strip().split()[-1])
+            got = subprocess.run([probe, "--mfma-peak"], capture_output=True, text=True, timeout=120)
+            fields = got.stdout.strip().split()
+            measured_peak = float(fields[0])              # constant operands
             result["measured_mfma_peak_tflops"] = measured_peak
             result["pct_of_measured_mfma_peak_attn"] = 100.0 * tflops_attn / measured_peak
+            if len(fields) > 1:                           # operands that change from one MFMA to the next
+                result["measured_mfma_peak_random_operands_tflops"] = float(fields[1])
+                result["pct_of_measured_mfma_peak_random_operands_attn"] = 100.0 * tflops_attn / float(fields[1])
         except Exception as exc:              # the probe is optional: its absence or failure changes no figure above
             result["measured_mfma_peak_tflops"] = None
             print("bench.py: MFMA peak probe failed: %r" % (exc,), file=sys.stderr)
