@@ -277,3 +277,26 @@ def test_decode_token_masks_that_are_no_topk_subset_are_replaced():
     torch.cuda.synchronize()
     mk = focus.focus_decode_state_views(p, state)["mk"][:, :, :4].cpu().numpy()
     assert (mk == np.array([0b0011, 0b0011, 0b0011, 0b0110])).all()
+
+
+def decode_sweep_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        K = int(rng.choice([1, 2, 4, 6, 8, 16, 32]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        n = int(rng.integers(40, 1500))
+        steps = int(rng.integers(2, 9))
+        cases.append((int(rng.choice([1, 2])), Hkv * int(rng.choice([1, 2, 3, 4, 8])), Hkv, n, int(rng.choice([64, 80, 96, 128, 256])),
+                      str(rng.choice(["bf16", "f16", "f32"])), K, int(rng.integers(1, min(K, 4) + 1)),
+                      int(rng.choice([1, 3, 16, 100, n + 7])), float(rng.choice([0.0, 0.0, 20.0])),
+                      int(rng.integers(0, n - steps + 1)), steps))
+    return cases
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,n,d,dtype,K,topk,w,cap,n0,steps", decode_sweep_cases(24, 20260404))
+def test_decode_random_parameter_sweep(B, Hq, Hkv, n, d, dtype, K, topk, w, cap, n0, steps):
+    wl = workloads.Workload("dsweep", 49, B, Hq, Hkv, n, d, dtype, K, topk, w, softcap=cap, mixture=3 if K > 2 else 0)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = run_decode(wl, inp, n0, steps)
+    check_decode(wl, inp, res, n0, steps)

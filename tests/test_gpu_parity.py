@@ -220,6 +220,41 @@ def test_two_streams_at_once():
             assert torch.equal(out, ref["out"]) and torch.equal(lse, ref["lse"]), rep
 
 
+def sweep_cases(count, seed):
+    """Seeded draws over the whole parameter space of the prefill path (small n, so the oracle checks every row)."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        K = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 32]))
+        topk = int(rng.integers(1, min(K, 4) + 1))
+        Hkv = int(rng.choice([1, 2, 3]))
+        G = int(rng.choice([1, 2, 4, 5]))
+        n = int(rng.integers(1, 1400))
+        kw = dict(B=int(rng.choice([1, 2])), Hq=Hkv * G, Hkv=Hkv, n=n, d=int(rng.choice([64, 80, 96, 128, 256])),
+                  dtype=str(rng.choice(["bf16", "f16", "f32"])), K=K, topk=topk,
+                  window=int(rng.choice([1, 2, 7, 32, 100, 333, max(1, n // 2), n + 5])),
+                  causal=bool(rng.random() < 0.7), softcap=float(rng.choice([0.0, 0.0, 7.0, 50.0])),
+                  mixture=int(rng.choice([0, 0, 4])))
+        if kw["dtype"] == "f32" and kw["d"] == 256 and n > 500:
+            continue                                   # keep the vector kernel's share of the run time small
+        cases.append(small("sweep%d" % len(cases), **kw))
+    return cases
+
+
+@pytest.mark.parametrize("wl", sweep_cases(48, 20260403), ids=lambda w: w.name)
+def test_random_parameter_sweep(wl):
+    say("case", wl)
+    inp = workloads.make_inputs(wl, "cuda")
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    stats = harness.check_attn(wl, inp, res, mq, mk)
+    try:
+        harness.check_pair_totals(wl, res, mq, mk)
+    except RuntimeError as exc:                        # the oracle's closed form refuses more than 2e6 subsets
+        assert "pair_counts" in str(exc)
+    say(wl.name, stats)
+
+
 def test_deterministic_bytes():
     wl = small("determinism", n=1500, dtype="bf16", d=128, K=8, topk=2)
     inp = workloads.make_inputs(wl, "cuda")
