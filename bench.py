@@ -329,7 +329,7 @@ def main():
         # the same steps replayed from ONE captured HIP graph (position in device memory, advanced inside the
         # graph): what a generation loop pays per token without per-step launch work on the host
         focus.focus_decode_prefill(p, n0, kc, cents, state)          # lists back to n0; the caches keep their rows
-        posd = torch.full((1,), n0, dtype=torch.int32, device="cuda")
+        posd = torch.full((wl.B,), n0, dtype=torch.int32, device="cuda")
         qb, kb, vb = qs[0].clone(), ks[0].clone(), vs[0].clone()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())

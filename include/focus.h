@@ -230,12 +230,14 @@ focus_status focus_decode_step_tokens(const focus_params *p, int32_t pos, const 
                                       void *k_cache, void *v_cache, void *state, size_t state_bytes,
                                       void *out, float *lse, int32_t *row_pairs, void *stream);
 
-/* The same step with the position read from DEVICE memory by the kernels when they run: a HIP graph
- * captured once around this call serves every step of a generation loop (the caller writes the new
- * token's q, k, v into the captured buffers and advances *pos_dev on the device between replays).
- * The launch shapes are those of the last position the caches can hold; work-groups past the real
- * sequence exit at once.  A position outside [0, n) cannot be checked on the host: the step then
- * does nothing (caches, state and outputs untouched). */
+/* The same step with the positions read from DEVICE memory by the kernels when they run:
+ * pos_dev [B] int32, one position per sequence.  A HIP graph captured once around this call serves every
+ * step of a generation loop (the caller writes the new tokens' q, k, v into the captured buffers and
+ * advances pos_dev on the device between replays), and the sequences of a batch may stand at different
+ * positions.  A sequence whose position is outside [0, n) is skipped: its caches, state and outputs stay
+ * untouched (a finished or not yet started sequence of a continuous batch; the host cannot check device
+ * values).  The launch shapes are those of the last position the caches can hold; work-groups past a
+ * sequence's real length exit at once. */
 focus_status focus_decode_step_at(const focus_params *p, const int32_t *pos_dev, const void *q_new,
                                   const void *k_new, const void *v_new, const float *centroids,
                                   void *k_cache, void *v_cache, void *state, size_t state_bytes,

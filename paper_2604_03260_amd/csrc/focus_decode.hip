@@ -197,11 +197,12 @@ __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMa
     __shared__ float s_x[256];
     __shared__ float s_c[32 * 257];               // row stride d + 1: the K lanes read K different rows
     const int lane = threadIdx.x;
-    // the position comes from the launch, or from device memory when a captured graph serves every step;
-    // a position outside the caches does nothing (the host could not check it)
-    const int pos = pos_dev ? *pos_dev : pos_arg;
-    if (pos < 0 || pos >= L.n) return;
+    // the position comes from the launch (one for all sequences), or from device memory, one per sequence,
+    // when a captured graph serves every step or the sequences of a batch stand at different positions;
+    // a position outside the caches makes the step skip that sequence (the host could not check it)
     const int b = blockIdx.y, hh = blockIdx.x;
+    const int pos = pos_dev ? pos_dev[b] : pos_arg;
+    if (pos < 0 || pos >= L.n) return;
     const bool is_q = hh < L.Hq;
     const int h = is_q ? hh : hh - L.Hq;
     const int hk = is_q ? hm.kv[h] : h;
@@ -362,12 +363,12 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     __shared__ int s_j[DEC_CHUNK];                // cache row of every key of the chunk, -1 = skipped
     __shared__ float s_red[4][SLOTS][PW];
 
-    const int pos = pos_dev ? *pos_dev : pos_arg;
-    if (pos < 0 || pos >= L.n) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane / LPK, sub = lane % LPK;
     const int chunk = blockIdx.x, bhq = blockIdx.y;
     const int b = bhq / L.Hq, h = bhq % L.Hq;
+    const int pos = pos_dev ? pos_dev[b] : pos_arg;
+    if (pos < 0 || pos >= L.n) return;
     const size_t bhk = (size_t)b * L.Hkv + hm.kv[h];
     const int lo_w = max(0, pos - L.window + 1);  // first position of the window
     const uint32_t gq = ((const uint32_t*)(st + L.off_mq))[bhq];
@@ -533,13 +534,13 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     __shared__ int s_wcnt[4];
     __shared__ float s_red[4][SLOTS][PW];
 
-    const int pos = pos_dev ? *pos_dev : pos_arg;
-    if (pos < 0 || pos >= L.n) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane / LPK, sub = lane % LPK;
     const int chunk = blockIdx.x;
     const size_t bhk = blockIdx.y;
     const int b = (int)(bhk / L.Hkv), hk = (int)(bhk % L.Hkv);
+    const int pos = pos_dev ? pos_dev[b] : pos_arg;
+    if (pos < 0 || pos >= L.n) return;
     const size_t bhq0 = (size_t)b * L.Hq + (size_t)hk * G;
     const int lo_w = max(0, pos - L.window + 1);
     uint32_t gq[G];
@@ -736,9 +737,9 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int p
     constexpr int NG = 256 / TPG;                 // whole groups; the threads past NG * TPG (d = 80, 96) only help with the max
     __shared__ float s_w[4];
     __shared__ float s_acc[NG][D + 4];
-    const int pos = pos_dev ? *pos_dev : pos_arg;
-    if (pos < 0 || pos >= L.n) return;                // the other kernels of the step did nothing either
     const int tid = threadIdx.x, t = tid % TPG, grp = tid / TPG, bhq = blockIdx.x;
+    const int pos = pos_dev ? pos_dev[bhq / L.Hq] : pos_arg;
+    if (pos < 0 || pos >= L.n) return;                // the other kernels of the step skipped this sequence too
     const float* p0 = part + (size_t)bhq * L.max_chunks * PW;
     float mx = -INFINITY;
     for (int c = tid; c < nchunks; c += 256) mx = fmaxf(mx, p0[(size_t)c * PW + D]);

@@ -260,8 +260,9 @@ def focus_decode_step_tokens(p, pos, token_mask, q_new, k_new, v_new, k_cache, v
 
 def focus_decode_step_at(p, pos_dev, q_new, k_new, v_new, centroids, k_cache, v_cache, state, out, lse=None,
                          row_pairs=None):
-    """The step with the position in device memory (an int32 tensor of one element): capturable once."""
-    assert pos_dev.dtype == torch.int32 and pos_dev.is_cuda
+    """The step with the positions in device memory (int32 [B], one per sequence; outside [0, n) = skip the
+    sequence): capturable once, and the sequences of a batch may stand at different positions."""
+    assert pos_dev.dtype == torch.int32 and pos_dev.is_cuda and pos_dev.numel() == p.B
     _check(load_library().focus_decode_step_at(ctypes.byref(p), _ptr(pos_dev), _ptr(q_new), _ptr(k_new), _ptr(v_new),
                                                _ptr(centroids), _ptr(k_cache), _ptr(v_cache), _ptr(state),
                                                state.numel() * state.element_size(), _ptr(out), _ptr(lse),

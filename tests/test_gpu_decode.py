@@ -156,7 +156,7 @@ def test_decode_step_with_the_position_on_the_device_replays_from_one_graph(kw):
     out = torch.empty_like(q_new)
     lse = torch.empty((wl.B, wl.Hq), dtype=torch.float32, device="cuda")
     rp = torch.empty((wl.B, wl.Hq), dtype=torch.int32, device="cuda")
-    pos = torch.full((1,), n0, dtype=torch.int32, device="cuda")
+    pos = torch.full((wl.B,), n0, dtype=torch.int32, device="cuda")
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -171,7 +171,7 @@ def test_decode_step_with_the_position_on_the_device_replays_from_one_graph(kw):
         graph.replay()
         torch.cuda.synchronize()
         outs.append(out.clone()); lses.append(lse.clone()); pairs.append(rp.clone())
-    assert int(pos.item()) == n0 + steps
+    assert pos.tolist() == [n0 + steps] * wl.B
     res = dict(out=torch.stack(outs, 2), lse=torch.stack(lses, 2), row_pairs=torch.stack(pairs, 2), kc=kc, vc=vc)
     check_decode(wl, inp, res, n0, steps)
     # the same steps with the position as a host argument: identical state, outputs equal up to the
@@ -203,7 +203,7 @@ def test_decode_step_with_a_device_position_outside_the_caches_does_nothing():
     before = (kc.clone(), vc.clone(), state.clone())
     out = torch.full((wl.B, wl.Hq, wl.d), 7.0, dtype=torch.bfloat16, device="cuda")
     for bad in (-1, 256, 1 << 30):
-        pos = torch.full((1,), bad, dtype=torch.int32, device="cuda")
+        pos = torch.full((wl.B,), bad, dtype=torch.int32, device="cuda")
         focus.focus_decode_step_at(p, pos, inp["q"][:, :, 0].contiguous(), inp["k"][:, :, 0].contiguous(),
                                    inp["v"][:, :, 0].contiguous(), inp["centroids"], kc, vc, state, out)
         torch.cuda.synchronize()
@@ -300,3 +300,55 @@ def test_decode_random_parameter_sweep(B, Hq, Hkv, n, d, dtype, K, topk, w, cap,
     inp = workloads.make_inputs(wl, "cuda")
     res = run_decode(wl, inp, n0, steps)
     check_decode(wl, inp, res, n0, steps)
+
+
+def test_decode_sequences_of_a_batch_at_different_positions():
+    # continuous batching: three sequences with prefixes of different lengths share one step call; a sequence
+    # that has not started or has finished is skipped by giving it a position outside the caches
+    wl = workloads.Workload("dec_ragged", 44, 3, 8, 2, 900, 128, "bf16", 4, 2, 32)
+    inp = workloads.make_inputs(wl, "cuda")
+    p = harness.params_of(wl)
+    state = focus.alloc_decode_state(p)
+    starts = [300, 640, 880]                                          # first decoded position of every sequence
+    ends = [330, 660, 900]
+    n0 = min(starts)
+    kc = torch.zeros_like(inp["k"]); vc = torch.zeros_like(inp["v"])
+    kc[:, :, :n0] = inp["k"][:, :, :n0]; vc[:, :, :n0] = inp["v"][:, :, :n0]
+    focus.focus_decode_prefill(p, n0, kc, inp["centroids"], state)
+    # bring the longer prefixes in token by token (the shorter sequences sit out), then decode all three
+    outs = {}
+    cur = [n0] * wl.B
+    q_new = torch.empty((wl.B, wl.Hq, wl.d), dtype=torch.bfloat16, device="cuda")
+    k_new = torch.empty((wl.B, wl.Hkv, wl.d), dtype=torch.bfloat16, device="cuda")
+    v_new = torch.empty_like(k_new)
+    out = torch.empty_like(q_new)
+    rp = torch.empty((wl.B, wl.Hq), dtype=torch.int32, device="cuda")
+    while any(c < e for c, e in zip(cur, ends)):
+        # a sequence takes part while it is below its end; sequence b decodes "for real" from starts[b] on
+        active = [c < e for c, e in zip(cur, ends)]
+        pos = torch.tensor([c if a else -1 for c, a in zip(cur, active)], dtype=torch.int32, device="cuda")
+        for b in range(wl.B):
+            i = min(cur[b], wl.n - 1)
+            q_new[b] = inp["q"][b, :, i]; k_new[b] = inp["k"][b, :, i]; v_new[b] = inp["v"][b, :, i]
+        out.fill_(float("nan")); rp.fill_(-5)
+        focus.focus_decode_step_at(p, pos, q_new, k_new, v_new, inp["centroids"], kc, vc, state, out, None, rp)
+        torch.cuda.synchronize()
+        for b in range(wl.B):
+            if active[b]:
+                if cur[b] >= starts[b]:
+                    outs[(b, cur[b])] = (out[b].clone(), rp[b].clone())
+                cur[b] += 1
+            else:
+                assert bool(torch.isnan(out[b].float()).all()) and bool((rp[b] == -5).all())   # skipped: untouched
+    pb = harness.problem_of(wl)
+    qh, kh, vh = (workloads.to_host_bits(inp[x]) for x in ("q", "k", "v"))
+    mq, mk = harness.oracle_membership(wl, inp)
+    keys = sorted(outs)
+    rows = np.array([(b, h, i) for (b, i) in keys for h in range(wl.Hq)], dtype=np.int32)
+    o_ref, _, p_ref = fo.attn_rows(pb, qh, kh, vh, mq, mk, rows=rows)
+    o = torch.stack([outs[k][0] for k in keys]).float().cpu().numpy().astype(np.float64).reshape(-1, wl.d)
+    rpg = torch.stack([outs[k][1] for k in keys]).cpu().numpy().astype(np.int64).reshape(-1)
+    err = np.abs(o - o_ref)
+    tol = harness.TOL[wl.dtype]
+    assert err.max() <= tol["out_max"] and err.mean() <= tol["out_mean"], (err.max(), err.mean())
+    assert np.array_equal(rpg, p_ref)
