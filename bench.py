@@ -26,7 +26,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 FP64_VECTOR_PEAK_TFLOPS = 78.6
 # HBM bytes per launch of the attention kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this
 # command (profiles/attn_mfma_kernel_cfg3_counters.txt); None where no counter run was made
-MEASURED_TRAFFIC_BYTES = {"cfg3": 6.08e9}
+MEASURED_TRAFFIC_BYTES = {"cfg3": 5.88e9}
 
 
 def main():
