@@ -265,10 +265,10 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     L->K = p->K; L->topk = p->topk; L->window = p->window; L->dtype = p->dtype;
     L->scale = (p->scale > 0.0f) ? p->scale : (float)(1.0 / std::sqrt((double)p->d));
     L->softcap = p->softcap;
-    // longest concatenated key sequence: the window plus list prefixes, which together hold at most topk * n
-    // entries (every key sits in exactly topk lists)
-    const int64_t vmax = (int64_t)std::min(p->window, p->n) + (int64_t)p->topk * (int64_t)p->n;
-    L->max_chunks = (int)((vmax + DEC_CHUNK - 1) / DEC_CHUNK);
+    // longest key sequence a step walks: n entries (the group lists are used only while they are shorter than
+    // the range of positions below the window)
+    L->max_chunks = (p->n + DEC_CHUNK - 1) / DEC_CHUNK;
+    L->max_parts = std::min(L->max_chunks, DEC_MAX_PARTS);
     for (int h = 0; h < p->Hq; ++h)
         hm->kv[h] = (uint8_t)(p->head_map ? p->head_map[h] : h / (p->Hq / p->Hkv));
     const size_t BHq = (size_t)p->B * p->Hq, BHk = (size_t)p->B * p->Hkv, n = (size_t)p->n;
@@ -279,7 +279,7 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     L->off_counts = take(BHk * (size_t)p->K * 4);
     L->off_wp = take(BHk * (size_t)p->K * 4);
     L->off_mq = take(BHq * 4);
-    L->off_part = take(BHq * (size_t)L->max_chunks * (size_t)(p->d + 4) * 4);
+    L->off_part = take(BHq * (size_t)L->max_parts * (size_t)(p->d + 4) * 4);
     L->total = off;
     return FOCUS_OK;
 }

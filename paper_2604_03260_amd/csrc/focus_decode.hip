@@ -345,6 +345,13 @@ __device__ inline float slice_dot(const Raw8<float>& q, const Raw8<float>& k)
 
 constexpr float DEC_LOG2E = 1.4426950408889634f;
 
+// Two ways to enumerate the keys below the window.  List mode walks the position lists of the query's groups
+// (list entry -> position -> mask, two dependent loads per entry; a key that sits in several of the lists
+// comes up once per list and is dropped from all but the first).  Scan mode walks the positions themselves and
+// tests every key's mask against the query's (one coalesced load, consecutive K/V rows).  The lists win when
+// they hold fewer entries than there are positions below the window; from there on the scan is the shorter walk.
+__device__ inline bool decode_scan_mode(int list_entries, int below_window) { return list_entries >= below_window; }
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos_arg, const int* __restrict__ pos_dev, int span,
                                                           const T* __restrict__ q_new,
@@ -394,11 +401,12 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
         }
         s_beg[nseg] = run;
         s_nseg = nseg;
+        if (decode_scan_mode(run - (pos - lo_w + 1), lo_w)) { s_nseg = 0; s_beg[0] = pos + 1; }
     }
     __syncthreads();
-    const int nseg = s_nseg;
+    const int nseg = s_nseg;                      // 0: scan mode, the sequence is the positions 0..pos themselves
     const int vtotal = s_beg[nseg];
-    float* mypart = part + ((size_t)bhq * L.max_chunks + chunk) * PW;
+    float* mypart = part + ((size_t)bhq * L.max_parts + chunk) * PW;
     if (chunk * span * DEC_CHUNK >= vtotal) {     // nothing for this work-group
         for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
         return;
@@ -428,7 +436,9 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
             const int v = v0 + i;
             int sgi = 0;
             while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
-            if (sgi == 0) {
+            if (nseg == 0) {
+                j = (v >= lo_w || (mk[v] & gq) != 0u) ? v : -1;
+            } else if (sgi == 0) {
                 j = lo_w + v;
             } else {
                 j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
@@ -524,15 +534,17 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     constexpr int ACT = D / 8;
     constexpr int SLOTS = 64 / LPK;
     constexpr int PW = D + 4;
-    constexpr int U = (G <= 2 && sizeof(T) == 2) ? 8 : 4;
+    constexpr int U = (G <= 2 && sizeof(T) == 2) ? 8 : 4;    // keys per slot and round: U K rows and U V rows in flight
+    constexpr int KPT = DEC_CHUNK / 256;                     // keys every thread resolves per chunk
+    constexpr int HB = G < 4 ? G : 4;                        // heads folded through LDS at a time
     __shared__ int s_beg[34];
     __shared__ int s_grp[33];
     __shared__ uint32_t s_prev[33];
     __shared__ int s_nseg;
-    __shared__ int s_j[DEC_CHUNK + SLOTS * U];    // cache rows of the chunk's keys, squeezed; padded with -1
-    __shared__ uint8_t s_hb[DEC_CHUNK + SLOTS * U];   // which of the G heads attend the key
-    __shared__ int s_wcnt[4];
-    __shared__ float s_red[4][SLOTS][PW];
+    __shared__ int s_j[DEC_CHUNK + 4 * SLOTS * U];    // cache rows of the chunk's keys, squeezed; padded with -1
+    __shared__ uint8_t s_hb[DEC_CHUNK + 4 * SLOTS * U];   // which of the G heads attend the key
+    __shared__ int s_wcnt[4 * KPT];
+    __shared__ float s_red[HB][4 * SLOTS][PW];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane / LPK, sub = lane % LPK;
@@ -564,14 +576,15 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
         }
         s_beg[nseg] = run;
         s_nseg = nseg;
+        if (decode_scan_mode(run - (pos - lo_w + 1), lo_w)) { s_nseg = 0; s_beg[0] = pos + 1; }
     }
     __syncthreads();
-    const int nseg = s_nseg;
+    const int nseg = s_nseg;                      // 0: scan mode, the sequence is the positions 0..pos themselves
     const int vtotal = s_beg[nseg];
     // this work-group walks `span` consecutive chunks of the sequence and leaves one partial per head
     if (chunk * span * DEC_CHUNK >= vtotal) {
         for (int i = 0; i < G; ++i) {
-            float* mypart = part + ((bhq0 + i) * L.max_chunks + chunk) * PW;
+            float* mypart = part + ((bhq0 + i) * L.max_parts + chunk) * PW;
             for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
         }
         return;
@@ -591,70 +604,34 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
         for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
     }
     const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
-    const T* kbase = kc + bhk * L.n * D + sub * 8;
-    const T* vbase = vc + bhk * L.n * D + sub * 8;
+    const T* kbase = kc + bhk * L.n * D + (act ? sub * 8 : 0);
+    const T* vbase = vc + bhk * L.n * D + (act ? sub * 8 : 0);
 
-    for (int cc = 0; cc < span; ++cc) {
-    const int v0 = (chunk * span + cc) * DEC_CHUNK;
-    if (v0 >= vtotal) break;                      // uniform over the work-group
-    if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
-    // resolve one key per thread, then squeeze the skipped ones out (stable: wave ballots + wave offsets)
-    {
-        const int nk0 = min(vtotal - v0, DEC_CHUNK);
-        int j = -1;
-        uint32_t hb = 0;
-        if (tid < nk0) {
-            const int v = v0 + tid;
-            int sgi = 0;
-            while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
-            if (sgi == 0) {
-                j = lo_w + v;
-                hb = (1u << G) - 1u;
-            } else {
-                j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
-                const uint32_t mkj = mk[j];
-                if ((mkj & s_prev[sgi]) != 0u) {
-                    j = -1;                                           // already taken from an earlier group
-                } else {
-#pragma unroll
-                    for (int i = 0; i < G; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
-                }
-            }
-        }
-        const unsigned long long bal = __ballot(j >= 0);
-        if (lane == 0) s_wcnt[wave] = __popcll(bal);
-        for (int i = tid; i < DEC_CHUNK + SLOTS * U; i += 256) s_j[i] = -1;
-        __syncthreads();
-        int before = 0;
-        for (int w2 = 0; w2 < wave; ++w2) before += s_wcnt[w2];
-        if (j >= 0) {
-            const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-            const int dst = before + __popcll(bal & lt);
-            s_j[dst] = j;
-            s_hb[dst] = (uint8_t)hb;
-        }
-        __syncthreads();
-    }
-    const int nk = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-
-    for (int r0 = wave * (SLOTS * U); r0 < nk; r0 += 4 * SLOTS * U) {
+    // one round: U keys per slot.  `fetch` issues the K and V row loads of a round, `fold` does its arithmetic.
+    struct Round {
         int jpos[U];
         uint32_t hbs[U];
         Raw8<T> kr[U], vr[U];
+    };
+    auto fetch = [&](Round& R, int r0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            jpos[u] = s_j[r0 + u * SLOTS + slot];                     // the array is padded by one round of -1
-            hbs[u] = (jpos[u] >= 0) ? (uint32_t)s_hb[r0 + u * SLOTS + slot] : 0u;
-            const int j = max(jpos[u], 0);
-            if (act) { kr[u].load(kbase + (size_t)j * D); vr[u].load(vbase + (size_t)j * D); }
-            else { kr[u].zero(); vr[u].zero(); }
+            R.jpos[u] = s_j[r0 + u * SLOTS + slot];                   // the array is padded by one round of -1
+            R.hbs[u] = (R.jpos[u] >= 0) ? (uint32_t)s_hb[r0 + u * SLOTS + slot] : 0u;
+            const int j = max(R.jpos[u], 0);
+            // lanes past d / 8 slices (d = 80, 96) read the row's first slice again: their q is zero and their
+            // output is never stored
+            R.kr[u].load(kbase + (size_t)j * D);
+            R.vr[u].load(vbase + (size_t)j * D);
         }
+    };
+    auto fold = [&](const Round& R) {
         float vx[U][8];
 #pragma unroll
-        for (int u = 0; u < U; ++u) vr[u].unpack(vx[u]);
+        for (int u = 0; u < U; ++u) R.vr[u].unpack(vx[u]);
         uint32_t hb_or = 0;
 #pragma unroll
-        for (int u = 0; u < U; ++u) hb_or |= hbs[u];
+        for (int u = 0; u < U; ++u) hb_or |= R.hbs[u];
 #pragma unroll
         for (int i = 0; i < G; ++i) {
             // a list segment holds the keys of one group: with few groups per key most heads want none of
@@ -664,10 +641,10 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
             float mx = -INFINITY;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float dot = slice_sum<LPK>(slice_dot(qr[i], kr[u]));
+                const float dot = slice_sum<LPK>(slice_dot(qr[i], R.kr[u]));
                 float x = dot * sl2;
                 if (cap > 0.f) x = cap * DEC_LOG2E * tanhf(dot * L.scale / cap);
-                const bool on = (hbs[u] >> i) & 1u;
+                const bool on = (R.hbs[u] >> i) & 1u;
                 xs[u] = on ? x : -INFINITY;
                 mx = fmaxf(mx, xs[u]);
                 cnt[i] += on ? 1 : 0;
@@ -688,14 +665,97 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
                 }
             }
         }
+    };
+
+    for (int cc = 0; cc < span; ++cc) {
+    const int v0 = (chunk * span + cc) * DEC_CHUNK;
+    if (v0 >= vtotal) break;                      // uniform over the work-group
+    if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
+    // resolve KPT keys per thread (all loads independent), then squeeze the skipped ones out: wave ballots
+    // give every (pass, wavefront) its count, the kept keys land in pass-major, wavefront-major order
+    {
+        const int nk0 = min(vtotal - v0, DEC_CHUNK);
+        int js[KPT];
+        uint32_t hbv[KPT];
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            int j = -1;
+            uint32_t hb = 0;
+            const int i0 = it * 256 + tid;
+            if (i0 < nk0) {
+                const int v = v0 + i0;
+                int sgi = 0;
+                while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
+                if (nseg == 0) {
+                    if (v >= lo_w) {
+                        hb = (1u << G) - 1u;
+                    } else {
+                        const uint32_t mkj = mk[v];
+#pragma unroll
+                        for (int i = 0; i < G; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
+                    }
+                    j = hb ? v : -1;
+                } else if (sgi == 0) {
+                    j = lo_w + v;
+                    hb = (1u << G) - 1u;
+                } else {
+                    j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
+                    const uint32_t mkj = mk[j];
+                    if ((mkj & s_prev[sgi]) != 0u) {
+                        j = -1;                                       // already taken from an earlier group
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < G; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
+                    }
+                }
+            }
+            js[it] = j;
+            hbv[it] = hb;
+        }
+        unsigned long long bal[KPT];
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            bal[it] = __ballot(js[it] >= 0);
+            if (lane == 0) s_wcnt[it * 4 + wave] = __popcll(bal[it]);
+        }
+        for (int i = tid; i < DEC_CHUNK + 4 * SLOTS * U; i += 256) s_j[i] = -1;
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            int before = 0;
+            for (int w2 = 0; w2 < it * 4 + wave; ++w2) before += s_wcnt[w2];
+            if (js[it] >= 0) {
+                const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+                const int dst = before + __popcll(bal[it] & lt);
+                s_j[dst] = js[it];
+                s_hb[dst] = (uint8_t)hbv[it];
+            }
+        }
+        __syncthreads();
+    }
+    int nk = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < 4 * KPT; ++w2) nk += s_wcnt[w2];
+
+    constexpr int RSTEP = 4 * SLOTS * U;          // keys of one round of the four wavefronts
+    // (Keeping the loads of the next round in flight while this one is folded costs a second set of row
+    // registers and a wavefront of occupancy: slower at every context length measured.)
+    for (int r0 = wave * (SLOTS * U); r0 < nk; r0 += RSTEP) {
+        Round ra;
+        fetch(ra, r0);
+        fold(ra);
     }
     }   // chunks of the span
-    // fold the (wavefront, slot) partials of one head at a time through LDS
+    // fold the (wavefront, slot) partials through LDS, HB heads at a time: 256 / HB threads per head
+    constexpr int TPH = 256 / HB;
+    const int hsel = tid / TPH, t = tid % TPH;
 #pragma unroll
-    for (int i = 0; i < G; ++i) {
-        if (i > 0) __syncthreads();
-        {
-            float* r = s_red[wave][slot];
+    for (int h0 = 0; h0 < G; h0 += HB) {
+        if (h0 > 0) __syncthreads();
+#pragma unroll
+        for (int ii = 0; ii < HB; ++ii) {
+            const int i = h0 + ii;
+            float* r = s_red[ii][wave * SLOTS + slot];
             if (act) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) r[sub * 8 + e] = o[i][e];
@@ -703,22 +763,28 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
             if (sub == 0) { r[D] = m[i]; r[D + 1] = l[i]; r[D + 2] = (float)cnt[i]; }
         }
         __syncthreads();
-        if (tid < D) {
+        {
+            const float (*rr)[PW] = s_red[hsel];
             float mx = -INFINITY;
-            for (int w2 = 0; w2 < 4; ++w2)
-                for (int s2 = 0; s2 < SLOTS; ++s2) mx = fmaxf(mx, s_red[w2][s2][D]);
-            float acc = 0.f, lsum = 0.f, csum = 0.f;
-            for (int w2 = 0; w2 < 4; ++w2)
-                for (int s2 = 0; s2 < SLOTS; ++s2) {
-                    const float ms = s_red[w2][s2][D];
-                    const float wgt = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - mx);
-                    acc += wgt * s_red[w2][s2][tid];
-                    lsum += wgt * s_red[w2][s2][D + 1];
-                    csum += s_red[w2][s2][D + 2];
-                }
-            float* mypart = part + ((bhq0 + i) * L.max_chunks + chunk) * PW;
-            mypart[tid] = acc;
-            if (tid == 0) { mypart[D] = mx; mypart[D + 1] = lsum; mypart[D + 2] = csum; mypart[D + 3] = 0.f; }
+#pragma unroll
+            for (int s2 = 0; s2 < 4 * SLOTS; ++s2) mx = fmaxf(mx, rr[s2][D]);
+            float wgt[4 * SLOTS];
+            float lsum = 0.f, csum = 0.f;
+#pragma unroll
+            for (int s2 = 0; s2 < 4 * SLOTS; ++s2) {
+                const float ms = rr[s2][D];
+                wgt[s2] = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - mx);
+                lsum += wgt[s2] * rr[s2][D + 1];
+                csum += rr[s2][D + 2];
+            }
+            float* mypart = part + ((bhq0 + h0 + hsel) * L.max_parts + chunk) * PW;
+            for (int c = t; c < D; c += TPH) {
+                float acc = 0.f;
+#pragma unroll
+                for (int s2 = 0; s2 < 4 * SLOTS; ++s2) acc += wgt[s2] * rr[s2][c];
+                mypart[c] = acc;
+            }
+            if (t == 0) { mypart[D] = mx; mypart[D + 1] = lsum; mypart[D + 2] = csum; mypart[D + 3] = 0.f; }
         }
     }
 }
@@ -740,7 +806,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int p
     const int tid = threadIdx.x, t = tid % TPG, grp = tid / TPG, bhq = blockIdx.x;
     const int pos = pos_dev ? pos_dev[bhq / L.Hq] : pos_arg;
     if (pos < 0 || pos >= L.n) return;                // the other kernels of the step skipped this sequence too
-    const float* p0 = part + (size_t)bhq * L.max_chunks * PW;
+    const float* p0 = part + (size_t)bhq * L.max_parts * PW;
     float mx = -INFINITY;
     for (int c = tid; c < nchunks; c += 256) mx = fmaxf(mx, p0[(size_t)c * PW + D]);
 #pragma unroll
@@ -827,17 +893,15 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     const int G = (L.Hq % L.Hkv == 0) ? L.Hq / L.Hkv : 0;
     bool grouped = (G == 1 || G == 2 || G == 4 || G == 8);
     for (int h = 0; grouped && h < L.Hq; ++h) grouped = hm.kv[h] == h / G;
-    // upper bound of the concatenated key sequence known on the host: the window plus list prefixes that hold
-    // at most topk * pos entries together (every cached key sits in exactly topk lists), for one head's groups
-    // as for the union of several heads' groups
-    // (with the position in device memory: the bound of the last position the caches can hold; work-groups
-    // past the real sequence leave an empty partial)
+    // upper bound of the key sequence known on the host: pos + 1 entries.  The lists are walked only while they
+    // hold fewer entries than there are positions below the window, the positions themselves otherwise.
+    // (With the position in device memory: the bound of the last position the caches can hold; work-groups
+    // past the real sequence leave an empty partial.)
     if (pos_dev) pos = L.n - 1;
-    const long vmax = (long)std::min(L.window, pos + 1) + (long)L.topk * (long)pos;
-    const int nchunks = (int)std::min((long)L.max_chunks, (vmax + DEC_CHUNK - 1) / DEC_CHUNK);
-    // a work-group walks `span` chunks and leaves one partial: at most about 384 partials per head, so the merge
-    // stays short at any context length
-    const int span = (nchunks + 383) / 384;
+    const int nchunks = std::min(L.max_chunks, (pos + DEC_CHUNK) / DEC_CHUNK);
+    // a work-group walks `span` chunks and leaves one partial: at most DEC_MAX_PARTS partials per head, so the
+    // merge stays short at any context length
+    const int span = (nchunks + DEC_MAX_PARTS - 1) / DEC_MAX_PARTS;
     const int nparts = (nchunks + span - 1) / span;
     if (grouped) {
         dim3 grid(nparts, L.B * L.Hkv);

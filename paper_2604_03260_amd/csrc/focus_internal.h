@@ -144,19 +144,24 @@ struct RouteLayout {
 };
 
 // Shapes and state offsets of the incremental (one token per step) path.
-constexpr int DEC_CHUNK = 256;    // keys of the concatenated key sequence per work-group of the decode attention
+#ifndef FOCUS_DEC_CHUNK
+#define FOCUS_DEC_CHUNK 512
+#endif
+constexpr int DEC_CHUNK = FOCUS_DEC_CHUNK;   // keys of the key sequence a work-group of the decode attention resolves at a time
+constexpr int DEC_MAX_PARTS = 384;           // partial results per head the merge reads at most
 struct DecodeLayout {
     int B, Hq, Hkv, n, d;      // n = capacity of the caches
     int K, topk, window;
     int dtype;
     float scale, softcap;
-    int max_chunks;            // chunks of DEC_CHUNK keys the longest concatenated sequence can have
+    int max_chunks;            // chunks of DEC_CHUNK keys the longest key sequence (n entries) has
+    int max_parts;             // partial results per head: min(max_chunks, DEC_MAX_PARTS)
     size_t off_mk;             // [B,Hkv,n] uint32 membership of the cached keys
     size_t off_lists;          // [B,Hkv,K,n] int32 positions of every group, ascending
     size_t off_counts;         // [B,Hkv,K] int32 list lengths
     size_t off_wp;             // [B,Hkv,K] int32 list entries below the current step's window
     size_t off_mq;             // [B,Hq] uint32 membership of the current queries
-    size_t off_part;           // [B,Hq,max_chunks,d+4] fp32 partial (o, max, sum, count) per chunk
+    size_t off_part;           // [B,Hq,max_parts,d+4] fp32 partial (o, max, sum, count) per work-group
     size_t total;
 };
 
