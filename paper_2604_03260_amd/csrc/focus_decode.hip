@@ -17,6 +17,7 @@
 //   3. merges the chunks' partial (o, max, sum) by their log-sum-exp weights (App. D "Merge", n-ary).
 #include "focus_internal.h"
 #include <algorithm>
+#include <type_traits>
 
 namespace focus {
 
@@ -789,6 +790,338 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     }
 }
 
+// ---------------------------------------------------------------- step 2, grouped-query form on the matrix cores
+// The same walk as decode_attn_gqa_kernel for 16-bit caches with 128- or 256-byte rows, with both products on
+// v_mfma_f32_16x16x32: a wavefront takes 32 keys per round as two blocks of 16.
+//   S^T[key, head] = K[key, :] . Q[head, :]   A = K rows straight from the cache (lane: key l%16, components
+//                                             32*kb + 8*(l/16) ..+8, one 16-byte load per product), B = the G <= 8
+//                                             query heads of the KV head (columns past G are zero);
+//   the accumulator lane (head l%16, keys 4*(l/16) ..+4 of either block) does the softmax step of its head;
+//   its 8 probabilities, rounded to 16 bits, ARE the B operand of
+//   O^T[c, head] += V^T[c, key] P^T[key, head]  A = 16 components x 32 keys of V^T.
+// V^T is not in memory: the V rows of the round land in LDS by global_load_lds (no registers), and each lane
+// picks the 8 keys of its k-slice for its component with 16-bit LDS reads.  The rows of one wave load sit
+// 1 KB + 32 bytes apart from the next load's, so the four keys the lane groups read together fall on
+// different banks.  The softmax reference moves only when the maximum has drifted by more than 8 (log2
+// units), so the accumulators are rarely rescaled.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 dec_bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 dec_f16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float dec_f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t dec_u32x4;
+
+template <bool F16> struct DecHalf;
+template <> struct DecHalf<false> {
+    typedef dec_bf16x8 V8;
+    static __device__ inline dec_f32x4 mfma(V8 a, V8 b, dec_f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+    static __device__ inline uint32_t pack2(float lo, float hi, float& sum)
+    {
+        const __bf16 a = (__bf16)lo, b = (__bf16)hi;
+        sum += (float)a + (float)b;
+        return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+    }
+};
+template <> struct DecHalf<true> {
+    typedef dec_f16x8 V8;
+    static __device__ inline dec_f32x4 mfma(V8 a, V8 b, dec_f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+    static __device__ inline uint32_t pack2(float lo, float hi, float& sum)
+    {
+        const _Float16 a = (_Float16)lo, b = (_Float16)hi;
+        sum += (float)a + (float)b;
+        return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+    }
+};
+
+// 64 lanes x 16 bytes: lane l fetches global (sbase + voff) into LDS byte address lds_addr + 16*l
+// (sbase and lds_addr wave-uniform)
+__device__ inline void dec_dma16(const void* sbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
+}
+
+constexpr float DEC_RESCALE_THRESHOLD = 8.f;
+
+template <bool F16, int D>
+__global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout L, int G, int pos_arg, const int* __restrict__ pos_dev,
+                                                                   int span, const uint16_t* __restrict__ q_new,
+                                                                   const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
+                                                                   const char* __restrict__ st, float* __restrict__ part)
+{
+    typedef DecHalf<F16> HT;
+    typedef typename HT::V8 V8;
+    static_assert(D == 64 || D == 128, "rows of 128 or 256 bytes");
+    constexpr int RB = D * 2;                     // bytes of a cache row
+    constexpr int LPR = RB / 16;                  // lanes that load one V row
+    constexpr int RPI = 64 / LPR;                 // V rows per wave load
+    constexpr int NI = 32 / RPI;                  // wave loads per round of 32 keys
+    constexpr int IPITCH = 1024 + 32;             // LDS bytes from one wave load to the next
+    constexpr int VBYTES = NI * IPITCH;           // V rows of a round, per wavefront
+    constexpr int KB = D / 32;                    // products of one S^T block
+    constexpr int NB = D / 16;                    // 16-component blocks of O^T
+    constexpr int PW = D + 4;
+    constexpr int KPT = DEC_CHUNK / 256;
+    constexpr int RSTEP = 4 * 32;                 // keys of one round of the four wavefronts
+    constexpr int GMAX = 8;
+    constexpr int RED_BYTES = GMAX * 4 * PW * 4;
+    constexpr int BUF_BYTES = 4 * VBYTES > RED_BYTES ? 4 * VBYTES : RED_BYTES;
+    __shared__ int s_beg[34];
+    __shared__ int s_grp[33];
+    __shared__ uint32_t s_prev[33];
+    __shared__ int s_nseg;
+    __shared__ int s_j[DEC_CHUNK + RSTEP];        // cache rows of the chunk's keys, squeezed; padded with -1
+    __shared__ __attribute__((aligned(4))) uint8_t s_hb[DEC_CHUNK + RSTEP];   // which heads attend the key; 0 in the padding
+    __shared__ int s_wcnt[4 * KPT];
+    __shared__ __attribute__((aligned(16))) char s_buf[BUF_BYTES];   // V rows of the rounds; the partials at the end
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m16 = lane & 15, qg = lane >> 4;
+    const int chunk = blockIdx.x;
+    const size_t bhk = blockIdx.y;
+    const int b = (int)(bhk / L.Hkv), hk = (int)(bhk % L.Hkv);
+    const int pos = pos_dev ? pos_dev[b] : pos_arg;
+    if (pos < 0 || pos >= L.n) return;
+    const size_t bhq0 = (size_t)b * L.Hq + (size_t)hk * G;
+    const int lo_w = max(0, pos - L.window + 1);
+    uint32_t gq[GMAX];
+    uint32_t gu = 0;
+#pragma unroll
+    for (int i = 0; i < GMAX; ++i) { gq[i] = (i < G) ? ((const uint32_t*)(st + L.off_mq))[bhq0 + i] : 0u; gu |= gq[i]; }
+    const int* wptr = (const int*)(st + L.off_wp) + bhk * L.K;
+    const int* lists = (const int*)(st + L.off_lists) + bhk * L.K * L.n;
+    const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + bhk * L.n;
+
+    if (tid == 0) {
+        int nseg = 1, run = pos - lo_w + 1;
+        uint32_t prev = 0;
+        s_beg[0] = 0; s_grp[0] = -1; s_prev[0] = 0;
+        for (int g = 0; g < L.K; ++g) {
+            if (!((gu >> g) & 1u)) continue;
+            s_beg[nseg] = run; s_grp[nseg] = g; s_prev[nseg] = prev;
+            run += wptr[g];
+            prev |= (1u << g);
+            ++nseg;
+        }
+        s_beg[nseg] = run;
+        s_nseg = nseg;
+        if (decode_scan_mode(run - (pos - lo_w + 1), lo_w)) { s_nseg = 0; s_beg[0] = pos + 1; }
+    }
+    __syncthreads();
+    const int nseg = s_nseg;                      // 0: scan mode, the sequence is the positions 0..pos themselves
+    const int vtotal = s_beg[nseg];
+    if (chunk * span * DEC_CHUNK >= vtotal) {
+        for (int i = 0; i < G; ++i) {
+            float* mypart = part + ((bhq0 + i) * L.max_parts + chunk) * PW;
+            for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
+        }
+        return;
+    }
+    // B operand of S^T: the query heads, column m16 (zero past G)
+    V8 qv[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        dec_u32x4 w = {0u, 0u, 0u, 0u};
+        if (m16 < G) w = *(const dec_u32x4*)(q_new + (bhq0 + m16) * D + 32 * kb + 8 * qg);
+        qv[kb] = __builtin_bit_cast(V8, w);
+    }
+    dec_f32x4 oacc[NB];
+#pragma unroll
+    for (int blk = 0; blk < NB; ++blk) oacc[blk] = dec_f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_ref = -INFINITY, lsum = 0.f;          // of head m16, over the keys of this lane group so far
+    int cnt = 0;
+    const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
+    const uint16_t* kbase = kc + bhk * L.n * D + 8 * qg;
+    const uint16_t* vbase = vc + bhk * L.n * D;
+    const unsigned lds_v = (unsigned)(uintptr_t)(&s_buf[0]) + (unsigned)wave * VBYTES;
+    const char* my_v = s_buf + wave * VBYTES;
+    // k-slot e of lane group qg holds key 16*(e/4) + 4*qg + e%4 of the round: LDS offset of that key's V row
+    int vrow[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int key = 16 * (e / 4) + 4 * qg + e % 4;
+        vrow[e] = (key / RPI) * IPITCH + (key % RPI) * RB + 2 * m16;
+    }
+
+    for (int cc = 0; cc < span; ++cc) {
+    const int v0 = (chunk * span + cc) * DEC_CHUNK;
+    if (v0 >= vtotal) break;                      // uniform over the work-group
+    if (cc > 0) __syncthreads();                  // the last chunk's keys have been read
+    {
+        const int nk0 = min(vtotal - v0, DEC_CHUNK);
+        int js[KPT];
+        uint32_t hbv[KPT];
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            int j = -1;
+            uint32_t hb = 0;
+            const int i0 = it * 256 + tid;
+            if (i0 < nk0) {
+                const int v = v0 + i0;
+                int sgi = 0;
+                while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
+                if (nseg == 0) {
+                    if (v >= lo_w) {
+                        hb = (1u << G) - 1u;
+                    } else {
+                        const uint32_t mkj = mk[v];
+#pragma unroll
+                        for (int i = 0; i < GMAX; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
+                    }
+                    j = hb ? v : -1;
+                } else if (sgi == 0) {
+                    j = lo_w + v;
+                    hb = (1u << G) - 1u;
+                } else {
+                    j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
+                    const uint32_t mkj = mk[j];
+                    if ((mkj & s_prev[sgi]) != 0u) {
+                        j = -1;                                       // already taken from an earlier group
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < GMAX; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
+                    }
+                }
+            }
+            js[it] = j;
+            hbv[it] = hb;
+        }
+        unsigned long long bal[KPT];
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            bal[it] = __ballot(js[it] >= 0);
+            if (lane == 0) s_wcnt[it * 4 + wave] = __popcll(bal[it]);
+        }
+        for (int i = tid; i < DEC_CHUNK + RSTEP; i += 256) { s_j[i] = -1; s_hb[i] = 0; }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            int before = 0;
+            for (int w2 = 0; w2 < it * 4 + wave; ++w2) before += s_wcnt[w2];
+            if (js[it] >= 0) {
+                const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+                const int dst = before + __popcll(bal[it] & lt);
+                s_j[dst] = js[it];
+                s_hb[dst] = (uint8_t)hbv[it];
+            }
+        }
+        __syncthreads();
+    }
+    int nk = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < 4 * KPT; ++w2) nk += s_wcnt[w2];
+
+    for (int r0 = wave * 32; r0 < nk; r0 += RSTEP) {
+        // the V rows of the round -> LDS (wave load i holds keys i*RPI ..+RPI of the round)
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int jv = max(s_j[r0 + i * RPI + lane / LPR], 0);
+            dec_dma16(vbase, (unsigned)jv * (unsigned)RB + (unsigned)(lane % LPR) * 16u, lds_v + i * IPITCH);
+        }
+        // the K rows of the two blocks -> registers
+        const int ja = max(s_j[r0 + m16], 0), jb = max(s_j[r0 + 16 + m16], 0);
+        V8 ka[KB], kb2[KB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            ka[kb] = __builtin_bit_cast(V8, *(const dec_u32x4*)(kbase + (size_t)ja * D + 32 * kb));
+            kb2[kb] = __builtin_bit_cast(V8, *(const dec_u32x4*)(kbase + (size_t)jb * D + 32 * kb));
+        }
+        const uint32_t hba = *(const uint32_t*)(&s_hb[r0 + 4 * qg]);
+        const uint32_t hbb = *(const uint32_t*)(&s_hb[r0 + 16 + 4 * qg]);
+        dec_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            sa = HT::mfma(ka[kb], qv[kb], sa);
+            sb = HT::mfma(kb2[kb], qv[kb], sb);
+        }
+        float x[8];
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float sc = (e < 4) ? sa[e % 4] : sb[e % 4];
+            const uint32_t byte = (((e < 4) ? hba : hbb) >> (8 * (e % 4))) & 0xffu;
+            const bool on = (byte >> m16) & 1u;
+            float xv = sc * sl2;
+            if (cap > 0.f) xv = cap * DEC_LOG2E * tanhf(sc * L.scale / cap);
+            x[e] = on ? xv : -INFINITY;
+            mloc = fmaxf(mloc, x[e]);
+            cnt += on ? 1 : 0;
+        }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        const bool move = mloc > m_ref + DEC_RESCALE_THRESHOLD;       // also true for the first attended key (m_ref = -inf)
+        if (__any(move)) {
+            const float m_new = move ? mloc : m_ref;
+            const float alpha = (m_ref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            lsum *= alpha;
+#pragma unroll
+            for (int blk = 0; blk < NB; ++blk) oacc[blk] *= alpha;
+        }
+        const float mr = (m_ref == -INFINITY) ? 0.f : m_ref;
+        dec_u32x4 pw;
+        float psum = 0.f;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2)
+            pw[e2] = HT::pack2(__builtin_amdgcn_exp2f(x[2 * e2] - mr), __builtin_amdgcn_exp2f(x[2 * e2 + 1] - mr), psum);
+        lsum += psum;
+        const V8 pb = __builtin_bit_cast(V8, pw);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");              // the V rows have landed
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk) {
+            dec_u32x4 vw;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const uint32_t lo = *(const uint16_t*)(my_v + vrow[2 * e2] + 32 * blk);
+                const uint32_t hi = *(const uint16_t*)(my_v + vrow[2 * e2 + 1] + 32 * blk);
+                vw[e2] = lo | (hi << 16);
+            }
+            oacc[blk] = HT::mfma(__builtin_bit_cast(V8, vw), pb, oacc[blk]);
+        }
+        asm volatile("" ::: "memory");                                // the reads stay ahead of the next round's loads
+    }
+    }   // chunks of the span
+    // the lane groups of a head share the reference; their sums and counts add up
+    lsum += __shfl_xor(lsum, 16, 64); lsum += __shfl_xor(lsum, 32, 64);
+    cnt += __shfl_xor(cnt, 16, 64); cnt += __shfl_xor(cnt, 32, 64);
+    __syncthreads();                              // every wavefront is done with its V rows
+    float (*red)[4][PW] = (float (*)[4][PW])s_buf;
+    if (m16 < G) {
+        float* r = red[m16][wave];
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[16 * blk + 4 * qg + e] = oacc[blk][e];
+        if (qg == 0) { r[D] = m_ref; r[D + 1] = lsum; r[D + 2] = (float)cnt; }
+    }
+    __syncthreads();
+    {
+        const int hsel = tid >> 5, t = tid & 31;  // 32 threads per head
+        if (hsel < G) {
+            const float (*rr)[PW] = red[hsel];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) mx = fmaxf(mx, rr[w2][D]);
+            float wgt[4];
+            float ls = 0.f, cs = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+                const float ms = rr[w2][D];
+                wgt[w2] = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - mx);
+                ls += wgt[w2] * rr[w2][D + 1];
+                cs += rr[w2][D + 2];
+            }
+            float* mypart = part + ((bhq0 + hsel) * L.max_parts + chunk) * PW;
+            for (int c = t; c < D; c += 32) {
+                float acc = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) acc += wgt[w2] * rr[w2][c];
+                mypart[c] = acc;
+            }
+            if (t == 0) { mypart[D] = mx; mypart[D + 1] = ls; mypart[D + 2] = cs; mypart[D + 3] = 0.f; }
+        }
+    }
+}
+
 // ---------------------------------------------------------------- step 3: merge of the chunks
 // One work-group per (batch, query head).  A chunk's partial is read by D/4 threads (4 components each);
 // the 256 / (D/4) groups of threads take the chunks round-robin, then fold through LDS.
@@ -905,6 +1238,17 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     const int nparts = (nchunks + span - 1) / span;
     if (grouped) {
         dim3 grid(nparts, L.B * L.Hkv);
+        // 16-bit caches with 128- or 256-byte rows whose byte offsets fit 32 bits: the matrix-core form
+        if constexpr (sizeof(T) == 2 && (D == 64 || D == 128)) {
+            if ((size_t)L.n * D * 2 <= 0xffffffffull) {
+                hipLaunchKernelGGL((decode_attn_gqa_mfma_kernel<std::is_same<T, f16_bits>::value, D>), grid, dim3(256), 0, s, L, G, pos,
+                                   pos_dev, span, (const uint16_t*)q_new, (const uint16_t*)kc, (const uint16_t*)vc, (const char*)st,
+                                   part);
+                hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(L.B * L.Hq), dim3(256), 0, s, L, pos, pos_dev, nparts, part, out,
+                                   lse, row_pairs);
+                return hipGetLastError();
+            }
+        }
 #define FOCUS_DEC_GQA(G_) hipLaunchKernelGGL((decode_attn_gqa_kernel<T, D, G_>), grid, dim3(256), 0, s, L, pos, pos_dev, span, q_new, kc, vc, (const char*)st, part)
         if (G == 1) FOCUS_DEC_GQA(1); else if (G == 2) FOCUS_DEC_GQA(2); else if (G == 4) FOCUS_DEC_GQA(4); else FOCUS_DEC_GQA(8);
 #undef FOCUS_DEC_GQA
