@@ -209,19 +209,57 @@ __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMa
     const int hk = is_q ? hm.kv[h] : h;
     const int d = L.d;
     const T* x = is_q ? q_new + ((size_t)b * L.Hq + h) * d : k_new + ((size_t)b * L.Hkv + h) * d;
+    const size_t bhk = (size_t)b * L.Hkv + h;     // KV-head wavefronts only
+    // Everything that does not depend on the scores is loaded first, so that the scoring hides those round
+    // trips: the vector itself, for a key also its V row, the lengths and window pointers of the lists and the
+    // two list entries the window's lower edge can pass in this step.
+    T xr[4], vr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = lane + 64 * i;
+        if (t < d) xr[i] = x[t];
+        if (!is_q && t < d) vr[i] = v_new[bhk * d + t];
+    }
+    int cn = 0, w = 0, l0 = 0, l1 = 0;
+    const int* list = (const int*)(st + L.off_lists) + (bhk * L.K + lane) * L.n;   // of group `lane`
+    if (!is_q && lane < L.K) {
+        cn = ((const int*)(st + L.off_counts))[bhk * L.K + lane];
+        w = ((const int*)(st + L.off_wp))[bhk * L.K + lane];
+        if (w < cn) l0 = list[w];
+        if (w + 1 < cn) l1 = list[w + 1];
+    }
     uint32_t mask;
     if (token_mask) {
         // the new token's membership comes from the per-layer router: the same for every head, as query and as key
         mask = decode_valid_mask(token_mask[b], L.K, L.topk);
     } else {
-        for (int t = lane; t < d; t += 64) s_x[t] = dec_to_f32<T>(x[t]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (lane + 64 * i < d) s_x[lane + 64 * i] = dec_to_f32<T>(xr[i]);
         const float* c = cents + (size_t)hk * L.K * d;
-        for (int e = lane; e < L.K * d; e += 64) s_c[(e / d) * (d + 1) + e % d] = c[e];
+        // eight loads in flight per lane (one at a time, the staging alone is a chain of K * d / 64 round trips)
+        for (int e0 = lane; e0 < L.K * d; e0 += 64 * 8) {
+            float cv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) cv[i] = (e0 + 64 * i < L.K * d) ? c[e0 + 64 * i] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = e0 + 64 * i;
+                if (e < L.K * d) s_c[(e / d) * (d + 1) + e % d] = cv[i];
+            }
+        }
         __syncthreads();
         double s = 0.0;
         if (lane < L.K) {
+            // index order, eight components per LDS round trip (d is a multiple of 8)
             const float* cr = s_c + lane * (d + 1);
-            for (int t = 0; t < d; ++t) s = fma((double)s_x[t], (double)cr[t], s);
+            for (int t = 0; t < d; t += 8) {
+                float xs[8], cs[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { xs[i] = s_x[t + i]; cs[i] = cr[t + i]; }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) s = fma((double)xs[i], (double)cs[i], s);
+            }
         }
         mask = wave_topk_mask(s, lane, L.K, L.topk);
     }
@@ -229,30 +267,33 @@ __global__ __launch_bounds__(64) void decode_route_kernel(DecodeLayout L, HeadMa
         if (lane == 0) ((uint32_t*)(st + L.off_mq))[(size_t)b * L.Hq + h] = mask;
         return;
     }
-    const size_t bhk = (size_t)b * L.Hkv + h;
     if (lane == 0) ((uint32_t*)(st + L.off_mk))[bhk * L.n + pos] = mask;
-    if (lane < L.K && ((mask >> lane) & 1u)) {
-        int* cnt = (int*)(st + L.off_counts) + bhk * L.K + lane;
-        int* list = (int*)(st + L.off_lists) + (bhk * L.K + lane) * L.n;
-        const int cn = *cnt;                      // single writer: this lane owns the group's list
-        list[cn] = pos;
-        *cnt = cn + 1;
-    }
     if (lane < L.K) {
-        // window pointer: number of list entries below this step's window.  The window's lower edge moves
-        // with pos and positions are unique, so the pointer normally advances by at most one per step.
+        if ((mask >> lane) & 1u) {
+            // single writer: this lane owns the group's list
+            ((int*)(st + L.off_lists))[(bhk * L.K + lane) * L.n + cn] = pos;
+            ((int*)(st + L.off_counts))[bhk * L.K + lane] = cn + 1;
+        }
+        // window pointer: number of list entries below this step's window, among the cn entries before this
+        // step's append (pos itself is in the window).  The window's lower edge moves with pos and positions are
+        // unique, so the pointer normally advances by at most one per step.
         const int lo_w = pos - L.window + 1;
-        const int cn = ((const int*)(st + L.off_counts))[bhk * L.K + lane] - (((mask >> lane) & 1u) ? 1 : 0);
-        const int* list = (const int*)(st + L.off_lists) + (bhk * L.K + lane) * L.n;
-        int* wp = (int*)(st + L.off_wp) + bhk * L.K + lane;
-        int w = *wp;
-        while (w < cn && list[w] < lo_w) ++w;     // entries before this step's append only (pos itself is in the window)
-        *wp = w;
+        if (w < cn && l0 < lo_w) {
+            ++w;
+            if (w < cn && l1 < lo_w) {
+                ++w;
+                while (w < cn && list[w] < lo_w) ++w;
+            }
+        }
+        ((int*)(st + L.off_wp))[bhk * L.K + lane] = w;
     }
-    const T* vrow = v_new + bhk * d;
     T* kdst = kc + (bhk * L.n + pos) * d;
     T* vdst = vc + (bhk * L.n + pos) * d;
-    for (int t = lane; t < d; t += 64) { kdst[t] = x[t]; vdst[t] = vrow[t]; }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = lane + 64 * i;
+        if (t < d) { kdst[t] = xr[i]; vdst[t] = vr[i]; }
+    }
 }
 
 // ---------------------------------------------------------------- step 2: attention over one chunk of the key sequence
