@@ -13,7 +13,11 @@
 //      step 1 advances with the window);
 //      a key that sits in several of the query's groups is taken from the first of them only (its
 //      mask tells).  The concatenation [window | list prefix of group 1 | group 2 | ...] is cut into
-//      chunks of DEC_CHUNK keys, one work-group each, with an online softmax per 8-component slice;
+//      chunks of DEC_CHUNK keys with an online softmax per chunk.  When the lists together hold at least
+//      as many entries as there are positions below the window (few groups, several of them per query),
+//      the positions 0..pos are walked instead and every key's mask is tested against the query's;
+//      grouped-query heads share one walk over the union of their keys, and 16-bit caches with 64 or 128
+//      components per row run both products on the matrix cores;
 //   3. merges the chunks' partial (o, max, sum) by their log-sum-exp weights (App. D "Merge", n-ary).
 #include "focus_internal.h"
 #include <algorithm>
@@ -877,7 +881,7 @@ template <> struct DecHalf<true> {
 __device__ inline void dec_dma16(const void* sbase, unsigned voff, unsigned lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
 }
 
 constexpr float DEC_RESCALE_THRESHOLD = 8.f;

@@ -83,6 +83,11 @@ CASES = [
     (1, 4, 2, 1000, 256, "bf16", 4, 2, 50, 0.0, 992, 8),         # 32 lanes per key
     (1, 2, 2, 600, 256, "f32", 8, 1, 16, 0.0, 594, 6),
     (1, 3, 1, 40000, 256, "f16", 4, 2, 200, 0.0, 39997, 3),      # long context, per-head kernel, d = 256
+    (1, 2, 1, 250000, 64, "bf16", 4, 2, 300, 0.0, 249997, 3),    # work-groups that walk two chunks, positions walked (matrix cores)
+    (1, 3, 1, 250000, 64, "bf16", 4, 2, 300, 0.0, 249998, 2),    # ... in the per-head kernel
+    (1, 4, 2, 300000, 128, "bf16", 16, 1, 512, 0.0, 299997, 3),  # ... group lists walked: they are the shorter walk
+    (1, 4, 1, 262144, 128, "f16", 4, 2, 1024, 30.0, 262141, 3),  # ... four heads per KV head, half precision, softcap
+    (1, 8, 1, 5000, 128, "f32", 4, 2, 100, 0.0, 4996, 4),        # eight fp32 heads on one KV head (vector kernel)
 ]
 
 
