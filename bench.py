@@ -361,7 +361,7 @@ def main():
         jj = torch.arange(wl.n, device="cuda")
         att = ((mk_t & gu[:, :, None]) != 0) | (jj[None, None, :] > pos_last - wl.window)
         unique_rows = int(att.sum().item())
-        elem = 2 if wl.dtype == "bf16" else 4
+        elem = 2 if wl.dtype in ("bf16", "f16") else 4
         dec_bytes = 2.0 * unique_rows * wl.d * elem
         per_head_rows = int(drp.to(torch.int64).sum().item())
         result["decode"] = {
