@@ -398,6 +398,114 @@ constexpr float DEC_LOG2E = 1.4426950408889634f;
 // they hold fewer entries than there are positions below the window; from there on the scan is the shorter walk.
 __device__ inline bool decode_scan_mode(int list_entries, int below_window) { return list_entries >= below_window; }
 
+// The walk of one work-group, in LDS.  List mode: segment 0 is the window, segment s > 0 the list prefix of one
+// group; scan mode (nseg = 0): one run of pos + 1 positions.
+struct DecWalk {
+    int beg[34];              // first entry of every segment; beg[nseg] (beg[0] in scan mode) = entries in all
+    int grp[33];              // group of the segment
+    uint32_t prev[33];        // groups of the segments before it: a key that sits in one of them was taken there
+    int nseg;
+};
+
+// One thread fills the walk for the groups in `groups` (of one query, or of all query heads of a KV head).
+__device__ inline void decode_walk_init(DecWalk& W, uint32_t groups, const int* __restrict__ wptr, int K, int pos, int lo_w)
+{
+    int nseg = 1, run = pos - lo_w + 1;
+    uint32_t prev = 0;
+    W.beg[0] = 0; W.grp[0] = -1; W.prev[0] = 0;
+    for (int g = 0; g < K; ++g) {
+        if (!((groups >> g) & 1u)) continue;
+        W.beg[nseg] = run; W.grp[nseg] = g; W.prev[nseg] = prev;
+        run += wptr[g];                           // list entries below the window (kept by the route kernel)
+        prev |= (1u << g);
+        ++nseg;
+    }
+    W.beg[nseg] = run;
+    W.nseg = nseg;
+    if (decode_scan_mode(run - (pos - lo_w + 1), lo_w)) { W.nseg = 0; W.beg[0] = pos + 1; }
+}
+
+// Entry v of the walk -> cache row of its key, or -1 when no head attends it or an earlier segment had it;
+// hb = the set of heads that attend it (bit i: the key's groups meet gq[i]; every head inside the window).
+template <int NH>
+__device__ inline int decode_walk_key(const DecWalk& W, int nseg, int v, int lo_w, const int* __restrict__ lists, int n,
+                                      const uint32_t* __restrict__ mk, const uint32_t (&gq)[NH], uint32_t all_heads, uint32_t& hb)
+{
+    hb = 0;
+    if (nseg == 0) {
+        if (v >= lo_w) {
+            hb = all_heads;
+        } else {
+            const uint32_t mkj = mk[v];
+#pragma unroll
+            for (int i = 0; i < NH; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
+        }
+        return hb ? v : -1;
+    }
+    int sgi = 0;
+    while (sgi + 1 < nseg && v >= W.beg[sgi + 1]) ++sgi;
+    if (sgi == 0) {
+        hb = all_heads;
+        return lo_w + v;
+    }
+    const int j = lists[(size_t)W.grp[sgi] * n + (v - W.beg[sgi])];
+    const uint32_t pv = W.prev[sgi];
+    if (NH == 1) {                                // the key is in a group of the one query: only the dedup needs its mask
+        hb = 1u;
+        return (pv != 0u && (mk[j] & pv) != 0u) ? -1 : j;
+    }
+    const uint32_t mkj = mk[j];
+    if ((mkj & pv) != 0u) return -1;
+#pragma unroll
+    for (int i = 0; i < NH; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
+    return j;
+}
+
+// A chunk of the walk for the grouped-query kernels (256 threads): every thread resolves KPT entries (all loads
+// independent), then the skipped ones are squeezed out: wave ballots give every (pass, wavefront) its count, the
+// kept keys land in pass-major, wavefront-major order in s_j / s_hb, padded with -1 / 0 up to `cap` entries.
+// Returns the number of keys kept.  Two barriers inside.
+template <int KPT, int NH>
+__device__ inline int decode_resolve_chunk(const DecWalk& W, int nseg, int v0, int nk0, int lo_w, const int* __restrict__ lists, int n,
+                                           const uint32_t* __restrict__ mk, const uint32_t (&gq)[NH], uint32_t all_heads,
+                                           int* s_j, uint8_t* s_hb, int cap, int* s_wcnt)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int js[KPT];
+    uint32_t hbv[KPT];
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        js[it] = -1;
+        hbv[it] = 0;
+        const int i0 = it * 256 + tid;
+        if (i0 < nk0) js[it] = decode_walk_key<NH>(W, nseg, v0 + i0, lo_w, lists, n, mk, gq, all_heads, hbv[it]);
+    }
+    unsigned long long bal[KPT];
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        bal[it] = __ballot(js[it] >= 0);
+        if (lane == 0) s_wcnt[it * 4 + wave] = __popcll(bal[it]);
+    }
+    for (int i = tid; i < cap; i += 256) { s_j[i] = -1; s_hb[i] = 0; }
+    __syncthreads();
+    int nk = 0;
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        int before = 0;
+        for (int w2 = 0; w2 < it * 4 + wave; ++w2) before += s_wcnt[w2];
+        if (js[it] >= 0) {
+            const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+            const int dst = before + __popcll(bal[it] & lt);
+            s_j[dst] = js[it];
+            s_hb[dst] = (uint8_t)hbv[it];
+        }
+    }
+#pragma unroll
+    for (int w2 = 0; w2 < 4 * KPT; ++w2) nk += s_wcnt[w2];
+    __syncthreads();
+    return nk;
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMap hm, int pos_arg, const int* __restrict__ pos_dev, int span,
                                                           const T* __restrict__ q_new,
@@ -409,10 +517,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     constexpr int SLOTS = 64 / LPK;               // keys a wavefront handles side by side
     constexpr int PW = D + 4;                     // floats of one partial: o[D], max (log2 units), sum, count
     constexpr int U = sizeof(T) == 2 ? 8 : 4;     // keys in flight per slice: U K rows and U V rows loaded before use
-    __shared__ int s_beg[34];                     // start of every segment in the concatenated sequence
-    __shared__ int s_grp[33];
-    __shared__ uint32_t s_prev[33];
-    __shared__ int s_nseg;
+    __shared__ DecWalk s_walk;
     __shared__ int s_j[DEC_CHUNK];                // cache row of every key of the chunk, -1 = skipped
     __shared__ float s_red[4][SLOTS][PW];
 
@@ -429,29 +534,11 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     const int* lists = (const int*)(st + L.off_lists) + bhk * L.K * L.n;
     const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + bhk * L.n;
 
-    // segments: the window, then for every group of the query the list entries below the window
-    if (tid == 0) {
-        int nseg = 1, run = pos - lo_w + 1;
-        uint32_t prev = 0;
-        s_beg[0] = 0;
-        s_grp[0] = -1;
-        s_prev[0] = 0;
-        for (int g = 0; g < L.K; ++g) {
-            if (!((gq >> g) & 1u)) continue;
-            s_beg[nseg] = run;
-            s_grp[nseg] = g;
-            s_prev[nseg] = prev;
-            run += wptr[g];                       // list entries below the window (kept by the route kernel)
-            prev |= (1u << g);
-            ++nseg;
-        }
-        s_beg[nseg] = run;
-        s_nseg = nseg;
-        if (decode_scan_mode(run - (pos - lo_w + 1), lo_w)) { s_nseg = 0; s_beg[0] = pos + 1; }
-    }
+    if (tid == 0) decode_walk_init(s_walk, gq, wptr, L.K, pos, lo_w);
     __syncthreads();
-    const int nseg = s_nseg;                      // 0: scan mode, the sequence is the positions 0..pos themselves
-    const int vtotal = s_beg[nseg];
+    const int nseg = s_walk.nseg;
+    const int vtotal = s_walk.beg[nseg];
+    const uint32_t gq1[1] = {gq};
     float* mypart = part + ((size_t)bhq * L.max_parts + chunk) * PW;
     if (chunk * span * DEC_CHUNK >= vtotal) {     // nothing for this work-group
         for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
@@ -478,20 +565,8 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     const int nk = min(vtotal - v0, DEC_CHUNK);
     for (int i = tid; i < DEC_CHUNK; i += 256) {
         int j = -1;
-        if (i < nk) {
-            const int v = v0 + i;
-            int sgi = 0;
-            while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
-            if (nseg == 0) {
-                j = (v >= lo_w || (mk[v] & gq) != 0u) ? v : -1;
-            } else if (sgi == 0) {
-                j = lo_w + v;
-            } else {
-                j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
-                const uint32_t pv = s_prev[sgi];
-                if (pv != 0u && (mk[j] & pv) != 0u) j = -1;           // already taken from an earlier group
-            }
-        }
+        uint32_t hb;
+        if (i < nk) j = decode_walk_key<1>(s_walk, nseg, v0 + i, lo_w, lists, L.n, mk, gq1, 1u, hb);
         s_j[i] = j;
     }
     __syncthreads();
@@ -583,10 +658,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     constexpr int U = (G <= 2 && sizeof(T) == 2) ? 8 : 4;    // keys per slot and round: U K rows and U V rows in flight
     constexpr int KPT = DEC_CHUNK / 256;                     // keys every thread resolves per chunk
     constexpr int HB = G < 4 ? G : 4;                        // heads folded through LDS at a time
-    __shared__ int s_beg[34];
-    __shared__ int s_grp[33];
-    __shared__ uint32_t s_prev[33];
-    __shared__ int s_nseg;
+    __shared__ DecWalk s_walk;
     __shared__ int s_j[DEC_CHUNK + 4 * SLOTS * U];    // cache rows of the chunk's keys, squeezed; padded with -1
     __shared__ uint8_t s_hb[DEC_CHUNK + 4 * SLOTS * U];   // which of the G heads attend the key
     __shared__ int s_wcnt[4 * KPT];
@@ -609,24 +681,10 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     const int* lists = (const int*)(st + L.off_lists) + bhk * L.K * L.n;
     const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + bhk * L.n;
 
-    if (tid == 0) {
-        int nseg = 1, run = pos - lo_w + 1;
-        uint32_t prev = 0;
-        s_beg[0] = 0; s_grp[0] = -1; s_prev[0] = 0;
-        for (int g = 0; g < L.K; ++g) {
-            if (!((gu >> g) & 1u)) continue;
-            s_beg[nseg] = run; s_grp[nseg] = g; s_prev[nseg] = prev;
-            run += wptr[g];
-            prev |= (1u << g);
-            ++nseg;
-        }
-        s_beg[nseg] = run;
-        s_nseg = nseg;
-        if (decode_scan_mode(run - (pos - lo_w + 1), lo_w)) { s_nseg = 0; s_beg[0] = pos + 1; }
-    }
+    if (tid == 0) decode_walk_init(s_walk, gu, wptr, L.K, pos, lo_w);
     __syncthreads();
-    const int nseg = s_nseg;                      // 0: scan mode, the sequence is the positions 0..pos themselves
-    const int vtotal = s_beg[nseg];
+    const int nseg = s_walk.nseg;
+    const int vtotal = s_walk.beg[nseg];
     // this work-group walks `span` consecutive chunks of the sequence and leaves one partial per head
     if (chunk * span * DEC_CHUNK >= vtotal) {
         for (int i = 0; i < G; ++i) {
@@ -717,72 +775,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     const int v0 = (chunk * span + cc) * DEC_CHUNK;
     if (v0 >= vtotal) break;                      // uniform over the work-group
     if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
-    // resolve KPT keys per thread (all loads independent), then squeeze the skipped ones out: wave ballots
-    // give every (pass, wavefront) its count, the kept keys land in pass-major, wavefront-major order
-    {
-        const int nk0 = min(vtotal - v0, DEC_CHUNK);
-        int js[KPT];
-        uint32_t hbv[KPT];
-#pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            int j = -1;
-            uint32_t hb = 0;
-            const int i0 = it * 256 + tid;
-            if (i0 < nk0) {
-                const int v = v0 + i0;
-                int sgi = 0;
-                while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
-                if (nseg == 0) {
-                    if (v >= lo_w) {
-                        hb = (1u << G) - 1u;
-                    } else {
-                        const uint32_t mkj = mk[v];
-#pragma unroll
-                        for (int i = 0; i < G; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
-                    }
-                    j = hb ? v : -1;
-                } else if (sgi == 0) {
-                    j = lo_w + v;
-                    hb = (1u << G) - 1u;
-                } else {
-                    j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
-                    const uint32_t mkj = mk[j];
-                    if ((mkj & s_prev[sgi]) != 0u) {
-                        j = -1;                                       // already taken from an earlier group
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < G; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
-                    }
-                }
-            }
-            js[it] = j;
-            hbv[it] = hb;
-        }
-        unsigned long long bal[KPT];
-#pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            bal[it] = __ballot(js[it] >= 0);
-            if (lane == 0) s_wcnt[it * 4 + wave] = __popcll(bal[it]);
-        }
-        for (int i = tid; i < DEC_CHUNK + 4 * SLOTS * U; i += 256) s_j[i] = -1;
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            int before = 0;
-            for (int w2 = 0; w2 < it * 4 + wave; ++w2) before += s_wcnt[w2];
-            if (js[it] >= 0) {
-                const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-                const int dst = before + __popcll(bal[it] & lt);
-                s_j[dst] = js[it];
-                s_hb[dst] = (uint8_t)hbv[it];
-            }
-        }
-        __syncthreads();
-    }
-    int nk = 0;
-#pragma unroll
-    for (int w2 = 0; w2 < 4 * KPT; ++w2) nk += s_wcnt[w2];
-
+    const int nk = decode_resolve_chunk<KPT, G>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
+                                                (1u << G) - 1u, s_j, s_hb, DEC_CHUNK + 4 * SLOTS * U, s_wcnt);
     constexpr int RSTEP = 4 * SLOTS * U;          // keys of one round of the four wavefronts
     // (Keeping the loads of the next round in flight while this one is folded costs a second set of row
     // registers and a wavefront of occupancy: slower at every context length measured.)
@@ -909,10 +903,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     constexpr int GMAX = 8;
     constexpr int RED_BYTES = GMAX * 4 * PW * 4;
     constexpr int BUF_BYTES = 4 * VBYTES > RED_BYTES ? 4 * VBYTES : RED_BYTES;
-    __shared__ int s_beg[34];
-    __shared__ int s_grp[33];
-    __shared__ uint32_t s_prev[33];
-    __shared__ int s_nseg;
+    __shared__ DecWalk s_walk;
     __shared__ int s_j[DEC_CHUNK + RSTEP];        // cache rows of the chunk's keys, squeezed; padded with -1
     __shared__ __attribute__((aligned(4))) uint8_t s_hb[DEC_CHUNK + RSTEP];   // which heads attend the key; 0 in the padding
     __shared__ int s_wcnt[4 * KPT];
@@ -936,24 +927,10 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     const int* lists = (const int*)(st + L.off_lists) + bhk * L.K * L.n;
     const uint32_t* mk = (const uint32_t*)(st + L.off_mk) + bhk * L.n;
 
-    if (tid == 0) {
-        int nseg = 1, run = pos - lo_w + 1;
-        uint32_t prev = 0;
-        s_beg[0] = 0; s_grp[0] = -1; s_prev[0] = 0;
-        for (int g = 0; g < L.K; ++g) {
-            if (!((gu >> g) & 1u)) continue;
-            s_beg[nseg] = run; s_grp[nseg] = g; s_prev[nseg] = prev;
-            run += wptr[g];
-            prev |= (1u << g);
-            ++nseg;
-        }
-        s_beg[nseg] = run;
-        s_nseg = nseg;
-        if (decode_scan_mode(run - (pos - lo_w + 1), lo_w)) { s_nseg = 0; s_beg[0] = pos + 1; }
-    }
+    if (tid == 0) decode_walk_init(s_walk, gu, wptr, L.K, pos, lo_w);
     __syncthreads();
-    const int nseg = s_nseg;                      // 0: scan mode, the sequence is the positions 0..pos themselves
-    const int vtotal = s_beg[nseg];
+    const int nseg = s_walk.nseg;
+    const int vtotal = s_walk.beg[nseg];
     if (chunk * span * DEC_CHUNK >= vtotal) {
         for (int i = 0; i < G; ++i) {
             float* mypart = part + ((bhq0 + i) * L.max_parts + chunk) * PW;
@@ -991,69 +968,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     const int v0 = (chunk * span + cc) * DEC_CHUNK;
     if (v0 >= vtotal) break;                      // uniform over the work-group
     if (cc > 0) __syncthreads();                  // the last chunk's keys have been read
-    {
-        const int nk0 = min(vtotal - v0, DEC_CHUNK);
-        int js[KPT];
-        uint32_t hbv[KPT];
-#pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            int j = -1;
-            uint32_t hb = 0;
-            const int i0 = it * 256 + tid;
-            if (i0 < nk0) {
-                const int v = v0 + i0;
-                int sgi = 0;
-                while (sgi + 1 < nseg && v >= s_beg[sgi + 1]) ++sgi;
-                if (nseg == 0) {
-                    if (v >= lo_w) {
-                        hb = (1u << G) - 1u;
-                    } else {
-                        const uint32_t mkj = mk[v];
-#pragma unroll
-                        for (int i = 0; i < GMAX; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
-                    }
-                    j = hb ? v : -1;
-                } else if (sgi == 0) {
-                    j = lo_w + v;
-                    hb = (1u << G) - 1u;
-                } else {
-                    j = lists[(size_t)s_grp[sgi] * L.n + (v - s_beg[sgi])];
-                    const uint32_t mkj = mk[j];
-                    if ((mkj & s_prev[sgi]) != 0u) {
-                        j = -1;                                       // already taken from an earlier group
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < GMAX; ++i) hb |= ((mkj & gq[i]) != 0u) ? (1u << i) : 0u;
-                    }
-                }
-            }
-            js[it] = j;
-            hbv[it] = hb;
-        }
-        unsigned long long bal[KPT];
-#pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            bal[it] = __ballot(js[it] >= 0);
-            if (lane == 0) s_wcnt[it * 4 + wave] = __popcll(bal[it]);
-        }
-        for (int i = tid; i < DEC_CHUNK + RSTEP; i += 256) { s_j[i] = -1; s_hb[i] = 0; }
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < KPT; ++it) {
-            int before = 0;
-            for (int w2 = 0; w2 < it * 4 + wave; ++w2) before += s_wcnt[w2];
-            if (js[it] >= 0) {
-                const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-                const int dst = before + __popcll(bal[it] & lt);
-                s_j[dst] = js[it];
-                s_hb[dst] = (uint8_t)hbv[it];
-            }
-        }
-        __syncthreads();
-    }
-    int nk = 0;
-#pragma unroll
-    for (int w2 = 0; w2 < 4 * KPT; ++w2) nk += s_wcnt[w2];
+    const int nk = decode_resolve_chunk<KPT, GMAX>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
+                                                   (1u << G) - 1u, s_j, s_hb, DEC_CHUNK + RSTEP, s_wcnt);
 
     for (int r0 = wave * 32; r0 < nk; r0 += RSTEP) {
         // the V rows of the round -> LDS (wave load i holds keys i*RPI ..+RPI of the round)
