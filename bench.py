@@ -205,6 +205,27 @@ def main():
                 del o_sd
             except Exception as exc:
                 print("bench.py: torch SDPA sanity run skipped: %r" % (exc,), file=sys.stderr)
+            # ... and what the vendor's GEMM library sustains on N(0,1) operands of this dtype on this machine: the
+            # rate a dense bf16/fp16 contraction on real data reaches here (the chip's clock follows the data)
+            try:
+                gen = torch.Generator(device="cuda").manual_seed(4242)
+                ga = torch.randn((8192, 8192), generator=gen, device="cuda", dtype=torch.float32).to(q.dtype)
+                gb = torch.randn((8192, 8192), generator=gen, device="cuda", dtype=torch.float32).to(q.dtype)
+                for _ in range(3):
+                    gc = ga @ gb
+                torch.cuda.synchronize()
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                ev[0].record()
+                for _ in range(20):
+                    gc = ga @ gb
+                ev[1].record()
+                torch.cuda.synchronize()
+                ms_mm = ev[0].elapsed_time(ev[1]) / 20
+                result["torch_matmul_8192"] = {"ms": ms_mm, "tflops": 2.0 * 8192.0 ** 3 / (ms_mm * 1e-3) / 1e12,
+                                               "what": "torch.matmul of two 8192 x 8192 N(0,1) matrices of the workload's dtype"}
+                del ga, gb, gc
+            except Exception as exc:
+                print("bench.py: torch matmul sanity run skipped: %r" % (exc,), file=sys.stderr)
 
     # context: other shapes through the same step (assign + attention), reported beside the headline workload:
     # the GPT-2 124M shape (short sequences), and the headline shape in half precision and at other head dims
