@@ -16,8 +16,8 @@
 //      chunks of DEC_CHUNK keys with an online softmax per chunk.  When the lists together hold at least
 //      as many entries as there are positions below the window (few groups, several of them per query),
 //      the positions 0..pos are walked instead and every key's mask is tested against the query's;
-//      grouped-query heads share one walk over the union of their keys, and 16-bit caches with 64 or 128
-//      components per row run both products on the matrix cores;
+//      grouped-query heads share one walk over the union of their keys, and 16-bit caches run both
+//      products on the matrix cores;
 //   3. merges the chunks' partial (o, max, sum) by their log-sum-exp weights (App. D "Merge", n-ary).
 #include "focus_internal.h"
 #include <algorithm>
@@ -830,7 +830,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
 }
 
 // ---------------------------------------------------------------- step 2, grouped-query form on the matrix cores
-// The same walk as decode_attn_gqa_kernel for 16-bit caches with 128- or 256-byte rows, with both products on
+// The same walk as decode_attn_gqa_kernel for 16-bit caches, with both products on
 // v_mfma_f32_16x16x32: a wavefront takes 32 keys per round as two blocks of 16.
 //   S^T[key, head] = K[key, :] . Q[head, :]   A = K rows straight from the cache (lane: key l%16, components
 //                                             32*kb + 8*(l/16) ..+8, one 16-byte load per product), B = the G <= 8
@@ -888,14 +888,14 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
 {
     typedef DecHalf<F16> HT;
     typedef typename HT::V8 V8;
-    static_assert(D == 64 || D == 128, "rows of 128 or 256 bytes");
+    static_assert(D % 16 == 0 && D >= 64 && D <= 256, "whole 16-component blocks");
     constexpr int RB = D * 2;                     // bytes of a cache row
-    constexpr int LPR = RB / 16;                  // lanes that load one V row
-    constexpr int RPI = 64 / LPR;                 // V rows per wave load
-    constexpr int NI = 32 / RPI;                  // wave loads per round of 32 keys
+    constexpr int LPR = RB / 16;                  // lanes that load one V row (8, 10, 12, 16, 32)
+    constexpr int RPI = 64 / LPR;                 // whole V rows per wave load (the lanes past RPI * LPR repeat lane 0)
+    constexpr int NI = (32 + RPI - 1) / RPI;      // wave loads per round of 32 keys
     constexpr int IPITCH = 1024 + 32;             // LDS bytes from one wave load to the next
     constexpr int VBYTES = NI * IPITCH;           // V rows of a round, per wavefront
-    constexpr int KB = D / 32;                    // products of one S^T block
+    constexpr int KB = (D + 31) / 32;             // products of one S^T block (the last one partly zero for d = 80)
     constexpr int NB = D / 16;                    // 16-component blocks of O^T
     constexpr int PW = D + 4;
     constexpr int KPT = DEC_CHUNK / 256;
@@ -943,7 +943,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
         dec_u32x4 w = {0u, 0u, 0u, 0u};
-        if (m16 < G) w = *(const dec_u32x4*)(q_new + (bhq0 + m16) * D + 32 * kb + 8 * qg);
+        if (m16 < G && 32 * kb + 8 * qg < D) w = *(const dec_u32x4*)(q_new + (bhq0 + m16) * D + 32 * kb + 8 * qg);
         qv[kb] = __builtin_bit_cast(V8, w);
     }
     dec_f32x4 oacc[NB];
@@ -955,6 +955,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     const uint16_t* kbase = kc + bhk * L.n * D + 8 * qg;
     const uint16_t* vbase = vc + bhk * L.n * D;
     const unsigned lds_v = (unsigned)(uintptr_t)(&s_buf[0]) + (unsigned)wave * VBYTES;
+    const int dlane = (lane < RPI * LPR) ? lane : 0;                  // the lane whose row chunk this lane loads
     const char* my_v = s_buf + wave * VBYTES;
     // k-slot e of lane group qg holds key 16*(e/4) + 4*qg + e%4 of the round: LDS offset of that key's V row
     int vrow[8];
@@ -973,18 +974,24 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
 
     for (int r0 = wave * 32; r0 < nk; r0 += RSTEP) {
         // the V rows of the round -> LDS (wave load i holds keys i*RPI ..+RPI of the round)
+        // (a wave load past the 32nd key fetches rows of the next round or row 0: read by nobody)
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int jv = max(s_j[r0 + i * RPI + lane / LPR], 0);
-            dec_dma16(vbase, (unsigned)jv * (unsigned)RB + (unsigned)(lane % LPR) * 16u, lds_v + i * IPITCH);
+            const int jv = max(s_j[r0 + i * RPI + dlane / LPR], 0);
+            dec_dma16(vbase, (unsigned)jv * (unsigned)RB + (unsigned)(dlane % LPR) * 16u, lds_v + i * IPITCH);
         }
         // the K rows of the two blocks -> registers
         const int ja = max(s_j[r0 + m16], 0), jb = max(s_j[r0 + 16 + m16], 0);
         V8 ka[KB], kb2[KB];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            ka[kb] = __builtin_bit_cast(V8, *(const dec_u32x4*)(kbase + (size_t)ja * D + 32 * kb));
-            kb2[kb] = __builtin_bit_cast(V8, *(const dec_u32x4*)(kbase + (size_t)jb * D + 32 * kb));
+            dec_u32x4 wa = {0u, 0u, 0u, 0u}, wb = {0u, 0u, 0u, 0u};
+            if (32 * kb + 8 * qg < D) {                               // false only in the last product of d = 80
+                wa = *(const dec_u32x4*)(kbase + (size_t)ja * D + 32 * kb);
+                wb = *(const dec_u32x4*)(kbase + (size_t)jb * D + 32 * kb);
+            }
+            ka[kb] = __builtin_bit_cast(V8, wa);
+            kb2[kb] = __builtin_bit_cast(V8, wb);
         }
         const uint32_t hba = *(const uint32_t*)(&s_hb[r0 + 4 * qg]);
         const uint32_t hbb = *(const uint32_t*)(&s_hb[r0 + 16 + 4 * qg]);
@@ -1199,8 +1206,8 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     const int nparts = (nchunks + span - 1) / span;
     if (grouped) {
         dim3 grid(nparts, L.B * L.Hkv);
-        // 16-bit caches with 128- or 256-byte rows whose byte offsets fit 32 bits: the matrix-core form
-        if constexpr (sizeof(T) == 2 && (D == 64 || D == 128)) {
+        // 16-bit caches whose byte offsets fit 32 bits: the matrix-core form
+        if constexpr (sizeof(T) == 2) {
             if ((size_t)L.n * D * 2 <= 0xffffffffull) {
                 hipLaunchKernelGGL((decode_attn_gqa_mfma_kernel<std::is_same<T, f16_bits>::value, D>), grid, dim3(256), 0, s, L, G, pos,
                                    pos_dev, span, (const uint16_t*)q_new, (const uint16_t*)kc, (const uint16_t*)vc, (const char*)st,
