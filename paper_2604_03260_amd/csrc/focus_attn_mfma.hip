@@ -74,6 +74,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int NTHR = 256;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift before O is rescaled
+constexpr float CAP_POLY_Z = 0.3f;          // |score*scale/softcap| up to which tanh is taken as its Taylor polynomial to z^5
 
 // within a 16-key group: MFMA k-slot p16 = h*8 + e  <->  key 8*(e/4) + 4*h + e%4,
 // the order in which a lane of the S^T accumulator holds its keys
@@ -350,6 +351,12 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     const float sl2 = L.scale * LOG2E;
     const float cap_l2 = L.softcap * LOG2E;
     const float two_over_cap_l2 = (L.softcap > 0.f) ? 2.f * L.scale * LOG2E / L.softcap : 0.f;
+    // cap*log2(e)*tanh(s*a), a = scale/cap, as s*(c1 + c3 s^2 + c5 s^4) while |s*a| <= CAP_POLY_Z
+    const float cap_a = (L.softcap > 0.f) ? L.scale / L.softcap : 0.f;
+    const float cap_c1 = L.scale * LOG2E;
+    const float cap_c3 = -cap_c1 * cap_a * cap_a * (1.f / 3.f);
+    const float cap_c5 = cap_c1 * cap_a * cap_a * cap_a * cap_a * (2.f / 15.f);
+    const float cap_poly_lim = (L.softcap > 0.f) ? CAP_POLY_Z / cap_a : 0.f;
 
     const char* kc_base = ws + L.off_kc + (size_t)bhk * L.NKP * (D * 2);
     const char* vt_base = ws + L.off_vt + (size_t)bhk * L.NKP * (D * 2);
@@ -542,9 +549,22 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         }                                                                                                \
     } else                                                                                               \
     if constexpr (SOFTCAP) {                                                                             \
-        _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                 \
-            const float e2_ = __builtin_amdgcn_exp2f(SIN[r] * two_over_cap_l2);                          \
-            SIN[r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2_);                           \
+        /* cap*tanh(z), z = s*scale/cap.  While every |z| of the unit is below CAP_POLY_Z the odd Taylor */ \
+        /* polynomial to z^5 stands in for tanh (error below 17 z^7 / 315: 6e-4 in the logit at cap 50, */ \
+        /* under the rounding of the 16-bit probabilities): four plain instructions per score instead   */ \
+        /* of an exp2 and a reciprocal.  Otherwise the exact form 1 - 2 / (1 + e^(2z)).                 */ \
+        float am_ = fabsf(SIN[0]);                                                                       \
+        _Pragma("unroll") for (int r = 1; r < 16; ++r) am_ = fmaxf(am_, fabsf(SIN[r]));                  \
+        if (__any(!(am_ <= cap_poly_lim))) {                                                             \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                             \
+                const float e2_ = __builtin_amdgcn_exp2f(SIN[r] * two_over_cap_l2);                      \
+                SIN[r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2_);                       \
+            }                                                                                            \
+        } else {                                                                                         \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                             \
+                const float u_ = SIN[r] * SIN[r];                                                        \
+                SIN[r] *= fmaf(fmaf(u_, cap_c5, cap_c3), u_, cap_c1);                                    \
+            }                                                                                            \
         }                                                                                                \
     }                                                                                                    \
     if (SOFT) {                          /* masked above */                                              \
