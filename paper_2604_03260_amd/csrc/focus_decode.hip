@@ -427,9 +427,12 @@ __device__ inline void decode_walk_init(DecWalk& W, uint32_t groups, const int* 
 
 // Entry v of the walk -> cache row of its key, or -1 when no head attends it or an earlier segment had it;
 // hb = the set of heads that attend it (bit i: the key's groups meet gq[i]; every head inside the window).
+// single: every key sits in one group only (topk = 1), so a list entry's heads follow from its list's group and
+// the key's mask is not read.
 template <int NH>
 __device__ inline int decode_walk_key(const DecWalk& W, int nseg, int v, int lo_w, const int* __restrict__ lists, int n,
-                                      const uint32_t* __restrict__ mk, const uint32_t (&gq)[NH], uint32_t all_heads, uint32_t& hb)
+                                      const uint32_t* __restrict__ mk, const uint32_t (&gq)[NH], uint32_t all_heads, bool single,
+                                      uint32_t& hb)
 {
     hb = 0;
     if (nseg == 0) {
@@ -450,6 +453,11 @@ __device__ inline int decode_walk_key(const DecWalk& W, int nseg, int v, int lo_
     }
     const int j = lists[(size_t)W.grp[sgi] * n + (v - W.beg[sgi])];
     const uint32_t pv = W.prev[sgi];
+    if (single) {
+#pragma unroll
+        for (int i = 0; i < NH; ++i) hb |= ((gq[i] >> W.grp[sgi]) & 1u) << i;
+        return j;
+    }
     if (NH == 1) {                                // the key is in a group of the one query: only the dedup needs its mask
         hb = 1u;
         return (pv != 0u && (mk[j] & pv) != 0u) ? -1 : j;
@@ -467,7 +475,7 @@ __device__ inline int decode_walk_key(const DecWalk& W, int nseg, int v, int lo_
 // Returns the number of keys kept.  Two barriers inside.
 template <int KPT, int NH>
 __device__ inline int decode_resolve_chunk(const DecWalk& W, int nseg, int v0, int nk0, int lo_w, const int* __restrict__ lists, int n,
-                                           const uint32_t* __restrict__ mk, const uint32_t (&gq)[NH], uint32_t all_heads,
+                                           const uint32_t* __restrict__ mk, const uint32_t (&gq)[NH], uint32_t all_heads, bool single,
                                            int* s_j, uint8_t* s_hb, int cap, int* s_wcnt)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -478,7 +486,7 @@ __device__ inline int decode_resolve_chunk(const DecWalk& W, int nseg, int v0, i
         js[it] = -1;
         hbv[it] = 0;
         const int i0 = it * 256 + tid;
-        if (i0 < nk0) js[it] = decode_walk_key<NH>(W, nseg, v0 + i0, lo_w, lists, n, mk, gq, all_heads, hbv[it]);
+        if (i0 < nk0) js[it] = decode_walk_key<NH>(W, nseg, v0 + i0, lo_w, lists, n, mk, gq, all_heads, single, hbv[it]);
     }
     unsigned long long bal[KPT];
 #pragma unroll
@@ -540,7 +548,7 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
     const int vtotal = s_walk.beg[nseg];
     const uint32_t gq1[1] = {gq};
     float* mypart = part + ((size_t)bhq * L.max_parts + chunk) * PW;
-    if (chunk * span * DEC_CHUNK >= vtotal) {     // nothing for this work-group
+    if ((long)chunk * DEC_CHUNK >= vtotal) {     // nothing for this work-group
         for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
         return;
     }
@@ -558,15 +566,17 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(DecodeLayout L, HeadMa
 
     // rounds of SLOTS*U keys per wavefront, the 4 wavefronts interleaved; one softmax update per round
     for (int cc = 0; cc < span; ++cc) {
-    const int v0 = (chunk * span + cc) * DEC_CHUNK;
-    if (v0 >= vtotal) break;                      // uniform over the work-group
+    // chunks chunk, chunk + gridDim.x, ...: however short the walk turns out, its chunks spread over the work-groups
+    const long v0l = ((long)chunk + (long)cc * gridDim.x) * DEC_CHUNK;
+    if (v0l >= vtotal) break;                      // uniform over the work-group
+    const int v0 = (int)v0l;
     if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
     // resolve the whole chunk at once: list entry -> position -> (mask check); all loads independent
     const int nk = min(vtotal - v0, DEC_CHUNK);
     for (int i = tid; i < DEC_CHUNK; i += 256) {
         int j = -1;
         uint32_t hb;
-        if (i < nk) j = decode_walk_key<1>(s_walk, nseg, v0 + i, lo_w, lists, L.n, mk, gq1, 1u, hb);
+        if (i < nk) j = decode_walk_key<1>(s_walk, nseg, v0 + i, lo_w, lists, L.n, mk, gq1, 1u, L.topk == 1, hb);
         s_j[i] = j;
     }
     __syncthreads();
@@ -685,8 +695,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     __syncthreads();
     const int nseg = s_walk.nseg;
     const int vtotal = s_walk.beg[nseg];
-    // this work-group walks `span` consecutive chunks of the sequence and leaves one partial per head
-    if (chunk * span * DEC_CHUNK >= vtotal) {
+    // this work-group walks up to `span` chunks of the sequence, gridDim.x apart, and leaves one partial per head
+    if ((long)chunk * DEC_CHUNK >= vtotal) {
         for (int i = 0; i < G; ++i) {
             float* mypart = part + ((bhq0 + i) * L.max_parts + chunk) * PW;
             for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
@@ -772,11 +782,13 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     };
 
     for (int cc = 0; cc < span; ++cc) {
-    const int v0 = (chunk * span + cc) * DEC_CHUNK;
-    if (v0 >= vtotal) break;                      // uniform over the work-group
+    // chunks chunk, chunk + gridDim.x, ...: however short the walk turns out, its chunks spread over the work-groups
+    const long v0l = ((long)chunk + (long)cc * gridDim.x) * DEC_CHUNK;
+    if (v0l >= vtotal) break;                      // uniform over the work-group
+    const int v0 = (int)v0l;
     if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
     const int nk = decode_resolve_chunk<KPT, G>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
-                                                (1u << G) - 1u, s_j, s_hb, DEC_CHUNK + 4 * SLOTS * U, s_wcnt);
+                                                (1u << G) - 1u, L.topk == 1, s_j, s_hb, DEC_CHUNK + 4 * SLOTS * U, s_wcnt);
     constexpr int RSTEP = 4 * SLOTS * U;          // keys of one round of the four wavefronts
     // (Keeping the loads of the next round in flight while this one is folded costs a second set of row
     // registers and a wavefront of occupancy: slower at every context length measured.)
@@ -931,7 +943,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     __syncthreads();
     const int nseg = s_walk.nseg;
     const int vtotal = s_walk.beg[nseg];
-    if (chunk * span * DEC_CHUNK >= vtotal) {
+    if ((long)chunk * DEC_CHUNK >= vtotal) {
         for (int i = 0; i < G; ++i) {
             float* mypart = part + ((bhq0 + i) * L.max_parts + chunk) * PW;
             for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
@@ -966,11 +978,13 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     }
 
     for (int cc = 0; cc < span; ++cc) {
-    const int v0 = (chunk * span + cc) * DEC_CHUNK;
-    if (v0 >= vtotal) break;                      // uniform over the work-group
+    // chunks chunk, chunk + gridDim.x, ...: however short the walk turns out, its chunks spread over the work-groups
+    const long v0l = ((long)chunk + (long)cc * gridDim.x) * DEC_CHUNK;
+    if (v0l >= vtotal) break;                      // uniform over the work-group
+    const int v0 = (int)v0l;
     if (cc > 0) __syncthreads();                  // the last chunk's keys have been read
     const int nk = decode_resolve_chunk<KPT, GMAX>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
-                                                   (1u << G) - 1u, s_j, s_hb, DEC_CHUNK + RSTEP, s_wcnt);
+                                                   (1u << G) - 1u, L.topk == 1, s_j, s_hb, DEC_CHUNK + RSTEP, s_wcnt);
 
     for (int r0 = wave * 32; r0 < nk; r0 += RSTEP) {
         // the V rows of the round -> LDS (wave load i holds keys i*RPI ..+RPI of the round)
