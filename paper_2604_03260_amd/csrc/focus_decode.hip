@@ -1115,37 +1115,39 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int p
 {
     constexpr int PW = D + 4;
     constexpr int TPG = D / 4;                    // threads per group
-    constexpr int NG = 256 / TPG;                 // whole groups; the threads past NG * TPG (d = 80, 96) only help with the max
-    __shared__ float s_w[4];
+    constexpr int NG = 256 / TPG;                 // whole groups; the threads past NG * TPG (d = 80, 96) idle
     __shared__ float s_acc[NG][D + 4];
     const int tid = threadIdx.x, t = tid % TPG, grp = tid / TPG, bhq = blockIdx.x;
     const int pos = pos_dev ? pos_dev[bhq / L.Hq] : pos_arg;
     if (pos < 0 || pos >= L.n) return;                // the other kernels of the step skipped this sequence too
     const float* p0 = part + (size_t)bhq * L.max_parts * PW;
-    float mx = -INFINITY;
-    for (int c = tid; c < nchunks; c += 256) mx = fmaxf(mx, p0[(size_t)c * PW + D]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-    if ((tid & 63) == 0) s_w[tid >> 6] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(s_w[0], s_w[1]), fmaxf(s_w[2], s_w[3]));
+    // every group of threads folds its share of the partials against a running maximum of its own (one pass over
+    // the partials, four of them in flight per group); the groups then meet in LDS
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float lsum = 0.f, csum = 0.f;
-    // four partials in flight per group of threads: the loop is a chain of dependent L2 round trips otherwise
+    float mrun = -INFINITY, lsum = 0.f, csum = 0.f;
     constexpr int MU = 4;
     for (int c0 = grp; grp < NG && c0 < nchunks; c0 += NG * MU) {
         float4 tail[MU], ov[MU];
 #pragma unroll
         for (int u = 0; u < MU; ++u) {
-            const int c = min(c0 + u * NG, nchunks - 1);              // clamped loads, weighed zero below
+            const int c = min(c0 + u * NG, nchunks - 1);              // clamped loads, skipped below
             const float* p = p0 + (size_t)c * PW;
             tail[u] = *(const float4*)(p + D);                        // max (log2 units), sum, count, unused
             ov[u] = *(const float4*)(p + 4 * t);
         }
+        float mnew = mrun;
+#pragma unroll
+        for (int u = 0; u < MU; ++u)
+            if (c0 + u * NG < nchunks) mnew = fmaxf(mnew, tail[u].x);
+        if (mnew == -INFINITY) continue;                              // nothing attended so far
+        const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);      // mrun = -inf: 0
+        mrun = mnew;
+        acc.x *= alpha; acc.y *= alpha; acc.z *= alpha; acc.w *= alpha;
+        lsum *= alpha;
 #pragma unroll
         for (int u = 0; u < MU; ++u) {
             if (c0 + u * NG >= nchunks || tail[u].x == -INFINITY) continue;
-            const float wgt = __builtin_amdgcn_exp2f(tail[u].x - mx);
+            const float wgt = __builtin_amdgcn_exp2f(tail[u].x - mnew);
             acc.x = fmaf(wgt, ov[u].x, acc.x); acc.y = fmaf(wgt, ov[u].y, acc.y);
             acc.z = fmaf(wgt, ov[u].z, acc.z); acc.w = fmaf(wgt, ov[u].w, acc.w);
             lsum = fmaf(wgt, tail[u].y, lsum);
@@ -1154,12 +1156,22 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeLayout L, int p
     }
     if (grp < NG) {
         *(float4*)(&s_acc[grp][4 * t]) = acc;
-        if (t == 0) { s_acc[grp][D] = lsum; s_acc[grp][D + 1] = csum; }
+        if (t == 0) { s_acc[grp][D] = lsum; s_acc[grp][D + 1] = csum; s_acc[grp][D + 2] = mrun; }
     }
     __syncthreads();
     if (tid < D) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int g2 = 0; g2 < NG; ++g2) mx = fmaxf(mx, s_acc[g2][D + 2]);
         float a = 0.f, ls = 0.f, cs = 0.f;
-        for (int g2 = 0; g2 < NG; ++g2) { a += s_acc[g2][tid]; ls += s_acc[g2][D]; cs += s_acc[g2][D + 1]; }
+#pragma unroll
+        for (int g2 = 0; g2 < NG; ++g2) {
+            const float mg = s_acc[g2][D + 2];
+            const float wgt = (mg == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mg - mx);
+            a = fmaf(wgt, s_acc[g2][tid], a);
+            ls = fmaf(wgt, s_acc[g2][D], ls);
+            cs += s_acc[g2][D + 1];
+        }
         out[(size_t)bhq * D + tid] = dec_from_f32<T>(ls > 0.f ? a / ls : 0.f);
         if (tid == 0) {
             if (lse) lse[bhq] = (mx + __builtin_amdgcn_logf(ls)) * (1.f / DEC_LOG2E);
