@@ -1218,8 +1218,10 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     float* part = (float*)(st + L.off_part);
     // grouped-query form when query heads hk*G .. hk*G+G-1 share KV head hk (the default map)
     const int G = (L.Hq % L.Hkv == 0) ? L.Hq / L.Hkv : 0;
-    bool grouped = (G == 1 || G == 2 || G == 4 || G == 8);
-    for (int h = 0; grouped && h < L.Hq; ++h) grouped = hm.kv[h] == h / G;
+    bool default_map = G >= 1;
+    for (int h = 0; default_map && h < L.Hq; ++h) default_map = hm.kv[h] == h / G;
+    // the vector form is built for 1, 2, 4 and 8 heads per KV head, the matrix-core form takes any number up to 8
+    bool grouped = default_map && (G == 1 || G == 2 || G == 4 || G == 8);
     // upper bound of the key sequence known on the host: pos + 1 entries.  The lists are walked only while they
     // hold fewer entries than there are positions below the window, the positions themselves otherwise.
     // (With the position in device memory: the bound of the last position the caches can hold; work-groups
@@ -1230,11 +1232,12 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     // merge stays short at any context length
     const int span = (nchunks + DEC_MAX_PARTS - 1) / DEC_MAX_PARTS;
     const int nparts = (nchunks + span - 1) / span;
+    if (sizeof(T) == 2 && default_map && G <= 8 && (size_t)L.n * D * 2 <= 0xffffffffull) grouped = true;
     if (grouped) {
         dim3 grid(nparts, L.B * L.Hkv);
         // 16-bit caches whose byte offsets fit 32 bits: the matrix-core form
         if constexpr (sizeof(T) == 2) {
-            if ((size_t)L.n * D * 2 <= 0xffffffffull) {
+            if (G <= 8 && (size_t)L.n * D * 2 <= 0xffffffffull) {
                 hipLaunchKernelGGL((decode_attn_gqa_mfma_kernel<std::is_same<T, f16_bits>::value, D>), grid, dim3(256), 0, s, L, G, pos,
                                    pos_dev, span, (const uint16_t*)q_new, (const uint16_t*)kc, (const uint16_t*)vc, (const char*)st,
                                    part);

@@ -72,19 +72,22 @@ CASES = [
     (1, 2, 2, 520, 64, "bf16", 1, 1, 4, 0.0, 515, 5),
     (1, 8, 1, 600, 64, "bf16", 8, 2, 16, 0.0, 590, 10),         # 8 query heads on one KV head
     (2, 16, 2, 900, 128, "f32", 6, 2, 30, 0.0, 880, 8),
-    (1, 6, 2, 400, 64, "bf16", 4, 2, 10, 0.0, 390, 10),          # 3 query heads per KV head: per-head kernel
+    (1, 6, 2, 400, 64, "bf16", 4, 2, 10, 0.0, 390, 10),          # 3 query heads per KV head (matrix cores)
+    (1, 6, 2, 400, 64, "f32", 4, 2, 10, 0.0, 390, 10),           # ... in fp32: per-head kernel
+    (2, 14, 2, 900, 128, "f16", 8, 2, 50, 0.0, 893, 7),          # 7 query heads per KV head
+    (1, 5, 1, 700, 96, "bf16", 4, 1, 30, 0.0, 695, 5),           # 5 query heads per KV head, d = 96
     (1, 2, 1, 60000, 64, "bf16", 4, 2, 300, 0.0, 59996, 4),      # long context: several chunks per work-group
-    (1, 3, 1, 60000, 64, "bf16", 4, 2, 300, 0.0, 59997, 3),      # ... in the per-head kernel
+    (1, 3, 1, 60000, 64, "f32", 4, 2, 300, 0.0, 59997, 3),       # ... in the per-head kernel
     (1, 4, 2, 1500, 128, "f16", 4, 2, 64, 0.0, 1490, 10),        # IEEE half precision
-    (1, 3, 1, 900, 64, "f16", 8, 2, 20, 30.0, 892, 8),           # ... per-head kernel, softcap
+    (1, 3, 1, 900, 64, "f16", 8, 2, 20, 30.0, 892, 8),           # ... three heads on one KV head, softcap
     (1, 8, 2, 1200, 80, "bf16", 4, 2, 40, 0.0, 1192, 8),         # head dims inside 16 lanes per key: 10 of them hold data
     (2, 4, 4, 800, 96, "f32", 8, 2, 25, 0.0, 792, 8),
-    (1, 6, 2, 700, 96, "f16", 4, 2, 30, 0.0, 694, 6),            # 3 heads per KV head: per-head kernel at d = 96
+    (1, 6, 2, 700, 96, "f16", 4, 2, 30, 0.0, 694, 6),            # 3 heads per KV head at d = 96
     (1, 4, 2, 1000, 256, "bf16", 4, 2, 50, 0.0, 992, 8),         # 32 lanes per key
     (1, 2, 2, 600, 256, "f32", 8, 1, 16, 0.0, 594, 6),
-    (1, 3, 1, 40000, 256, "f16", 4, 2, 200, 0.0, 39997, 3),      # long context, per-head kernel, d = 256
+    (1, 3, 1, 40000, 256, "f16", 4, 2, 200, 0.0, 39997, 3),      # long context, three heads on one KV head, d = 256
     (1, 2, 1, 250000, 64, "bf16", 4, 2, 300, 0.0, 249997, 3),    # work-groups that walk two chunks, positions walked (matrix cores)
-    (1, 3, 1, 250000, 64, "bf16", 4, 2, 300, 0.0, 249998, 2),    # ... in the per-head kernel
+    (1, 3, 1, 250000, 64, "f32", 4, 2, 300, 0.0, 249998, 2),     # ... in the per-head kernel
     (1, 4, 2, 300000, 128, "bf16", 16, 1, 512, 0.0, 299997, 3),  # ... group lists walked: they are the shorter walk
     (1, 4, 1, 262144, 128, "f16", 4, 2, 1024, 30.0, 262141, 3),  # ... four heads per KV head, half precision, softcap
     (1, 8, 1, 5000, 128, "f32", 4, 2, 100, 0.0, 4996, 4),        # eight fp32 heads on one KV head (vector kernel)
