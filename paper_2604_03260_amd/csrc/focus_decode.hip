@@ -473,10 +473,10 @@ __device__ inline int decode_walk_key(const DecWalk& W, int nseg, int v, int lo_
 // independent), then the skipped ones are squeezed out: wave ballots give every (pass, wavefront) its count, the
 // kept keys land in pass-major, wavefront-major order in s_j / s_hb, padded with -1 / 0 up to `cap` entries.
 // Returns the number of keys kept.  Two barriers inside.
-template <int KPT, int NH>
+template <int KPT, int NH, typename HB>
 __device__ inline int decode_resolve_chunk(const DecWalk& W, int nseg, int v0, int nk0, int lo_w, const int* __restrict__ lists, int n,
                                            const uint32_t* __restrict__ mk, const uint32_t (&gq)[NH], uint32_t all_heads, bool single,
-                                           int* s_j, uint8_t* s_hb, int cap, int* s_wcnt)
+                                           int* s_j, HB* s_hb, int cap, int* s_wcnt)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int js[KPT];
@@ -505,7 +505,7 @@ __device__ inline int decode_resolve_chunk(const DecWalk& W, int nseg, int v0, i
             const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
             const int dst = before + __popcll(bal[it] & lt);
             s_j[dst] = js[it];
-            s_hb[dst] = (uint8_t)hbv[it];
+            s_hb[dst] = (HB)hbv[it];
         }
     }
 #pragma unroll
@@ -787,7 +787,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
     if (v0l >= vtotal) break;                      // uniform over the work-group
     const int v0 = (int)v0l;
     if (cc > 0) __syncthreads();                  // the last chunk's rows have been read
-    const int nk = decode_resolve_chunk<KPT, G>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
+    const int nk = decode_resolve_chunk<KPT, G, uint8_t>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
                                                 (1u << G) - 1u, L.topk == 1, s_j, s_hb, DEC_CHUNK + 4 * SLOTS * U, s_wcnt);
     constexpr int RSTEP = 4 * SLOTS * U;          // keys of one round of the four wavefronts
     // (Keeping the loads of the next round in flight while this one is folded costs a second set of row
@@ -845,7 +845,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_kernel(DecodeLayout L, in
 // The same walk as decode_attn_gqa_kernel for 16-bit caches, with both products on
 // v_mfma_f32_16x16x32: a wavefront takes 32 keys per round as two blocks of 16.
 //   S^T[key, head] = K[key, :] . Q[head, :]   A = K rows straight from the cache (lane: key l%16, components
-//                                             32*kb + 8*(l/16) ..+8, one 16-byte load per product), B = the G <= 8
+//                                             32*kb + 8*(l/16) ..+8, one 16-byte load per product), B = the G <= 16
 //                                             query heads of the KV head (columns past G are zero);
 //   the accumulator lane (head l%16, keys 4*(l/16) ..+4 of either block) does the softmax step of its head;
 //   its 8 probabilities, rounded to 16 bits, ARE the B operand of
@@ -893,7 +893,7 @@ __device__ inline void dec_dma16(const void* sbase, unsigned voff, unsigned lds_
 constexpr float DEC_RESCALE_THRESHOLD = 8.f;
 
 template <bool F16, int D>
-__global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout L, int G, int pos_arg, const int* __restrict__ pos_dev,
+__global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout L, int Gall, int pos_arg, const int* __restrict__ pos_dev,
                                                                    int span, const uint16_t* __restrict__ q_new,
                                                                    const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
                                                                    const char* __restrict__ st, float* __restrict__ part)
@@ -912,12 +912,12 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     constexpr int PW = D + 4;
     constexpr int KPT = DEC_CHUNK / 256;
     constexpr int RSTEP = 4 * 32;                 // keys of one round of the four wavefronts
-    constexpr int GMAX = 8;
+    constexpr int GMAX = 16;                      // query heads per work-group: the columns of the products
     constexpr int RED_BYTES = GMAX * 4 * PW * 4;
     constexpr int BUF_BYTES = 4 * VBYTES > RED_BYTES ? 4 * VBYTES : RED_BYTES;
     __shared__ DecWalk s_walk;
     __shared__ int s_j[DEC_CHUNK + RSTEP];        // cache rows of the chunk's keys, squeezed; padded with -1
-    __shared__ __attribute__((aligned(4))) uint8_t s_hb[DEC_CHUNK + RSTEP];   // which heads attend the key; 0 in the padding
+    __shared__ __attribute__((aligned(8))) uint16_t s_hb[DEC_CHUNK + RSTEP];  // which heads attend the key; 0 in the padding
     __shared__ int s_wcnt[4 * KPT];
     __shared__ __attribute__((aligned(16))) char s_buf[BUF_BYTES];   // V rows of the rounds; the partials at the end
 
@@ -925,11 +925,15 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m16 = lane & 15, qg = lane >> 4;
     const int chunk = blockIdx.x;
-    const size_t bhk = blockIdx.y;
+    // more than GMAX query heads per KV head (Gall): the heads go in sub-groups of GMAX, one work-group row each
+    const int nsub = (Gall + GMAX - 1) / GMAX;
+    const size_t bhk = blockIdx.y / nsub;
+    const int sub = (int)(blockIdx.y % nsub);
+    const int G = min(GMAX, Gall - sub * GMAX);
     const int b = (int)(bhk / L.Hkv), hk = (int)(bhk % L.Hkv);
     const int pos = pos_dev ? pos_dev[b] : pos_arg;
     if (pos < 0 || pos >= L.n) return;
-    const size_t bhq0 = (size_t)b * L.Hq + (size_t)hk * G;
+    const size_t bhq0 = (size_t)b * L.Hq + (size_t)hk * Gall + (size_t)sub * GMAX;
     const int lo_w = max(0, pos - L.window + 1);
     uint32_t gq[GMAX];
     uint32_t gu = 0;
@@ -983,8 +987,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     if (v0l >= vtotal) break;                      // uniform over the work-group
     const int v0 = (int)v0l;
     if (cc > 0) __syncthreads();                  // the last chunk's keys have been read
-    const int nk = decode_resolve_chunk<KPT, GMAX>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
-                                                   (1u << G) - 1u, L.topk == 1, s_j, s_hb, DEC_CHUNK + RSTEP, s_wcnt);
+    const int nk = decode_resolve_chunk<KPT, GMAX, uint16_t>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
+                                                             (1u << G) - 1u, L.topk == 1, s_j, s_hb, DEC_CHUNK + RSTEP, s_wcnt);
 
     for (int r0 = wave * 32; r0 < nk; r0 += RSTEP) {
         // the V rows of the round -> LDS (wave load i holds keys i*RPI ..+RPI of the round)
@@ -1007,8 +1011,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
             ka[kb] = __builtin_bit_cast(V8, wa);
             kb2[kb] = __builtin_bit_cast(V8, wb);
         }
-        const uint32_t hba = *(const uint32_t*)(&s_hb[r0 + 4 * qg]);
-        const uint32_t hbb = *(const uint32_t*)(&s_hb[r0 + 16 + 4 * qg]);
+        const uint64_t hba = *(const uint64_t*)(&s_hb[r0 + 4 * qg]);           // 16 head bits for each of the four keys
+        const uint64_t hbb = *(const uint64_t*)(&s_hb[r0 + 16 + 4 * qg]);
         dec_f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
@@ -1020,8 +1024,8 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float sc = (e < 4) ? sa[e % 4] : sb[e % 4];
-            const uint32_t byte = (((e < 4) ? hba : hbb) >> (8 * (e % 4))) & 0xffu;
-            const bool on = (byte >> m16) & 1u;
+            const uint32_t heads = (uint32_t)(((e < 4) ? hba : hbb) >> (16 * (e % 4))) & 0xffffu;
+            const bool on = (heads >> m16) & 1u;
             float xv = sc * sl2;
             if (cap > 0.f) xv = cap * DEC_LOG2E * tanhf(sc * L.scale / cap);
             x[e] = on ? xv : -INFINITY;
@@ -1077,7 +1081,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     }
     __syncthreads();
     {
-        const int hsel = tid >> 5, t = tid & 31;  // 32 threads per head
+        const int hsel = tid >> 4, t = tid & 15;  // 16 threads per head
         if (hsel < G) {
             const float (*rr)[PW] = red[hsel];
             float mx = -INFINITY;
@@ -1093,7 +1097,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
                 cs += rr[w2][D + 2];
             }
             float* mypart = part + ((bhq0 + hsel) * L.max_parts + chunk) * PW;
-            for (int c = t; c < D; c += 32) {
+            for (int c = t; c < D; c += 16) {
                 float acc = 0.f;
 #pragma unroll
                 for (int w2 = 0; w2 < 4; ++w2) acc += wgt[w2] * rr[w2][c];
@@ -1220,7 +1224,8 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     const int G = (L.Hq % L.Hkv == 0) ? L.Hq / L.Hkv : 0;
     bool default_map = G >= 1;
     for (int h = 0; default_map && h < L.Hq; ++h) default_map = hm.kv[h] == h / G;
-    // the vector form is built for 1, 2, 4 and 8 heads per KV head, the matrix-core form takes any number up to 8
+    // the vector form is built for 1, 2, 4 and 8 heads per KV head; the matrix-core form takes any number (more
+    // than 16 in sub-groups of 16, each walking the keys of its own heads)
     bool grouped = default_map && (G == 1 || G == 2 || G == 4 || G == 8);
     // upper bound of the key sequence known on the host: pos + 1 entries.  The lists are walked only while they
     // hold fewer entries than there are positions below the window, the positions themselves otherwise.
@@ -1232,12 +1237,13 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     // merge stays short at any context length
     const int span = (nchunks + DEC_MAX_PARTS - 1) / DEC_MAX_PARTS;
     const int nparts = (nchunks + span - 1) / span;
-    if (sizeof(T) == 2 && default_map && G <= 8 && (size_t)L.n * D * 2 <= 0xffffffffull) grouped = true;
+    if (sizeof(T) == 2 && default_map && (size_t)L.n * D * 2 <= 0xffffffffull) grouped = true;
     if (grouped) {
         dim3 grid(nparts, L.B * L.Hkv);
         // 16-bit caches whose byte offsets fit 32 bits: the matrix-core form
         if constexpr (sizeof(T) == 2) {
-            if (G <= 8 && (size_t)L.n * D * 2 <= 0xffffffffull) {
+            if ((size_t)L.n * D * 2 <= 0xffffffffull) {
+                grid.y = L.B * L.Hkv * ((G + 15) / 16);
                 hipLaunchKernelGGL((decode_attn_gqa_mfma_kernel<std::is_same<T, f16_bits>::value, D>), grid, dim3(256), 0, s, L, G, pos,
                                    pos_dev, span, (const uint16_t*)q_new, (const uint16_t*)kc, (const uint16_t*)vc, (const char*)st,
                                    part);

@@ -76,6 +76,10 @@ CASES = [
     (1, 6, 2, 400, 64, "f32", 4, 2, 10, 0.0, 390, 10),           # ... in fp32: per-head kernel
     (2, 14, 2, 900, 128, "f16", 8, 2, 50, 0.0, 893, 7),          # 7 query heads per KV head
     (1, 5, 1, 700, 96, "bf16", 4, 1, 30, 0.0, 695, 5),           # 5 query heads per KV head, d = 96
+    (1, 16, 1, 900, 128, "bf16", 4, 2, 40, 0.0, 894, 6),         # 16 query heads on one KV head: every column of the products
+    (1, 24, 2, 800, 64, "f16", 8, 1, 30, 0.0, 795, 5),           # 12 per KV head
+    (1, 40, 1, 1100, 128, "bf16", 8, 2, 64, 0.0, 1095, 5),       # 40 on one KV head: sub-groups of 16, 16 and 8
+    (1, 16, 1, 900, 128, "f32", 4, 2, 40, 0.0, 896, 4),          # ... in fp32: per-head kernel
     (1, 2, 1, 60000, 64, "bf16", 4, 2, 300, 0.0, 59996, 4),      # long context: several chunks per work-group
     (1, 3, 1, 60000, 64, "f32", 4, 2, 300, 0.0, 59997, 3),       # ... in the per-head kernel
     (1, 4, 2, 1500, 128, "f16", 4, 2, 64, 0.0, 1490, 10),        # IEEE half precision
