@@ -172,16 +172,6 @@ __device__ inline float halfwave_max(float x)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-// 64 lanes x 16 bytes: lane l fetches global (sbase + voff) into LDS byte address lds_addr + 16*l.
-// sbase and lds_addr must be wave-uniform.
-__device__ inline void dma16(const void* sbase, unsigned voff, unsigned lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
-}
-
-__device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)p; }
-
 // 16-byte LDS read whose completion the compiler does not track (see F4_WAIT_OPERANDS)
 template <typename V8>
 __device__ inline V8 lds_read16_async(unsigned addr)
@@ -391,11 +381,11 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         const char* src_ = kc_base + (size_t)(TILE) * TILE_BYTES;                                    \
         _Pragma("unroll") for (int i = 0; i < NKI; ++i)                                              \
             if ((i + 1) * MFMA_WAVES <= NKB || wave + MFMA_WAVES * i < NKB)                          \
-                dma16(src_, voff_k[i], lds_k0 + (STAGE) * K_LDS + (wave + MFMA_WAVES * i) * 1024);   \
+                lds_dma16(src_, voff_k[i], lds_k0 + (STAGE) * K_LDS + (wave + MFMA_WAVES * i) * 1024);   \
         if constexpr (SOFT) {            /* the keys' soft assignments travel with the key tile */          \
             const char* gsrc_ = gk_base + (size_t)(TILE) * (KT * GROW);                              \
             _Pragma("unroll") for (int i = 0; i < KT * GROW / 1024 / MFMA_WAVES; ++i)                 \
-                dma16(gsrc_ + (wave + MFMA_WAVES * i) * 1024, (unsigned)lane * 16, lds_g0 + (STAGE) * (KT * GROW) + (wave + MFMA_WAVES * i) * 1024); \
+                lds_dma16(gsrc_ + (wave + MFMA_WAVES * i) * 1024, (unsigned)lane * 16, lds_g0 + (STAGE) * (KT * GROW) + (wave + MFMA_WAVES * i) * 1024); \
         }                                                                                            \
     } while (0)
 #define F4_DMA_V(TILE, STAGE)                                                                        \
@@ -403,14 +393,14 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         const char* src_ = vt_base + (size_t)(TILE) * TILE_BYTES;                                    \
         _Pragma("unroll") for (int i = 0; i < NVI; ++i)                                              \
             if ((i + 1) * MFMA_WAVES <= NVB || wave + MFMA_WAVES * i < NVB)                          \
-                dma16(src_, voff_v[i], lds_v0 + (STAGE) * V_LDS + (wave + MFMA_WAVES * i) * 1024);   \
+                lds_dma16(src_, voff_v[i], lds_v0 + (STAGE) * V_LDS + (wave + MFMA_WAVES * i) * 1024);   \
     } while (0)
 #define F4_DMA_KPOS(TILE, BUF)                                                                       \
     do {                                                                                             \
         if (wave == 0 && lane < KT / 4) {                                                            \
-            dma16(kpos_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_kp0 + (BUF) * (KT * 4)); \
+            lds_dma16(kpos_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_kp0 + (BUF) * (KT * 4)); \
             if constexpr (COARSE)                                                                    \
-                dma16(kmsk_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_km0 + (BUF) * (KT * 4)); \
+                lds_dma16(kmsk_base + (size_t)(TILE) * (KT * 4), (unsigned)lane * 16, lds_km0 + (BUF) * (KT * 4)); \
         }                                                                                            \
     } while (0)
 #define F4_WAIT_DMA() asm volatile("s_waitcnt vmcnt(0)" ::: "memory")

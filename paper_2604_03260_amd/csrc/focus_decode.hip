@@ -882,14 +882,6 @@ template <> struct DecHalf<true> {
     }
 };
 
-// 64 lanes x 16 bytes: lane l fetches global (sbase + voff) into LDS byte address lds_addr + 16*l
-// (sbase and lds_addr wave-uniform)
-__device__ inline void dec_dma16(const void* sbase, unsigned voff, unsigned lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
-}
-
 constexpr float DEC_RESCALE_THRESHOLD = 8.f;
 
 template <bool F16, int D>
@@ -970,7 +962,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     const float sl2 = L.scale * DEC_LOG2E, cap = L.softcap;
     const uint16_t* kbase = kc + bhk * L.n * D + 8 * qg;
     const uint16_t* vbase = vc + bhk * L.n * D;
-    const unsigned lds_v = (unsigned)(uintptr_t)(&s_buf[0]) + (unsigned)wave * VBYTES;
+    const unsigned lds_v = lds_addr_of(&s_buf[0]) + (unsigned)wave * VBYTES;
     const int dlane = (lane < RPI * LPR) ? lane : 0;                  // the lane whose row chunk this lane loads
     const char* my_v = s_buf + wave * VBYTES;
     // k-slot e of lane group qg holds key 16*(e/4) + 4*qg + e%4 of the round: LDS offset of that key's V row
@@ -996,7 +988,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int jv = max(s_j[r0 + i * RPI + dlane / LPR], 0);
-            dec_dma16(vbase, (unsigned)jv * (unsigned)RB + (unsigned)(dlane % LPR) * 16u, lds_v + i * IPITCH);
+            lds_dma16(vbase, (unsigned)jv * (unsigned)RB + (unsigned)(dlane % LPR) * 16u, lds_v + i * IPITCH);
         }
         // the K rows of the two blocks -> registers
         const int ja = max(s_j[r0 + m16], 0), jb = max(s_j[r0 + 16 + m16], 0);

@@ -17,6 +17,17 @@ constexpr int KPOS_PAD = 0x7fffffff;  // position stored in padded key slots: ne
 
 // Element types as the kernels see them: float, uint16_t for a bfloat16 bit pattern, f16_bits for an IEEE half.
 struct f16_bits { uint16_t v; };
+// Direct global -> LDS load of one wavefront: lane l fetches the 16 bytes at (sbase + voff) into LDS byte address
+// lds_addr + 16*l (global_load_lds_dwordx4; sbase and lds_addr wave-uniform, voff per lane).  Counted by vmcnt
+// like any vector memory load: `s_waitcnt vmcnt(0)` before the data is read from LDS.
+__device__ inline void lds_dma16(const void* sbase, unsigned voff, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+// LDS byte address of a __shared__ object (the low half of its generic address)
+__device__ inline unsigned lds_addr_of(const void* p) { return (unsigned)(uintptr_t)p; }
+
 __device__ inline float f16_bits_to_f32(uint16_t b)
 {
     _Float16 h;
