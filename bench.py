@@ -27,6 +27,8 @@ FP64_VECTOR_PEAK_TFLOPS = 78.6
 # HBM bytes per launch of the attention kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this
 # command (profiles/attn_mfma_kernel_cfg3_counters.txt); None where no counter run was made
 MEASURED_TRAFFIC_BYTES = {"cfg3": 5.88e9}
+# ... and of the three kernels of one incremental step (profiles/decode_step_cfg3_kernel_trace.txt)
+MEASURED_DECODE_TRAFFIC_BYTES = {"cfg3": 1.38e8}
 
 
 def main():
@@ -391,7 +393,8 @@ def main():
             "ms_per_token_graph_loop": t_dec_graph,      # three input copies + one graph replay per token, enqueued back to back
             "attended_keys_all_heads": per_head_rows,
             "roofline": {"bound": "hbm", "kernel": "decode_attn (whole step timed)", "achieved": dec_bytes / (t_dec * 1e-3) / 1e9,
-                         "peak": 8000.0, "unit": "GB/s", "frac": dec_bytes / (t_dec * 1e-3) / 1e9 / 8000.0, "traffic": None,
+                         "peak": 8000.0, "unit": "GB/s", "frac": dec_bytes / (t_dec * 1e-3) / 1e9 / 8000.0,
+                         "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get(wl.name),
                          "note": "algorithmic bytes = K and V rows of the keys at least one query head of the KV head "
                                  "attends, read once (%d rows, %.1f MB); per-head reads would be %.1f MB"
                                  % (unique_rows, dec_bytes / 1e6, 2.0 * per_head_rows * wl.d * elem / 1e6)},
