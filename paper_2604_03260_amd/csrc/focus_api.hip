@@ -268,7 +268,7 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     // longest key sequence a step walks: n entries (the group lists are used only while they are shorter than
     // the range of positions below the window)
     L->max_chunks = (p->n + DEC_CHUNK - 1) / DEC_CHUNK;
-    L->max_parts = std::min(L->max_chunks, DEC_MAX_PARTS);
+    L->max_parts = std::min((p->n + DEC_CHUNK_SHORT - 1) / DEC_CHUNK_SHORT, DEC_MAX_PARTS);
     for (int h = 0; h < p->Hq; ++h)
         hm->kv[h] = (uint8_t)(p->head_map ? p->head_map[h] : h / (p->Hq / p->Hkv));
     const size_t BHq = (size_t)p->B * p->Hq, BHk = (size_t)p->B * p->Hkv, n = (size_t)p->n;

@@ -884,7 +884,9 @@ template <> struct DecHalf<true> {
 
 constexpr float DEC_RESCALE_THRESHOLD = 8.f;
 
-template <bool F16, int D>
+// CH: entries of the walk a work-group resolves at a time (the long or the short chunk: the short one when the
+// launch would otherwise leave most of the chip idle, one round per wavefront and four times the work-groups).
+template <bool F16, int D, int CH>
 __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout L, int Gall, int pos_arg, const int* __restrict__ pos_dev,
                                                                    int span, const uint16_t* __restrict__ q_new,
                                                                    const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
@@ -902,14 +904,14 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     constexpr int KB = (D + 31) / 32;             // products of one S^T block (the last one partly zero for d = 80)
     constexpr int NB = D / 16;                    // 16-component blocks of O^T
     constexpr int PW = D + 4;
-    constexpr int KPT = DEC_CHUNK / 256;
+    constexpr int KPT = CH >= 256 ? CH / 256 : 1;
     constexpr int RSTEP = 4 * 32;                 // keys of one round of the four wavefronts
     constexpr int GMAX = 16;                      // query heads per work-group: the columns of the products
     constexpr int RED_BYTES = GMAX * 4 * PW * 4;
     constexpr int BUF_BYTES = 4 * VBYTES > RED_BYTES ? 4 * VBYTES : RED_BYTES;
     __shared__ DecWalk s_walk;
-    __shared__ int s_j[DEC_CHUNK + RSTEP];        // cache rows of the chunk's keys, squeezed; padded with -1
-    __shared__ __attribute__((aligned(8))) uint16_t s_hb[DEC_CHUNK + RSTEP];  // which heads attend the key; 0 in the padding
+    __shared__ int s_j[CH + RSTEP];        // cache rows of the chunk's keys, squeezed; padded with -1
+    __shared__ __attribute__((aligned(8))) uint16_t s_hb[CH + RSTEP];  // which heads attend the key; 0 in the padding
     __shared__ int s_wcnt[4 * KPT];
     __shared__ __attribute__((aligned(16))) char s_buf[BUF_BYTES];   // V rows of the rounds; the partials at the end
 
@@ -939,7 +941,7 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
     __syncthreads();
     const int nseg = s_walk.nseg;
     const int vtotal = s_walk.beg[nseg];
-    if ((long)chunk * DEC_CHUNK >= vtotal) {
+    if ((long)chunk * CH >= vtotal) {
         for (int i = 0; i < G; ++i) {
             float* mypart = part + ((bhq0 + i) * L.max_parts + chunk) * PW;
             for (int e = tid; e < PW; e += 256) mypart[e] = (e == D) ? -INFINITY : 0.f;
@@ -975,12 +977,12 @@ __global__ __launch_bounds__(256) void decode_attn_gqa_mfma_kernel(DecodeLayout 
 
     for (int cc = 0; cc < span; ++cc) {
     // chunks chunk, chunk + gridDim.x, ...: however short the walk turns out, its chunks spread over the work-groups
-    const long v0l = ((long)chunk + (long)cc * gridDim.x) * DEC_CHUNK;
+    const long v0l = ((long)chunk + (long)cc * gridDim.x) * CH;
     if (v0l >= vtotal) break;                      // uniform over the work-group
     const int v0 = (int)v0l;
     if (cc > 0) __syncthreads();                  // the last chunk's keys have been read
-    const int nk = decode_resolve_chunk<KPT, GMAX, uint16_t>(s_walk, nseg, v0, min(vtotal - v0, DEC_CHUNK), lo_w, lists, L.n, mk, gq,
-                                                             (1u << G) - 1u, L.topk == 1, s_j, s_hb, DEC_CHUNK + RSTEP, s_wcnt);
+    const int nk = decode_resolve_chunk<KPT, GMAX, uint16_t>(s_walk, nseg, v0, min(vtotal - v0, CH), lo_w, lists, L.n, mk, gq,
+                                                             (1u << G) - 1u, L.topk == 1, s_j, s_hb, CH + RSTEP, s_wcnt);
 
     for (int r0 = wave * 32; r0 < nk; r0 += RSTEP) {
         // the V rows of the round -> LDS (wave load i holds keys i*RPI ..+RPI of the round)
@@ -1224,11 +1226,11 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
     // (With the position in device memory: the bound of the last position the caches can hold; work-groups
     // past the real sequence leave an empty partial.)
     if (pos_dev) pos = L.n - 1;
-    const int nchunks = std::min(L.max_chunks, (pos + DEC_CHUNK) / DEC_CHUNK);
+    int nchunks = std::min(L.max_chunks, (pos + DEC_CHUNK) / DEC_CHUNK);
     // a work-group walks `span` chunks and leaves one partial: at most DEC_MAX_PARTS partials per head, so the
     // merge stays short at any context length
-    const int span = (nchunks + DEC_MAX_PARTS - 1) / DEC_MAX_PARTS;
-    const int nparts = (nchunks + span - 1) / span;
+    int span = (nchunks + DEC_MAX_PARTS - 1) / DEC_MAX_PARTS;
+    int nparts = (nchunks + span - 1) / span;
     if (sizeof(T) == 2 && default_map && (size_t)L.n * D * 2 <= 0xffffffffull) grouped = true;
     if (grouped) {
         dim3 grid(nparts, L.B * L.Hkv);
@@ -1236,9 +1238,26 @@ static hipError_t decode_step_d(const DecodeLayout& L, const HeadMap& hm, int po
         if constexpr (sizeof(T) == 2) {
             if ((size_t)L.n * D * 2 <= 0xffffffffull) {
                 grid.y = L.B * L.Hkv * ((G + 15) / 16);
-                hipLaunchKernelGGL((decode_attn_gqa_mfma_kernel<std::is_same<T, f16_bits>::value, D>), grid, dim3(256), 0, s, L, G, pos,
-                                   pos_dev, span, (const uint16_t*)q_new, (const uint16_t*)kc, (const uint16_t*)vc, (const char*)st,
-                                   part);
+                // shorter chunks (fewer rounds per wavefront) while all their work-groups are resident at once, three
+                // per CU: below that the long chunks leave most of the chip idle (4096 cached tokens: 27 -> 20 us)
+                int ch = DEC_CHUNK;
+                for (int c = DEC_CHUNK_SHORT; c < DEC_CHUNK; c *= 2) {
+                    const int nc = (pos + c) / c;
+                    if ((long)nc * grid.y <= 3 * 256 && nc <= L.max_parts) { ch = c; break; }
+                }
+                if (ch != DEC_CHUNK) {
+                    nchunks = (pos + ch) / ch;
+                    span = 1;                                                // one chunk, one partial per work-group
+                    nparts = nchunks;
+                    grid.x = nparts;
+                }
+                constexpr bool f16 = std::is_same<T, f16_bits>::value;
+#define FOCUS_DEC_MFMA(CH_) hipLaunchKernelGGL((decode_attn_gqa_mfma_kernel<f16, D, CH_>), grid, dim3(256), 0, s, L, G, pos, pos_dev, span, \
+                                               (const uint16_t*)q_new, (const uint16_t*)kc, (const uint16_t*)vc, (const char*)st, part)
+                if (ch == DEC_CHUNK_SHORT) FOCUS_DEC_MFMA(DEC_CHUNK_SHORT);
+                else if (ch == 2 * DEC_CHUNK_SHORT) FOCUS_DEC_MFMA(2 * DEC_CHUNK_SHORT);
+                else FOCUS_DEC_MFMA(DEC_CHUNK);
+#undef FOCUS_DEC_MFMA
                 hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(L.B * L.Hq), dim3(256), 0, s, L, pos, pos_dev, nparts, part, out,
                                    lse, row_pairs);
                 return hipGetLastError();

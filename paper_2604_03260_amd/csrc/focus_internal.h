@@ -159,6 +159,8 @@ struct RouteLayout {
 #define FOCUS_DEC_CHUNK 512
 #endif
 constexpr int DEC_CHUNK = FOCUS_DEC_CHUNK;   // keys of the key sequence a work-group of the decode attention resolves at a time
+constexpr int DEC_CHUNK_SHORT = 128;         // ... in launches that would otherwise leave most of the chip idle (128 or 256)
+static_assert(DEC_CHUNK == 4 * DEC_CHUNK_SHORT, "the launch picks among DEC_CHUNK_SHORT, twice that, and DEC_CHUNK");
 constexpr int DEC_MAX_PARTS = 384;           // partial results per head the merge reads at most
 struct DecodeLayout {
     int B, Hq, Hkv, n, d;      // n = capacity of the caches
@@ -166,7 +168,7 @@ struct DecodeLayout {
     int dtype;
     float scale, softcap;
     int max_chunks;            // chunks of DEC_CHUNK keys the longest key sequence (n entries) has
-    int max_parts;             // partial results per head: min(max_chunks, DEC_MAX_PARTS)
+    int max_parts;             // partial results per head: min(chunks of DEC_CHUNK_SHORT keys, DEC_MAX_PARTS)
     size_t off_mk;             // [B,Hkv,n] uint32 membership of the cached keys
     size_t off_lists;          // [B,Hkv,K,n] int32 positions of every group, ascending
     size_t off_counts;         // [B,Hkv,K] int32 list lengths
