@@ -52,9 +52,19 @@ constexpr int NBW = 4;          // sort blocks handled by one work-group of the 
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// The kernels of the bucketing serve the query side, the key side, or both in one launch (which = 1, 0, -1):
+// with both, the rows [0, B*Hq) of the launch are query (batch, head) pairs and the B*Hkv after them key pairs.
+constexpr int MAX_GRID_ROWS = 65535;
+__device__ inline int side_of_row(const Layout& L, int which, unsigned row) { return which < 0 ? (int)(row < (unsigned)(L.B * L.Hq)) : which; }
+__device__ inline int row_in_side(const Layout& L, int which, unsigned row)
+{
+    return (which < 0 && row >= (unsigned)(L.B * L.Hq)) ? (int)row - L.B * L.Hq : (int)row;
+}
+
 template <typename T, int KMAX>
-__global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, const T* __restrict__ x,
-                                                        const double* __restrict__ cent64, int is_query,
+__global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, const T* __restrict__ xq,
+                                                        const T* __restrict__ xk,
+                                                        const double* __restrict__ cent64, int which,
                                                         char* __restrict__ ws)
 {
     __shared__ __align__(16) char s_rows[SB * ROW_STRIDE];
@@ -63,7 +73,9 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
 
     const int tid = threadIdx.x;
     const int blk0 = blockIdx.x * NBW;
-    const int bh = blockIdx.y;
+    const int is_query = side_of_row(L, which, blockIdx.y);
+    const int bh = row_in_side(L, which, blockIdx.y);
+    const T* x = is_query ? xq : xk;
     const int H = is_query ? L.Hq : L.Hkv;
     const int h = bh % H;
     const int hk = is_query ? hm.kv[h] : h;
@@ -196,27 +208,17 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
 #undef FOCUS_SCORE_LOAD
 }
 
-// centroids fp32 [Hkv][K][d] -> fp64 [Hkv][dcent][KMAX] (zero-padded groups, zero rows from d to dcent)
-__global__ void cent_to_f64_kernel(const float* __restrict__ cents, double* __restrict__ out, int Hkv, int K, int d,
-                                   int dcent, int kmax)
-{
-    const int total = Hkv * dcent * kmax;
-    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
-        const int g = e % kmax, t = (e / kmax) % dcent, hk = e / (kmax * dcent);
-        out[e] = (g < K && t < d) ? (double)cents[((size_t)hk * K + g) * d + t] : 0.0;
-    }
-}
-
 // ---------------------------------------------------------------- scans over sort blocks
 // One work-group per (column, batch*head): exclusive scan of a histogram column
 // over the sort blocks, total in row nblk.
-__global__ __launch_bounds__(256) void scan_blocks_kernel(Layout L, int is_query, char* __restrict__ ws)
+__global__ __launch_bounds__(256) void scan_blocks_kernel(Layout L, int which, char* __restrict__ ws)
 {
     __shared__ int s_wave[4];
     __shared__ int s_carry;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = blockIdx.x;           // [0,NC): class column, [NC,NC+K): group column
-    const int bh = blockIdx.y;
+    const int is_query = side_of_row(L, which, blockIdx.y);
+    const int bh = row_in_side(L, which, blockIdx.y);
     int* base;
     int stride;
     if (col < L.NC) {
@@ -251,13 +253,14 @@ __global__ __launch_bounds__(256) void scan_blocks_kernel(Layout L, int is_query
 }
 
 // ---------------------------------------------------------------- per-head plan
-__global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int is_query, char* __restrict__ ws)
+__global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int which, char* __restrict__ ws)
 {
     __shared__ int s_cnt[MAX_CLASSES];
     __shared__ int s_nt[MAX_CLASSES];
     __shared__ int s_total;
     const int tid = threadIdx.x;
-    const int bh = blockIdx.x;
+    const int is_query = side_of_row(L, which, blockIdx.x);
+    const int bh = row_in_side(L, which, blockIdx.x);
     const int NC = L.NC, K = L.K;
     const int* bc_tot = (const int*)(ws + (is_query ? L.off_qbc : L.off_kbc)) + ((size_t)bh * (L.nblk + 1) + L.nblk) * NC;
     const int* bg_tot = (const int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + L.nblk) * K;
@@ -337,7 +340,28 @@ __global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int is_query,
     }
 }
 
-// ---------------------------------------------------------------- fills
+// ---------------------------------------------------------------- start of an assign pass
+// Pads of the class-ordered position arrays (qperm -1, kpos KPOS_PAD, the key masks of coarse classes 0) and, when
+// centroids are given, their fp64 table: one launch.
+__global__ __launch_bounds__(256) void assign_init_kernel(int* __restrict__ qperm, size_t nq, int* __restrict__ kpos, size_t nk,
+                                                          int* __restrict__ kmsk, const float* __restrict__ cents,
+                                                          double* __restrict__ cent64, int Hkv, int K, int d, int dcent, int kmax)
+{
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (size_t i = i0; i < nq; i += step) qperm[i] = -1;
+    for (size_t i = i0; i < nk; i += step) kpos[i] = KPOS_PAD;
+    if (kmsk)
+        for (size_t i = i0; i < nk; i += step) kmsk[i] = 0;
+    if (cents) {
+        const size_t total = (size_t)Hkv * dcent * kmax;
+        for (size_t e = i0; e < total; e += step) {
+            const int g = (int)(e % kmax), t = (int)((e / kmax) % dcent), hk = (int)(e / ((size_t)kmax * dcent));
+            cent64[e] = (g < K && t < d) ? (double)cents[((size_t)hk * K + g) * d + t] : 0.0;
+        }
+    }
+}
+
 __global__ void fill_i32_kernel(int* __restrict__ p, size_t count, int value)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -346,12 +370,14 @@ __global__ void fill_i32_kernel(int* __restrict__ p, size_t count, int value)
 }
 
 // ---------------------------------------------------------------- scatter
-__global__ __launch_bounds__(SB) void scatter_kernel(Layout L, int is_query, char* __restrict__ ws)
+__global__ __launch_bounds__(SB) void scatter_kernel(Layout L, int which, char* __restrict__ ws)
 {
     __shared__ int s_wc[4][MAX_CLASSES];
     __shared__ int s_wg[4][32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int blk = blockIdx.x, bh = blockIdx.y;
+    const int blk = blockIdx.x;
+    const int is_query = side_of_row(L, which, blockIdx.y);
+    const int bh = row_in_side(L, which, blockIdx.y);
     const int n = L.n, NC = L.NC, K = L.K;
     const int pos = blk * SB + tid;
     const bool valid = pos < n;
@@ -470,18 +496,25 @@ __global__ __launch_bounds__(SB) void token_classes_kernel(Layout L, const uint3
     }
 }
 
+// scores and memberships of the queries and of the keys, one launch: query rows first, key rows after them
 template <typename T>
-hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, int is_query, char* ws, hipStream_t st)
+hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* q, const void* k, char* ws, hipStream_t st)
 {
-    const int H = is_query ? L.Hq : L.Hkv;
-    dim3 grid((L.nblk + NBW - 1) / NBW, L.B * H);
     const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
     const double* cent64 = (const double*)(ws + L.off_cent64);
-    switch (kmax) {
-        case 4: hipLaunchKernelGGL((score_topk_kernel<T, 4>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
-        case 8: hipLaunchKernelGGL((score_topk_kernel<T, 8>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
-        case 16: hipLaunchKernelGGL((score_topk_kernel<T, 16>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
-        default: hipLaunchKernelGGL((score_topk_kernel<T, 32>), grid, dim3(SB), 0, st, L, hm, (const T*)x, cent64, is_query, ws); break;
+    // (more rows than one launch can have: the two sides one after the other)
+    const bool both = L.B * (L.Hq + L.Hkv) <= MAX_GRID_ROWS;
+    for (int which = both ? -1 : 1; which >= -1; --which) {
+        dim3 grid((L.nblk + NBW - 1) / NBW, which < 0 ? L.B * (L.Hq + L.Hkv) : which ? L.B * L.Hq : L.B * L.Hkv);
+#define FOCUS_SCORE(KM_) hipLaunchKernelGGL((score_topk_kernel<T, KM_>), grid, dim3(SB), 0, st, L, hm, (const T*)q, (const T*)k, cent64, which, ws)
+        switch (kmax) {
+            case 4: FOCUS_SCORE(4); break;
+            case 8: FOCUS_SCORE(8); break;
+            case 16: FOCUS_SCORE(16); break;
+            default: FOCUS_SCORE(32); break;
+        }
+#undef FOCUS_SCORE
+        if (which <= 0) break;
     }
     return hipGetLastError();
 }
@@ -490,24 +523,31 @@ hipError_t launch_score(const Layout& L, const HeadMap& hm, const void* x, int i
 
 namespace {
 
-// pads of the class-ordered position arrays
-void launch_pad_fills(const Layout& L, char* ws, hipStream_t st)
+// pads of the class-ordered position arrays and, with centroids given, their fp64 table [Hkv][dcent][kmax]
+void launch_assign_init(const Layout& L, const float* centroids, char* ws, hipStream_t st)
 {
     const size_t nq = (size_t)L.B * L.Hq * L.NQP, nk = (size_t)L.B * L.Hkv * L.NKP;
-    const int gq = (int)min((size_t)8192, (nq + 255) / 256), gk = (int)min((size_t)8192, (nk + 255) / 256);
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(gq), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, -1);
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kpos), nk, KPOS_PAD);
-    if (L.coarse) hipLaunchKernelGGL(fill_i32_kernel, dim3(gk), dim3(256), 0, st, (int*)(ws + L.off_kmsk), nk, 0);
+    const int grid = (int)min((size_t)8192, (max(nq, nk) + 255) / 256);
+    const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
+    const int row_bytes = L.d * L.elem;
+    const int dcent = (row_bytes + ROW_CHUNK_BYTES - 1) / ROW_CHUNK_BYTES * (ROW_CHUNK_BYTES / L.elem);
+    hipLaunchKernelGGL(assign_init_kernel, dim3(grid), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, (int*)(ws + L.off_kpos), nk,
+                       L.coarse ? (int*)(ws + L.off_kmsk) : nullptr, centroids, (double*)(ws + L.off_cent64), L.Hkv, L.K, L.d,
+                       dcent, kmax);
 }
 
 // from masks, class ids and block histograms to the class-ordered arrays, group lists and job lists
 hipError_t launch_bucketing(const Layout& L, const void* k, char* ws, hipStream_t st)
 {
-    for (int is_query = 1; is_query >= 0; --is_query) {
-        const int H = is_query ? L.Hq : L.Hkv;
-        hipLaunchKernelGGL(scan_blocks_kernel, dim3(L.NC + L.K, L.B * H), dim3(256), 0, st, L, is_query, ws);
-        hipLaunchKernelGGL(plan_heads_kernel, dim3(L.B * H), dim3(256), 0, st, L, is_query, ws);
-        hipLaunchKernelGGL(scatter_kernel, dim3(L.nblk, L.B * H), dim3(SB), 0, st, L, is_query, ws);
+    // query side and key side in the same launches: rows [0, B*Hq) and the B*Hkv rows after them
+    // (more rows than one launch can have: the two sides one after the other)
+    const bool both = L.B * (L.Hq + L.Hkv) <= MAX_GRID_ROWS;
+    for (int which = both ? -1 : 1; which >= -1; --which) {
+        const int rows = which < 0 ? L.B * (L.Hq + L.Hkv) : which ? L.B * L.Hq : L.B * L.Hkv;
+        hipLaunchKernelGGL(scan_blocks_kernel, dim3(L.NC + L.K, rows), dim3(256), 0, st, L, which, ws);
+        hipLaunchKernelGGL(plan_heads_kernel, dim3(rows), dim3(256), 0, st, L, which, ws);
+        hipLaunchKernelGGL(scatter_kernel, dim3(L.nblk, rows), dim3(SB), 0, st, L, which, ws);
+        if (which <= 0) break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -521,31 +561,18 @@ hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, cons
                          const float* centroids, char* ws, hipStream_t st)
 {
     hipError_t e;
-    launch_pad_fills(L, ws, st);
-    {
-        const int kmax = L.K <= 4 ? 4 : L.K <= 8 ? 8 : L.K <= 16 ? 16 : 32;
-        const int row_bytes = L.d * L.elem;
-        const int dcent = (row_bytes + ROW_CHUNK_BYTES - 1) / ROW_CHUNK_BYTES * (ROW_CHUNK_BYTES / L.elem);
-        hipLaunchKernelGGL(cent_to_f64_kernel, dim3(64), dim3(256), 0, st, centroids, (double*)(ws + L.off_cent64),
-                           L.Hkv, L.K, L.d, dcent, kmax);
-    }
-    if (L.dtype == 0) {
-        if ((e = launch_score<float>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
-        if ((e = launch_score<float>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
-    } else if (L.dtype == 2) {
-        if ((e = launch_score<f16_bits>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
-        if ((e = launch_score<f16_bits>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
-    } else {
-        if ((e = launch_score<uint16_t>(L, hm, q, 1, ws, st)) != hipSuccess) return e;
-        if ((e = launch_score<uint16_t>(L, hm, k, 0, ws, st)) != hipSuccess) return e;
-    }
+    launch_assign_init(L, centroids, ws, st);
+    if (L.dtype == 0) e = launch_score<float>(L, hm, q, k, ws, st);
+    else if (L.dtype == 2) e = launch_score<f16_bits>(L, hm, q, k, ws, st);
+    else e = launch_score<uint16_t>(L, hm, q, k, ws, st);
+    if (e != hipSuccess) return e;
     return launch_bucketing(L, k, ws, st);
 }
 
 hipError_t launch_assign_tokens(const Layout& L, const uint32_t* token_masks, const void* k, char* ws,
                                 int32_t* invalid_count, hipStream_t st)
 {
-    launch_pad_fills(L, ws, st);
+    launch_assign_init(L, nullptr, ws, st);
     if (invalid_count) hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, st, invalid_count, (size_t)1, 0);
     hipLaunchKernelGGL(token_classes_kernel, dim3(L.nblk, L.B), dim3(SB), 0, st, L, token_masks, ws, invalid_count);
     hipError_t e = hipGetLastError();

@@ -184,7 +184,9 @@ def test_assign_at_the_maximum_sequence_length():
 def test_many_heads_and_many_sequences():
     # the widest head count the head map holds, and a batch whose B*H runs into the thousands
     for wl in (small("heads256", Hq=256, Hkv=32, n=300, d=64, dtype="bf16", window=16),
-               small("batch160", B=160, Hq=8, Hkv=2, n=200, d=128, dtype="bf16", K=8, topk=2, window=10)):
+               small("batch160", B=160, Hq=8, Hkv=2, n=200, d=128, dtype="bf16", K=8, topk=2, window=10),
+               # more (batch, head) rows than one launch of the bucketing kernels can have: the two sides go one by one
+               small("batch4200", B=4200, Hq=12, Hkv=4, n=24, d=64, dtype="bf16", K=4, topk=2, window=5)):
         say("case", wl)
         inp = workloads.make_inputs(wl, "cuda")
         res = harness.run_gpu(wl, inp)
