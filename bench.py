@@ -161,10 +161,10 @@ def main():
 
     # the matrix-core rate this machine sustains in a register-only MFMA loop (the stand-alone probe the build
     # leaves beside the library), as a second denominator next to the nominal peak
-    probe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_03260_amd", "_build", "issue_rates")
+    probe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_03260_amd", "_build", "mfma_peak")
     if half and os.path.exists(probe):
         try:
-            got = subprocess.run([probe, "--mfma-peak"], capture_output=True, text=True, timeout=120)
+            got = subprocess.run([probe], capture_output=True, text=True, timeout=120)
             fields = got.stdout.strip().split()
             measured_peak = float(fields[0])              # constant operands
             result["measured_mfma_peak_tflops"] = measured_peak

@@ -25,7 +25,12 @@
  *   - The caller owns all buffers.  The library allocates no device memory and
  *     keeps no state between calls.  The workspace is caller-allocated,
  *     256-byte aligned, at least focus_workspace_size() bytes, and carries the
- *     result of focus_assign to focus_attn_fwd (same params, same k).
+ *     result of focus_assign to focus_attn_fwd (same params, same k).  Both
+ *     calls WRITE it: focus_assign fills the membership, the lists, the schedule
+ *     and the class-ordered copy of the keys; focus_attn_fwd (and its variants)
+ *     adds the class-ordered, transposed copy of the values before its attention
+ *     launch, so v may change between two attention calls on one workspace, while
+ *     k may not.  Two attention calls that share a workspace must not overlap.
  *   - focus_assign and focus_attn_fwd only enqueue work on `stream`
  *     (a hipStream_t passed as void*, NULL = default stream) and return; the
  *     caller synchronises.  Inputs are never modified; out must not alias them.
@@ -100,6 +105,13 @@ focus_status focus_attn_fwd(const focus_params *p, const void *q, const void *k,
                             const void *v, void *workspace, size_t workspace_bytes,
                             void *out, float *lse, int32_t *row_pairs, void *stream);
 
+/* focus_attn_fwd (same contract, same checks) forced through the fp32 vector-ALU kernel in every dtype:
+ * no matrix cores, slow.  It exists so that tests can cross-check the matrix-core kernel on the device at
+ * sizes a CPU reference cannot cover in full; it is not part of the hot path (App. D Eq. 3, as above). */
+focus_status focus_attn_fwd_vector(const focus_params *p, const void *q, const void *k,
+                                   const void *v, void *workspace, size_t workspace_bytes,
+                                   void *out, float *lse, int32_t *row_pairs, void *stream);
+
 /* ---- the soft-gated attention of training (Sec. 2 Eq. 2) ----
  *
  * Every causal pair is computed: logit_ij = scale * q_i.k_j * gate_ij with gate_ij = 1 inside the
@@ -115,6 +127,10 @@ focus_status focus_soft_workspace_size(const focus_params *p, size_t *bytes);
 focus_status focus_attn_soft_fwd(const focus_params *p, float lambda, const float *g,
                                  const void *q, const void *k, const void *v, void *workspace,
                                  size_t workspace_bytes, void *out, float *lse, void *stream);
+/* The same (Sec. 2 Eq. 2) forced through the vector-ALU kernel: the tests' on-device cross-check. */
+focus_status focus_attn_soft_fwd_vector(const focus_params *p, float lambda, const float *g,
+                                        const void *q, const void *k, const void *v, void *workspace,
+                                        size_t workspace_bytes, void *out, float *lse, void *stream);
 
 /* ---- the per-layer router in front of the attention (Sec. 2 Eq. 1 and the Sinkhorn recipe) ----
  *
@@ -134,9 +150,9 @@ typedef struct {
 /* Bytes of workspace focus_route needs.  Pure host code. */
 focus_status focus_route_workspace_size(const focus_route_params *rp, size_t *bytes);
 
-/* z_i = W_g^T h_i, S[i,g] = z_i . C[g] (Sec. 2 Eq. 1), all in fp64: the products of the
- * projection are added in chunks of 64 consecutive hidden components (index order inside a
- * chunk, chunk sums in chunk order), S over the d_g components in index order.
+/* z_i = W_g^T h_i, S[i,g] = z_i . C[g] (Sec. 2 Eq. 1), all in fp64: the (exact) products of the
+ * projection are added one by one over the hidden components in index order, S over the d_g
+ * components in index order.
  * sinkhorn_iters = 0: g_i = S[i,:] / tau.  Otherwise Q = exp((S - max S of the sequence) / tau),
  * then N rounds per batch element of {every column divided by its sum over the n tokens, every
  * row divided by its sum over the K groups} (evaluated as diagonal scalings of Q), g_i = Q[i,:].
@@ -268,6 +284,10 @@ const char *focus_last_error(void);
 
 /* major*10000 + minor*100 + patch */
 int focus_version(void);
+
+/* Identifier of the sources this library was compiled from (a hash the build computes over them;
+ * "unknown" when built by hand).  The Python binding refuses to run a library older than its sources. */
+const char *focus_build_id(void);
 
 #ifdef __cplusplus
 }

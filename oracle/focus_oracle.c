@@ -124,7 +124,26 @@ int focus_oracle_scores(const oracle_params *p, const void *x, int is_query,
  * Sec. 2 "Efficiency at inference": keep the topk highest-scoring groups.
  * Group g is kept when fewer than topk groups beat it; g' beats g when its
  * score is larger, or equal with g' < g.  masks: [B,H,n] bit g set = member.
+ * The paper says nothing of scores that are not numbers: a token with a NaN
+ * among its K scores has no ranking and is given the first topk groups
+ * (infinities are ordinary values of the order).
  */
+static uint32_t topk_of_scores(const double *s, int K, int topk)
+{
+    for (int g = 0; g < K; ++g)
+        if (isnan(s[g])) return (topk == 32) ? 0xffffffffu : ((1u << topk) - 1u);
+    uint32_t m = 0;
+    for (int g = 0; g < K; ++g) {
+        int beaten_by = 0;
+        for (int o = 0; o < K; ++o) {
+            if (o == g) continue;
+            if (s[o] > s[g] || (s[o] == s[g] && o < g)) ++beaten_by;
+        }
+        if (beaten_by < topk) m |= (1u << g);
+    }
+    return m;
+}
+
 int focus_oracle_topk_masks(const oracle_params *p, const double *scores, int H,
                             uint32_t *masks)
 {
@@ -133,17 +152,7 @@ int focus_oracle_topk_masks(const oracle_params *p, const double *scores, int H,
     const int64_t rows = (int64_t)p->B * H * p->n;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
-        const double *s = scores + r * K;
-        uint32_t m = 0;
-        for (int g = 0; g < K; ++g) {
-            int beaten_by = 0;
-            for (int o = 0; o < K; ++o) {
-                if (o == g) continue;
-                if (s[o] > s[g] || (s[o] == s[g] && o < g)) ++beaten_by;
-            }
-            if (beaten_by < p->topk) m |= (1u << g);
-        }
-        masks[r] = m;
+        masks[r] = topk_of_scores(scores + r * K, K, p->topk);
     }
     return 0;
 }
@@ -524,10 +533,9 @@ int focus_oracle_num_threads(void)
  *                                     by its sum over the groups };  g_i = Q[i,:]
  * Inference keeps the topk largest entries of g_i (Sec. 2 "Efficiency at inference").
  *
- * Readings (restated in the design notes): fp64 throughout; the projection adds
- * products in chunks of 64 consecutive hidden components, in index order inside a
- * chunk and chunk by chunk after that; S adds over the dg components in index
- * order; before the exponential the largest score of the sequence is subtracted
+ * Readings (restated in the design notes): fp64 throughout; the projection is the
+ * plain inner product, its products added one by one in index order t = 0 .. dm-1;
+ * S adds over the dg components in index order; before the exponential the largest score of the sequence is subtracted
  * (the first column step divides any common factor out again, so the recipe is
  * unchanged, and exp cannot overflow); Sinkhorn runs per batch element over its
  * n tokens; ties in the top-k go to the smaller group index.
@@ -542,6 +550,7 @@ int focus_oracle_route(int32_t B, int32_t n, int32_t dm, int32_t dg, int32_t K, 
     if (B < 1 || n < 1 || dm < 1 || dg < 1 || K < 1 || K > 32 || topk < 1 || topk > K) return -1;
     if (!(tau > 0.0) || iters < 0 || !hidden || !wg || !cent || !masks) return -1;
     if (dtype < 0 || dtype > 2) return -1;
+    if (dg > 256) return -1;                    /* z of one token lives in a 256-entry array below */
     double *Q = (double *)malloc(sizeof(double) * (size_t)n * K);
     if (!Q) return -2;
     for (int b = 0; b < B; ++b) {
@@ -550,14 +559,9 @@ int focus_oracle_route(int32_t B, int32_t n, int32_t dm, int32_t dg, int32_t K, 
         for (int i = 0; i < n; ++i) {
             double z[256];
             const int64_t row = ((int64_t)b * n + i) * dm;
-            for (int j = 0; j < dg && j < 256; ++j) {
+            for (int j = 0; j < dg; ++j) {
                 double acc = 0.0;
-                for (int c0 = 0; c0 < dm; c0 += 64) {
-                    double part = 0.0;
-                    int c1 = c0 + 64 < dm ? c0 + 64 : dm;
-                    for (int t = c0; t < c1; ++t) part += widen(hidden, dtype, row + t) * (double)wg[(int64_t)t * dg + j];
-                    acc += part;
-                }
+                for (int t = 0; t < dm; ++t) acc += widen(hidden, dtype, row + t) * (double)wg[(int64_t)t * dg + j];
                 z[j] = acc;
                 if (z_out) z_out[((int64_t)b * n + i) * dg + j] = acc;
             }
@@ -588,16 +592,7 @@ int focus_oracle_route(int32_t B, int32_t n, int32_t dm, int32_t dg, int32_t K, 
         }
         for (int i = 0; i < n; ++i) {
             const double *s = Q + (int64_t)i * K;
-            uint32_t m = 0;
-            for (int g = 0; g < K; ++g) {
-                int beaten_by = 0;
-                for (int o = 0; o < K; ++o) {
-                    if (o == g) continue;
-                    if (s[o] > s[g] || (s[o] == s[g] && o < g)) ++beaten_by;
-                }
-                if (beaten_by < topk) m |= (1u << g);
-            }
-            masks[(int64_t)b * n + i] = m;
+            masks[(int64_t)b * n + i] = topk_of_scores(s, K, topk);
             if (g_out) for (int g = 0; g < K; ++g) g_out[((int64_t)b * n + i) * K + g] = s[g];
         }
     }

@@ -9,9 +9,25 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfocus.so")
 SOURCES = ["focus_api.hip", "focus_assign.hip", "focus_attn_simple.hip", "focus_attn_mfma.hip",
            "focus_route.hip", "focus_decode.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=on",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=on", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-Wno-unused-command-line-argument"]
+
+
+def source_id():
+    """Hash of everything the library is compiled from (sources, internal headers, the public header, the
+    flags).  The build stores it in the library (focus_build_id); the binding compares it on load."""
+    import hashlib
+    h = hashlib.sha256()
+    names = sorted(os.listdir(CSRC))
+    for name in names:
+        path = os.path.join(CSRC, name)
+        if os.path.isfile(path) and name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(path, "rb").read())
+    h.update(open(os.path.join(os.path.dirname(HERE), "include", "focus.h"), "rb").read())
+    h.update(" ".join(FLAGS).encode())
+    return h.hexdigest()[:16]
 
 
 # The attention kernel reads its LDS operands with inline ds_read whose completion the compiler does not track
@@ -47,6 +63,8 @@ def build_library(verbose=False):
     for s in SOURCES:
         o = os.path.join(HERE, "_build", s.replace(".hip", ".o"))
         cmd = [hipcc] + [f for f in FLAGS if f != "-shared"] + ["-c", os.path.join(CSRC, s), "-o", o]
+        if s == "focus_api.hip":
+            cmd.insert(1, '-DFOCUS_BUILD_ID="%s"' % source_id())
         err = None
         if s == NO_SPILL_SOURCE:
             cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
@@ -76,11 +94,11 @@ def build_library(verbose=False):
 
 
 def build_probes(verbose=False):
-    """Stand-alone measurement programs under csrc/probes (not part of the library)."""
+    """The stand-alone MFMA-rate program under csrc/probes that bench.py runs as a child process (not part of the library)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = os.path.join(HERE, "_build", "issue_rates")
+    out = os.path.join(HERE, "_build", "mfma_peak")
     os.makedirs(os.path.dirname(out), exist_ok=True)
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-w", "-o", out, os.path.join(CSRC, "probes", "issue_rates.hip")]
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-w", "-o", out, os.path.join(CSRC, "probes", "mfma_peak.hip")]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

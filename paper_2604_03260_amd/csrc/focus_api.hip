@@ -1,6 +1,9 @@
 // Host side of libfocus.so: argument checks, workspace layout, dispatch.
 // Everything that computes runs in the HIP kernels of the other translation units.
+// the library is compiled with hidden visibility: only what the public header declares is exported
+#pragma GCC visibility push(default)
 #include "../../include/focus.h"
+#pragma GCC visibility pop
 #include "focus_internal.h"
 
 #include <algorithm>
@@ -321,7 +324,7 @@ namespace {
 // one launch of the attention kernels over the whole mask (pair_set 0) or one of its two disjoint parts
 focus_status attn_launch(const focus_params* p, int pair_set, const void* q, const void* k, const void* v,
                          void* workspace, size_t workspace_bytes, void* out, float* lse, int32_t* row_pairs,
-                         void* stream, const char* who)
+                         void* stream, const char* who, bool force_vector = false)
 {
     focus::Layout L;
     focus::HeadMap hm;
@@ -339,7 +342,7 @@ focus_status attn_launch(const focus_params* p, int pair_set, const void* q, con
     if (st != FOCUS_OK) return st;
     L.pair_set = pair_set;
     hipError_t e;
-    if (L.dtype != FOCUS_F32)
+    if (L.dtype != FOCUS_F32 && !force_vector)
         e = focus::launch_attn_mfma(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
     else
         e = focus::launch_attn_simple(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
@@ -389,6 +392,9 @@ focus_status focus_attn_fwd_two_call(const focus_params* p, const void* q, const
         return fail(FOCUS_EUNSUPPORTED, "focus_attn_fwd_two_call takes contiguous tensors (use focus_attn_fwd_set and "
                                         "focus_attn_merge on contiguous partial outputs, or the fused focus_attn_fwd)");
     if (misaligned16(part_out)) return fail(FOCUS_EINVAL, "part_out must be 16-byte aligned");
+    if (!out) return fail(FOCUS_EINVAL, "out must not be NULL");
+    if (misaligned16(out)) return fail(FOCUS_EINVAL, "out must be 16-byte aligned");
+    if (out == q || out == k || out == v) return fail(FOCUS_EINVAL, "out must not alias an input");
     const size_t rows = (size_t)p->B * (size_t)p->Hq * (size_t)p->n;
     const size_t elem = (p->dtype == FOCUS_F32) ? 4 : 2;
     char* oa = (char*)part_out;
@@ -401,28 +407,17 @@ focus_status focus_attn_fwd_two_call(const focus_params* p, const void* q, const
     st = attn_launch(p, 2, q, k, v, workspace, workspace_bytes, ob, lb, nullptr, stream,
                      "focus_attn_fwd_two_call (set B)");
     if (st != FOCUS_OK) return st;
-    if (!out) return fail(FOCUS_EINVAL, "out must not be NULL");
     return focus_attn_merge((int64_t)rows, p->d, p->dtype, oa, la, ob, lb, out, lse, stream);
 }
 
-// Same contract as focus_attn_fwd, but always through the fp32 vector kernel
-// (no matrix cores).  Used by tests to cross-check the MFMA kernel at sizes the
-// CPU oracle cannot cover in full; not declared in the public header.
+// Same contract and the same argument checks as focus_attn_fwd, but always through the fp32 vector kernel
+// (no matrix cores): the on-device cross-check of the MFMA kernel at sizes the CPU oracle cannot cover in full.
 focus_status focus_attn_fwd_vector(const focus_params* p, const void* q, const void* k, const void* v,
                                    void* workspace, size_t workspace_bytes, void* out, float* lse,
                                    int32_t* row_pairs, void* stream)
 {
-    focus::Layout L;
-    focus::HeadMap hm;
-    focus_status st = make_layout(p, &L, &hm);
-    if (st != FOCUS_OK) return st;
-    if (!q || !k || !v || !out) return fail(FOCUS_EINVAL, "q, k, v and out must not be NULL");
-    st = check_ws(L, workspace, workspace_bytes);
-    if (st != FOCUS_OK) return st;
-    hipError_t e = focus::launch_attn_simple(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs,
-                                             (hipStream_t)stream);
-    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_attn_fwd_vector: %s", hipGetErrorString(e));
-    return FOCUS_OK;
+    return attn_launch(p, 0, q, k, v, workspace, workspace_bytes, out, lse, row_pairs, stream,
+                       "focus_attn_fwd_vector", true);
 }
 
 namespace {
@@ -491,7 +486,7 @@ focus_status focus_attn_soft_fwd(const focus_params* p, float lambda, const floa
     return soft_launch(p, lambda, g, q, k, v, workspace, workspace_bytes, out, lse, stream, false);
 }
 
-// The same through the fp32 vector kernel (cross-check of the MFMA kernel in tests; not in the public header).
+// The same through the fp32 vector kernel (cross-check of the MFMA kernel in tests).
 focus_status focus_attn_soft_fwd_vector(const focus_params* p, float lambda, const float* g, const void* q,
                                         const void* k, const void* v, void* workspace, size_t workspace_bytes,
                                         void* out, float* lse, void* stream)
@@ -568,6 +563,7 @@ focus_status decode_prefill_common(const focus_params* p, int32_t n_ctx, const v
     if (st != FOCUS_OK) return st;
     if (n_ctx < 0 || n_ctx > p->n) return fail(FOCUS_EINVAL, "n_ctx must be in [0, n] (got %d, n=%d)", n_ctx, p->n);
     if (!token_masks && (!k_cache || !centroids)) return fail(FOCUS_EINVAL, "k_cache and centroids must not be NULL");
+    if (!token_masks && misaligned16(k_cache)) return fail(FOCUS_EINVAL, "k_cache must be 16-byte aligned");
     if (!state) return fail(FOCUS_EINVAL, "state is NULL");
     if (((uintptr_t)state & 255) != 0) return fail(FOCUS_EWORKSPACE, "state is not 256-byte aligned");
     if (state_bytes < L.total) return fail(FOCUS_EWORKSPACE, "state has %zu bytes, %zu needed", state_bytes, L.total);
@@ -589,8 +585,9 @@ focus_status decode_step_common(const focus_params* p, int32_t pos, const int32_
     if (!pos_dev && (pos < 0 || pos >= p->n)) return fail(FOCUS_EINVAL, "pos must be in [0, n) (got %d, n=%d)", pos, p->n);
     if (!q_new || !k_new || !v_new || (!centroids && !token_mask) || !k_cache || !v_cache || !out)
         return fail(FOCUS_EINVAL, "q_new, k_new, v_new, centroids (or the token mask), k_cache, v_cache and out must not be NULL");
-    if (misaligned16(q_new) || misaligned16(k_cache) || misaligned16(v_cache))
-        return fail(FOCUS_EINVAL, "q_new, k_cache and v_cache must be 16-byte aligned");
+    if (misaligned16(q_new) || misaligned16(k_new) || misaligned16(v_new) || misaligned16(k_cache) ||
+        misaligned16(v_cache) || misaligned16(out))
+        return fail(FOCUS_EINVAL, "q_new, k_new, v_new, k_cache, v_cache and out must be 16-byte aligned");
     if (!state) return fail(FOCUS_EINVAL, "state is NULL");
     if (((uintptr_t)state & 255) != 0) return fail(FOCUS_EWORKSPACE, "state is not 256-byte aligned");
     if (state_bytes < L.total) return fail(FOCUS_EWORKSPACE, "state has %zu bytes, %zu needed", state_bytes, L.total);
@@ -685,5 +682,10 @@ focus_status focus_workspace_views(const focus_params* p, void* workspace, const
 const char* focus_last_error(void) { return g_err; }
 
 int focus_version(void) { return 100; }
+
+#ifndef FOCUS_BUILD_ID
+#define FOCUS_BUILD_ID "unknown"
+#endif
+const char* focus_build_id(void) { return FOCUS_BUILD_ID; }
 
 }  // extern "C"

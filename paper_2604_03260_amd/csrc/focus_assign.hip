@@ -180,6 +180,9 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
                 if (beaten < L.topk) mask |= (1u << g);
             }
         }
+        // A NaN score loses no comparison and would add its group to the topk others: a membership that is not
+        // a topk-subset has no class.  Such a token (only a NaN can cause it) takes the first topk groups.
+        if (__popc(mask) != L.topk) mask = (L.topk == 32) ? 0xffffffffu : ((1u << L.topk) - 1u);
 #pragma unroll
         for (int g = 0; g < KMAX; ++g) acc[g] = 0.0;
         // class = colex rank of the membership set among all topk-subsets

@@ -80,8 +80,10 @@ __device__ inline uint32_t wave_topk_mask(double s, int lane, int K, int topk)
         const double so = __shfl(s, o, 64);
         beaten += (o != lane && (so > s || (so == s && o < lane))) ? 1 : 0;
     }
-    const unsigned long long member = __ballot(lane < K && beaten < topk);
-    return (uint32_t)member;
+    uint32_t member = (uint32_t)__ballot(lane < K && beaten < topk);
+    // a NaN score loses no comparison: more than topk bits, replaced by the first topk groups
+    if (__popc(member) != topk) member = (topk == 32) ? 0xffffffffu : ((1u << topk) - 1u);
+    return member;
 }
 
 // A membership given from outside (the per-layer router) must be a topk-subset of the K groups: anything else
@@ -145,6 +147,7 @@ __global__ __launch_bounds__(256) void decode_prefill_score_kernel(DecodeLayout 
         for (int o = 0; o < KMAX; ++o) beaten += (o < K && o != g && (s[o] > s[g] || (s[o] == s[g] && o < g))) ? 1 : 0;
         if (g < K && beaten < L.topk) m |= (1u << g);
     }
+    if (__popc(m) != L.topk) m = (L.topk == 32) ? 0xffffffffu : ((1u << L.topk) - 1u);   // NaN scores
     ((uint32_t*)(st + L.off_mk))[(size_t)bhk * L.n + j] = m;
 }
 

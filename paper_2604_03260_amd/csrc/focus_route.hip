@@ -4,9 +4,10 @@
 //   or Q = exp(S / tau) followed by N rounds of {columns / their sum over the sequence's tokens,
 //   rows / their sum over the groups}; the top-k entries of a row become the token's membership.
 //
-// Everything is fp64.  The projection adds exact products (fp32 x bf16/fp16/fp32 fits in fp64) in a
-// fixed order -- 64 consecutive hidden components in index order, the chunk sums in chunk order --
-// so z, S and, without Sinkhorn, the membership are reproducible bit for bit.
+// Everything is fp64.  The projection is the plain inner product of Eq. 1: its products are exact
+// (fp32 x bf16/fp16/fp32 fits in fp64) and are added one by one in index order t = 0 .. d_model-1 (one
+// fused multiply-add per term, which rounds once, like an exact product followed by an add), so z, S
+// and, without Sinkhorn, the membership are reproducible bit for bit.
 //
 // Kernels:
 //   to_f64            W_g and C as fp64 tables (wave-uniform operands come from scalar loads);
@@ -32,7 +33,7 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int RT = 64;                       // tokens per work-group of the projection (one per lane)
-constexpr int RC = 64;                       // hidden components per chunk (the unit of the summation order)
+constexpr int RC = 64;                       // hidden components per LDS stage (staging only: the sum runs on across stages)
 
 __global__ void to_f64_kernel(const float* __restrict__ src, double* __restrict__ dst, size_t count)
 {
@@ -68,6 +69,7 @@ __device__ inline uint32_t topk_mask(const double (&s)[KP], int K, int topk)
             if (o != g) beaten += (o < K && (s[o] > s[g] || (s[o] == s[g] && o < g))) ? 1 : 0;
         if (g < K && beaten < topk) m |= (1u << g);
     }
+    if (__popc(m) != topk) m = (topk == 32) ? 0xffffffffu : ((1u << topk) - 1u);   // a NaN among the scores
     return m;
 }
 
@@ -127,9 +129,6 @@ __global__ __launch_bounds__(64 * NW) void route_project_kernel(RouteLayout R, c
         }
         __syncthreads();               // also orders this write after every wave's reads two chunks ago
         if (ch + 1 < nchunk) FOCUS_ROUTE_LOAD(ch + 1);
-        double part[JW];
-#pragma unroll
-        for (int j = 0; j < JW; ++j) part[j] = 0.0;
         const int tbase = ch * RC;
         const int tcount = min(RC, dm - tbase);          // dm is a multiple of 8: whole pieces only
 #pragma unroll 1
@@ -156,11 +155,9 @@ __global__ __launch_bounds__(64 * NW) void route_project_kernel(RouteLayout R, c
             for (int e = 0; e < EPC; ++e) {
                 const double* wr = w64 + (size_t)(tbase + cc * EPC + e) * DG + wave * JW;   // wave-uniform
 #pragma unroll
-                for (int j = 0; j < JW; ++j) part[j] = fma(xv[e], wr[j], part[j]);
+                for (int j = 0; j < JW; ++j) acc[j] = fma(xv[e], wr[j], acc[j]);
             }
         }
-#pragma unroll
-        for (int j = 0; j < JW; ++j) acc[j] = __dadd_rn(acc[j], part[j]);
     }
 #undef FOCUS_ROUTE_LOAD
 
@@ -204,6 +201,7 @@ __global__ __launch_bounds__(64 * NW) void route_project_kernel(RouteLayout R, c
                 }
                 if (beaten < R.topk) m |= (1u << g);
             }
+            if (__popc(m) != R.topk) m = (R.topk == 32) ? 0xffffffffu : ((1u << R.topk) - 1u);   // NaN scores
             masks[tok] = m;
             if (soft) for (int g = 0; g < K; ++g) soft[tok * K + g] = mine[g];
         } else {

@@ -27,7 +27,8 @@ EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_work
            "focus_decode_state_views", "focus_decode_step_at",
            "focus_decode_prefill_tokens", "focus_decode_step_tokens",
            "focus_soft_workspace_size", "focus_attn_soft_fwd",
-           "focus_last_error", "focus_version")
+           "focus_attn_fwd_vector", "focus_attn_soft_fwd_vector",
+           "focus_last_error", "focus_version", "focus_build_id")
 
 
 class FocusRouteParams(ctypes.Structure):
@@ -60,14 +61,30 @@ _lib = None
 
 
 def load_library():
-    """Loads libfocus.so; builds it first only when no built library is present."""
+    """Loads libfocus.so; builds it first when no built library is present, or when the one present was
+    compiled from other sources than those on disk (a stale library must never pass for the current code)."""
     global _lib
     if _lib is not None:
         return _lib
+    from . import build as _build
     if not os.path.exists(LIB_PATH):
-        from . import build as _build
         _build.build_library()
     lib = ctypes.CDLL(LIB_PATH)
+    want = _build.source_id()
+    try:
+        lib.focus_build_id.restype = ctypes.c_char_p
+        have = lib.focus_build_id().decode()
+    except AttributeError:
+        have = "none"
+    if have != want:
+        import sys
+        sys.stderr.write("libfocus.so was built from other sources (%s, now %s): rebuilding\n" % (have, want))
+        del lib
+        _build.build_library()
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.focus_build_id.restype = ctypes.c_char_p
+        if lib.focus_build_id().decode() != want:
+            raise RuntimeError("libfocus.so does not match its sources after a rebuild")
     vp, sz = ctypes.c_void_p, ctypes.c_size_t
     pp = ctypes.POINTER(FocusParams)
     lib.focus_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
@@ -116,6 +133,7 @@ def load_library():
     lib.focus_last_error.restype = ctypes.c_char_p
     lib.focus_version.argtypes = []
     lib.focus_version.restype = ctypes.c_int
+    lib.focus_build_id.argtypes = []
     _lib = lib
     return lib
 

@@ -58,10 +58,16 @@ def check_assign(wl, inp, res, head_map=None):
     return mq, mk
 
 
-def check_attn(wl, inp, res, mq, mk, rows=None, head_map=None, scale=0.0, tol=None):
-    """Outputs against the oracle on `rows` ((b,h,i) triples) or every row."""
+def host_inputs(inp):
+    """q, k, v as the host arrays the oracle takes (the same bytes)."""
+    return tuple(workloads.to_host_bits(inp[x]) for x in ("q", "k", "v"))
+
+
+def check_attn(wl, inp, res, mq, mk, rows=None, head_map=None, scale=0.0, tol=None, host=None):
+    """Outputs against the oracle on `rows` ((b,h,i) triples) or every row.  host: host_inputs(inp), when
+    a caller checks several slices of rows and wants the device-to-host copies made once."""
     pb = problem_of(wl, head_map, scale)
-    qh, kh, vh = (workloads.to_host_bits(inp[x]) for x in ("q", "k", "v"))
+    qh, kh, vh = host if host is not None else host_inputs(inp)
     o_ref, lse_ref, pairs_ref = fo.attn_rows(pb, qh, kh, vh, mq, mk, rows=rows)
     if rows is None:
         sel = lambda t: t.reshape((-1,) + tuple(t.shape[3:]))

@@ -17,12 +17,27 @@ def declared_symbols():
     return sorted(set(re.findall(r"\b(focus_[a-z_]+)\s*\(", text)))
 
 
-def test_every_declared_symbol_is_exported():
+def exported_symbols():
+    """The dynamic symbol table of the built library, read from the ELF file itself."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", focus.LIB_PATH], check=True, capture_output=True, text=True).stdout
+    # text symbols only: everything the library defines and exports as code
+    return sorted({line.split()[-1] for line in out.splitlines() if len(line.split()) == 3 and line.split()[1] in "Tt"})
+
+
+def test_declared_and_exported_symbols_are_the_same_set():
     lib = focus.load_library()
     names = declared_symbols()
     assert set(names) == set(focus.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
+    assert exported_symbols() == names, "the library exports exactly what include/focus.h declares"
+
+
+def test_library_matches_the_sources_on_disk():
+    from paper_2604_03260_amd import build
+    lib = focus.load_library()
+    assert lib.focus_build_id().decode() == build.source_id()
 
 
 def test_version_and_error_string():

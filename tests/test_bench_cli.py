@@ -11,9 +11,3 @@ def test_more_than_one_gpu_is_refused_with_a_message():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr
-
-
-def test_length_sweep_module_parses_its_arguments_without_a_gpu():
-    r = subprocess.run([sys.executable, "-m", "paper_2604_03260_amd.length_sweep", "--help"], cwd=ROOT,
-                       capture_output=True, text=True, timeout=300)
-    assert r.returncode == 0 and "--max-n" in r.stdout

@@ -152,8 +152,9 @@ def test_two_call_full_size_sampled(name):
     wl = workloads.CONFIGS[name]
     inp = workloads.make_inputs(wl, "cuda")
     res = run_sets(wl, inp)
-    mq = res["views"]["mq"].cpu().numpy().view(np.uint32)
-    mk = res["views"]["mk"].cpu().numpy().view(np.uint32)
+    mq, mk = harness.oracle_membership(wl, inp)          # the oracle's own membership, not the device's
+    assert np.array_equal(res["views"]["mq"].cpu().numpy().view(np.uint32), mq)
+    assert np.array_equal(res["views"]["mk"].cpu().numpy().view(np.uint32), mk)
     rows = workloads.sample_rows(wl, 768)
     check_set(wl, inp, res["A"], mq, mk, "A", rows=rows)
     check_set(wl, inp, res["B"], mq, mk, "B", rows=rows)

@@ -357,6 +357,31 @@ def test_topk_ties_lower_index_wins():
     assert list(fo.topk_masks(pb1, sc)[0, 0]) == [0b0010, 0b0001, 0b0001]
 
 
+def test_scores_that_are_not_numbers_give_the_first_topk_groups():
+    """The paper is silent on non-finite scores.  Reading: infinities are ordinary values of the ranking;
+    a token with a NaN among its scores has no ranking and takes the first topk groups, so that every
+    membership is a topk-subset (what the per-group lists of topk*n entries rest on)."""
+    pb = fo.Problem(1, 1, 1, 6, 4, 4, 2, 4)
+    inf, nan = float("inf"), float("nan")
+    sc = np.array([[[[0.0, 3.0, nan, 1.0],            # a NaN: first two groups, not {1, 3} and not {1, 2, 3}
+                     [nan, nan, nan, nan],
+                     [inf, 1.0, inf, -inf],           # infinities rank; the tie between groups 0 and 2 is no issue
+                     [-inf, -inf, -inf, 5.0],         # tie among -inf: lower index wins
+                     [1.0, 2.0, 3.0, 4.0],
+                     [inf, nan, 0.0, 0.0]]]])
+    m = fo.topk_masks(pb, sc)[0, 0]
+    assert [int(x) for x in m] == [0b0011, 0b0011, 0b0101, 0b1001, 0b1100, 0b0011]
+    assert all(bin(int(x)).count("1") == 2 for x in m)
+    # through the scoring itself: an Inf component against a zero centroid component makes a NaN score
+    x = np.ones((1, 1, 6, 4), dtype=np.float32)
+    x[0, 0, 2, 1] = inf
+    c = np.array([[[1, 0, 0, 0], [0, 1, 0, 0], [0, 0, 1, 0], [0, 0, 0, 1]]], dtype=np.float32)
+    assert int(fo.membership(pb, x, c, True)[0, 0, 2]) == 0b0011
+    c2 = np.array([[[1, 1, 0, 0], [0, 1, 0, 0], [0, -1, 1, 0], [0, 1, 0, 1]]], dtype=np.float32)   # no zero against the Inf
+    c2[c2 == 0] = 0.5
+    assert int(fo.membership(pb, x, c2, True)[0, 0, 2]) == 0b0011   # +inf, +inf, -inf, +inf: groups 0 and 1
+
+
 def test_group_lists_are_ascending_positions():
     rng = np.random.default_rng(5)
     B, H, n, K, topk = 2, 3, 200, 5, 2

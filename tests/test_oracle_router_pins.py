@@ -1,7 +1,7 @@
 """Pins of the router oracle (Sec. 2 Eq. 1 + Sinkhorn recipe) against things other than itself.
 
 R1 the projection against a library matmul (and exactly, on small integers);
-R2 the 64-chunk accumulation order; R3 no normalisation = plain top-k of (h W_g) C^T / tau;
+R2 the sequential accumulation order of the inner product; R3 no normalisation = plain top-k of (h W_g) C^T / tau;
 R4 a literal Python transcription of the recipe without the max shift on a tiny case;
 R5 Sinkhorn invariants: rows sum to one, cross-ratios of exp(S/tau) are preserved
 (diagonal scaling), columns balance to n/K in the limit; R6 degenerate cases
@@ -61,22 +61,43 @@ def test_r1_bf16_hidden_is_widened_exactly():
     assert np.abs(z - ref.numpy()).max() < 1e-13
 
 
-def test_r2_accumulation_is_chunked_by_64():
-    # 1 + 64 tiny terms in the second chunk: added chunk-wise they survive, added one by one to 2^53 they vanish.
-    dm = 128
-    h = np.zeros((1, 1, dm), dtype=np.float32)
+def test_r2_accumulation_is_sequential_in_index_order():
+    """Eq. 1 is a plain inner product; the oracle adds its terms one by one, t = 0 .. d_model-1.
+
+    Checked against math.fsum-free, exactly representable cases that tell the sequential order
+    from a blocked or pairwise one: 2^53 followed by ones loses every one when they are added
+    singly (round to even), and keeps them when they are first summed among themselves."""
+    dm = 192
     wg = np.ones((dm, 1), dtype=np.float32)
-    h[0, 0, 0] = 2.0 ** 53
-    h[0, 0, 64:128] = 1.0
     c = np.ones((1, 1), dtype=np.float32)
+    h = np.zeros((1, 1, dm), dtype=np.float32)
+    h[0, 0, 0] = 2.0 ** 53
+    h[0, 0, 64:192] = 1.0                       # two whole blocks of 64 ones: any 64-blocked sum keeps them
     _, z, _ = fo.route(h, wg, c, 1, iters=0, want_soft=True)
-    assert z[0, 0, 0] == 2.0 ** 53 + 64.0
-    # inside a chunk the order is sequential: the same ones right after the big term are lost
+    assert z[0, 0, 0] == 2.0 ** 53
+    # the ones first, the large term last: every term survives
     h2 = np.zeros((1, 1, dm), dtype=np.float32)
-    h2[0, 0, 0] = 2.0 ** 53
-    h2[0, 0, 1:64] = 1.0
+    h2[0, 0, :191] = 1.0
+    h2[0, 0, 191] = 2.0 ** 53
     _, z2, _ = fo.route(h2, wg, c, 1, iters=0, want_soft=True)
-    assert z2[0, 0, 0] == 2.0 ** 53
+    assert z2[0, 0, 0] == 2.0 ** 53 + 192.0              # 191 + 2^53 is a tie: rounds to the even neighbour
+    # a python left-to-right float sum is the same recipe (floats are fp64, products here are exact)
+    rng = np.random.default_rng(12)
+    h3 = rng.standard_normal((1, 3, 150)).astype(np.float32)
+    w3 = rng.standard_normal((150, 2)).astype(np.float32)
+    _, z3, _ = fo.route(h3, w3, np.ones((1, 2), dtype=np.float32), 1, iters=0, want_soft=True)
+    for i in range(3):
+        for j in range(2):
+            acc = 0.0
+            for t in range(150):
+                acc += float(h3[0, i, t]) * float(w3[t, j])
+            assert z3[0, i, j] == acc
+
+
+def test_router_width_beyond_the_oracle_buffer_is_refused():
+    h, wg, c = rand_router(13, 1, 4, 16, 257, 2)
+    with pytest.raises(Exception):
+        fo.route(h, wg, c, 1, iters=0)
 
 
 # ---------------------------------------------------------------- R3 plain top-k
