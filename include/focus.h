@@ -166,6 +166,19 @@ focus_status focus_route(const focus_route_params *rp, const void *hidden, const
                          const float *centroids, void *route_workspace, size_t workspace_bytes,
                          uint32_t *token_masks, double *soft, void *stream);
 
+/* focus_route for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels and
+ * results as focus_route, but the scratch is a buffer inside the library's own device image (16 MiB per GPU,
+ * held until the process ends) instead of route_workspace; the call allocates nothing.  A problem whose
+ * focus_route_workspace_size() exceeds 16 MiB (about B*n*K*8 + d_model*d_g*8 bytes: e.g. n = 131072 with
+ * K = 8 still fits, n = 262144 with K = 8 does not) is refused with FOCUS_EWORKSPACE before anything is
+ * launched.  All calls on one GPU share that one buffer: two calls that overlap in time on the same GPU
+ * (different streams or threads) race; calls on one stream are safe back to back.  Nothing in the buffer is
+ * read before the same call has written it, so leftovers of an earlier call do no harm. */
+focus_status focus_route_noalloc(const focus_route_params *rp, const void *hidden, const float *w_g,
+                                 const float *centroids, uint32_t *token_masks, double *soft,
+                                 void *stream);
+
 /* focus_assign for memberships given per token (the router's output): token_masks [B,n]
  * uint32 DEVICE, each a topk-subset of the K groups, shared by all query and KV heads of
  * the token.  Fills the workspace exactly as focus_assign does (masks, counts, lists,

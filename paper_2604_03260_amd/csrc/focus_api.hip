@@ -524,6 +524,28 @@ focus_status focus_route(const focus_route_params* rp, const void* hidden, const
     return FOCUS_OK;
 }
 
+focus_status focus_route_noalloc(const focus_route_params* rp, const void* hidden, const float* w_g,
+                                 const float* centroids, uint32_t* token_masks, double* soft, void* stream)
+{
+    focus::RouteLayout R;
+    focus_status st = make_route_layout(rp, &R);
+    if (st != FOCUS_OK) return st;
+    if (!hidden || !w_g || !centroids || !token_masks)
+        return fail(FOCUS_EINVAL, "hidden, w_g, centroids and token_masks must not be NULL");
+    if (misaligned16(hidden)) return fail(FOCUS_EINVAL, "hidden must be 16-byte aligned");
+    if (R.total > focus::ROUTE_STATIC_SCRATCH_BYTES)
+        return fail(FOCUS_EWORKSPACE, "focus_route_noalloc: this problem needs %zu bytes of scratch, the library's "
+                                      "static buffer holds %zu (use focus_route with a workspace of your own)",
+                    R.total, focus::ROUTE_STATIC_SCRATCH_BYTES);
+    char* ws = nullptr;
+    hipError_t e = focus::route_static_scratch(&ws);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_route_noalloc: static scratch: %s", hipGetErrorString(e));
+    // every part of the scratch the kernels read is written earlier in the same call: nothing needs clearing
+    e = focus::launch_route(R, hidden, w_g, centroids, ws, token_masks, soft, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_route_noalloc: %s", hipGetErrorString(e));
+    return FOCUS_OK;
+}
+
 focus_status focus_assign_tokens(const focus_params* p, const uint32_t* token_masks, const void* k, void* workspace,
                                  size_t workspace_bytes, int32_t* invalid_count, void* stream)
 {

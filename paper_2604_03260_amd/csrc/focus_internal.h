@@ -186,6 +186,10 @@ hipError_t launch_decode_step(const DecodeLayout& L, const HeadMap& hm, int pos,
                               void* out, float* lse, int32_t* row_pairs, hipStream_t s);
 hipError_t launch_route(const RouteLayout& R, const void* hidden, const float* wg, const float* cent, char* ws,
                         uint32_t* masks, double* soft, hipStream_t st);
+// The router's scratch for callers that may not allocate: a buffer of ROUTE_STATIC_SCRATCH_BYTES that lives in
+// the library's device image; *ptr is its address on the CURRENT device (looked up once per device).
+constexpr size_t ROUTE_STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+hipError_t route_static_scratch(char** ptr);
 hipError_t launch_assign_tokens(const Layout& L, const uint32_t* token_masks, const void* k, char* ws,
                                 int32_t* invalid_count, hipStream_t st);
 hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, const void* k,

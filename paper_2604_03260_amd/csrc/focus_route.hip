@@ -24,9 +24,36 @@
 //                     rows and leaves its own partial sums for the next pass.  The last pass writes
 //                     the masks (ties to the smaller group index) and, if asked, the soft assignment.
 #include "focus_internal.h"
+#include <mutex>
 #include <type_traits>
 
 namespace focus {
+
+// Scratch of focus_route_noalloc: device memory of the library's own image, one copy per GPU, held until the
+// process ends.  Host code never uses this name as an address: route_static_scratch() asks the runtime for the
+// array's device address once per device and hands that pointer to the kernels like any workspace.
+static __device__ __align__(256) unsigned char scratch[ROUTE_STATIC_SCRATCH_BYTES];
+
+hipError_t route_static_scratch(char** ptr)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static char* per_device[MAX_DEVICES] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));      // the copy of the array on the current device
+        if (e != hipSuccess) return e;
+        if (!p || ((uintptr_t)p & 255) != 0) return hipErrorInvalidSymbol;
+        per_device[dev] = (char*)p;
+    }
+    *ptr = per_device[dev];
+    return hipSuccess;
+}
 
 namespace {
 

@@ -21,7 +21,7 @@ DTYPES = {"f32": FOCUS_F32, "bf16": FOCUS_BF16, "f16": FOCUS_F16}
 TORCH_DTYPE_CODES = {torch.float32: FOCUS_F32, torch.bfloat16: FOCUS_BF16, torch.float16: FOCUS_F16}
 
 EXPORTS = ("focus_workspace_size", "focus_assign", "focus_attn_fwd", "focus_workspace_views",
-           "focus_route_workspace_size", "focus_route", "focus_assign_tokens",
+           "focus_route_workspace_size", "focus_route", "focus_route_noalloc", "focus_assign_tokens",
            "focus_attn_fwd_set", "focus_attn_merge", "focus_attn_fwd_two_call",
            "focus_decode_state_size", "focus_decode_prefill", "focus_decode_step",
            "focus_decode_state_views", "focus_decode_step_at",
@@ -127,6 +127,8 @@ def load_library():
     lib.focus_route_workspace_size.restype = ctypes.c_int
     lib.focus_route.argtypes = [rp, vp, vp, vp, vp, sz, vp, vp, vp]
     lib.focus_route.restype = ctypes.c_int
+    lib.focus_route_noalloc.argtypes = [rp, vp, vp, vp, vp, vp, vp]
+    lib.focus_route_noalloc.restype = ctypes.c_int
     lib.focus_assign_tokens.argtypes = [pp, vp, vp, vp, sz, vp, vp]
     lib.focus_assign_tokens.restype = ctypes.c_int
     lib.focus_last_error.argtypes = []
@@ -326,6 +328,12 @@ def focus_route(rp, hidden, w_g, centroids, route_workspace, token_masks, soft=N
                                       _ptr(route_workspace),
                                       route_workspace.numel() * route_workspace.element_size(),
                                       _ptr(token_masks), _ptr(soft), _stream()))
+
+
+def focus_route_noalloc(rp, hidden, w_g, centroids, token_masks, soft=None):
+    """focus_route with the library's static scratch instead of a workspace (no allocation anywhere)."""
+    _check(load_library().focus_route_noalloc(ctypes.byref(rp), _ptr(hidden), _ptr(w_g), _ptr(centroids),
+                                              _ptr(token_masks), _ptr(soft), _stream()))
 
 
 def focus_assign_tokens(p, token_masks, k, workspace, invalid_count=None):

@@ -247,3 +247,12 @@ def test_strides_are_refused_where_they_are_not_built():
     st = lib.focus_attn_fwd_two_call(ctypes.byref(p), fake, fake, fake, fake, ctypes.c_size_t(1 << 40), fake, fake, fake, fake,
                                      ctypes.c_void_p(0))
     assert st == focus.FOCUS_EUNSUPPORTED
+
+
+def test_noalloc_router_refuses_what_does_not_fit_its_scratch():
+    rp = focus.make_route_params(1, 1 << 20, 1024, 16, 8, 2, dtype="bf16", sinkhorn_iters=10, tau=0.1)
+    assert focus.focus_route_workspace_size(rp) > (16 << 20)
+    fake = ctypes.c_void_p(0x1000)
+    st = focus.load_library().focus_route_noalloc(ctypes.byref(rp), fake, fake, fake, fake, ctypes.c_void_p(0),
+                                                  ctypes.c_void_p(0))
+    assert st == focus.FOCUS_EWORKSPACE and "static buffer" in focus.focus_last_error()
