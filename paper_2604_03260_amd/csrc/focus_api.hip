@@ -175,6 +175,8 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->off_kmsk = L->coarse ? take(BHk * L->NKP * 4) : off;
     L->off_jobs = take(BHq * L->NT * 4);
     L->off_gk = (soft && p->dtype != FOCUS_F32) ? take((size_t)p->B * L->NKP * 128) : off;
+    L->off_kn2 = take(BHk * focus::KN2_SLOTS * 4);
+    L->off_nrflag = take(BHq * L->NT * 4);
     if (p->dtype != FOCUS_F32) {
         L->off_kc = take(BHk * L->NKP * (size_t)L->dp * 2);
         L->off_vt = take(BHk * L->NKP * (size_t)L->dp * 2);

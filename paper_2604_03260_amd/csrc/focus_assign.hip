@@ -344,14 +344,16 @@ __global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int which, ch
 }
 
 // ---------------------------------------------------------------- start of an assign pass
-// Pads of the class-ordered position arrays (qperm -1, kpos KPOS_PAD, the key masks of coarse classes 0) and, when
-// centroids are given, their fp64 table: one launch.
+// Pads of the class-ordered position arrays (qperm -1, kpos KPOS_PAD, the key masks of coarse classes 0), the
+// largest-key-norm slots (0) and, when centroids are given, their fp64 table: one launch.
 __global__ __launch_bounds__(256) void assign_init_kernel(int* __restrict__ qperm, size_t nq, int* __restrict__ kpos, size_t nk,
-                                                          int* __restrict__ kmsk, const float* __restrict__ cents,
+                                                          int* __restrict__ kmsk, unsigned* __restrict__ kn2, size_t nkn2,
+                                                          const float* __restrict__ cents,
                                                           double* __restrict__ cent64, int Hkv, int K, int d, int dcent, int kmax)
 {
     const size_t step = (size_t)gridDim.x * blockDim.x;
     const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (size_t i = i0; i < nkn2; i += step) kn2[i] = 0u;
     for (size_t i = i0; i < nq; i += step) qperm[i] = -1;
     for (size_t i = i0; i < nk; i += step) kpos[i] = KPOS_PAD;
     if (kmsk)
@@ -535,8 +537,8 @@ void launch_assign_init(const Layout& L, const float* centroids, char* ws, hipSt
     const int row_bytes = L.d * L.elem;
     const int dcent = (row_bytes + ROW_CHUNK_BYTES - 1) / ROW_CHUNK_BYTES * (ROW_CHUNK_BYTES / L.elem);
     hipLaunchKernelGGL(assign_init_kernel, dim3(grid), dim3(256), 0, st, (int*)(ws + L.off_qperm), nq, (int*)(ws + L.off_kpos), nk,
-                       L.coarse ? (int*)(ws + L.off_kmsk) : nullptr, centroids, (double*)(ws + L.off_cent64), L.Hkv, L.K, L.d,
-                       dcent, kmax);
+                       L.coarse ? (int*)(ws + L.off_kmsk) : nullptr, (unsigned*)(ws + L.off_kn2), (size_t)L.B * L.Hkv * KN2_SLOTS,
+                       centroids, (double*)(ws + L.off_cent64), L.Hkv, L.K, L.d, dcent, kmax);
 }
 
 // from masks, class ids and block histograms to the class-ordered arrays, group lists and job lists

@@ -35,9 +35,19 @@
 //    belongs in its LDS slot.  The loads of K(t+2), V(t+1) and the key positions
 //    of tile t+2 are issued in the middle of tile t, right after the one barrier
 //    per tile, and waited for with s_waitcnt vmcnt(0) just before the next one.
-//  * The softmax reference max of a row only moves when the true max has drifted
-//    by more than RESCALE_THRESHOLD (log2 units), so O is rarely rescaled; the
-//    row sum adds the bf16-rounded probabilities (v_dot2), the numbers PV uses.
+//  * Softmax without a reference where the data allow it.  softmax is invariant under a shift of the logits,
+//    so the usual running row max is only there to keep exp in range.  focus_assign leaves the largest squared
+//    key norm of every KV head in the workspace; with |q_i| from the row itself, Cauchy-Schwarz bounds every
+//    logit of row i (log2 units) by b_i = scale*log2(e)*|q_i|*max|k| (and by the cap, with a softcap).  A
+//    work-group whose rows all have b_i <= NOREF_BOUND takes p = exp2(logit) as it is, in [2^-60, 2^60]: no row
+//    max, no exchange between the half-waves, no rescaling of O, and (without a softcap) no multiply-subtract
+//    either, because the query rows are pre-multiplied by scale*log2(e) when they are loaded (one more 16-bit
+//    rounding of q, a relative 2^-9 per component: about 1e-3 absolute in a logit, below the rounding of the
+//    16-bit probabilities).  The sums stay far inside fp32 (2^60 * 2^24 keys * |v|), and out = O / l is the same
+//    exact softmax.  Any other work-group (large norms, non-finite keys) runs the second copy of the loop:
+//  * there the reference max of a row only moves when the true max has drifted
+//    by more than RESCALE_THRESHOLD (log2 units), so O is rarely rescaled.
+//  * The row sum adds the bf16-rounded probabilities (v_dot2), the numbers PV uses.
 #include "focus_internal.h"
 #include "focus_tileplan.h"
 #include <algorithm>
@@ -74,6 +84,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int NTHR = 256;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift before O is rescaled
+constexpr float NOREF_BOUND = 60.f;         // largest |logit| bound (log2 units) up to which exp2 needs no reference
+constexpr float NOREF_SLACK = 1.01f;        // the bound is taken this much larger than computed (fp32 rounding of the norms)
 constexpr float CAP_POLY_Z = 0.3f;          // |score*scale/softcap| up to which tanh is taken as its Taylor polynomial to z^5
 
 // within a 16-key group: MFMA k-slot p16 = h*8 + e  <->  key 8*(e/4) + 4*h + e%4,
@@ -81,12 +93,33 @@ constexpr float CAP_POLY_Z = 0.3f;          // |score*scale/softcap| up to which
 __host__ __device__ constexpr int slot_to_key16(int p16) { return 8 * ((p16 % 8) / 4) + 4 * (p16 / 8) + (p16 % 8) % 4; }
 
 // ---------------------------------------------------------------- gathers into class order
+// sum of the squares of the eight 16-bit values of a chunk (bf16 or IEEE half bit patterns)
+__device__ inline float chunk_norm2(const uint4& val, bool f16)
+{
+    const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+    float acc = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float a = f16 ? f16_bits_to_f32((uint16_t)(w[e] & 0xffffu)) : __uint_as_float(w[e] << 16);
+        const float b = f16 ? f16_bits_to_f32((uint16_t)(w[e] >> 16)) : __uint_as_float(w[e] & 0xffff0000u);
+        acc = fmaf(a, a, acc);
+        acc = fmaf(b, b, acc);
+    }
+    return acc;
+}
+
+// Also leaves the largest squared key norm of the (batch, KV head) in the workspace (off_kn2: KN2_SLOTS partial
+// maxima per head, cleared by the first launch of the assign pass): a non-negative float orders like its bit
+// pattern, so one atomicMax on the bits per work-group does it, and a NaN or infinite norm ends up above every
+// finite one.
 template <int D>
 __global__ __launch_bounds__(NTHR) void gather_k_kernel(Layout L, const uint16_t* __restrict__ k, char* __restrict__ ws)
 {
     constexpr int CPR = D / 8;                       // 16-byte chunks per row of the copy
     const int cin = L.d / 8;                         // ... and of a source row (d <= D)
     const int tile = blockIdx.x, bhk = blockIdx.y, tid = threadIdx.x;
+    const bool f16 = L.dtype == 2;
+    unsigned n2max = 0u;
     const int* kpos = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP + (size_t)tile * KT;
     uint4* dst = (uint4*)(ws + L.off_kc) + ((size_t)bhk * L.NKP + (size_t)tile * KT) * CPR;
     // source rows through the strides of k (multiples of 8 elements = one 16-byte chunk)
@@ -98,6 +131,25 @@ __global__ __launch_bounds__(NTHR) void gather_k_kernel(Layout L, const uint16_t
         uint4 val = make_uint4(0, 0, 0, 0);
         if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * pitch + ch];
         dst[id] = val;
+        // the CPR chunks of a row sit in CPR consecutive lanes (CPR a power of two <= 32, rows do not straddle waves)
+        float n2 = chunk_norm2(val, f16);
+#pragma unroll
+        for (int off = 1; off < CPR; off <<= 1) n2 += __shfl_xor(n2, off, 64);
+        const unsigned bits = __float_as_uint(n2) & 0x7fffffffu;     // a NaN may carry a sign bit
+        n2max = bits > n2max ? bits : n2max;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const unsigned o = (unsigned)__shfl_xor((int)n2max, off, 64);
+        n2max = o > n2max ? o : n2max;
+    }
+    __shared__ unsigned s_n2[NTHR / 64];
+    if ((tid & 63) == 0) s_n2[tid >> 6] = n2max;
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < NTHR / 64; ++w) n2max = s_n2[w] > n2max ? s_n2[w] : n2max;
+        // KN2_SLOTS slots per head, so that the work-groups of a head do not queue up on one address
+        if (n2max != 0u) atomicMax((unsigned*)(ws + L.off_kn2) + (size_t)bhk * KN2_SLOTS + (tile % KN2_SLOTS), n2max);
     }
 }
 
@@ -224,12 +276,16 @@ __device__ inline void pin_operands(V8 (&a)[N])
 // matrix cores next to the scores: G^T = g_K g_Q^T with both sides split into bf16 high and low parts (three
 // products per 16 groups), the query side pre-multiplied by -lambda*log2(e) so that the gate is 1/(1 + 2^G).
 // Runs one wavefront per SIMD (two more accumulators and the operands of G do not fit 256 registers).
-template <int D, int KS, int DB, int MFMA_WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE, bool SOFT>
+// NOREF: the softmax without a reference (head of this file).  Every launch runs the kernel twice: the NOREF
+// instantiation first, whose work-groups check their bound, leave a flag (1 = done here, 0 = not mine) and do
+// the tile or return; then the other instantiation, whose work-groups return at once where the flag says done.
+template <int D, int KS, int DB, int MFMA_WAVES, bool SOFTCAP, bool PAIRS, bool F16, bool COARSE, bool SOFT, bool NOREF>
 __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_WAVES) void attn_mfma_kernel(
     Layout L, HeadMap hm, int default_map, const uint16_t* __restrict__ q, const float* __restrict__ g,
-    const char* __restrict__ ws, uint16_t* __restrict__ out, float* __restrict__ lse,
+    char* ws_rw, uint16_t* __restrict__ out, float* __restrict__ lse,
     int32_t* __restrict__ row_pairs)
 {
+    const char* ws = ws_rw;              // everything but the flag of this work-group is only read
     typedef Half<F16> HT;
     typedef typename HT::T elem_t;
     typedef typename HT::V8 V8;
@@ -251,9 +307,16 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     constexpr int NVI = (NVB + MFMA_WAVES - 1) / MFMA_WAVES;
     constexpr int ATHR = 64 * MFMA_WAVES;                // threads of the work-group
 
+    static_assert(!(SOFT && NOREF), "the soft gate keeps the running reference");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n32 = lane & 31, hh = lane >> 5;
+    int* nrflag = (int*)(ws_rw + L.off_nrflag) + blockIdx.x;
+    if constexpr (NOREF) {
+        if (tid == 0) *nrflag = 1;                 // unless the bound check below says otherwise
+    } else if constexpr (!SOFT) {
+        if (*(volatile int*)nrflag != 0) return;   // the no-reference launch before this one did the tile
+    }
 
     const int BH = L.B * L.Hq;
     const int job = blockIdx.x / BH;
@@ -313,6 +376,37 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         for (int ks = 0; ks < KS; ++ks) qreg[ks] = rvalid ? qrow[2 * ks + hh] : zero;
     }
 
+    // Softmax without a reference (see the head of this file): every logit of row i is bounded by
+    // b_i = scale*log2(e) * |q_i| * max|k| (by the cap too, with a softcap); the whole work-group needs b_i <= NOREF_BOUND.
+    if constexpr (NOREF) {
+        float qn2 = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qn2 = fmaf((float)qreg[ks][e], (float)qreg[ks][e], qn2);
+        qn2 += __shfl_xor(qn2, 32, 64);                              // the other half of the row's components
+        unsigned kn2b = ((const unsigned*)(ws + L.off_kn2))[(size_t)bhk * KN2_SLOTS + lane];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const unsigned o = (unsigned)__shfl_xor((int)kn2b, off, 64);
+            kn2b = o > kn2b ? o : kn2b;
+        }
+        const float kn2 = __uint_as_float(kn2b);
+        float bnd = L.scale * LOG2E * NOREF_SLACK * sqrtf(qn2 * kn2);
+        if constexpr (SOFTCAP) bnd = fminf(bnd, L.softcap * LOG2E);  // capped logits never leave [-cap, cap]
+        if (__syncthreads_and((bnd <= NOREF_BOUND) ? 1 : 0) == 0) {  // a NaN bound compares false
+            if (tid == 0) *nrflag = 0;
+            return;
+        }
+        if constexpr (!SOFTCAP) {    // logits come off the matrix cores in log2 units
+            const float sl2q = L.scale * LOG2E;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qreg[ks][e] = (elem_t)((float)qreg[ks][e] * sl2q);
+        }
+    }
+
     // soft gate: this row's assignment times -lambda*log2(e), as bf16 high and low parts in B-operand order
     bf16x8 gqh[2], gql[2];
     const bool kg2 = L.K > 16;          // a second k-step of 16 groups
@@ -335,7 +429,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float m_ref = -INFINITY, l_run = 0.f;
+    float m_ref = NOREF ? 0.f : -INFINITY, l_run = 0.f;
     int npairs = 0;
 
     const float sl2 = L.scale * LOG2E;
@@ -520,6 +614,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
 
     // softmax step on one unit's scores: SIN (f32x16, consumed) -> POUT (2 x bf16x8), split in two parts.
     // PPEND: probabilities of the previous unit whose PV product has not been issued yet.
+    // NOREF: no row max, no rescaling, exp2 of the logit itself.
 #define F4_SOFTMAX_PRE(SIN, U, KPB, PPEND, GIN)                                                          \
     if constexpr (SOFT) {                                                                                \
         /* Eq. 2: score * (local ? 1 : sigmoid(lambda g_i.g_j)), then the causal mask (pads sit at INT_MAX) */ \
@@ -585,7 +680,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     } else {                                                                                             \
         if constexpr (PAIRS) npairs += 16;                                                               \
     }                                                                                                    \
-    {                                                                                                    \
+    if (!NOREF) {                                                                                        \
         float mx_ = SIN[0];                                                                              \
         _Pragma("unroll") for (int r = 1; r < 16; ++r) mx_ = fmaxf(mx_, SIN[r]);                         \
         mx_ = halfwave_max(mx_);                                                                         \
@@ -606,11 +701,11 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     }
 #define F4_SOFTMAX_EXP(SIN, POUT)                                                                        \
     {                                                                                                    \
-        const float m_use_ = (m_ref == -INFINITY) ? 0.f : m_ref;                                         \
+        const float m_use_ = NOREF ? 0.f : (m_ref == -INFINITY) ? 0.f : m_ref;                           \
         float psum_ = 0.f;                                                                               \
         _Pragma("unroll") for (int r = 0; r < 16; r += 2) {                                              \
-            const float a0_ = SOFTCAP ? (SIN[r] - m_use_) : fmaf(SIN[r], sl2, -m_use_);                  \
-            const float a1_ = SOFTCAP ? (SIN[r + 1] - m_use_) : fmaf(SIN[r + 1], sl2, -m_use_);          \
+            const float a0_ = NOREF ? SIN[r] : SOFTCAP ? (SIN[r] - m_use_) : fmaf(SIN[r], sl2, -m_use_); \
+            const float a1_ = NOREF ? SIN[r + 1] : SOFTCAP ? (SIN[r + 1] - m_use_) : fmaf(SIN[r + 1], sl2, -m_use_); \
             V2 pr_;                                                                                      \
             pr_[0] = (elem_t)__builtin_amdgcn_exp2f(a0_);                                                \
             pr_[1] = (elem_t)__builtin_amdgcn_exp2f(a1_);                                                \
@@ -761,9 +856,13 @@ hipError_t launch_one(const Layout& L, const HeadMap& hm, int default_map, const
                       float* lse, int32_t* row_pairs, hipStream_t st, const float* g = nullptr)
 {
     const unsigned grid = (unsigned)((size_t)L.NT * L.B * L.Hq);
-    hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16, COARSE, SOFT>), dim3(grid),
-                       dim3(64 * WAVES), 0, st, L, hm, default_map, (const uint16_t*)q, g, (const char*)ws,
-                       (uint16_t*)out, lse, row_pairs);
+    if constexpr (!SOFT)
+        hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16, COARSE, SOFT, true>), dim3(grid),
+                           dim3(64 * WAVES), 0, st, L, hm, default_map, (const uint16_t*)q, g, ws, (uint16_t*)out, lse,
+                           row_pairs);
+    hipLaunchKernelGGL((attn_mfma_kernel<D, KS, DB, WAVES, SOFTCAP, PAIRS, F16, COARSE, SOFT, false>), dim3(grid),
+                       dim3(64 * WAVES), 0, st, L, hm, default_map, (const uint16_t*)q, g, ws, (uint16_t*)out, lse,
+                       row_pairs);
     return hipGetLastError();
 }
 

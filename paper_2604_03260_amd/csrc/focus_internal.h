@@ -13,6 +13,7 @@ constexpr int LONG_N = 1 << 18; // from this sequence length on the MFMA kernel 
 constexpr int KT = 64;         // keys per attention tile; class segments of the permuted keys are padded to this
 constexpr int MAX_CLASSES = 256;
 constexpr int MAX_HQ = 256;
+constexpr int KN2_SLOTS = 64;  // partial maxima of the squared key norms per (batch, KV head), one per lane of a wavefront
 constexpr int KPOS_PAD = 0x7fffffff;  // position stored in padded key slots: never <= a query position
 
 // Element types as the kernels see them: float, uint16_t for a bfloat16 bit pattern, f16_bits for an IEEE half.
@@ -91,6 +92,11 @@ struct Layout {
     size_t off_jobs;                   // [B,Hq,NT] (class << 24 | tile) heaviest first, -1 unused
     size_t off_gk;                     // [B,NKP,2,32] bf16: the soft assignment of every key position as bf16 high and
                                        // low parts, groups padded to 32, chunks swizzled per key (soft gate, 16-bit types)
+    size_t off_kn2;                    // [B,Hkv,KN2_SLOTS] bit patterns of partial maxima of the squared key norms of the
+                                       // head (16-bit types; cleared by assign_init, raised by gather_k, the attention
+                                       // kernel takes the largest)
+    size_t off_nrflag;                 // [B,Hq,NT] per work-group of the attention launch: 1 = the no-reference
+                                       // instantiation did the tile, 0 = left to the other one (16-bit types)
     size_t off_kc;                     // [B,Hkv,NKP,dp] keys in class order (16-bit types)
     size_t off_vt;                     // [B,Hkv,NKP/KT,dp,KT] values, transposed per key tile (16-bit types)
     size_t total;

@@ -144,6 +144,31 @@ def test_nan_and_inf_tokens_keep_a_valid_membership(dtype, K, topk):
     say("nonfinite", harness.check_attn(wl, inp, res, mq, mk, rows=rows))
 
 
+@pytest.mark.parametrize("case", ["some_rows", "all_keys", "softcap_rows", "d256_rows", "f16_k8"])
+def test_large_norms_take_the_running_reference(case):
+    """The 16-bit kernel skips the softmax reference where Cauchy-Schwarz bounds every logit of a work-group's rows
+    (|q_i| * max|k| * scale * log2 e <= 60); rows or keys with large norms must fall back to the running row max.
+    Both forms inside one launch (some work-groups each), the fallback alone, with a softcap, at head dim 256."""
+    kw = dict(n=1500, dtype="bf16", d=128, K=4, topk=2, window=40, Hq=4, Hkv=2)
+    if case == "softcap_rows":
+        kw.update(softcap=30.0, K=8, topk=2)
+    if case == "d256_rows":
+        kw.update(d=256, Hq=2, Hkv=1)
+    if case == "f16_k8":
+        kw.update(dtype="f16", K=8, topk=1, d=96)
+    wl = small("norms_" + case, **kw)
+    inp = workloads.make_inputs(wl, "cuda")
+    if case == "all_keys":
+        inp["k"] *= 12.0                        # every bound far above 60: only the running-reference form runs
+    else:
+        inp["q"][0, 0, 200:330] *= 40.0         # logits in the hundreds for these rows (and their work-groups)
+        inp["q"][0, wl.Hq - 1, 1000] *= 25.0
+    res = harness.run_gpu(wl, inp)
+    mq, mk = harness.check_assign(wl, inp, res)
+    say(wl.name, harness.check_attn(wl, inp, res, mq, mk))
+    harness.check_pair_totals(wl, res, mq, mk)
+
+
 def test_disjoint_roles_only_window_survives():
     # queries all land in group 0 and keys in group 1: the mask is the window alone
     wl = small("window_only", n=900, K=2, topk=1, window=37, Hq=2, Hkv=2)
