@@ -623,7 +623,8 @@ def main():
     ap.add_argument("--workload", default="cfg5", help="headline workload (default cfg5, the largest configuration)")
     ap.add_argument("--legs-workload", default="cfg3",
                     help="workload of the side legs (two-call, router, soft gate, other head dims and types)")
-    ap.add_argument("--only-headline", action="store_true", help="the headline step only (profiling runs)")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="the headline step and its dense comparator only (profiling runs; add --no-dense to drop the latter)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other configurations")
@@ -665,7 +666,7 @@ def main():
         cal2 = cal.clone()
         torch.cuda.synchronize()
         del cal, cal2
-    dense_steps = 0 if (args.no_dense or only) else max(2, min(steps // 4, 5))
+    dense_steps = 0 if args.no_dense else max(1 if only else 2, min(steps // 4, 5))
     head, r = measure(torch, focus, workloads, wl, steps, warmup, dense_steps, keep=True)
     out_focus = r.out
     half = wl.dtype in ("bf16", "f16")
