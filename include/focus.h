@@ -97,7 +97,15 @@ focus_status focus_assign(const focus_params *p, const void *q, const void *k,
                           size_t workspace_bytes, void *stream);
 
 /* App. D Eq. 3 with top-k sets, exact softmax (Sec. 1), after focus_assign on
- * the same workspace.  out [B,Hq,n,d] in p->dtype.  lse (nullable) [B,Hq,n]
+ * the same workspace.  For 16-bit causal problems of n >= 16384 whose window spans
+ * would be mostly masked in class-ordered tiles, the launch runs as two passes
+ * (the pairs inside the window over position-ordered tiles, then the pairs outside
+ * it that share a group over class-ordered tiles) and merges the two partial
+ * softmaxes of every row through their log-sum-exp (App. D's merge): the same exact
+ * softmax, each allowed pair once; focus_workspace_size and focus_assign account
+ * for the second layout.  The environment variable FOCUS_TWO_PASS=0/1, read when a
+ * call derives its layout, overrides that choice (tests and measurements; it must
+ * not change between focus_workspace_size, focus_assign and focus_attn_fwd).  out [B,Hq,n,d] in p->dtype.  lse (nullable) [B,Hq,n]
  * fp32: natural log of the sum of exp of the final logits of the row.
  * row_pairs (nullable) [B,Hq,n] int32: number of pairs the row attended.  The
  * workspace is written (staging of V). */

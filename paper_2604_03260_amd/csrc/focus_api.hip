@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 namespace {
@@ -42,7 +43,8 @@ bool contiguous_tensors(const focus_params* p)
 
 // Validates the params and derives the workspace layout and the head map.
 // soft: the layout of the soft-gated attention (one class in position order whatever K, topk and the window are).
-focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap* hm, bool soft = false)
+// local: the position-ordered second layout that a two-pass problem embeds in its workspace.
+focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap* hm, bool soft = false, bool local = false)
 {
     using namespace focus;
     if (!p) return fail(FOCUS_EINVAL, "params is NULL");
@@ -85,7 +87,8 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->scale = (p->scale > 0.0f) ? p->scale : (float)(1.0 / std::sqrt((double)p->d));
     L->softcap = p->softcap;
     L->soft = soft ? 1 : 0;
-    L->dense = (soft || p->window >= p->n || 2 * p->topk > p->K) ? 1 : 0;
+    L->local_only = local ? 1 : 0;
+    L->dense = (soft || local || p->window >= p->n || 2 * p->topk > p->K) ? 1 : 0;
     if (L->dense) {
         L->NC = 1;
     } else {
@@ -175,6 +178,31 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->off_kmsk = L->coarse ? take(BHk * L->NKP * 4) : off;
     L->off_jobs = take(BHq * L->NT * 4);
     L->off_gk = (soft && p->dtype != FOCUS_F32) ? take((size_t)p->B * L->NKP * 128) : off;
+    // Two passes (see attn_launch) where the rows of a class tile spread over so many positions that the window
+    // spans of the classes without a common group, rectangles of key tiles around a diagonal band, would be mostly
+    // masked: estimated share of wasted matrix work = (window pairs among all pairs) x spread / (window + spread)
+    // with uniform memberships; from 4 % on, and only where the second set of launches is small change (n >= 16384).
+    if (!soft && !local && !L->dense && !L->coarse && p->causal && p->dtype != FOCUS_F32) {
+        double share = 1.0;                                  // P(two topk-subsets of K meet)
+        {
+            double none = 1.0;                               // C(K-k, k) / C(K, k)
+            for (int i = 0; i < p->topk; ++i) none *= (double)(p->K - p->topk - i) / (double)(p->K - i);
+            share = 1.0 - none;
+        }
+        const double w = (double)L->window, spread = (double)L->NC * L->BQ;
+        const double local_share = w / (0.5 * p->n * share + w);
+        const char* force = getenv("FOCUS_TWO_PASS");        // "0" / "1": override of the estimate (tests, measurements)
+        const bool est = p->n >= 16384 && local_share * spread / (w + spread) >= 0.04;
+        L->two_pass = (force && (force[0] == '0' || force[0] == '1')) ? (force[0] == '1') : est;
+    }
+    if (L->two_pass) {
+        focus::Layout L2;
+        focus::HeadMap hm2;
+        focus_status st2 = make_layout(p, &L2, &hm2, false, true);
+        if (st2 != FOCUS_OK) return st2;
+        L->off_local = take(L2.total);
+        L->off_lse1 = take(BHq * n * 4);
+    }
     L->off_kn2 = take(BHk * focus::KN2_SLOTS * 4);
     L->off_nrflag = take(BHq * L->NT * 4);
     if (p->dtype != FOCUS_F32) {
@@ -289,6 +317,17 @@ focus_status make_decode_layout(const focus_params* p, focus::DecodeLayout* L, f
     return FOCUS_OK;
 }
 
+// The embedded local layout of a two-pass problem: every token in one class, position order (the bucketing with a
+// constant membership, as the soft gate uses it), with its own class-ordered -- here: position-ordered -- key copy.
+hipError_t assign_local_layout(const focus_params* p, const focus::Layout& L, const void* k, char* ws, hipStream_t st)
+{
+    if (!L.two_pass) return hipSuccess;
+    focus::Layout L2;
+    focus::HeadMap hm2;
+    if (make_layout(p, &L2, &hm2, false, true) != FOCUS_OK) return hipErrorInvalidValue;
+    return focus::launch_assign_tokens(L2, nullptr, k, ws + L.off_local, nullptr, st);
+}
+
 }  // namespace
 
 extern "C" {
@@ -317,6 +356,7 @@ focus_status focus_assign(const focus_params* p, const void* q, const void* k, c
     st = check_ws(L, workspace, workspace_bytes);
     if (st != FOCUS_OK) return st;
     hipError_t e = focus::launch_assign(L, hm, q, k, centroids, (char*)workspace, (hipStream_t)stream);
+    if (e == hipSuccess) e = assign_local_layout(p, L, k, (char*)workspace, (hipStream_t)stream);
     if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_assign: %s", hipGetErrorString(e));
     return FOCUS_OK;
 }
@@ -344,7 +384,24 @@ focus_status attn_launch(const focus_params* p, int pair_set, const void* q, con
     if (st != FOCUS_OK) return st;
     L.pair_set = pair_set;
     hipError_t e;
-    if (L.dtype != FOCUS_F32 && !force_vector)
+    if (L.two_pass && pair_set == 0 && !force_vector) {
+        // Pass 1: every pair inside the window (whatever the groups) over position-ordered 128-row tiles: the
+        // band is then covered by tiles of consecutive positions, almost none of them masked.  Pass 2: the pairs
+        // outside the window that share a group, over the class-ordered tiles; its epilogue merges the two partial
+        // softmaxes of a row through their log-sum-exp (App. D's merge), so each allowed pair still counts once.
+        focus::Layout L2;
+        focus::HeadMap hm2;
+        st = make_layout(p, &L2, &hm2, false, true);
+        if (st != FOCUS_OK) return st;
+        float* lse1 = lse ? lse : (float*)((char*)workspace + L.off_lse1);
+        e = focus::launch_attn_mfma(L2, hm2, q, k, v, nullptr, (char*)workspace + L.off_local, out, lse1, row_pairs,
+                                    (hipStream_t)stream);
+        if (e == hipSuccess) {
+            L.pair_set = 3;
+            L.merge_prev = 1;
+            e = focus::launch_attn_mfma(L, hm, q, k, v, nullptr, (char*)workspace, out, lse1, row_pairs, (hipStream_t)stream);
+        }
+    } else if (L.dtype != FOCUS_F32 && !force_vector)
         e = focus::launch_attn_mfma(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
     else
         e = focus::launch_attn_simple(L, hm, q, k, v, nullptr, (char*)workspace, out, lse, row_pairs, (hipStream_t)stream);
@@ -560,6 +617,7 @@ focus_status focus_assign_tokens(const focus_params* p, const uint32_t* token_ma
     st = check_ws(L, workspace, workspace_bytes);
     if (st != FOCUS_OK) return st;
     hipError_t e = focus::launch_assign_tokens(L, token_masks, k, (char*)workspace, invalid_count, (hipStream_t)stream);
+    if (e == hipSuccess) e = assign_local_layout(p, L, k, (char*)workspace, (hipStream_t)stream);
     if (e != hipSuccess) return fail(FOCUS_EHIP, "focus_assign_tokens: %s", hipGetErrorString(e));
     return FOCUS_OK;
 }

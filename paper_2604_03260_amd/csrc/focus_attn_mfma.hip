@@ -349,13 +349,16 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     //                otherwise |qpos - kp| < w: qadj = qpos + w - 1, wlim = 2w - 1.
     unsigned mq_row = 0u;
     if constexpr (COARSE) mq_row = rvalid ? ((const unsigned*)(ws + L.off_mq))[(size_t)bhq * L.n + qpos] : 0u;
-    const int qadj_inter = L.causal ? qpos : qpos + (1 << 30);
+    // pair_set 3 (causal): a key of a class that shares a group counts when it lies at or below qpos - w; rows whose
+    // window reaches position 0 have no such key (and -1 keeps the pads, at INT_MAX, out without wrapping around)
+    const int qadj_inter = L.pair_set == 3 ? max(qpos - w, -1) : L.causal ? qpos : qpos + (1 << 30);
     const int qadj_local = L.causal ? qpos : qpos + w - 1;
     const unsigned wlim_local = L.causal ? (unsigned)w : (unsigned)(2 * w - 1);
     if (total == 0) {
-        // Only a launch restricted to one of the two pair sets can leave a tile without keys
-        // (the whole mask always holds the diagonal): its rows are empty, out = 0 and lse = -inf.
-        if (rvalid) {
+        // Only a launch restricted to a part of the mask can leave a tile without keys
+        // (the whole mask always holds the diagonal): its rows are empty, out = 0 and lse = -inf --
+        // or, in the second pass of a two-pass launch, they keep what the first pass left.
+        if (rvalid && !L.merge_prev) {
             uint16_t* orow = out + (size_t)b * L.os[0] + (size_t)h * L.os[1] + (size_t)qpos * L.os[2] + hh * (d / 2);
             for (int e = 0; e < d / 2; e += 4) *(uint2*)(orow + e) = make_uint2(0u, 0u);
             if (hh == 0) {
@@ -826,16 +829,41 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if constexpr (PAIRS) npairs += __shfl_xor(npairs, 32, 64);
     if (!rvalid) return;
-    const float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;      // an empty row (restricted pair set): out = 0, lse = -inf
+    float inv = (l_tot > 0.f) ? 1.f / l_tot : 0.f;            // an empty row (restricted pair set): out = 0, lse = -inf
     uint16_t* orow = out + (size_t)b * L.os[0] + (size_t)h * L.os[1] + (size_t)qpos * L.os[2];
+    // Second pass of a two-pass launch: this row's result over the pairs inside the window is in out / lse
+    // (16-bit, natural log).  out = (e^{l1} o1 + e^{l2} o2) / (e^{l1} + e^{l2}), App. D's merge, in log2 units.
+    float w1 = 0.f, lse2_l2 = m_ref + __builtin_amdgcn_logf(l_tot);      // -inf for an empty row
+    if (L.merge_prev) {
+        if (!(l_tot > 0.f)) return;                           // nothing outside the window: the first pass stands
+        const float lse1_l2 = lse[(size_t)bhq * L.n + qpos] * LOG2E;
+        const float top = fmaxf(lse1_l2, lse2_l2);
+        w1 = __builtin_amdgcn_exp2f(lse1_l2 - top);
+        const float w2 = __builtin_amdgcn_exp2f(lse2_l2 - top);
+        const float den = 1.f / (w1 + w2);
+        inv *= w2 * den;
+        w1 *= den;
+        lse2_l2 = top + __builtin_amdgcn_logf(w1 / den + w2);
+    }
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
             const int dcol = db * 32 + 8 * r4 + 4 * hh;
             if (DB * 32 > KS * 16 && dcol >= d) continue;        // rows of O^T past a head dim that is no multiple of 32
-            elem_t e0 = (elem_t)(o[db][r4 * 4 + 0] * inv), e1 = (elem_t)(o[db][r4 * 4 + 1] * inv);
-            elem_t e2 = (elem_t)(o[db][r4 * 4 + 2] * inv), e3 = (elem_t)(o[db][r4 * 4 + 3] * inv);
+            float f0 = o[db][r4 * 4 + 0] * inv, f1 = o[db][r4 * 4 + 1] * inv;
+            float f2 = o[db][r4 * 4 + 2] * inv, f3 = o[db][r4 * 4 + 3] * inv;
+            if (L.merge_prev) {
+                const uint2 prev = *(const uint2*)(orow + dcol);
+                elem_t p0_, p1_, p2_, p3_;
+                const uint16_t b0 = (uint16_t)(prev.x & 0xffffu), b1 = (uint16_t)(prev.x >> 16);
+                const uint16_t b2 = (uint16_t)(prev.y & 0xffffu), b3 = (uint16_t)(prev.y >> 16);
+                __builtin_memcpy(&p0_, &b0, 2); __builtin_memcpy(&p1_, &b1, 2);
+                __builtin_memcpy(&p2_, &b2, 2); __builtin_memcpy(&p3_, &b3, 2);
+                f0 = fmaf(w1, (float)p0_, f0); f1 = fmaf(w1, (float)p1_, f1);
+                f2 = fmaf(w1, (float)p2_, f2); f3 = fmaf(w1, (float)p3_, f3);
+            }
+            elem_t e0 = (elem_t)f0, e1 = (elem_t)f1, e2 = (elem_t)f2, e3 = (elem_t)f3;
             uint16_t u0, u1, u2, u3;
             __builtin_memcpy(&u0, &e0, 2); __builtin_memcpy(&u1, &e1, 2);
             __builtin_memcpy(&u2, &e2, 2); __builtin_memcpy(&u3, &e3, 2);
@@ -846,8 +874,8 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         }
     }
     if (hh == 0) {
-        if (lse) lse[(size_t)bhq * L.n + qpos] = (m_ref + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E);
-        if constexpr (PAIRS) row_pairs[(size_t)bhq * L.n + qpos] = npairs;
+        if (lse) lse[(size_t)bhq * L.n + qpos] = lse2_l2 * (1.f / LOG2E);
+        if constexpr (PAIRS) row_pairs[(size_t)bhq * L.n + qpos] = npairs + (L.merge_prev ? row_pairs[(size_t)bhq * L.n + qpos] : 0);
     }
 }
 

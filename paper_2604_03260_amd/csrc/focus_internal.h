@@ -64,7 +64,14 @@ struct Layout {
     int coarse;                // C(K,topk) exceeds MAX_CLASSES: classes are sets of S super-groups (group g folds
     int S;                     // onto g % S), a superset test; the kernels then test the real masks per pair
     int pair_set;              // which pairs a launch attends: 0 the whole mask, 1 only pairs that share a group
-                               // (set A of App. D), 2 only window pairs that share none (set B)
+                               // (set A of App. D), 2 only window pairs that share none (set B), 3 pairs that share
+                               // a group and lie outside the window (second pass of a two-pass launch)
+    int two_pass;              // the whole-mask attention launch of this problem runs as two passes: every pair inside
+                               // the window over position-ordered rows and keys (the embedded local layout), then the
+                               // pairs outside the window that share a group over class-ordered ones, merged per row
+    int local_only;            // this IS the embedded local layout: one class in position order, window pairs only
+    int merge_prev;            // launch flag of the second pass: out / lse / row_pairs hold the first pass's partial
+                               // result of every row; merge instead of overwriting (App. D's log-sum-exp merge)
     int nblk;                  // ceil(n / SB)
     int NQP;                   // padded per-head length of the class-ordered query index
     int NKP;                   // padded per-head length of the class-ordered key arrays (multiple of KT)
@@ -95,6 +102,8 @@ struct Layout {
     size_t off_kn2;                    // [B,Hkv,KN2_SLOTS] bit patterns of partial maxima of the squared key norms of the
                                        // head (16-bit types; cleared by assign_init, raised by gather_k, the attention
                                        // kernel takes the largest)
+    size_t off_local;                  // the embedded local layout's own workspace (two_pass)
+    size_t off_lse1;                   // [B,Hq,n] fp32: log-sum-exp of the first pass when the caller passes no lse (two_pass)
     size_t off_nrflag;                 // [B,Hq,NT] per work-group of the attention launch: 1 = the no-reference
                                        // instantiation did the tile, 0 = left to the other one (16-bit types)
     size_t off_kc;                     // [B,Hkv,NKP,dp] keys in class order (16-bit types)

@@ -43,8 +43,9 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
     const int nvalid = min(L.BQ, qcc[c] - t * L.BQ);
     const int i_lo = qperm[row0];
     const int i_hi = qperm[row0 + nvalid - 1];
-    // keys with position < x_hi are causal for the tile / not beyond every window (non-causal)
-    const int x_hi = L.causal ? i_hi + 1 : min(L.n, i_hi + L.window);
+    // keys with position < x_hi are causal for the tile / not beyond every window (non-causal); the pass over
+    // the pairs outside the window (pair_set 3, causal) ends below the window of the tile's last row instead
+    const int x_hi = L.pair_set == 3 ? max(0, i_hi - L.window + 1) : L.causal ? i_hi + 1 : min(L.n, i_hi + L.window);
     const int x_lo = max(0, i_lo - L.window + 1);           // keys with position < x_lo are outside every window
     const uint8_t* kcls = (const uint8_t*)(ws + L.off_kcls) + (size_t)bhk * ((size_t)L.nblk * SB);
     const int bh_i = x_hi / SB, bl_i = x_lo / SB;
@@ -67,7 +68,8 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
     const uint32_t mymask = clsmask[c];
     for (int c2 = tid; c2 < NC; c2 += nthr) {
         const int pre_hi = kbc[(size_t)bh_i * NC + c2] + P.cnt_hi[c2];
-        const bool inter = (clsmask[c2] & mymask) != 0;
+        // the local layout's one class holds every key: all of them count as "window only" there
+        const bool inter = !L.local_only && (clsmask[c2] & mymask) != 0;
         const int koff = kco[c2];
         int a = 0, b = 0;
         // Coarse classes that share a super-group hold pairs of both sets: set B then visits their window span
@@ -79,7 +81,7 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
                 a = koff / KT;
                 b = (koff + upto + KT - 1) / KT;
             }
-        } else if (L.pair_set != 1) {                      // set A skips the classes that share none
+        } else if (L.pair_set != 1 && L.pair_set != 3) {   // sets A and 3 skip the classes that share none
             const int pre_lo = kbc[(size_t)bl_i * NC + c2] + P.cnt_lo[c2];
             if (pre_hi > pre_lo) {
                 a = (koff + pre_lo) / KT;
@@ -94,7 +96,7 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
         // for a class without a common group they must also lie above i_hi - window for every row.
         // Non-causal: for a class with a common group every tile without pads; otherwise the keys must lie
         // below i_lo + window for every row instead of at or below i_lo.
-        const int safe_end = L.causal ? i_lo + 1 : min(L.n, i_lo + L.window);
+        const int safe_end = L.pair_set == 3 ? max(0, i_lo - L.window + 1) : L.causal ? i_lo + 1 : min(L.n, i_lo + L.window);
         const int cnt_below = (!L.causal && (inter || safe_end >= L.n)) ? kbc[(size_t)L.nblk * NC + c2]
                                                                         : kbc[(size_t)(safe_end / SB) * NC + c2];
         int ib = a, ie = a;
@@ -106,6 +108,10 @@ __device__ inline bool plan_query_tile(const Layout& L, const char* __restrict__
             const int lo_blk = (x_in <= 0) ? 0 : min(L.nblk, (x_in + SB - 1) / SB);
             ib = max(a, (koff + kbc[(size_t)lo_blk * NC + c2] + KT - 1) / KT);
             ie = min(b, (koff + cnt_below) / KT);
+            if (L.local_only) {          // position order: slot = position, so the bounds are exact per key tile
+                ib = max(a, (max(x_in, 0) + KT - 1) / KT);
+                ie = min(b, (i_lo + 1) / KT);
+            }
             if (ie < ib) ie = ib;
         }
         P.ibeg[c2] = ib;

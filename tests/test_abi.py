@@ -256,3 +256,21 @@ def test_noalloc_router_refuses_what_does_not_fit_its_scratch():
     st = focus.load_library().focus_route_noalloc(ctypes.byref(rp), fake, fake, fake, fake, ctypes.c_void_p(0),
                                                   ctypes.c_void_p(0))
     assert st == focus.FOCUS_EWORKSPACE and "static buffer" in focus.focus_last_error()
+
+
+def test_two_pass_is_chosen_where_the_window_spans_would_be_mostly_masked(monkeypatch):
+    """The second, position-ordered layout is embedded in the workspace only for shapes whose estimated share of
+    masked matrix work is worth a second pass (host-side decision, visible in the workspace size)."""
+    from paper_2604_03260_amd import workloads
+    monkeypatch.delenv("FOCUS_TWO_PASS", raising=False)
+
+    def size(wl, window=None):
+        return focus.focus_workspace_size(focus.make_params(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.K, wl.topk,
+                                                            wl.window if window is None else window, dtype=wl.dtype,
+                                                            softcap=wl.softcap))
+    bigger = lambda wl: size(wl) > 1.2 * size(wl, wl.n)            # dense mode never embeds a second layout
+    C = workloads.CONFIGS
+    assert bigger(C["cfg4a"]) and bigger(C["cfg4b"])
+    assert not bigger(C["cfg3"]) and not bigger(C["cfg5"]) and not bigger(C["cfg2"]) and not bigger(C["cfg1"])
+    monkeypatch.setenv("FOCUS_TWO_PASS", "1")
+    assert bigger(C["cfg3"]) and not bigger(C["cfg1"])             # fp32 has no two-pass form

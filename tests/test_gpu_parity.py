@@ -169,6 +169,33 @@ def test_large_norms_take_the_running_reference(case):
     harness.check_pair_totals(wl, res, mq, mk)
 
 
+TWO_PASS_CASES = [w for w in SMALL_CASES if w.dtype != "f32" and w.causal and w.name in (
+    "ragged_bf16", "tile_multiple", "tile_plus_one", "hard_k8", "k8_top2_mix", "k16_top1", "k5_top2",
+    "k12_top3_220_classes", "k2_top1", "softcap_bf16", "batch_mha", "gqa8", "d80_bf16", "d96_bf16", "d256_bf16",
+    "d256_bf16_softcap_k8", "f16_d64", "f16_d128_k8", "f16_d96_softcap", "f16_d256")]
+
+
+@pytest.mark.parametrize("wl", TWO_PASS_CASES, ids=[w.name for w in TWO_PASS_CASES])
+@pytest.mark.parametrize("outputs", ["all", "out_only"])
+def test_two_pass_launch_all_rows(wl, outputs, monkeypatch):
+    """The whole-mask launch as two passes (window pairs over position-ordered tiles, then the pairs outside the
+    window that share a group over class-ordered tiles, merged per row), forced on shapes the size estimate would
+    leave to one pass: every row against the oracle, pair counts exact, with and without lse / row_pairs."""
+    monkeypatch.setenv("FOCUS_TWO_PASS", "1")
+    inp = workloads.make_inputs(wl, "cuda")
+    p1 = harness.params_of(wl)
+    monkeypatch.setenv("FOCUS_TWO_PASS", "0")
+    one_pass_bytes = focus.focus_workspace_size(p1)
+    monkeypatch.setenv("FOCUS_TWO_PASS", "1")
+    assert focus.focus_workspace_size(p1) > one_pass_bytes          # the override is in force: a second layout is embedded
+    full = outputs == "all"
+    res = harness.run_gpu(wl, inp, want_pairs=full, want_lse=full)
+    mq, mk = harness.check_assign(wl, inp, res)
+    say(wl.name, harness.check_attn(wl, inp, res, mq, mk))
+    if full:
+        harness.check_pair_totals(wl, res, mq, mk)
+
+
 def test_disjoint_roles_only_window_survives():
     # queries all land in group 0 and keys in group 1: the mask is the window alone
     wl = small("window_only", n=900, K=2, topk=1, window=37, Hq=2, Hkv=2)
