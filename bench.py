@@ -39,6 +39,43 @@ def note(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
+class ClockSampler:
+    """Samples the GPU core clock with `rocm-smi -c --json` (a child process about every 0.3 s; reads sysfs, touches no
+    HIP state) while timed steps run: the clock the chip actually holds under this kernel on this data."""
+
+    def __init__(self):
+        import threading
+        self.samples, self.stop, self.thread = [], False, threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        while not self.stop:
+            try:
+                r = subprocess.run(["rocm-smi", "-c", "--json"], capture_output=True, text=True, timeout=10)
+                card = json.loads(r.stdout)
+                card = card[sorted(card.keys())[0]]
+                m = re.search(r"(\d+)\s*Mhz", card.get("sclk clock speed:", ""), re.I)
+                if m:
+                    self.samples.append((time.perf_counter(), int(m.group(1))))
+            except Exception:
+                return
+            time.sleep(0.05)
+
+    def __enter__(self):
+        self.thread.start()
+        return self
+
+    def __exit__(self, *a):
+        self.stop = True
+        self.thread.join(timeout=15)
+
+    def summary(self, t0, t1):
+        xs = [v for t, v in self.samples if t0 <= t <= t1]
+        if not xs:
+            return None
+        return {"mean": sum(xs) / len(xs), "min": min(xs), "max": max(xs), "samples": len(xs),
+                "what": "sclk from rocm-smi -c while the timed steps ran (nominal 2400 MHz)"}
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed counter summary of that kernel and workload
     (profiles/<kernel>_<workload>_counters.txt, a line `traffic_bytes_per_launch = <number>`), else None:
@@ -69,9 +106,13 @@ def assign_bytes(wl):
 class Runner:
     """One workload resident on the device: inputs, params, workspace, outputs."""
 
-    def __init__(self, torch, focus, workloads, wl, window=None):
+    def __init__(self, torch, focus, workloads, wl, window=None, zero_inputs=False):
         self.torch, self.focus, self.wl = torch, focus, wl
         self.inp = workloads.make_inputs(wl, "cuda")
+        if zero_inputs:                         # same launches, no switching activity in the multipliers
+            for name in ("q", "k", "v"):
+                self.inp[name].zero_()
+        self.t_timed = (0.0, 0.0)
         self.p = self.params(wl.window if window is None else window)
         self.ws = focus.alloc_workspace(self.p)
         self.out = torch.empty_like(self.inp["q"])
@@ -122,21 +163,23 @@ class Runner:
                     note("%s: step %d of %d done" % (label, s + 1, steps))
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        self.t_timed = (t0, t0 + wall)
         t_assign = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
         t_attn = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
         return wall * 1e3 / steps, t_assign, t_attn
 
 
-def measure(torch, focus, workloads, wl, steps, warmup, dense_steps, keep=False):
+def measure(torch, focus, workloads, wl, steps, warmup, dense_steps, keep=False, clock=None, zero_inputs=False):
     """The step on one workload: times, exact pair count, the two rooflines, the dense comparator."""
-    note("workload", describe(wl))
-    r = Runner(torch, focus, workloads, wl)
+    note("workload", describe(wl) + (" (q, k, v zeroed)" if zero_inputs else ""))
+    r = Runner(torch, focus, workloads, wl, zero_inputs=zero_inputs)
     allowed = r.count_pairs()
     kcounts = focus.focus_workspace_views(r.p, r.ws)["k_group_counts"].to(torch.float64)
     dominance = float((kcounts.max(dim=-1).values / wl.n).mean().item())
     causal_pairs = wl.B * wl.Hq * (wl.n * (wl.n + 1) // 2)
     useful_flop = 4.0 * wl.d * allowed
     ms_step, ms_assign, ms_attn = r.timed(steps, warmup, label=wl.name)
+    sclk = clock.summary(*r.t_timed) if clock else None
     half = wl.dtype in ("bf16", "f16")          # both 16-bit types run on the matrix cores at the same peak
     peak = BF16_MFMA_PEAK_TFLOPS if half else FP32_VECTOR_PEAK_TFLOPS
     kernel = "attn_mfma_kernel" if half else "attn_simple_kernel"
@@ -150,6 +193,7 @@ def measure(torch, focus, workloads, wl, steps, warmup, dense_steps, keep=False)
         "tokens_per_s": wl.B * wl.n / (ms_step * 1e-3),
         "allowed_pairs": allowed, "allowed_fraction": allowed / causal_pairs,
         "largest_group_fraction": dominance,
+        "sclk_mhz": sclk,
         "roofline": {
             "bound": "mfma" if half else "alu", "kernel": kernel,
             "achieved": tflops_attn, "peak": peak, "unit": "TFLOP/s", "frac": tflops_attn / peak,
@@ -173,6 +217,7 @@ def measure(torch, focus, workloads, wl, steps, warmup, dense_steps, keep=False)
         ms_step_d, _, ms_attn_d = r.timed(dense_steps, 1, pd, wsd, label=wl.name + " dense")
         r.out = keep_out
         res["dense"] = {"ms_attn": ms_attn_d, "ms_per_step": ms_step_d,
+                        "sclk_mhz": clock.summary(*r.t_timed) if clock else None,
                         "tflops_attn": 4.0 * wl.d * causal_pairs / (ms_attn_d * 1e-3) / 1e12,
                         "frac_of_peak": 4.0 * wl.d * causal_pairs / (ms_attn_d * 1e-3) / 1e12 / peak,
                         "what": "this library with window = n (plain causal attention through the same kernel)"}
@@ -632,6 +677,10 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of q (known size) so a counter run can be calibrated")
+    ap.add_argument("--no-clock", action="store_true", help="do not sample the core clock with rocm-smi during the steps")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="zero q, k, v of the headline workload: the same launches without switching activity in the "
+                         "multipliers (what the chip's clock does to the timings; every token then ties into one class)")
     ap.add_argument("--sweep", choices=["lengths", "decode"], default=None)
     ap.add_argument("--sweep-window", type=int, default=1024)
     ap.add_argument("--min-n", type=int, default=1 << 10)
@@ -667,7 +716,13 @@ def main():
         torch.cuda.synchronize()
         del cal, cal2
     dense_steps = 0 if args.no_dense else max(1 if only else 2, min(steps // 4, 5))
-    head, r = measure(torch, focus, workloads, wl, steps, warmup, dense_steps, keep=True)
+    clock = None if args.no_clock else ClockSampler()
+    if clock:
+        clock.__enter__()
+    head, r = measure(torch, focus, workloads, wl, steps, warmup, dense_steps, keep=True, clock=clock,
+                      zero_inputs=args.zero_inputs)
+    if clock:
+        clock.__exit__()
     out_focus = r.out
     half = wl.dtype in ("bf16", "f16")
     result = {
@@ -683,13 +738,14 @@ def main():
         "vs_baseline": None,
         "dtype": wl.dtype,
         "data": "synthetic",
-        "config": {"workload": describe(wl)},
+        "config": {"workload": describe(wl) + (" (q, k, v zeroed)" if args.zero_inputs else "")},
         "tokens_per_s": head["tokens_per_s"],
         "ms_assign": head["ms_assign"],
         "ms_attn": head["ms_attn"],
         "allowed_pairs": head["allowed_pairs"],
         "allowed_fraction": head["allowed_fraction"],
         "largest_group_fraction": head["largest_group_fraction"],
+        "sclk_mhz": head["sclk_mhz"],
         "pct_of_peak_step": 100.0 * head["useful_tflops_step"] / head["roofline"]["peak"],
         "roofline": head["roofline"],
         "roofline_assign": head["roofline_assign"],

@@ -141,7 +141,26 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     // bf16 at long n: 256-row tiles (8 wavefronts share every K/V tile: half the L2->LDS traffic per FLOP,
     // which is what bounds the kernel once a KV head's K/V no longer sits in L2/MALL)
     L->dp = (p->d <= 64) ? 64 : (p->d <= 128) ? 128 : 256;
-    L->BQ = (p->dtype != FOCUS_F32 && p->n >= LONG_N && p->d <= 128 && !L->coarse && !soft) ? 256 : BQ_VECTOR;
+    const bool can256 = p->dtype != FOCUS_F32 && p->d <= 128 && !L->coarse && !soft;   // shapes with an 8-wavefront kernel
+    L->BQ = (can256 && p->n >= LONG_N) ? 256 : BQ_VECTOR;
+    // Two passes (see attn_launch) where the rows of a class tile spread over so many positions that the window
+    // spans of the classes without a common group, rectangles of key tiles around a diagonal band, would be mostly
+    // masked: estimated share of wasted matrix work = (window pairs among all pairs) x spread / (window + spread)
+    // with uniform memberships; from 4 % on, and only where the second set of launches is small change (n >= 16384).
+    if (!soft && !local && !L->dense && !L->coarse && p->causal && p->dtype != FOCUS_F32) {
+        double none = 1.0;                                   // C(K-k, k) / C(K, k): P(two topk-subsets of K do not meet)
+        for (int i = 0; i < p->topk; ++i) none *= (double)(p->K - p->topk - i) / (double)(p->K - i);
+        const double w = (double)L->window, spread = (double)L->NC * L->BQ;
+        const double local_share = w / (0.5 * p->n * (1.0 - none) + w);
+        const char* force = getenv("FOCUS_TWO_PASS");        // "0" / "1": override of the estimate (tests, measurements)
+        const bool est = p->n >= 16384 && local_share * spread / (w + spread) >= 0.04;
+        L->two_pass = (force && (force[0] == '0' || force[0] == '1')) ? (force[0] == '1') : est;
+    }
+    // With two passes the spread of a tile's rows no longer costs masked work, so the 256-row tiles (every K/V tile
+    // fetched feeds twice the rows) pay from 131072 tokens on already (measured: cfg4a 61.8 -> 60.0 ms, cfg4b 177 -> 174 ms)
+    if ((L->two_pass || local) && can256 && p->n >= LONG_N_TWO_PASS) L->BQ = 256;
+    // class-major launch order only where the heads' K and V are far beyond the caches (see plan_heads_kernel)
+    L->class_major = (L->BQ == 256 && p->n >= LONG_N) ? 1 : 0;
     L->NT = (p->n + L->BQ - 1) / L->BQ + L->NC;
     L->NQP = L->NT * L->BQ;
     L->NKP = ((p->n + KT - 1) / KT + L->NC) * KT;
@@ -178,23 +197,6 @@ focus_status make_layout(const focus_params* p, focus::Layout* L, focus::HeadMap
     L->off_kmsk = L->coarse ? take(BHk * L->NKP * 4) : off;
     L->off_jobs = take(BHq * L->NT * 4);
     L->off_gk = (soft && p->dtype != FOCUS_F32) ? take((size_t)p->B * L->NKP * 128) : off;
-    // Two passes (see attn_launch) where the rows of a class tile spread over so many positions that the window
-    // spans of the classes without a common group, rectangles of key tiles around a diagonal band, would be mostly
-    // masked: estimated share of wasted matrix work = (window pairs among all pairs) x spread / (window + spread)
-    // with uniform memberships; from 4 % on, and only where the second set of launches is small change (n >= 16384).
-    if (!soft && !local && !L->dense && !L->coarse && p->causal && p->dtype != FOCUS_F32) {
-        double share = 1.0;                                  // P(two topk-subsets of K meet)
-        {
-            double none = 1.0;                               // C(K-k, k) / C(K, k)
-            for (int i = 0; i < p->topk; ++i) none *= (double)(p->K - p->topk - i) / (double)(p->K - i);
-            share = 1.0 - none;
-        }
-        const double w = (double)L->window, spread = (double)L->NC * L->BQ;
-        const double local_share = w / (0.5 * p->n * share + w);
-        const char* force = getenv("FOCUS_TWO_PASS");        // "0" / "1": override of the estimate (tests, measurements)
-        const bool est = p->n >= 16384 && local_share * spread / (w + spread) >= 0.04;
-        L->two_pass = (force && (force[0] == '0' || force[0] == '1')) ? (force[0] == '1') : est;
-    }
     if (L->two_pass) {
         focus::Layout L2;
         focus::HeadMap hm2;

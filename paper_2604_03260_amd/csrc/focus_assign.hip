@@ -343,7 +343,7 @@ __global__ __launch_bounds__(256) void plan_heads_kernel(Layout L, int which, ch
         for (int t = tid; t < ntc; t += 256) {
             const int s = ntc - 1 - t;
             int j = first + s;
-            if (L.BQ != 256) {
+            if (!L.class_major) {
                 j = 0;
                 for (int c2 = 0; c2 < NC; ++c2) {
                     j += min(s_nt[c2], s);

@@ -10,6 +10,7 @@ namespace focus {
 constexpr int SB = 256;        // positions per sort block (one work-group of the bucketing kernels)
 constexpr int BQ_VECTOR = 128; // query rows the fp32 vector kernel handles per pass (and its tile size)
 constexpr int LONG_N = 1 << 18; // from this sequence length on the MFMA kernel uses 8-wavefront work-groups (256-row tiles)
+constexpr int LONG_N_TWO_PASS = 1 << 17; // ... and from this length on where the attention launch runs as two passes
 constexpr int KT = 64;         // keys per attention tile; class segments of the permuted keys are padded to this
 constexpr int MAX_CLASSES = 256;
 constexpr int MAX_HQ = 256;
@@ -69,6 +70,7 @@ struct Layout {
     int two_pass;              // the whole-mask attention launch of this problem runs as two passes: every pair inside
                                // the window over position-ordered rows and keys (the embedded local layout), then the
                                // pairs outside the window that share a group over class-ordered ones, merged per row
+    int class_major;           // job list of the attention launch by class (long sequences) instead of by slot
     int local_only;            // this IS the embedded local layout: one class in position order, window pairs only
     int merge_prev;            // launch flag of the second pass: out / lse / row_pairs hold the first pass's partial
                                // result of every row; merge instead of overwriting (App. D's log-sum-exp merge)
