@@ -93,66 +93,6 @@ constexpr float CAP_POLY_Z = 0.3f;          // |score*scale/softcap| up to which
 __host__ __device__ constexpr int slot_to_key16(int p16) { return 8 * ((p16 % 8) / 4) + 4 * (p16 / 8) + (p16 % 8) % 4; }
 
 // ---------------------------------------------------------------- gathers into class order
-// sum of the squares of the eight 16-bit values of a chunk (bf16 or IEEE half bit patterns)
-__device__ inline float chunk_norm2(const uint4& val, bool f16)
-{
-    const uint32_t w[4] = {val.x, val.y, val.z, val.w};
-    float acc = 0.f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const float a = f16 ? f16_bits_to_f32((uint16_t)(w[e] & 0xffffu)) : __uint_as_float(w[e] << 16);
-        const float b = f16 ? f16_bits_to_f32((uint16_t)(w[e] >> 16)) : __uint_as_float(w[e] & 0xffff0000u);
-        acc = fmaf(a, a, acc);
-        acc = fmaf(b, b, acc);
-    }
-    return acc;
-}
-
-// Also leaves the largest squared key norm of the (batch, KV head) in the workspace (off_kn2: KN2_SLOTS partial
-// maxima per head, cleared by the first launch of the assign pass): a non-negative float orders like its bit
-// pattern, so one atomicMax on the bits per work-group does it, and a NaN or infinite norm ends up above every
-// finite one.
-template <int D>
-__global__ __launch_bounds__(NTHR) void gather_k_kernel(Layout L, const uint16_t* __restrict__ k, char* __restrict__ ws)
-{
-    constexpr int CPR = D / 8;                       // 16-byte chunks per row of the copy
-    const int cin = L.d / 8;                         // ... and of a source row (d <= D)
-    const int tile = blockIdx.x, bhk = blockIdx.y, tid = threadIdx.x;
-    const bool f16 = L.dtype == 2;
-    unsigned n2max = 0u;
-    const int* kpos = (const int*)(ws + L.off_kpos) + (size_t)bhk * L.NKP + (size_t)tile * KT;
-    uint4* dst = (uint4*)(ws + L.off_kc) + ((size_t)bhk * L.NKP + (size_t)tile * KT) * CPR;
-    // source rows through the strides of k (multiples of 8 elements = one 16-byte chunk)
-    const uint4* src = (const uint4*)k + ((size_t)(bhk / L.Hkv) * L.ks[0] + (size_t)(bhk % L.Hkv) * L.ks[1]) / 8;
-    const size_t pitch = (size_t)L.ks[2] / 8;
-    for (int id = tid; id < KT * CPR; id += NTHR) {
-        const int row = id / CPR, ch = id % CPR;
-        const int kp = kpos[row];
-        uint4 val = make_uint4(0, 0, 0, 0);
-        if (kp != KPOS_PAD && ch < cin) val = src[(size_t)kp * pitch + ch];
-        dst[id] = val;
-        // the CPR chunks of a row sit in CPR consecutive lanes (CPR a power of two <= 32, rows do not straddle waves)
-        float n2 = chunk_norm2(val, f16);
-#pragma unroll
-        for (int off = 1; off < CPR; off <<= 1) n2 += __shfl_xor(n2, off, 64);
-        const unsigned bits = __float_as_uint(n2) & 0x7fffffffu;     // a NaN may carry a sign bit
-        n2max = bits > n2max ? bits : n2max;
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const unsigned o = (unsigned)__shfl_xor((int)n2max, off, 64);
-        n2max = o > n2max ? o : n2max;
-    }
-    __shared__ unsigned s_n2[NTHR / 64];
-    if ((tid & 63) == 0) s_n2[tid >> 6] = n2max;
-    __syncthreads();
-    if (tid == 0) {
-        for (int w = 1; w < NTHR / 64; ++w) n2max = s_n2[w] > n2max ? s_n2[w] : n2max;
-        // KN2_SLOTS slots per head, so that the work-groups of a head do not queue up on one address
-        if (n2max != 0u) atomicMax((unsigned*)(ws + L.off_kn2) + (size_t)bhk * KN2_SLOTS + (tile % KN2_SLOTS), n2max);
-    }
-}
-
 template <int D>
 __global__ __launch_bounds__(NTHR) void gather_vt_kernel(Layout L, const uint16_t* __restrict__ v, char* __restrict__ ws)
 {
@@ -937,19 +877,6 @@ hipError_t launch_d(const Layout& L, const HeadMap& hm, int default_map, const v
 }
 
 }  // namespace
-
-// Class-ordered copy of the keys; part of focus_assign for bf16 problems.
-hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t st)
-{
-    dim3 ggrid(L.NKP / KT, L.B * L.Hkv);
-    if (L.dp == 64)
-        hipLaunchKernelGGL(gather_k_kernel<64>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)k, ws);
-    else if (L.dp == 128)
-        hipLaunchKernelGGL(gather_k_kernel<128>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)k, ws);
-    else
-        hipLaunchKernelGGL(gather_k_kernel<256>, ggrid, dim3(NTHR), 0, st, L, (const uint16_t*)k, ws);
-    return hipGetLastError();
-}
 
 // the soft assignments of the key positions as the matrix cores read them (see Layout::off_gk)
 __global__ __launch_bounds__(256) void soft_gather_g_kernel(Layout L, const float* __restrict__ g, char* __restrict__ ws)

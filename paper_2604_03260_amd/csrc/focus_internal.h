@@ -95,15 +95,15 @@ struct Layout {
     size_t off_clsmask;                // group bit mask of each class [NC]
     size_t off_cent64;                 // centroids as fp64 [Hkv][d rounded up to whole 128-byte row chunks][KMAX],
                                        // KMAX = K rounded up to 4/8/16/32
-    size_t off_qperm;                  // [B,Hq,NQP] positions in class order, -1 in pads
+    size_t off_qperm;                  // [B,Hq,NQP] positions in class order, -1 in pads (the scatter kernel writes both)
     size_t off_kpos;                   // [B,Hkv,NKP] positions in class order, KPOS_PAD in pads
     size_t off_kmsk;                   // [B,Hkv,NKP] membership masks in class order, 0 in pads (coarse classes only)
     size_t off_jobs;                   // [B,Hq,NT] (class << 24 | tile) heaviest first, -1 unused
     size_t off_gk;                     // [B,NKP,2,32] bf16: the soft assignment of every key position as bf16 high and
                                        // low parts, groups padded to 32, chunks swizzled per key (soft gate, 16-bit types)
     size_t off_kn2;                    // [B,Hkv,KN2_SLOTS] bit patterns of partial maxima of the squared key norms of the
-                                       // head (16-bit types; cleared by assign_init, raised by gather_k, the attention
-                                       // kernel takes the largest)
+                                       // head (16-bit types; cleared by assign_init, raised by the scatter kernel's key
+                                       // copy, the attention kernel takes the largest)
     size_t off_local;                  // the embedded local layout's own workspace (two_pass)
     size_t off_lse1;                   // [B,Hq,n] fp32: log-sum-exp of the first pass when the caller passes no lse (two_pass)
     size_t off_nrflag;                 // [B,Hq,NT] per work-group of the attention launch: 1 = the no-reference
@@ -211,7 +211,6 @@ hipError_t launch_assign_tokens(const Layout& L, const uint32_t* token_masks, co
                                 int32_t* invalid_count, hipStream_t st);
 hipError_t launch_assign(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                          const float* centroids, char* ws, hipStream_t st);
-hipError_t launch_gather_k(const Layout& L, const void* k, char* ws, hipStream_t st);
 hipError_t launch_attn_simple(const Layout& L, const HeadMap& hm, const void* q, const void* k,
                               const void* v, const float* g, char* ws, void* out, float* lse, int32_t* row_pairs,
                               hipStream_t st);
