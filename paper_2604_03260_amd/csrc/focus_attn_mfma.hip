@@ -87,6 +87,7 @@ constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift 
 constexpr float NOREF_BOUND = 60.f;         // largest |logit| bound (log2 units) up to which exp2 needs no reference
 constexpr float NOREF_SLACK = 1.01f;        // the bound is taken this much larger than computed (fp32 rounding of the norms)
 constexpr float CAP_POLY_Z = 0.3f;          // |score*scale/softcap| up to which tanh is taken as its Taylor polynomial to z^5
+constexpr float CAP_CUBIC_Z = 0.15f;        // ... and to z^3 (the z^5 term is then below 7.3e-4 log2 units at cap 50)
 
 // within a 16-key group: MFMA k-slot p16 = h*8 + e  <->  key 8*(e/4) + 4*h + e%4,
 // the order in which a lane of the S^T accumulator holds its keys
@@ -384,6 +385,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
     const float cap_c3 = -cap_c1 * cap_a * cap_a * (1.f / 3.f);
     const float cap_c5 = cap_c1 * cap_a * cap_a * cap_a * cap_a * (2.f / 15.f);
     const float cap_poly_lim = (L.softcap > 0.f) ? CAP_POLY_Z / cap_a : 0.f;
+    const float cap_cubic_lim = (L.softcap > 0.f) ? CAP_CUBIC_Z / cap_a : 0.f;
 
     const char* kc_base = ws + L.off_kc + (size_t)bhk * L.NKP * (D * 2);
     const char* vt_base = ws + L.off_vt + (size_t)bhk * L.NKP * (D * 2);
@@ -580,7 +582,9 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         /* cap*tanh(z), z = s*scale/cap.  While every |z| of the unit is below CAP_POLY_Z the odd Taylor */ \
         /* polynomial to z^5 stands in for tanh (error below 17 z^7 / 315: 6e-4 in the logit at cap 50, */ \
         /* under the rounding of the 16-bit probabilities): four plain instructions per score instead   */ \
-        /* of an exp2 and a reciprocal.  Otherwise the exact form 1 - 2 / (1 + e^(2z)).                 */ \
+        /* of an exp2 and a reciprocal.  Otherwise the exact form 1 - 2 / (1 + e^(2z)).  The 8-wavefront */ \
+        /* instantiations that do not count pairs (long sequences; the others have no register to spare) */ \
+        /* also drop the z^5 term while every |z| of the unit is below CAP_CUBIC_Z: three instructions.  */ \
         float am_ = fabsf(SIN[0]);                                                                       \
         _Pragma("unroll") for (int r = 1; r < 16; ++r) am_ = fmaxf(am_, fabsf(SIN[r]));                  \
         if (__any(!(am_ <= cap_poly_lim))) {                                                             \
@@ -588,11 +592,14 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
                 const float e2_ = __builtin_amdgcn_exp2f(SIN[r] * two_over_cap_l2);                      \
                 SIN[r] = cap_l2 - 2.f * cap_l2 * __builtin_amdgcn_rcpf(1.f + e2_);                       \
             }                                                                                            \
-        } else {                                                                                         \
+        } else if (PAIRS || COARSE || MFMA_WAVES != 8 || __any(!(am_ <= cap_cubic_lim))) {               \
             _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                             \
                 const float u_ = SIN[r] * SIN[r];                                                        \
                 SIN[r] *= fmaf(fmaf(u_, cap_c5, cap_c3), u_, cap_c1);                                    \
             }                                                                                            \
+        } else {                                                                                         \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r)                                               \
+                SIN[r] *= fmaf(SIN[r] * SIN[r], cap_c3, cap_c1);                                         \
         }                                                                                                \
     }                                                                                                    \
     if (SOFT) {                          /* masked above */                                              \
