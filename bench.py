@@ -681,6 +681,9 @@ def main():
     ap.add_argument("--zero-inputs", action="store_true",
                     help="zero q, k, v of the headline workload: the same launches without switching activity in the "
                          "multipliers (what the chip's clock does to the timings; every token then ties into one class)")
+    ap.add_argument("--lib", default=None,
+                    help="time another build of the library (a timing-only ablation build, build.py --ablate): headline "
+                         "step only, no parity-dependent legs; the line says so and its numbers are not results")
     ap.add_argument("--sweep", choices=["lengths", "decode"], default=None)
     ap.add_argument("--sweep-window", type=int, default=1024)
     ap.add_argument("--min-n", type=int, default=1 << 10)
@@ -699,6 +702,10 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.lib:
+        focus.LIB_PATH = os.path.abspath(args.lib)
+        args.only_headline = True
+        args.no_cpu_baseline = True
     if args.sweep == "lengths":
         return sweep_lengths(torch, focus, workloads, args)
     if args.sweep == "decode":
@@ -754,6 +761,9 @@ def main():
     for key in ("dense", "speedup_vs_dense_attn", "speedup_vs_dense_step"):
         if key in head:
             result[key] = head[key]
+    if args.lib:
+        result["library"] = args.lib
+        result["note"] = "timing of another build of the library (loop ablation): not a result of the method"
     if half and not only:
         leg_mfma_probe(result, head["roofline"]["achieved"])
 

@@ -93,6 +93,24 @@ def build_library(verbose=False):
     return LIB
 
 
+def build_ablation(bits, verbose=False):
+    """_build/libfocus_ablate_<bits>.so: the library with the attention kernel compiled with -DFOCUS_ABLATE=<bits>
+    (one ingredient of its key-tile loop taken out, see focus_attn_mfma.hip).  For timing only (profiles/
+    attn_loop_ablation.txt): its results are meaningless.  Needs the objects of a normal build."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    bdir = os.path.join(HERE, "_build")
+    o = os.path.join(bdir, "focus_attn_mfma_ablate_%d.o" % bits)
+    cmd = [hipcc, "-DFOCUS_ABLATE=%d" % bits] + [f for f in FLAGS if f != "-shared"] + \
+          ["-c", os.path.join(CSRC, NO_SPILL_SOURCE), "-o", o]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd, stderr=subprocess.DEVNULL)
+    objs = [o] + [os.path.join(bdir, s.replace(".hip", ".o")) for s in SOURCES if s != NO_SPILL_SOURCE]
+    out = os.path.join(bdir, "libfocus_ablate_%d.so" % bits)
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + objs)
+    return out
+
+
 def build_probes(verbose=False):
     """The stand-alone MFMA-rate program under csrc/probes that bench.py runs as a child process (not part of the library)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -106,5 +124,9 @@ def build_probes(verbose=False):
 
 
 if __name__ == "__main__":
+    if "--ablate" in sys.argv:                      # python build.py --ablate 1 2 4 8
+        for b in sys.argv[sys.argv.index("--ablate") + 1:]:
+            print(build_ablation(int(b), verbose=True))
+        sys.exit(0)
     print(build_library(verbose=True))
     print(build_probes(verbose=True))

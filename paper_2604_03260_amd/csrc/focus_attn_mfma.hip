@@ -82,6 +82,17 @@ template <> struct Half<true> {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NTHR = 256;
+
+// Timing-only builds for the loop ablation under profiles/ (python build.py --ablate BITS; never in libfocus.so).
+// Each bit takes one ingredient out of the key-tile loop so that its share of the time can be read off; the
+// results of such a build are meaningless.  Every variant stays inside its buffers and waits for nothing that
+// does not come: 1 = no barrier per tile (wavefronts may read a stage another one is still filling),
+// 2 = no v_exp_f32 (the probabilities are the converted logits), 4 = no K/V tile DMA in the loop (every tile
+// re-reads what the prologue loaded), 8 = no LDS operand reads in the loop (the MFMAs run on the registers'
+// last contents).
+#ifndef FOCUS_ABLATE
+#define FOCUS_ABLATE 0
+#endif
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float RESCALE_THRESHOLD = 8.f;    // log2 units the row max may drift before O is rescaled
 constexpr float NOREF_BOUND = 60.f;         // largest |logit| bound (log2 units) up to which exp2 needs no reference
@@ -657,8 +668,8 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
             const float a0_ = NOREF ? SIN[r] : SOFTCAP ? (SIN[r] - m_use_) : fmaf(SIN[r], sl2, -m_use_); \
             const float a1_ = NOREF ? SIN[r + 1] : SOFTCAP ? (SIN[r + 1] - m_use_) : fmaf(SIN[r + 1], sl2, -m_use_); \
             V2 pr_;                                                                                      \
-            pr_[0] = (elem_t)__builtin_amdgcn_exp2f(a0_);                                                \
-            pr_[1] = (elem_t)__builtin_amdgcn_exp2f(a1_);                                                \
+            pr_[0] = (elem_t)((FOCUS_ABLATE & 2) ? a0_ : __builtin_amdgcn_exp2f(a0_));                   \
+            pr_[1] = (elem_t)((FOCUS_ABLATE & 2) ? a1_ : __builtin_amdgcn_exp2f(a1_));                   \
             /* the row sum adds the ROUNDED probabilities, the same numbers the PV product uses */      \
             psum_ = HT::dot2(pr_, ones2, psum_);                                                         \
             POUT[r / 8][r % 8] = pr_[0];                                                                 \
@@ -678,6 +689,12 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
 #define F4_PIN2(P_) asm volatile("" : "+v"(P_[0]), "+v"(P_[1]))
     int kb_cur = 0;                                          // kpos buffer of tile t (t mod 3)
     // One key tile.  SC is the LDS stage of K(t), V(t); K(t+1), V(t-1) sit in the other.
+#if (FOCUS_ABLATE & 8)
+#undef F4_READ_K
+#undef F4_READ_V
+#define F4_READ_K(DST, KST, U, HALF) { asm volatile("" : "+v"(DST[0])); }
+#define F4_READ_V(DST, VST, U, HALF) { asm volatile("" : "+v"(DST[0])); }
+#endif
 #define F4_TILE(SC)                                                                                      \
     {                                                                                                    \
         const int sc = (SC), sn = (SC) ^ 1;                                                              \
@@ -710,10 +727,12 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         F4_PIN2(p0);                                                                                     \
         /* one barrier per tile: all are done with K(t), V(t-1); K(t+1), V(t) have landed */             \
         F4_WAIT_DMA();                                                                                   \
-        __syncthreads();                                                                                 \
-        F4_DMA_K(tl2, sc);                                                                               \
-        F4_DMA_V(tl1, sn);                                                                               \
-        F4_DMA_KPOS(tl2, kb_nn);                                                                         \
+        if (!(FOCUS_ABLATE & 1)) __syncthreads();                                                        \
+        if (!(FOCUS_ABLATE & 4)) {                                                                       \
+            F4_DMA_K(tl2, sc);                                                                           \
+            F4_DMA_V(tl1, sn);                                                                           \
+            F4_DMA_KPOS(tl2, kb_nn);                                                                     \
+        }                                                                                                \
         /* phase B: VALU softmax(S1) -> P1 ; MFMA O += V(t,u0) P0 and S0 = K(t+1,u0) Q^T */              \
         F4_READ_V(av, sc, 0, 0)                                                                          \
         F4_READ_K(ak, sn, 0, 0)                                                                          \

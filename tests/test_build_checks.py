@@ -24,3 +24,16 @@ def test_accepts_a_build_without_spills_in_the_attention_kernel():
 def test_refuses_spills_and_missing_reports(bad):
     with pytest.raises(RuntimeError):
         build.check_no_spills(bad)
+
+
+def test_the_library_build_never_ablates_the_attention_loop():
+    """FOCUS_ABLATE (timing-only builds of the loop ablation) defaults to 0 in the source and is set by
+    build_ablation alone, which writes to another file than the library."""
+    import os
+    import re
+    src = open(os.path.join(build.CSRC, "focus_attn_mfma.hip")).read()
+    assert re.search(r"#ifndef FOCUS_ABLATE\s*\n#define FOCUS_ABLATE 0\s*\n#endif", src)
+    assert not any("FOCUS_ABLATE" in f for f in build.FLAGS)
+    import inspect
+    assert "FOCUS_ABLATE" not in inspect.getsource(build.build_library)
+    assert "libfocus_ablate_%d.so" in inspect.getsource(build.build_ablation)
