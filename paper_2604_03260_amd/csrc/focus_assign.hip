@@ -276,6 +276,7 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     const double* __restrict__ cd = cent64 + (size_t)hk * dcent * KMAX;
     for (int e = tid; e < MAX_CLASSES; e += SB) s_hist_c[e] = 0;
     if (tid < 32) s_hist_g[tid] = 0;
+    __syncthreads();                                                 // (the steps below have no barrier of their own)
 
     double acc[KMAX];
 #pragma unroll
@@ -298,7 +299,7 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
         const int rows_ = min(SB, n - (blk0 + bi_) * SB);                                            \
         const char* g_ = xbase + (size_t)(blk0 + bi_) * SB * row_pitch + ph_ * ROW_CHUNK_BYTES;      \
         _Pragma("unroll") for (int i = 0; i < CPR; ++i) {                                            \
-            const int cid_ = tid + i * SB;                                                           \
+            const int cid_ = (tid & ~63) * CPR + i * 64 + (tid & 63);   /* chunk of this wavefront's 64 rows */ \
             const int r_ = cid_ / CPR, cc_ = cid_ % CPR;                                             \
             const u32x4 z_ = {0u, 0u, 0u, 0u};                                                       \
             const bool in_ = r_ < rows_ && ph_ * ROW_CHUNK_BYTES + cc_ * 16 < row_bytes;                 \
@@ -309,13 +310,17 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
     FOCUS_SCORE_LOAD(0);
     for (int step = 0; step < total_steps; ++step) {
         const int bi = step / phases, ph = step % phases;
-        __syncthreads();                                             // the previous step's reads are done
+        // Every wavefront stages and reads its own 64 rows: LDS executes a wavefront's accesses in order, so no
+        // barrier is needed, only the compiler must keep the order.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int i = 0; i < CPR; ++i) {
-            const int cid = tid + i * SB;
+            const int cid = (tid & ~63) * CPR + i * 64 + (tid & 63);
             *(u32x4*)(s_rows + (cid / CPR) * ROW_STRIDE + (cid % CPR) * 16) = st[i];
         }
-        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         if (step + 1 < total_steps) FOCUS_SCORE_LOAD(step + 1);
         const int tbase = ph * (ROW_CHUNK_BYTES / (int)sizeof(T));
 #pragma unroll 1
@@ -389,7 +394,7 @@ __global__ __launch_bounds__(SB) void score_topk_kernel(Layout L, HeadMap hm, co
         int* bg = (int*)(ws + (is_query ? L.off_qbg : L.off_kbg)) + ((size_t)bh * (L.nblk + 1) + blk) * K;
         for (int c = tid; c < L.NC; c += SB) { bc[c] = s_hist_c[c]; s_hist_c[c] = 0; }
         if (tid < K) { bg[tid] = s_hist_g[tid]; s_hist_g[tid] = 0; }
-        // the next block's atomics come after the two barriers of its first step
+        __syncthreads();                                             // cleared before the next block's atomics
     }
 #undef FOCUS_SCORE_LOAD
 }
