@@ -452,8 +452,10 @@ __global__ __launch_bounds__(SB) void scatter_kernel(Layout L, int which, const 
     __shared__ unsigned s_n2[SB / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int blk = blockIdx.x;
-    const int is_query = side_of_row(L, which, blockIdx.y);
-    const int bh = row_in_side(L, which, blockIdx.y);
+    // the key rows (the long ones: they copy their sort block of K) are dispatched first
+    const unsigned yrow = gridDim.y - 1u - blockIdx.y;
+    const int is_query = side_of_row(L, which, yrow);
+    const int bh = row_in_side(L, which, yrow);
     const int n = L.n, NC = L.NC, K = L.K;
     const int pos = blk * SB + tid;
     const bool valid = pos < n;
