@@ -17,3 +17,4 @@ def test_help_lists_the_sweeps_and_the_headline_default_without_a_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True,
                        timeout=300)
     assert r.returncode == 0 and "--sweep" in r.stdout and "cfg5" in r.stdout
+    assert "--lib" in r.stdout and "not results" in " ".join(r.stdout.split())     # timing-only builds say what they are
