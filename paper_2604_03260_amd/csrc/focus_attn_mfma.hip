@@ -89,7 +89,8 @@ constexpr int NTHR = 256;
 // does not come: 1 = no barrier per tile (wavefronts may read a stage another one is still filling),
 // 2 = no v_exp_f32 (the probabilities are the converted logits), 4 = no K/V tile DMA in the loop (every tile
 // re-reads what the prologue loaded), 8 = no LDS operand reads in the loop (the MFMAs run on the registers'
-// last contents).
+// last contents), 16 = no wait for the tile DMA inside the loop (a tile may be read before it has landed; the wait
+// after the loop stays).
 #ifndef FOCUS_ABLATE
 #define FOCUS_ABLATE 0
 #endif
@@ -726,7 +727,7 @@ __global__ __launch_bounds__(64 * MFMA_WAVES, (D == 256 || SOFT) ? 1 : 8 / MFMA_
         __builtin_amdgcn_iglp_opt(3);                                                                    \
         F4_PIN2(p0);                                                                                     \
         /* one barrier per tile: all are done with K(t), V(t-1); K(t+1), V(t) have landed */             \
-        F4_WAIT_DMA();                                                                                   \
+        if (!(FOCUS_ABLATE & 16)) F4_WAIT_DMA();                                                         \
         if (!(FOCUS_ABLATE & 1)) __syncthreads();                                                        \
         if (!(FOCUS_ABLATE & 4)) {                                                                       \
             F4_DMA_K(tl2, sc);                                                                           \
